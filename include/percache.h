@@ -1,0 +1,176 @@
+/*
+ * percache.h -- C ABI of the MI355X (gfx950) cache-reusing prefill and query-level match.
+ *
+ * The calls follow the online path of PerCache (arXiv 2601.11553, Sec. 3 "System Overview",
+ * Sec. 4.2 "Cache Reuse", App. B.1): a query embedding is first matched against the QA bank
+ * (percache_lookup); on a miss the K/V tensors of the retrieved chunks are taken from the
+ * cache (a slot-indexed, per-layer, device-resident store filled by percache_kv_put) and only
+ * the fresh suffix of the prompt is projected and attended (percache_prefill_reuse).
+ *
+ * Conventions
+ *   - "dev" pointers are device (HBM) pointers owned by the caller; "host" pointers are
+ *     ordinary host memory read before the call returns.  The library allocates no device
+ *     memory: the caller hands over one arena at create time and a workspace per call.
+ *   - Storage dtypes are fixed: hidden states, weights, Q/K/V and attention output are bf16;
+ *     query embeddings are fp16; similarities and softmax state are fp32.
+ *   - Every call validates its arguments on the host BEFORE enqueuing anything, so a call that
+ *     returns an error has had no effect.  Work is enqueued on the caller's stream (a
+ *     hipStream_t passed as void*; NULL = the default stream) and is complete once the caller
+ *     synchronises that stream.  No call synchronises the device except percache_create.
+ *   - One context serves one stream at a time; concurrent calls on one context are not safe.
+ *   - All functions return PC_OK (0) or a negative pc_status; percache_last_error gives text.
+ */
+#ifndef PERCACHE_H
+#define PERCACHE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct percache_ctx percache_ctx;
+
+typedef enum {
+  PC_OK = 0,
+  PC_EINVAL = -1, /* null pointer, negative count, bad alignment */
+  PC_ESHAPE = -2, /* a dimension the kernels do not support, or out of configured range */
+  PC_ESLOT = -3,  /* slot / layer index out of range, or slot empty */
+  PC_ELEN = -4,   /* used length exceeds stored length, capacity or max_pos */
+  PC_ENOMEM = -5, /* arena or workspace too small */
+  PC_EHIP = -6    /* HIP runtime error; text in percache_last_error */
+} pc_status;
+
+/* Immutable shape of one context.  Supported: head_dim 64 or 128; hidden a multiple of 64;
+ * n_q_heads a multiple of n_kv_heads; slot_capacity a multiple of 64; emb_dim 64, 128 or a multiple of 256. */
+typedef struct {
+  int32_t n_layers;      /* layers of K/V store */
+  int32_t hidden;        /* model width H */
+  int32_t n_q_heads;     /* Hq */
+  int32_t n_kv_heads;    /* Hkv */
+  int32_t head_dim;      /* D */
+  int32_t n_slots;       /* S: chunk slots per layer */
+  int32_t slot_capacity; /* C: tokens per slot */
+  int32_t max_pos;       /* RoPE table length; L_pre + T_f must not exceed it */
+  float rope_theta;      /* RoPE base */
+  int32_t bank_capacity; /* N_max: rows of the query-embedding bank (0 = no bank) */
+  int32_t emb_dim;       /* d: embedding width */
+} percache_config;
+
+/* Bytes of device memory the caller must provide for a context of this shape (0 on a bad
+ * config).  Holds the RoPE table, the embedding bank with its inverse norms, and the K and V
+ * stores of every layer. */
+size_t percache_arena_bytes(const percache_config *cfg);
+
+/* Builds a context over the caller's arena (256-byte aligned device memory of at least
+ * percache_arena_bytes).  Computes the RoPE table on the host in double precision and copies it
+ * in (this call synchronises).  All slots start empty and the bank starts with zero rows.
+ * The arena must outlive the context; percache_destroy frees host state only. */
+pc_status percache_create(const percache_config *cfg, void *arena_dev, size_t arena_bytes,
+                          percache_ctx **out);
+void percache_destroy(percache_ctx *ctx);
+/* Text of the last error on this context (never NULL; "" if none).  With ctx == NULL: the last
+ * error of percache_create on this thread. */
+const char *percache_last_error(const percache_ctx *ctx);
+
+/* ---------------------------------------------------------------- front tier (Sec. 4.2.1)
+ * The QA bank's embedding matrix E[N, d] (fp16, row-major).  percache_bank_put writes rows
+ * [index, index + n) from emb_dev ([n, d] fp16) and computes their inverse L2 norms; the bank
+ * size becomes max(size, index + n).  index must not exceed the current size (no holes). */
+pc_status percache_bank_put(percache_ctx *ctx, int32_t index, const void *emb_dev, int32_t n,
+                            void *stream);
+int32_t percache_bank_size(const percache_ctx *ctx);
+
+/* Cosine top-1 of each probe against every bank row, and the hit flag of Sec. 4.2.1:
+ *   sim[p] = max_j <probe_p, e_j> / (|probe_p| |e_j|),  idx[p] = the lowest j attaining it,
+ *   hit[p] = sim[p] > tau   (strict: the similarity must EXCEED the threshold).
+ * A zero-norm probe or row has similarity 0.  Empty bank: idx -1, sim -inf, hit 0.
+ *   probes_dev [n_probes, d] fp16;  idx_out_dev int32[n_probes];  sim_out_dev float[n_probes];
+ *   hit_out_dev uint8[n_probes];  workspace_dev >= percache_lookup_workspace_bytes. */
+size_t percache_lookup_workspace_bytes(const percache_ctx *ctx, int32_t n_probes);
+pc_status percache_lookup(percache_ctx *ctx, const void *probes_dev, int32_t n_probes, float tau,
+                          int32_t *idx_out_dev, float *sim_out_dev, uint8_t *hit_out_dev,
+                          void *workspace_dev, size_t workspace_bytes, void *stream);
+
+/* ---------------------------------------------------------------- K/V store (Sec. 4.1.1)
+ * One slot holds one knowledge chunk's K and V for one layer, as collected from the attention
+ * module during a prefill (K already rotated at the positions it had then).
+ *   k_dev, v_dev: [n_kv_heads, n_tokens, head_dim] bf16, 1 <= n_tokens <= slot_capacity.
+ * percache_kv_put overwrites the slot and records n_tokens; percache_kv_get copies the stored
+ * tokens back out in the same layout and reports the count (known on the host: no sync).
+ * percache_kv_evict marks a slot empty (no device work). */
+pc_status percache_kv_put(percache_ctx *ctx, int32_t layer, int32_t slot, const void *k_dev,
+                          const void *v_dev, int32_t n_tokens, void *stream);
+pc_status percache_kv_get(percache_ctx *ctx, int32_t layer, int32_t slot, void *k_out_dev,
+                          void *v_out_dev, int32_t *n_tokens_out_host, void *stream);
+pc_status percache_kv_evict(percache_ctx *ctx, int32_t layer, int32_t slot);
+/* Stored token count of a slot, 0 if empty, negative pc_status on a bad index. */
+int32_t percache_kv_len(const percache_ctx *ctx, int32_t layer, int32_t slot);
+
+/* ---------------------------------------------------------------- cache-reusing prefill
+ * (Sec. 4.2.2, App. B.1) for the attention module of one layer, `batch` independent queries.
+ *
+ * Chunk list, on the host: query b uses chunks slot_ids_host[b*max_chunks + c], c <
+ * n_chunks_host[b], in prompt order, taking the first used_len_host[b*max_chunks + c] tokens of
+ * each (used_len_host == NULL: the stored length; a shorter length drops the chunk's last tokens,
+ * App. B.2).  L_pre[b] is the sum of the used lengths.  n_chunks_host[b] == 0 is an ordinary
+ * causal prefill (full recomputation).
+ *
+ * Steps, all on device:
+ *   1. [Q|K|V] = x_fresh Wqkv^T on the fresh rows only (Wqkv rows: Q heads, K heads, V heads);
+ *   2. RoPE (pairs (m, m + D/2), angle pos * theta^(-2m/D)) on q and k of fresh token i at
+ *      position L_pre[b] + i;
+ *   3. fresh row i of head h attends over [cached chunk tokens ; fresh tokens t <= i] of kv
+ *      head h / (Hq/Hkv): softmax(q.k / sqrt(D)) weighted sum of values.
+ *
+ *   x_fresh_dev      [batch, t_fresh, hidden] bf16
+ *   wqkv_dev         [(Hq + 2 Hkv) * D, hidden] bf16
+ *   attn_out_dev     [batch, t_fresh, Hq * D] bf16
+ *   k_fresh_out_dev, v_fresh_out_dev  [batch, Hkv, t_fresh, D] bf16 (post-RoPE K), the layout
+ *                    percache_kv_put takes per query; either may be NULL (kept in workspace).
+ *   workspace_dev    >= percache_prefill_workspace_bytes(ctx, batch, t_fresh, max_chunks)
+ */
+size_t percache_prefill_workspace_bytes(const percache_ctx *ctx, int32_t batch, int32_t t_fresh,
+                                        int32_t max_chunks);
+pc_status percache_prefill_reuse(percache_ctx *ctx, int32_t layer, const void *x_fresh_dev,
+                                 const void *wqkv_dev, int32_t batch, int32_t t_fresh,
+                                 const int32_t *slot_ids_host, const int32_t *used_len_host,
+                                 const int32_t *n_chunks_host, int32_t max_chunks,
+                                 void *attn_out_dev, void *k_fresh_out_dev, void *v_fresh_out_dev,
+                                 void *workspace_dev, size_t workspace_bytes, void *stream);
+
+/* The two halves of percache_prefill_reuse as separate calls (same arguments and checks), so
+ * that each can be measured and tested on its own.
+ *   percache_qkv_rope: steps 1-2; q_out_dev [batch, Hq, t_fresh, D] bf16.
+ *   percache_attention_reuse: step 3 from given q / fresh k / fresh v.  n_splits > 0 forces the
+ *   number of partitions of the key axis that are processed by separate workgroups and merged
+ *   afterwards (0 = chosen by the library); results do not depend on it beyond fp32 rounding. */
+pc_status percache_qkv_rope(percache_ctx *ctx, const void *x_fresh_dev, const void *wqkv_dev,
+                            int32_t batch, int32_t t_fresh, const int32_t *slot_ids_host,
+                            const int32_t *used_len_host, const int32_t *n_chunks_host,
+                            int32_t max_chunks, int32_t layer, void *q_out_dev, void *k_fresh_out_dev,
+                            void *v_fresh_out_dev, void *workspace_dev, size_t workspace_bytes,
+                            void *stream);
+pc_status percache_attention_reuse(percache_ctx *ctx, int32_t layer, const void *q_dev,
+                                   const void *k_fresh_dev, const void *v_fresh_dev, int32_t batch,
+                                   int32_t t_fresh, const int32_t *slot_ids_host,
+                                   const int32_t *used_len_host, const int32_t *n_chunks_host,
+                                   int32_t max_chunks, int32_t n_splits, void *attn_out_dev,
+                                   void *workspace_dev, size_t workspace_bytes, void *stream);
+
+/* ---------------------------------------------------------------- kernel timing
+ * With profiling on, the launches of the three main kernels are bracketed by HIP events on the caller's
+ * stream (the paper reports per-stage latency breakdowns, Sec. 5.3 and Table "System Overhead"; this is
+ * the device-side counterpart).  percache_profile_read waits for the recorded events, returns the summed
+ * duration in milliseconds and the number of launches since the last read or enable, and clears the record
+ * (at most 256 launches per kernel are kept).  kernel: 0 lookup stream pass, 1 QKV projection + RoPE,
+ * 2 reuse attention (main kernel, without the split merge). */
+typedef enum { PC_KERNEL_LOOKUP = 0, PC_KERNEL_QKV_ROPE = 1, PC_KERNEL_ATTENTION = 2 } pc_kernel;
+pc_status percache_profile_enable(percache_ctx *ctx, int32_t on);
+pc_status percache_profile_read(percache_ctx *ctx, int32_t kernel, float *sum_ms_host, int32_t *count_host);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PERCACHE_H */

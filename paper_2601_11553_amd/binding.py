@@ -1,0 +1,273 @@
+"""Thin ctypes binding over libpercache.so: argument marshalling only.
+
+Every step of the hot path runs in the HIP kernels behind the C ABI declared in
+``include/percache.h``; the functions here have the same names and only turn torch
+tensors into device pointers (``.data_ptr()``), numpy/int lists into host arrays, and the
+current torch stream into a ``hipStream_t``.  There is no CPU fallback: if the shared library
+is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpercache.so")
+
+PC_OK = 0
+STATUS_NAMES = {0: "PC_OK", -1: "PC_EINVAL", -2: "PC_ESHAPE", -3: "PC_ESLOT", -4: "PC_ELEN", -5: "PC_ENOMEM", -6: "PC_EHIP"}
+
+EXPORTS = [
+    "percache_arena_bytes", "percache_create", "percache_destroy", "percache_last_error",
+    "percache_bank_put", "percache_bank_size", "percache_lookup_workspace_bytes", "percache_lookup",
+    "percache_kv_put", "percache_kv_get", "percache_kv_evict", "percache_kv_len",
+    "percache_prefill_workspace_bytes", "percache_prefill_reuse", "percache_qkv_rope", "percache_attention_reuse",
+    "percache_profile_enable", "percache_profile_read",
+]
+KERNEL_LOOKUP, KERNEL_QKV_ROPE, KERNEL_ATTENTION = 0, 1, 2
+
+
+class PercacheError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"{STATUS_NAMES.get(status, status)}: {text}")
+        self.status = status
+
+
+class Config(ctypes.Structure):
+    _fields_ = [
+        ("n_layers", ctypes.c_int32), ("hidden", ctypes.c_int32), ("n_q_heads", ctypes.c_int32),
+        ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32), ("n_slots", ctypes.c_int32),
+        ("slot_capacity", ctypes.c_int32), ("max_pos", ctypes.c_int32), ("rope_theta", ctypes.c_float),
+        ("bank_capacity", ctypes.c_int32), ("emb_dim", ctypes.c_int32),
+    ]
+
+
+_lib = None
+_vp, _i32, _sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+_pi32 = ctypes.POINTER(ctypes.c_int32)
+
+
+def load_library() -> ctypes.CDLL:
+    """Loads the built library; raises if it has not been built (no fallback path exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(f"{LIB_PATH} is missing: build it with `python -m paper_2601_11553_amd.build`")
+    lib = ctypes.CDLL(LIB_PATH)
+    cfgp = ctypes.POINTER(Config)
+    sig = {
+        "percache_arena_bytes": (_sz, [cfgp]),
+        "percache_create": (_i32, [cfgp, _vp, _sz, ctypes.POINTER(_vp)]),
+        "percache_destroy": (None, [_vp]),
+        "percache_last_error": (ctypes.c_char_p, [_vp]),
+        "percache_bank_put": (_i32, [_vp, _i32, _vp, _i32, _vp]),
+        "percache_bank_size": (_i32, [_vp]),
+        "percache_lookup_workspace_bytes": (_sz, [_vp, _i32]),
+        "percache_lookup": (_i32, [_vp, _vp, _i32, ctypes.c_float, _vp, _vp, _vp, _vp, _sz, _vp]),
+        "percache_kv_put": (_i32, [_vp, _i32, _i32, _vp, _vp, _i32, _vp]),
+        "percache_kv_get": (_i32, [_vp, _i32, _i32, _vp, _vp, _pi32, _vp]),
+        "percache_kv_evict": (_i32, [_vp, _i32, _i32]),
+        "percache_kv_len": (_i32, [_vp, _i32, _i32]),
+        "percache_prefill_workspace_bytes": (_sz, [_vp, _i32, _i32, _i32]),
+        "percache_prefill_reuse": (_i32, [_vp, _i32, _vp, _vp, _i32, _i32, _pi32, _pi32, _pi32, _i32, _vp, _vp, _vp, _vp, _sz, _vp]),
+        "percache_qkv_rope": (_i32, [_vp, _vp, _vp, _i32, _i32, _pi32, _pi32, _pi32, _i32, _i32, _vp, _vp, _vp, _vp, _sz, _vp]),
+        "percache_attention_reuse": (_i32, [_vp, _i32, _vp, _vp, _vp, _i32, _i32, _pi32, _pi32, _pi32, _i32, _i32, _vp, _vp, _sz, _vp]),
+        "percache_profile_enable": (_i32, [_vp, _i32]),
+        "percache_profile_read": (_i32, [_vp, _i32, ctypes.POINTER(ctypes.c_float), _pi32]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(lib, name)
+        fn.restype = res
+        fn.argtypes = args
+    _lib = lib
+    return lib
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else int(t.data_ptr())
+
+
+def _stream() -> Optional[int]:
+    import torch
+    return int(torch.cuda.current_stream().cuda_stream) or None
+
+
+def _host_i32(a, shape=None):
+    if a is None:
+        return None, None
+    arr = np.ascontiguousarray(a, dtype=np.int32)
+    if shape is not None:
+        arr = arr.reshape(shape)
+    return arr, arr.ctypes.data_as(_pi32)
+
+
+class Percache:
+    """One context = one arena (a torch uint8 CUDA tensor) + host bookkeeping.  Methods mirror the C calls."""
+
+    def __init__(self, *, n_layers=1, hidden=1024, n_q_heads=16, n_kv_heads=8, head_dim=128, n_slots=16,
+                 slot_capacity=512, max_pos=4096, rope_theta=10000.0, bank_capacity=0, emb_dim=0, device="cuda:0"):
+        import torch
+        self.lib = load_library()
+        self.cfg = Config(n_layers, hidden, n_q_heads, n_kv_heads, head_dim, n_slots, slot_capacity, max_pos,
+                          rope_theta, bank_capacity, emb_dim)
+        self.device = torch.device(device)
+        need = self.lib.percache_arena_bytes(ctypes.byref(self.cfg))
+        if need == 0:
+            # let create produce the message
+            out = _vp()
+            st = self.lib.percache_create(ctypes.byref(self.cfg), None, 0, ctypes.byref(out))
+            raise PercacheError(st, self.lib.percache_last_error(None).decode())
+        self.arena = torch.empty(need + 256, dtype=torch.uint8, device=self.device)
+        base = self.arena.data_ptr()
+        self._arena_ptr = (base + 255) // 256 * 256
+        out = _vp()
+        with torch.cuda.device(self.device):
+            st = self.lib.percache_create(ctypes.byref(self.cfg), self._arena_ptr, need, ctypes.byref(out))
+        if st != PC_OK:
+            raise PercacheError(st, self.lib.percache_last_error(None).decode())
+        self.ctx = out
+        self._ws = None
+        self._lookup_ws = None
+
+    # ------------------------------------------------------------------ helpers
+    def _check(self, st: int):
+        if st != PC_OK:
+            raise PercacheError(st, self.lib.percache_last_error(self.ctx).decode())
+
+    def close(self):
+        if getattr(self, "ctx", None):
+            self.lib.percache_destroy(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _workspace(self, nbytes: int):
+        import torch
+        if self._ws is None or self._ws.numel() < nbytes + 256:
+            self._ws = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
+        p = (self._ws.data_ptr() + 255) // 256 * 256
+        return p
+
+    def percache_profile_enable(self, on: bool = True):
+        self._check(self.lib.percache_profile_enable(self.ctx, 1 if on else 0))
+
+    def percache_profile_read(self, kernel: int):
+        """(summed milliseconds, launches) of one kernel kind since the last read; waits for the events."""
+        ms, n = ctypes.c_float(0), ctypes.c_int32(0)
+        self._check(self.lib.percache_profile_read(self.ctx, kernel, ctypes.byref(ms), ctypes.byref(n)))
+        return ms.value, n.value
+
+    # ------------------------------------------------------------------ front tier
+    def percache_bank_put(self, index: int, emb):
+        self._check(self.lib.percache_bank_put(self.ctx, index, _ptr(emb), emb.shape[0], _stream()))
+
+    def percache_bank_size(self) -> int:
+        return self.lib.percache_bank_size(self.ctx)
+
+    def percache_lookup(self, probes, tau: float, idx_out=None, sim_out=None, hit_out=None):
+        import torch
+        n = probes.shape[0]
+        if idx_out is None:
+            idx_out = torch.empty(n, dtype=torch.int32, device=self.device)
+            sim_out = torch.empty(n, dtype=torch.float32, device=self.device)
+            hit_out = torch.empty(n, dtype=torch.uint8, device=self.device)
+        need = self.lib.percache_lookup_workspace_bytes(self.ctx, n)
+        if self._lookup_ws is None or self._lookup_ws.numel() < need + 256:
+            self._lookup_ws = torch.empty(need + 256, dtype=torch.uint8, device=self.device)
+        ws = (self._lookup_ws.data_ptr() + 255) // 256 * 256
+        self._check(self.lib.percache_lookup(self.ctx, _ptr(probes), n, tau, _ptr(idx_out), _ptr(sim_out),
+                                             _ptr(hit_out), ws, need, _stream()))
+        return idx_out, sim_out, hit_out
+
+    # ------------------------------------------------------------------ K/V store
+    def percache_kv_put(self, layer: int, slot: int, k, v, n_tokens: Optional[int] = None):
+        n = k.shape[1] if n_tokens is None else n_tokens
+        self._check(self.lib.percache_kv_put(self.ctx, layer, slot, _ptr(k), _ptr(v), n, _stream()))
+
+    def percache_kv_get(self, layer: int, slot: int):
+        import torch
+        n = self.lib.percache_kv_len(self.ctx, layer, slot)
+        if n <= 0:
+            self._check(n if n < 0 else -3)
+        shape = (self.cfg.n_kv_heads, n, self.cfg.head_dim)
+        k = torch.empty(shape, dtype=torch.bfloat16, device=self.device)
+        v = torch.empty(shape, dtype=torch.bfloat16, device=self.device)
+        cnt = ctypes.c_int32(0)
+        self._check(self.lib.percache_kv_get(self.ctx, layer, slot, _ptr(k), _ptr(v), ctypes.byref(cnt), _stream()))
+        assert cnt.value == n
+        return k, v
+
+    def percache_kv_evict(self, layer: int, slot: int):
+        self._check(self.lib.percache_kv_evict(self.ctx, layer, slot))
+
+    def percache_kv_len(self, layer: int, slot: int) -> int:
+        return self.lib.percache_kv_len(self.ctx, layer, slot)
+
+    # ------------------------------------------------------------------ prefill
+    def _chunk_args(self, batch, slot_ids, used_len, n_chunks):
+        slot_ids = np.zeros((batch, 0), np.int32) if slot_ids is None else np.asarray(slot_ids, np.int32).reshape(batch, -1)
+        max_chunks = slot_ids.shape[1]
+        if n_chunks is None:
+            n_chunks = np.full(batch, max_chunks, np.int32)
+        ids, ids_p = _host_i32(slot_ids)
+        ul, ul_p = _host_i32(used_len, (batch, max_chunks)) if used_len is not None else (None, None)
+        nc, nc_p = _host_i32(n_chunks, (batch,))
+        return (ids, ul, nc), ids_p, ul_p, nc_p, max_chunks
+
+    def percache_prefill_workspace_bytes(self, batch, t_fresh, max_chunks) -> int:
+        return self.lib.percache_prefill_workspace_bytes(self.ctx, batch, t_fresh, max_chunks)
+
+    def percache_prefill_reuse(self, layer, x_fresh, wqkv, slot_ids=None, used_len=None, n_chunks=None,
+                               attn_out=None, k_fresh_out=None, v_fresh_out=None):
+        import torch
+        batch, t_fresh, _ = x_fresh.shape
+        keep, ids_p, ul_p, nc_p, max_chunks = self._chunk_args(batch, slot_ids, used_len, n_chunks)
+        c = self.cfg
+        if attn_out is None:
+            attn_out = torch.empty((batch, t_fresh, c.n_q_heads * c.head_dim), dtype=torch.bfloat16, device=self.device)
+        need = self.percache_prefill_workspace_bytes(batch, t_fresh, max_chunks)
+        ws = self._workspace(need)
+        self._check(self.lib.percache_prefill_reuse(self.ctx, layer, _ptr(x_fresh), _ptr(wqkv), batch, t_fresh, ids_p,
+                                                    ul_p, nc_p, max_chunks, _ptr(attn_out), _ptr(k_fresh_out),
+                                                    _ptr(v_fresh_out), ws, need, _stream()))
+        return attn_out
+
+    def percache_qkv_rope(self, layer, x_fresh, wqkv, slot_ids=None, used_len=None, n_chunks=None,
+                          q_out=None, k_out=None, v_out=None):
+        import torch
+        batch, t_fresh, _ = x_fresh.shape
+        keep, ids_p, ul_p, nc_p, max_chunks = self._chunk_args(batch, slot_ids, used_len, n_chunks)
+        c = self.cfg
+        if q_out is None:
+            q_out = torch.empty((batch, c.n_q_heads, t_fresh, c.head_dim), dtype=torch.bfloat16, device=self.device)
+            k_out = torch.empty((batch, c.n_kv_heads, t_fresh, c.head_dim), dtype=torch.bfloat16, device=self.device)
+            v_out = torch.empty_like(k_out)
+        need = self.percache_prefill_workspace_bytes(batch, t_fresh, max_chunks)
+        ws = self._workspace(need)
+        self._check(self.lib.percache_qkv_rope(self.ctx, _ptr(x_fresh), _ptr(wqkv), batch, t_fresh, ids_p, ul_p, nc_p,
+                                               max_chunks, layer, _ptr(q_out), _ptr(k_out), _ptr(v_out), ws, need,
+                                               _stream()))
+        return q_out, k_out, v_out
+
+    def percache_attention_reuse(self, layer, q, k_fresh, v_fresh, slot_ids=None, used_len=None, n_chunks=None,
+                                 n_splits: int = 0, attn_out=None):
+        import torch
+        batch, _, t_fresh, _ = q.shape
+        keep, ids_p, ul_p, nc_p, max_chunks = self._chunk_args(batch, slot_ids, used_len, n_chunks)
+        c = self.cfg
+        if attn_out is None:
+            attn_out = torch.empty((batch, t_fresh, c.n_q_heads * c.head_dim), dtype=torch.bfloat16, device=self.device)
+        need = self.percache_prefill_workspace_bytes(batch, t_fresh, max_chunks)
+        ws = self._workspace(need)
+        self._check(self.lib.percache_attention_reuse(self.ctx, layer, _ptr(q), _ptr(k_fresh), _ptr(v_fresh), batch,
+                                                      t_fresh, ids_p, ul_p, nc_p, max_chunks, n_splits, _ptr(attn_out),
+                                                      ws, need, _stream()))
+        return attn_out

@@ -1,0 +1,116 @@
+// Host-side state shared by the translation units of libpercache (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <string>
+#include <vector>
+
+#include "percache.h"
+
+namespace pc {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+typedef __attribute__((__vector_size__(8 * sizeof(_Float16)))) _Float16 f16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+// 16-byte register staging type (a native vector: arrays of it stay in registers)
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v, size_t a = kAlign) { return (v + a - 1) / a * a; }
+
+// Key-axis tile of the attention kernel; the chunk table counts cached tiles in this unit.
+constexpr int kKvTile = 64;
+
+// Device chunk table, one row per query (int32):
+//   [0] n_chunks  [1] L_pre  [2] cached tiles (sum over chunks of ceil(used/kKvTile))  [3] unused
+//   [4 + 2c] slot id of chunk c   [5 + 2c] used length of chunk c
+constexpr int kTblHeader = 4;
+inline int tbl_stride(int max_chunks) { return kTblHeader + 2 * (max_chunks > 0 ? max_chunks : 0); }
+
+constexpr int kStageRing = 16;
+
+}  // namespace pc
+
+struct percache_ctx {
+  percache_config cfg;
+  char *arena = nullptr;
+  size_t arena_bytes = 0;
+  // arena sub-regions
+  float *rope = nullptr;      // [max_pos][D/2] float2 (cos, sin)
+  _Float16 *bank = nullptr;   // [bank_capacity][emb_dim]
+  float *bank_inv = nullptr;  // [bank_capacity]
+  __bf16 *k_store = nullptr;  // [n_layers][n_slots][Hkv][C][D]
+  __bf16 *v_store = nullptr;  // same
+  size_t layer_stride = 0;    // elements per layer of one store
+  size_t slot_stride = 0;     // elements per slot
+  int32_t bank_size = 0;
+  std::vector<int32_t> slot_len;  // [n_layers * n_slots], 0 = empty
+  // pinned staging ring for chunk tables (host -> workspace copies ordered on the stream)
+  int32_t *stage[pc::kStageRing] = {};
+  hipEvent_t stage_ev[pc::kStageRing] = {};
+  bool stage_used[pc::kStageRing] = {};
+  size_t stage_ints = 0;
+  int stage_next = 0;
+  int n_cu = 256;
+  // optional kernel timing (event pairs per kernel kind)
+  bool prof_on = false;
+  std::vector<hipEvent_t> prof_beg[3], prof_end[3];
+  int prof_n[3] = {0, 0, 0};
+  std::string err;
+};
+
+namespace pc {
+
+pc_status fail(percache_ctx *ctx, pc_status st, const char *fmt, ...);
+
+#define PC_HIP(ctx, call)                                                              \
+  do {                                                                                 \
+    hipError_t e__ = (call);                                                           \
+    if (e__ != hipSuccess)                                                             \
+      return pc::fail((ctx), PC_EHIP, "%s: %s", #call, hipGetErrorString(e__));        \
+  } while (0)
+
+// Validates a chunk list against the host mirror of the slot table and writes the device
+// table rows into `rows` (batch * tbl_stride ints).  No device work.
+pc_status build_chunk_table(percache_ctx *ctx, int32_t layer, int32_t batch, int32_t t_fresh,
+                            const int32_t *slot_ids, const int32_t *used_len, const int32_t *n_chunks,
+                            int32_t max_chunks, std::vector<int32_t> &rows);
+// Copies table rows to device memory through the pinned ring, ordered on `stream`.
+pc_status upload_table(percache_ctx *ctx, const std::vector<int32_t> &rows, int32_t *dst_dev,
+                       hipStream_t stream);
+
+// Workspace carving for the prefill calls.
+struct PrefillWs {
+  int32_t *table;
+  __bf16 *q, *k, *v;
+  float *part_o;   // [rows][splits][D]
+  float *part_ml;  // [rows][splits][2]
+  int max_splits;  // partitions of the key axis the partial buffers can hold
+  size_t total;
+};
+constexpr int kMaxSplits = 64;
+// Largest number of key-axis partitions ever used for this shape (the library's own choice never exceeds it).
+int max_splits_for(const percache_config &cfg, int n_cu, int32_t batch, int32_t t_fresh);
+PrefillWs carve_prefill_ws(const percache_config &cfg, int n_cu, void *base, int32_t batch, int32_t t_fresh,
+                           int32_t max_chunks);
+
+constexpr int kProfMax = 256;
+// Record the begin / end event of launch number prof_n[kind] (no-ops unless profiling is on).
+void prof_begin(percache_ctx *ctx, int kind, hipStream_t stream);
+void prof_end(percache_ctx *ctx, int kind, hipStream_t stream);
+
+// kernel launchers (defined in the .hip files)
+pc_status launch_qkv_rope(percache_ctx *ctx, const __bf16 *x, const __bf16 *w, int batch, int t_fresh,
+                          const int32_t *table_dev, int tbl_stride, __bf16 *q, __bf16 *k, __bf16 *v,
+                          hipStream_t stream);
+pc_status launch_attention(percache_ctx *ctx, int layer, const __bf16 *q, const __bf16 *kf, const __bf16 *vf,
+                           int batch, int t_fresh, const int32_t *table_dev, int tbl_stride, int max_tiles,
+                           int n_splits, __bf16 *out, float *part_o, float *part_ml, hipStream_t stream);
+
+}  // namespace pc

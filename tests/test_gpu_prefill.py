@@ -1,0 +1,257 @@
+"""GPU parity of the cache-reusing prefill (Sec. 4.2.2, App. B.1/B.2) against the CPU oracle, through the C ABI.
+
+Bar for bf16 inputs, against the unrounded oracle: max-abs 2e-2 and mean-abs 2e-3, plus a relative Frobenius
+bound of 1e-2 (the outputs of flat softmaxes are small, so the absolute bounds alone constrain little).
+Integer/byte work (slot store round trip, slot permutation) is bit-exact.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2601_11553_amd import workloads as wl
+from paper_2601_11553_amd.binding import PercacheError
+
+from gpu_util import DEV, bf16, check_close, fill_slots, host, make_ctx
+
+pytestmark = pytest.mark.gpu
+
+
+def _oracle_query(w, b, X=None, samples=None):
+    sk, sv, ids = w.compact_store(b)
+    return oracle.prefill_reuse(w.X[b] if X is None else X, w.Wqkv, w.n_q_heads, w.n_kv_heads, w.head_dim,
+                                w.rope_theta, sk, sv, ids, w.used_len[b], samples=samples)
+
+
+def _run_and_check(w, tag, rel_fro=1e-2, max_abs=2e-2, mean_abs=2e-3):
+    pc = make_ctx(w)
+    fill_slots(pc, w, w.slot_ids.reshape(-1))
+    kf = torch.empty((w.batch, w.n_kv_heads, w.t_fresh, w.head_dim), dtype=torch.bfloat16, device=DEV)
+    vf = torch.empty_like(kf)
+    out = pc.percache_prefill_reuse(0, bf16(w.X), bf16(w.Wqkv), w.slot_ids, w.used_len, k_fresh_out=kf, v_fresh_out=vf)
+    torch.cuda.synchronize()
+    for b in range(w.batch):
+        O, Kf, Vf, _ = _oracle_query(w, b)
+        check_close(host(out[b]), O, f"{tag} attn b={b}", rel_fro=rel_fro, max_abs=max_abs, mean_abs=mean_abs)
+        check_close(host(kf[b]), Kf, f"{tag} k_fresh b={b}")
+        check_close(host(vf[b]), Vf, f"{tag} v_fresh b={b}")
+    pc.close()
+    return out
+
+
+# --------------------------------------------------------------------------- K/V store
+def test_kv_store_round_trip_and_errors():
+    w = wl.make_prefill("kv", 3, "bf16", 256, 4, 2, 64, 1, 16, 2, 128, 6)
+    pc = make_ctx(w, n_layers=2)
+    g = np.random.default_rng(1)
+    for layer, slot, n in [(0, 0, 128), (1, 5, 1), (0, 3, 77)]:
+        k = bf16(g.standard_normal((2, n, 64)).astype(np.float32))
+        v = bf16(g.standard_normal((2, n, 64)).astype(np.float32))
+        pc.percache_kv_put(layer, slot, k, v)
+        assert pc.percache_kv_len(layer, slot) == n
+        k2, v2 = pc.percache_kv_get(layer, slot)
+        torch.cuda.synchronize()
+        assert torch.equal(k, k2) and torch.equal(v, v2)
+    assert pc.percache_kv_len(1, 0) == 0
+    k = bf16(np.zeros((2, 129, 64), np.float32))
+    for args, status in [((0, 6, k[:, :8], k[:, :8]), -3), ((2, 0, k[:, :8], k[:, :8]), -3), ((0, 1, k, k), -4)]:
+        with pytest.raises(PercacheError) as e:
+            pc.percache_kv_put(*args)
+        assert e.value.status == status
+    with pytest.raises(PercacheError) as e:
+        pc.percache_kv_get(1, 0)
+    assert e.value.status == -3
+    pc.percache_kv_evict(0, 3)
+    assert pc.percache_kv_len(0, 3) == 0
+    # a prefill that names an empty slot, a bad slot, or too long a used length is refused before any launch
+    x, wq = bf16(w.X), bf16(w.Wqkv)
+    for ids, ul, status in [([[0, 3]], None, -3), ([[0, 9]], None, -3), ([[0, 0]], [[128, 129]], -4)]:
+        with pytest.raises(PercacheError) as e:
+            pc.percache_prefill_reuse(0, x, wq, ids, ul)
+        assert e.value.status == status
+    pc.close()
+
+
+# --------------------------------------------------------------------------- projection + RoPE
+@pytest.mark.parametrize("shape", [
+    dict(hidden=256, n_q_heads=4, n_kv_heads=2, head_dim=64, batch=1, t_fresh=16, n_chunks=2, chunk_tokens=64, n_slots=4),
+    dict(hidden=1024, n_q_heads=16, n_kv_heads=8, head_dim=128, batch=1, t_fresh=64, n_chunks=4, chunk_tokens=512, n_slots=16),
+    dict(hidden=512, n_q_heads=6, n_kv_heads=2, head_dim=128, batch=3, t_fresh=50, n_chunks=2, chunk_tokens=64, n_slots=8),
+    dict(hidden=320, n_q_heads=4, n_kv_heads=4, head_dim=64, batch=2, t_fresh=131, n_chunks=1, chunk_tokens=192, n_slots=3),
+])
+def test_qkv_rope_matches_oracle(shape):
+    w = wl.make_prefill("proj", 5, "bf16", last_used_len=shape["chunk_tokens"] - 3, **shape)
+    pc = make_ctx(w)
+    fill_slots(pc, w, w.slot_ids.reshape(-1))
+    q, k, v = pc.percache_qkv_rope(0, bf16(w.X), bf16(w.Wqkv), w.slot_ids, w.used_len)
+    torch.cuda.synchronize()
+    for b in range(w.batch):
+        Q, K, V = oracle.qkv_rope(w.X[b], w.Wqkv, w.n_q_heads, w.n_kv_heads, w.head_dim, int(w.l_pre[b]), w.rope_theta)
+        check_close(host(q[b]), Q, f"q b={b}")
+        check_close(host(k[b]), K, f"k b={b}")
+        check_close(host(v[b]), V, f"v b={b}")
+    pc.close()
+
+
+# --------------------------------------------------------------------------- config 0 (tiny layer, D = 64)
+def _config0_store():
+    w = wl.config0("bf16")
+    _, K, V, _ = oracle.prefill_reuse(w.prompt[: w.l_pre], w.Wqkv, w.n_q_heads, w.n_kv_heads, w.head_dim, w.rope_theta)
+    return w, wl.round_bf16(K), wl.round_bf16(V)
+
+
+@pytest.mark.parametrize("variant", ["2x64", "last60", "1x128"])
+def test_config0_reuse(variant):
+    """Cached K/V come from running the same layer on the chunk tokens (rounded to bf16 for the store)."""
+    w, K, V = _config0_store()
+    from paper_2601_11553_amd.binding import Percache
+    C = 128 if variant == "1x128" else 64
+    pc = Percache(n_layers=1, hidden=w.hidden, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
+                  n_slots=4, slot_capacity=C, max_pos=256, rope_theta=w.rope_theta, device=DEV)
+    if variant == "1x128":
+        sk, sv = K[None, :, :128], V[None, :, :128]
+        ids, used, fresh_from = [2], [128], 128
+    else:
+        sk = np.stack([K[:, :64], K[:, 64:128]])
+        sv = np.stack([V[:, :64], V[:, 64:128]])
+        ids, used, fresh_from = [3, 1], ([64, 64] if variant == "2x64" else [64, 60]), (128 if variant == "2x64" else 124)
+    for c, s in enumerate(ids):
+        pc.percache_kv_put(0, s, bf16(sk[c]), bf16(sv[c]))
+    X = w.prompt[fresh_from:]
+    out = pc.percache_prefill_reuse(0, bf16(X)[None], bf16(w.Wqkv), [ids], [used])
+    torch.cuda.synchronize()
+    ref, _, _, _ = oracle.prefill_reuse(X, w.Wqkv, w.n_q_heads, w.n_kv_heads, w.head_dim, w.rope_theta, sk, sv,
+                                        list(range(len(ids))), used)
+    check_close(host(out[0]), ref, f"cfg0 {variant}")
+    # the reuse result is also the full recomputation of the contiguous prompt (fresh rows)
+    full, _, _, _ = oracle.prefill_reuse(w.prompt, w.Wqkv, w.n_q_heads, w.n_kv_heads, w.head_dim, w.rope_theta)
+    check_close(host(out[0]), full[fresh_from:], f"cfg0 {variant} vs full recompute")
+    pc.close()
+
+
+# --------------------------------------------------------------------------- config 1 and variations
+def test_config1_full():
+    _run_and_check(wl.config1(), "cfg1")
+
+
+def test_ragged_batch_with_partial_and_empty_chunks():
+    """Several tiles per chunk plus ragged tails; per-query chunk counts differ; one chunk contributes nothing."""
+    w = wl.make_prefill("ragged", 7, "bf16", 512, 6, 2, 128, 3, 83, 3, 192, 12)
+    w.used_len[0] = [192, 100, 1]
+    w.used_len[1] = [65, 0, 190]
+    w.used_len[2] = [7, 192, 64]
+    _run_and_check(w, "ragged")
+    # explicit n_chunks smaller than the list width
+    pc = make_ctx(w)
+    fill_slots(pc, w, w.slot_ids.reshape(-1))
+    out = pc.percache_prefill_reuse(0, bf16(w.X), bf16(w.Wqkv), w.slot_ids, w.used_len, n_chunks=[3, 1, 0])
+    torch.cuda.synchronize()
+    for b, nc in enumerate([3, 1, 0]):
+        sk, sv, ids = w.compact_store(b)
+        O, _, _, _ = oracle.prefill_reuse(w.X[b], w.Wqkv, w.n_q_heads, w.n_kv_heads, w.head_dim, w.rope_theta, sk, sv,
+                                          ids[:nc], w.used_len[b][:nc])
+        check_close(host(out[b]), O, f"n_chunks={nc} b={b}")
+    pc.close()
+
+
+def test_full_recompute_path_is_plain_causal_prefill():
+    w = wl.make_prefill("causal", 8, "bf16", 256, 4, 2, 64, 2, 200, 0, 64, 1)
+    pc = make_ctx(w, max_pos=256)
+    out = pc.percache_prefill_reuse(0, bf16(w.X), bf16(w.Wqkv))
+    torch.cuda.synchronize()
+    for b in range(2):
+        O, _, _, _ = oracle.prefill_reuse(w.X[b], w.Wqkv, w.n_q_heads, w.n_kv_heads, w.head_dim, w.rope_theta)
+        check_close(host(out[b]), O, f"causal b={b}")
+    pc.close()
+
+
+def test_peaked_softmax_stress():
+    """Inputs scaled x16 so that scores have a standard deviation near 10: max/sum mistakes become visible.
+    Outputs are O(1) here, so only the relative bound is meaningful."""
+    w = wl.config1(x_scale=16.0, seed=21)
+    _run_and_check(w, "peaked", rel_fro=2e-2, max_abs=1.5e-1, mean_abs=1e-2)
+
+
+def test_split_count_and_slot_placement_do_not_change_results():
+    w = wl.config1(seed=9, t_fresh=48)
+    pc = make_ctx(w)
+    kv = fill_slots(pc, w, w.slot_ids.reshape(-1))
+    q, k, v = pc.percache_qkv_rope(0, bf16(w.X), bf16(w.Wqkv), w.slot_ids, w.used_len)
+    outs = {}
+    for ns in (1, 2, 3, 8, 33):
+        outs[ns] = pc.percache_attention_reuse(0, q, k, v, w.slot_ids, w.used_len, n_splits=ns).clone()
+    auto = pc.percache_attention_reuse(0, q, k, v, w.slot_ids, w.used_len).clone()
+    torch.cuda.synchronize()
+    Qo = host(q[0]); Ko = host(k[0]); Vo = host(v[0])
+    sk, sv, ids = w.compact_store(0)
+    ref = oracle.attention_reuse(Qo, Ko, Vo, sk, sv, ids, w.used_len[0])
+    for ns, o in outs.items():
+        check_close(host(o[0]), ref, f"splits={ns}", max_abs=4e-3, mean_abs=4e-4, rel_fro=4e-3)
+        assert (o.float() - outs[1].float()).abs().max().item() < 2e-3
+    check_close(host(auto[0]), ref, "splits=auto", max_abs=4e-3, mean_abs=4e-4, rel_fro=4e-3)
+    # same chunks placed in other slots and addressed by the permuted list: bit-identical output
+    perm = [int(s) for s in w.slot_ids[0]]
+    free = [s for s in range(w.n_slots) if s not in perm][: len(perm)]
+    for old, new in zip(perm, free):
+        pc.percache_kv_put(0, new, bf16(kv[old][0]), bf16(kv[old][1]))
+    moved = pc.percache_attention_reuse(0, q, k, v, [free], w.used_len, n_splits=3)
+    torch.cuda.synchronize()
+    assert torch.equal(moved, outs[3])
+    with pytest.raises(PercacheError):
+        pc.percache_attention_reuse(0, q, k, v, w.slot_ids, w.used_len, n_splits=65)
+    pc.close()
+
+
+def test_gpu_full_prefill_populates_store_then_reuse_matches():
+    """The GPU's own full prefill of a prompt, sliced into slots through kv_put (the cache slicer), then a
+    reuse prefill of the suffix: the suffix rows must agree with the full pass."""
+    H, Hq, Hkv, D, C, n_c, Tf = 512, 8, 4, 128, 128, 3, 40
+    w = wl.make_prefill("self", 13, "bf16", H, Hq, Hkv, D, 1, C * n_c + Tf, 0, C, 4)
+    pc = make_ctx(w, max_pos=512)
+    x, wq = bf16(w.X), bf16(w.Wqkv)
+    kf = torch.empty((1, Hkv, C * n_c + Tf, D), dtype=torch.bfloat16, device=DEV)
+    vf = torch.empty_like(kf)
+    full = pc.percache_prefill_reuse(0, x, wq, k_fresh_out=kf, v_fresh_out=vf).clone()
+    for c in range(n_c):
+        pc.percache_kv_put(0, c + 1, kf[0, :, c * C:(c + 1) * C].contiguous(), vf[0, :, c * C:(c + 1) * C].contiguous())
+    reuse = pc.percache_prefill_reuse(0, x[:, C * n_c:].contiguous(), wq, [[1, 2, 3]])
+    torch.cuda.synchronize()
+    check_close(host(reuse[0]), host(full[0, C * n_c:]), "gpu reuse vs gpu full", max_abs=8e-3, mean_abs=8e-4, rel_fro=8e-3)
+    O, _, _, _ = oracle.prefill_reuse(w.X[0], w.Wqkv, Hq, Hkv, D, w.rope_theta)
+    check_close(host(full[0]), O, "gpu full vs oracle full")
+    pc.close()
+
+
+# --------------------------------------------------------------------------- config 4 shape
+def test_config4_reduced():
+    """The 3B-shaped GQA layer (G = 3, hidden 3072) at reduced batch / chunk count; full oracle check."""
+    _run_and_check(wl.config4(batch=2, n_chunks=3, n_slots=8, t_fresh=256), "cfg4-reduced")
+
+
+def test_config4_full_size_sampled_rows():
+    """Full config 4 (batch 8, 16 x 1024 cached tokens, 256 fresh) in the launch configuration the benchmark
+    times; the oracle computes 96 sampled (query, row, head) outputs plus fresh K/V of one query."""
+    w = wl.config4()
+    pc = make_ctx(w)
+    fill_slots(pc, w, w.slot_ids.reshape(-1))
+    kf = torch.empty((w.batch, w.n_kv_heads, w.t_fresh, w.head_dim), dtype=torch.bfloat16, device=DEV)
+    vf = torch.empty_like(kf)
+    out = pc.percache_prefill_reuse(0, bf16(w.X), bf16(w.Wqkv), w.slot_ids, w.used_len, k_fresh_out=kf, v_fresh_out=vf)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all().item()
+    g = np.random.default_rng(4)
+    out_h = host(out).reshape(w.batch, w.t_fresh, w.n_q_heads, w.head_dim)
+    got, ref = [], []
+    for b in range(w.batch):
+        rows = g.integers(0, w.t_fresh, 12)
+        heads = g.integers(0, w.n_q_heads, 12)
+        rows[0], rows[1] = 0, w.t_fresh - 1
+        O, Kf, Vf, _ = _oracle_query(w, b, samples=(rows, heads))
+        got.append(np.stack([out_h[b, i, h] for i, h in zip(rows, heads)]))
+        ref.append(O)
+        if b == 0:
+            check_close(host(kf[0]), Kf, "cfg4 k_fresh b=0")
+            check_close(host(vf[0]), Vf, "cfg4 v_fresh b=0")
+        print(f"cfg4 b={b} sampled", flush=True)
+    check_close(np.concatenate(got), np.concatenate(ref), "cfg4 sampled rows")
+    pc.close()
