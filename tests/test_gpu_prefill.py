@@ -165,24 +165,41 @@ def test_full_recompute_path_is_plain_causal_prefill():
     pc.close()
 
 
+def _oracle_qkv_bf16(w, b=0):
+    """Oracle projection + RoPE of query b, rounded to the bf16 storage dtype: inputs for attention-only tests."""
+    Q, K, V = oracle.qkv_rope(w.X[b], w.Wqkv, w.n_q_heads, w.n_kv_heads, w.head_dim, int(w.l_pre[b]), w.rope_theta)
+    return wl.round_bf16(Q), wl.round_bf16(K), wl.round_bf16(V)
+
+
 def test_peaked_softmax_stress():
-    """Inputs scaled x16 so that scores have a standard deviation near 10: max/sum mistakes become visible.
-    Outputs are O(1) here, so only the relative bound is meaningful."""
+    """Hidden states scaled x16 so that scores have a standard deviation of 10 and more (fresh-fresh scores reach
+    +-100): mistakes in the running max / sum / rescale become O(1) errors.  At this scale the rounding of q and
+    k to bf16 alone moves scores by ~0.4, so the attention step is tested on its own from the oracle's q, k, v
+    rounded to bf16 (both sides get the same tensors); what remains is the rounding of probabilities to bf16."""
     w = wl.config1(x_scale=16.0, seed=21)
-    _run_and_check(w, "peaked", rel_fro=2e-2, max_abs=1.5e-1, mean_abs=1e-2)
+    pc = make_ctx(w)
+    fill_slots(pc, w, w.slot_ids.reshape(-1))
+    Q, K, V = _oracle_qkv_bf16(w)
+    sk, sv, ids = w.compact_store(0)
+    ref = oracle.attention_reuse(Q, K, V, sk, sv, ids, w.used_len[0])
+    for ns in (1, 5):
+        out = pc.percache_attention_reuse(0, bf16(Q)[None], bf16(K)[None], bf16(V)[None], w.slot_ids, w.used_len, n_splits=ns)
+        torch.cuda.synchronize()
+        check_close(host(out[0]), ref, f"peaked splits={ns}", max_abs=0.5, mean_abs=2e-2, rel_fro=6e-3)
+    pc.close()
 
 
 def test_split_count_and_slot_placement_do_not_change_results():
     w = wl.config1(seed=9, t_fresh=48)
     pc = make_ctx(w)
     kv = fill_slots(pc, w, w.slot_ids.reshape(-1))
-    q, k, v = pc.percache_qkv_rope(0, bf16(w.X), bf16(w.Wqkv), w.slot_ids, w.used_len)
+    Qo, Ko, Vo = _oracle_qkv_bf16(w)
+    q, k, v = bf16(Qo)[None], bf16(Ko)[None], bf16(Vo)[None]
     outs = {}
     for ns in (1, 2, 3, 8, 33):
         outs[ns] = pc.percache_attention_reuse(0, q, k, v, w.slot_ids, w.used_len, n_splits=ns).clone()
     auto = pc.percache_attention_reuse(0, q, k, v, w.slot_ids, w.used_len).clone()
     torch.cuda.synchronize()
-    Qo = host(q[0]); Ko = host(k[0]); Vo = host(v[0])
     sk, sv, ids = w.compact_store(0)
     ref = oracle.attention_reuse(Qo, Ko, Vo, sk, sv, ids, w.used_len[0])
     for ns, o in outs.items():
