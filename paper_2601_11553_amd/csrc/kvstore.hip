@@ -1,24 +1,73 @@
 // Slot-indexed per-layer K/V store: the device-resident form of the per-chunk tensor files of
-// Sec. 4.1.1 (cache slicer output).  Store layout per layer: [slot][kv head][token][head_dim] bf16,
-// so one (slot, head) tile is a single contiguous run that the attention kernel streams.
+// Sec. 4.1.1 (cache slicer output).
+//
+// Layout per layer and (slot, kv head), chosen for the attention kernel's streams:
+//   K: [token][head_dim] bf16                       -- one 64-key tile is a contiguous 16 KB run (D = 128)
+//   V: [token / 64][head_dim][64 keys] bf16 blocks  -- the transposed tile the PV product consumes, also one
+//      contiguous run; inside each group of 16 keys the order is pc::blocked_key (see percache_internal.hpp);
+//      keys past the stored count are zero in the last block.
+// percache_kv_put / percache_kv_get convert from / to the caller's dense [kv head][token][head_dim] tensors.
 #include "percache_internal.hpp"
 
 namespace {
+using pc::kKvTile;
 
-// Copies Hkv runs of n_tok*D elements between the caller's dense [Hkv, n_tok, D] tensor and the
-// slot's [Hkv, C, D] region, 16 bytes per lane.  blockIdx.y selects K (0) or V (1).
+// blockIdx.y == 0: K, Hkv runs of n_tok*D elements copied 16 bytes per lane.
+// blockIdx.y == 1: V, one output 16-byte vector (8 key positions of one head-dim index) per thread and step.
 template <bool kToStore>
-__global__ __launch_bounds__(256) void kv_copy_kernel(uint4 *__restrict__ slot_k, uint4 *__restrict__ slot_v,
-                                                      uint4 *__restrict__ dense_k, uint4 *__restrict__ dense_v,
-                                                      int n_heads, int run_vec, int slot_head_vec) {
-  uint4 *slot = blockIdx.y ? slot_v : slot_k;
-  uint4 *dense = blockIdx.y ? dense_v : dense_k;
-  const long total = (long)n_heads * run_vec;
-  for (long e = (long)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (long)gridDim.x * blockDim.x) {
-    int g = (int)(e / run_vec);
-    int r = (int)(e - (long)g * run_vec);
-    long s = (long)g * slot_head_vec + r;
-    if (kToStore) slot[s] = dense[e]; else dense[e] = slot[s];
+__global__ __launch_bounds__(256) void kv_copy_kernel(pc::u32x4 *__restrict__ slot_k, __bf16 *__restrict__ slot_v,
+                                                      pc::u32x4 *__restrict__ dense_k, __bf16 *__restrict__ dense_v,
+                                                      int n_heads, int n_tok, int D, int C) {
+  const long stride = (long)gridDim.x * blockDim.x;
+  const long tid0 = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (blockIdx.y == 0) {
+    const int run_vec = n_tok * D / 8, slot_head_vec = C * D / 8;
+    const long total = (long)n_heads * run_vec;
+    for (long e = tid0; e < total; e += stride) {
+      int g = (int)(e / run_vec);
+      int r = (int)(e - (long)g * run_vec);
+      long s = (long)g * slot_head_vec + r;
+      if (kToStore) slot_k[s] = dense_k[e]; else dense_k[e] = slot_k[s];
+    }
+    return;
+  }
+  const int n_tiles = (n_tok + kKvTile - 1) / kKvTile;
+  if (kToStore) {
+    // vector id -> (head, tile, chunk of 8 positions, head-dim index); d fastest so dense reads coalesce
+    const long total = (long)n_heads * n_tiles * 8 * D;
+    for (long e = tid0; e < total; e += stride) {
+      int d = (int)(e % D);
+      long r = e / D;
+      int chunk = (int)(r & 7);
+      r >>= 3;
+      int tile = (int)(r % n_tiles);
+      int g = (int)(r / n_tiles);
+      pc::bf16x8 o;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        int pos = chunk * 8 + k;
+        int t = tile * kKvTile + (pos & ~15) + pc::blocked_key(pos & 15);
+        o[k] = t < n_tok ? dense_v[((size_t)g * n_tok + t) * D + d] : (__bf16)0.f;
+      }
+      *(pc::bf16x8 *)(slot_v + (((size_t)g * C + (size_t)tile * kKvTile) * D) + (size_t)d * kKvTile + chunk * 8) = o;
+    }
+  } else {
+    // vector id -> (head, token, 8 head-dim indices)
+    const int dv = D / 8;
+    const long total = (long)n_heads * n_tok * dv;
+    for (long e = tid0; e < total; e += stride) {
+      int dc = (int)(e % dv);
+      long r = e / dv;
+      int t = (int)(r % n_tok);
+      int g = (int)(r / n_tok);
+      int tile = t / kKvTile, tin = t - tile * kKvTile;
+      int pos = (tin & ~15) + pc::blocked_key(tin & 15);
+      const __bf16 *src = slot_v + (((size_t)g * C + (size_t)tile * kKvTile) * D) + pos;
+      pc::bf16x8 o;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) o[k] = src[(size_t)(dc * 8 + k) * kKvTile];
+      *(pc::bf16x8 *)(dense_v + ((size_t)g * n_tok + t) * D + dc * 8) = o;
+    }
   }
 }
 
@@ -26,6 +75,20 @@ pc_status check_slot(percache_ctx *ctx, int32_t layer, int32_t slot) {
   if (!ctx) return PC_EINVAL;
   if (layer < 0 || layer >= ctx->cfg.n_layers) return pc::fail(ctx, PC_ESLOT, "layer %d out of range [0,%d)", layer, ctx->cfg.n_layers);
   if (slot < 0 || slot >= ctx->cfg.n_slots) return pc::fail(ctx, PC_ESLOT, "slot %d out of range [0,%d)", slot, ctx->cfg.n_slots);
+  return PC_OK;
+}
+
+template <bool kToStore>
+pc_status launch_copy(percache_ctx *ctx, int layer, int slot, void *k_dev, void *v_dev, int n_tokens, hipStream_t stream) {
+  const percache_config &c = ctx->cfg;
+  size_t off = (size_t)layer * ctx->layer_stride + (size_t)slot * ctx->slot_stride;
+  long total = (long)c.n_kv_heads * ((n_tokens + kKvTile - 1) / kKvTile) * kKvTile * c.head_dim / 8;
+  int blocks = (int)((total + 255) / 256);
+  if (blocks > 2048) blocks = 2048;
+  hipLaunchKernelGGL(kv_copy_kernel<kToStore>, dim3(blocks, 2), dim3(256), 0, stream, (pc::u32x4 *)(ctx->k_store + off),
+                     ctx->v_store + off, (pc::u32x4 *)k_dev, (__bf16 *)v_dev, c.n_kv_heads, n_tokens, c.head_dim,
+                     c.slot_capacity);
+  PC_HIP(ctx, hipGetLastError());
   return PC_OK;
 }
 
@@ -41,16 +104,8 @@ pc_status percache_kv_put(percache_ctx *ctx, int32_t layer, int32_t slot, const 
   if (((uintptr_t)k_dev | (uintptr_t)v_dev) % 16) return pc::fail(ctx, PC_EINVAL, "k_dev / v_dev must be 16-byte aligned");
   const percache_config &c = ctx->cfg;
   if (n_tokens < 1 || n_tokens > c.slot_capacity) return pc::fail(ctx, PC_ELEN, "n_tokens %d outside [1,%d]", n_tokens, c.slot_capacity);
-  size_t off = (size_t)layer * ctx->layer_stride + (size_t)slot * ctx->slot_stride;
-  int run_vec = n_tokens * c.head_dim / 8;
-  int slot_head_vec = c.slot_capacity * c.head_dim / 8;
-  long total = (long)c.n_kv_heads * run_vec;
-  int blocks = (int)((total + 255) / 256);
-  if (blocks > 2048) blocks = 2048;
-  hipLaunchKernelGGL(kv_copy_kernel<true>, dim3(blocks, 2), dim3(256), 0, (hipStream_t)stream,
-                     (uint4 *)(ctx->k_store + off), (uint4 *)(ctx->v_store + off), (uint4 *)k_dev, (uint4 *)v_dev,
-                     c.n_kv_heads, run_vec, slot_head_vec);
-  PC_HIP(ctx, hipGetLastError());
+  st = launch_copy<true>(ctx, layer, slot, (void *)k_dev, (void *)v_dev, n_tokens, (hipStream_t)stream);
+  if (st != PC_OK) return st;
   ctx->slot_len[(size_t)layer * c.n_slots + slot] = n_tokens;
   return PC_OK;
 }
@@ -64,16 +119,8 @@ pc_status percache_kv_get(percache_ctx *ctx, int32_t layer, int32_t slot, void *
   const percache_config &c = ctx->cfg;
   int n_tokens = ctx->slot_len[(size_t)layer * c.n_slots + slot];
   if (n_tokens <= 0) return pc::fail(ctx, PC_ESLOT, "slot %d of layer %d is empty", slot, layer);
-  size_t off = (size_t)layer * ctx->layer_stride + (size_t)slot * ctx->slot_stride;
-  int run_vec = n_tokens * c.head_dim / 8;
-  int slot_head_vec = c.slot_capacity * c.head_dim / 8;
-  long total = (long)c.n_kv_heads * run_vec;
-  int blocks = (int)((total + 255) / 256);
-  if (blocks > 2048) blocks = 2048;
-  hipLaunchKernelGGL(kv_copy_kernel<false>, dim3(blocks, 2), dim3(256), 0, (hipStream_t)stream,
-                     (uint4 *)(ctx->k_store + off), (uint4 *)(ctx->v_store + off), (uint4 *)k_out_dev,
-                     (uint4 *)v_out_dev, c.n_kv_heads, run_vec, slot_head_vec);
-  PC_HIP(ctx, hipGetLastError());
+  st = launch_copy<false>(ctx, layer, slot, k_out_dev, v_out_dev, n_tokens, (hipStream_t)stream);
+  if (st != PC_OK) return st;
   if (n_tokens_out_host) *n_tokens_out_host = n_tokens;
   return PC_OK;
 }

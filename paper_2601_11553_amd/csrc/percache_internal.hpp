@@ -27,6 +27,12 @@ inline size_t align_up(size_t v, size_t a = kAlign) { return (v + a - 1) / a * a
 // Key-axis tile of the attention kernel; the chunk table counts cached tiles in this unit.
 constexpr int kKvTile = 64;
 
+// V is stored (and handed to the attention kernel for the fresh part) in blocks of kKvTile keys laid out
+// [head_dim][kKvTile]; inside each group of 16 keys, position p holds key blocked_key(p) -- the order in
+// which the lanes of the 32x32 score accumulators hold keys ({0-3, 8-11} then {4-7, 12-15}).  The map is
+// its own inverse.
+__host__ __device__ inline int blocked_key(int p) { return 8 * ((p >> 2) & 1) + 4 * (p >> 3) + (p & 3); }
+
 // Device chunk table, one row per query (int32):
 //   [0] n_chunks  [1] L_pre  [2] cached tiles (sum over chunks of ceil(used/kKvTile))  [3] unused
 //   [4 + 2c] slot id of chunk c   [5 + 2c] used length of chunk c
@@ -89,6 +95,7 @@ pc_status upload_table(percache_ctx *ctx, const std::vector<int32_t> &rows, int3
 struct PrefillWs {
   int32_t *table;
   __bf16 *q, *k, *v;
+  __bf16 *v_blk;   // fresh V as 64-key blocks [B*Hkv][ceil(T/64)][D][64]
   float *part_o;   // [rows][splits][D]
   float *part_ml;  // [rows][splits][2]
   int max_splits;  // partitions of the key axis the partial buffers can hold
@@ -109,7 +116,8 @@ void prof_end(percache_ctx *ctx, int kind, hipStream_t stream);
 pc_status launch_qkv_rope(percache_ctx *ctx, const __bf16 *x, const __bf16 *w, int batch, int t_fresh,
                           const int32_t *table_dev, int tbl_stride, __bf16 *q, __bf16 *k, __bf16 *v,
                           hipStream_t stream);
-pc_status launch_attention(percache_ctx *ctx, int layer, const __bf16 *q, const __bf16 *kf, const __bf16 *vf,
+pc_status launch_v_repack(percache_ctx *ctx, const __bf16 *vf, __bf16 *vf_blk, int batch, int t_fresh, hipStream_t stream);
+pc_status launch_attention(percache_ctx *ctx, int layer, const __bf16 *q, const __bf16 *kf, const __bf16 *vf_blk,
                            int batch, int t_fresh, const int32_t *table_dev, int tbl_stride, int max_tiles,
                            int n_splits, __bf16 *out, float *part_o, float *part_ml, hipStream_t stream);
 

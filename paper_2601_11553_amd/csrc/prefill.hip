@@ -86,7 +86,9 @@ pc_status percache_attention_reuse(percache_ctx *ctx, int32_t layer, const void 
   hipStream_t s = (hipStream_t)stream;
   st = pc::upload_table(ctx, rows, p.ws.table, s);
   if (st != PC_OK) return st;
-  return pc::launch_attention(ctx, layer, (const __bf16 *)q_dev, (const __bf16 *)k_fresh_dev, (const __bf16 *)v_fresh_dev,
+  st = pc::launch_v_repack(ctx, (const __bf16 *)v_fresh_dev, p.ws.v_blk, batch, t_fresh, s);
+  if (st != PC_OK) return st;
+  return pc::launch_attention(ctx, layer, (const __bf16 *)q_dev, (const __bf16 *)k_fresh_dev, p.ws.v_blk,
                               batch, t_fresh, p.ws.table, p.tbl_stride, p.min_tiles, n_splits, (__bf16 *)attn_out_dev,
                               p.ws.part_o, p.ws.part_ml, s);
 }
@@ -114,7 +116,9 @@ pc_status percache_prefill_reuse(percache_ctx *ctx, int32_t layer, const void *x
   st = pc::launch_qkv_rope(ctx, (const __bf16 *)x_fresh_dev, (const __bf16 *)wqkv_dev, batch, t_fresh, p.ws.table,
                            p.tbl_stride, p.ws.q, kf, vf, s);
   if (st != PC_OK) return st;
-  return pc::launch_attention(ctx, layer, p.ws.q, kf, vf, batch, t_fresh, p.ws.table, p.tbl_stride, p.min_tiles, 0,
+  st = pc::launch_v_repack(ctx, vf, p.ws.v_blk, batch, t_fresh, s);
+  if (st != PC_OK) return st;
+  return pc::launch_attention(ctx, layer, p.ws.q, kf, p.ws.v_blk, batch, t_fresh, p.ws.table, p.tbl_stride, p.min_tiles, 0,
                               (__bf16 *)attn_out_dev, p.ws.part_o, p.ws.part_ml, s);
 }
 

@@ -10,10 +10,15 @@
 //   - scores are computed transposed, S^T = K Q^T, so that a lane's 32 accumulators all belong to ONE
 //     query row: the row max/sum are lane-local plus a single exchange with lane+32, and the bf16
 //     probabilities are already in the B-operand layout of O^T += V^T P^T (no LDS round trip for P);
-//   - V is transposed on its way into LDS; within each group of 16 keys the columns are stored in the
-//     order the accumulator layout delivers them, so each A operand is one 16-byte LDS read;
+//   - V is kept in the store (and handed over for the fresh part) as 64-key blocks [D][64] whose key
+//     order inside each group of 16 is the order the score accumulators deliver them, so K and V tiles
+//     are both staged with plain 16-byte copies and every MFMA operand is one 16-byte LDS read;
+//   - the running max is only refreshed when a tile exceeds it by more than 2^8 (probabilities stay
+//     below 256, harmless in bf16/fp32), so the rescale of the output accumulators is almost never run;
 //   - the key axis can be partitioned over workgroups (split-KV); partial (max, sum, output) triples are
-//     merged by a small second kernel with the usual log-sum-exp rule.
+//     merged by a small second kernel with the usual log-sum-exp rule;
+//   - workgroups that stream the same K/V run are placed on the same XCD (workgroup ids go round-robin
+//     over the 8 XCDs), so the run is fetched into one L2 only.
 #include "percache_internal.hpp"
 
 namespace {
@@ -21,9 +26,11 @@ using pc::bf16x8;
 using pc::f32x16;
 using pc::kKvTile;
 using pc::kTblHeader;
+using pc::u32x4;
 
 constexpr int TK = kKvTile;  // keys per tile
 constexpr int QROWS = 128;   // query rows per workgroup
+constexpr float kLazy = 8.f; // log2 slack before the running max is refreshed
 
 template <int D>
 struct Lds {
@@ -34,29 +41,34 @@ struct Lds {
   static constexpr int STAGE = K_BYTES + V_BYTES;
 };
 
-// position of key t (0..15) of a 16-key group inside its V^T row segment: lane group g = (t/4)%2 of the
-// score accumulators holds keys {4g..4g+3, 8+4g..8+4g+3}; they are stored contiguously at [8g, 8g+8).
-__device__ __forceinline__ int vt_pos16(int t) { return 8 * ((t >> 2) & 1) + 4 * (t >> 3) + (t & 3); }
-
-// 2^x on the hardware transcendental unit; arguments here are <= 0 (or -inf), results in [0, 1].
+// 2^x on the hardware transcendental unit; arguments here are bounded above by kLazy.
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// max / sum over the two lanes (l, l+32) that share a query row
+__device__ __forceinline__ float pair_max(float x) { return fmaxf(x, __shfl_xor(x, 32, 64)); }
+__device__ __forceinline__ float pair_sum(float x) { return x + __shfl_xor(x, 32, 64); }
 
 template <int D>
 __global__ __launch_bounds__(256, 2) void reuse_attention_kernel(
-    const __bf16 *__restrict__ Q, const __bf16 *__restrict__ Kf, const __bf16 *__restrict__ Vf,
+    const __bf16 *__restrict__ Q, const __bf16 *__restrict__ Kf, const __bf16 *__restrict__ Vf_blk,
     const __bf16 *__restrict__ k_store, const __bf16 *__restrict__ v_store, const int32_t *__restrict__ table,
-    int tbl_stride, int T, int Hq, int Hkv, int C, int n_splits, float scale_log2e, __bf16 *__restrict__ out,
-    float *__restrict__ part_o, float *__restrict__ part_ml) {
+    int tbl_stride, int T, int Hq, int Hkv, int C, int n_splits, int q_tiles, int n_groups, float scale_log2e,
+    __bf16 *__restrict__ out, float *__restrict__ part_o, float *__restrict__ part_ml) {
   using L = Lds<D>;
   constexpr int KS = D / 16;  // k-steps of the QK^T contraction
   constexpr int DB = D / 32;  // 32-wide blocks of the head dim (rows of O^T)
   __shared__ __align__(16) char lds[2 * L::STAGE];
 
+  // workgroup -> (stream group, q tile): the q tiles of one stream group are consecutive on one XCD
+  const int xcd = blockIdx.x & 7, jj = blockIdx.x >> 3;
+  const int sg = (jj / q_tiles) * 8 + xcd, qt = jj % q_tiles;
+  if (sg >= n_groups) return;
+  const int split = sg % n_splits, bg = sg / n_splits;
+  const int gkv = bg % Hkv, b = bg / Hkv;
+
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, g2 = lane >> 5;
   const int G = Hq / Hkv, R = G * T;
-  const int qt = blockIdx.x, gkv = blockIdx.y;
-  const int b = blockIdx.z / n_splits, split = blockIdx.z - b * n_splits;
 
   const int32_t *trow = table + (size_t)b * tbl_stride;
   const int n_chunks = trow[0];
@@ -83,6 +95,10 @@ __global__ __launch_bounds__(256, 2) void reuse_attention_kernel(
     const __bf16 *qrow = Q + (((size_t)b * Hq + head) * T + my_i) * D + g2 * 8;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) qf[ks] = *(const bf16x8 *)(qrow + ks * 16);
+    // Consume the fragments here, once: otherwise the loads are still "pending" at the loop header in the
+    // compiler's wait-count model and every iteration waits on its own K/V prefetch before the first MFMA.
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qf[ks]));
   }
 
   f32x16 o_acc[DB];
@@ -90,10 +106,10 @@ __global__ __launch_bounds__(256, 2) void reuse_attention_kernel(
   for (int db = 0; db < DB; ++db)
 #pragma unroll
     for (int r = 0; r < 16; ++r) o_acc[db][r] = 0.f;
-  float m_run = -INFINITY, l_run = 0.f;
+  float m_ref = -INFINITY, l_run = 0.f;  // m_ref: reference exponent (scaled, log2 domain)
 
   // ---- tile cursor over the chunk list
-  int cur_chunk = 0, cur_off = 0;  // chunk index, tile index inside the chunk
+  int cur_chunk = 0, cur_off = 0;  // chunk index, tile index inside the chunk (or inside the fresh part)
   {
     int rem = tile_begin;
     while (cur_chunk < n_chunks) {
@@ -102,29 +118,28 @@ __global__ __launch_bounds__(256, 2) void reuse_attention_kernel(
       rem -= ntc;
       ++cur_chunk;
     }
-    cur_off = rem;  // for fresh tiles: tile index inside the fresh part
+    cur_off = rem;
   }
 
-  // ---- global -> register staging of one tile
+  // ---- global -> register -> LDS staging of one tile (K rows as they are, V as a [D][64] block)
   constexpr int K_PASS = TK * (D / 8) / 256;  // 16-byte loads per thread for the K tile
+  constexpr int V_PASS = D * (TK / 8) / 256;  // same for the V block
   constexpr int TPR = D / 8;                  // threads per key row
-  pc::u32x4 rk[K_PASS], rv[2][2];
-  // V items: wavefront w transposes keys [16w, 16w+16); lane group lg and item it pick the key pair
-  const int v_lg = lane >> 4, v_dc0 = lane & 15;
+  u32x4 rk[K_PASS], rv[V_PASS];
   struct TileDesc { const __bf16 *k, *v; int valid; int t0; bool fresh; };
   auto describe = [&](int chunk, int off, TileDesc &td) __attribute__((always_inline)) {
     if (chunk < n_chunks) {
       int slot = trow[kTblHeader + 2 * chunk], used = trow[kTblHeader + 2 * chunk + 1];
-      size_t base = (((size_t)slot * Hkv + gkv) * C + (size_t)off * TK) * D;
+      size_t base = (((size_t)slot * Hkv + gkv) * C + (size_t)off * TK) * D;  // same offset in both layouts
       td.k = k_store + base;
       td.v = v_store + base;
       td.valid = min(TK, used - off * TK);
       td.t0 = 0;
       td.fresh = false;
     } else {
-      size_t base = (((size_t)b * Hkv + gkv) * T + (size_t)off * TK) * D;
-      td.k = Kf + base;
-      td.v = Vf + base;
+      const int ft = (T + TK - 1) / TK;
+      td.k = Kf + (((size_t)b * Hkv + gkv) * T + (size_t)off * TK) * D;
+      td.v = Vf_blk + (((size_t)b * Hkv + gkv) * ft + off) * (size_t)(TK * D);
       td.valid = min(TK, T - off * TK);
       td.t0 = off * TK;
       td.fresh = true;
@@ -137,8 +152,7 @@ __global__ __launch_bounds__(256, 2) void reuse_attention_kernel(
       if (cur_off >= ntc) {
         cur_off = 0;
         ++cur_chunk;
-        // skip chunks with no used tokens
-        while (cur_chunk < n_chunks && trow[kTblHeader + 2 * cur_chunk + 1] == 0) ++cur_chunk;
+        while (cur_chunk < n_chunks && trow[kTblHeader + 2 * cur_chunk + 1] == 0) ++cur_chunk;  // unused chunks
       }
     }
   };
@@ -146,18 +160,10 @@ __global__ __launch_bounds__(256, 2) void reuse_attention_kernel(
 #pragma unroll
     for (int p = 0; p < K_PASS; ++p) {
       int row = min(tid / TPR + p * (256 / TPR), td.valid - 1);
-      rk[p] = *(const pc::u32x4 *)(td.k + (size_t)row * D + (tid % TPR) * 8);
+      rk[p] = *(const u32x4 *)(td.k + (size_t)row * D + (tid % TPR) * 8);
     }
-    if (D == 128 || v_dc0 < 8) {
 #pragma unroll
-      for (int it = 0; it < 2; ++it) {
-        int x = (v_lg & 1) + 4 * (v_lg >> 1) + 2 * it;  // key-pair index inside the 16-key group
-        int t = wave * 16 + 2 * x;
-        int ra = min(t, td.valid - 1), rb = min(t + 1, td.valid - 1);
-        rv[it][0] = *(const pc::u32x4 *)(td.v + (size_t)ra * D + v_dc0 * 8);
-        rv[it][1] = *(const pc::u32x4 *)(td.v + (size_t)rb * D + v_dc0 * 8);
-      }
-    }
+    for (int p = 0; p < V_PASS; ++p) rv[p] = *(const u32x4 *)(td.v + (size_t)(p * 256 + tid) * 8);
   };
   auto store_tile = [&](int buf) __attribute__((always_inline)) {
     char *kb = lds + buf * L::STAGE;
@@ -165,30 +171,17 @@ __global__ __launch_bounds__(256, 2) void reuse_attention_kernel(
 #pragma unroll
     for (int p = 0; p < K_PASS; ++p) {
       int row = tid / TPR + p * (256 / TPR);
-      *(pc::u32x4 *)(kb + row * L::K_ROW + (tid % TPR) * 16) = rk[p];
+      *(u32x4 *)(kb + row * L::K_ROW + (tid % TPR) * 16) = rk[p];
     }
-    if (D == 128 || v_dc0 < 8) {
 #pragma unroll
-      for (int it = 0; it < 2; ++it) {
-        // item `it` of lane group v_lg is the key pair stored in 32-bit word (4 it + v_lg) of the 16-key
-        // group, i.e. word v_lg of 16-byte chunk (2 wave + it) of the V^T row
-        const uint32_t wa[4] = {rv[it][0].x, rv[it][0].y, rv[it][0].z, rv[it][0].w};
-        const uint32_t wc[4] = {rv[it][1].x, rv[it][1].y, rv[it][1].z, rv[it][1].w};
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          uint32_t w = (e & 1) ? ((wa[e >> 1] >> 16) | (wc[e >> 1] & 0xffff0000u))
-                               : ((wa[e >> 1] & 0xffffu) | (wc[e >> 1] << 16));
-          int d = v_dc0 * 8 + e;
-          int chunk = (2 * wave + it) ^ ((d >> 4) & 7);  // XOR swizzle: conflict-free writes and reads
-          *(uint32_t *)(vb + d * L::V_ROW + chunk * 16 + v_lg * 4) = w;
-        }
-      }
+    for (int p = 0; p < V_PASS; ++p) {
+      int d = (p * 256 + tid) >> 3, chunk = tid & 7;
+      *(u32x4 *)(vb + d * L::V_ROW + chunk * 16) = rv[p];
     }
   };
 
   TileDesc td;
   if (tile_begin < tile_end) {
-    // skip leading empty chunks
     while (cur_chunk < n_chunks && trow[kTblHeader + 2 * cur_chunk + 1] == 0) ++cur_chunk;
     describe(cur_chunk, cur_off, td);
     load_tile(td);
@@ -222,27 +215,37 @@ __global__ __launch_bounds__(256, 2) void reuse_attention_kernel(
       }
     }
 
-    // ---- mask (ragged tile end, causal part) and online softmax in the log2 domain
-    const bool need_mask = cur.valid < TK || (cur.fresh && cur.t0 + TK - 1 > my_i);
-    float mx = -INFINITY;
+    // ---- mask: only tiles with a ragged end or in the causal part take this path (wave-uniform test)
+    if (cur.valid < TK || cur.fresh) {
+#pragma unroll
+      for (int kbk = 0; kbk < 2; ++kbk)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          int t = kbk * 32 + (r >> 2) * 8 + g2 * 4 + (r & 3);
+          bool vis = t < cur.valid && (!cur.fresh || cur.t0 + t <= my_i);
+          s_acc[kbk][r] = vis ? s_acc[kbk][r] : -INFINITY;
+        }
+    }
+
+    // ---- online softmax in the log2 domain with a lazily refreshed reference exponent
+    float mx = s_acc[0][0];
 #pragma unroll
     for (int kbk = 0; kbk < 2; ++kbk)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float s = s_acc[kbk][r] * scale_log2e;
-        if (need_mask) {
-          int t = kbk * 32 + (r >> 2) * 8 + g2 * 4 + (r & 3);
-          bool vis = t < cur.valid && (!cur.fresh || cur.t0 + t <= my_i);
-          s = vis ? s : -INFINITY;
-        }
-        s_acc[kbk][r] = s;
-        mx = fmaxf(mx, s);
-      }
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m_run, mx);
-    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-    const float alpha = fast_exp2(m_run - m_use);
-    m_run = m_new;
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s_acc[kbk][r]);
+    mx = pair_max(mx);
+    const float mc = mx * scale_log2e;
+    const bool upd = mc > m_ref + kLazy;  // also true for the first finite tile (m_ref = -inf)
+    if (__builtin_amdgcn_ballot_w64(upd) != 0) {
+      const float alpha = upd ? fast_exp2(m_ref - mc) : 1.0f;  // m_ref = -inf gives 0
+      m_ref = upd ? mc : m_ref;
+      l_run *= alpha;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o_acc[db][r] *= alpha;
+    }
+    const float neg_m = (m_ref == -INFINITY) ? 0.f : -m_ref;
     float psum = 0.f;
     bf16x8 pf[2][2];
 #pragma unroll
@@ -251,27 +254,21 @@ __global__ __launch_bounds__(256, 2) void reuse_attention_kernel(
       for (int j = 0; j < 2; ++j)
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-          float p = fast_exp2(s_acc[kbk][j * 8 + e] - m_use);
+          float p = fast_exp2(__builtin_fmaf(s_acc[kbk][j * 8 + e], scale_log2e, neg_m));
           psum += p;
           pf[kbk][j][e] = (__bf16)p;
         }
-    l_run = l_run * alpha + psum;
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) o_acc[db][r] *= alpha;
+    l_run += psum;
 
     // ---- O^T += V^T P^T
 #pragma unroll
     for (int db = 0; db < DB; ++db) {
-      const int dd = db * 32 + l32;
-      const char *vrow = vb + dd * L::V_ROW;
-      const int sw = (dd >> 4) & 7;
+      const char *vrow = vb + (db * 32 + l32) * L::V_ROW + g2 * 16;
 #pragma unroll
       for (int kbk = 0; kbk < 2; ++kbk)
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
-          bf16x8 a = *(const bf16x8 *)(vrow + (((kbk * 4 + j * 2 + g2) ^ sw) * 16));
+          bf16x8 a = *(const bf16x8 *)(vrow + (kbk * 2 + j) * 32);
           o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[kbk][j], o_acc[db], 0, 0, 0);
         }
     }
@@ -281,7 +278,7 @@ __global__ __launch_bounds__(256, 2) void reuse_attention_kernel(
   }
 
   // ---- finish: combine the two lanes of a row, normalise, write
-  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  const float l_tot = pair_sum(l_run);
   const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
   if (!row_ok) return;
   if (n_splits == 1) {
@@ -306,7 +303,7 @@ __global__ __launch_bounds__(256, 2) void reuse_attention_kernel(
         *(float4 *)(po + db * 32 + q4 * 8 + g2 * 4) = v;
       }
     if (g2 == 0) {
-      part_ml[prow * 2] = m_run;
+      part_ml[prow * 2] = m_ref;
       part_ml[prow * 2 + 1] = l_tot;
     }
   }
@@ -332,7 +329,8 @@ __global__ __launch_bounds__(256) void splitkv_combine_kernel(const float *__res
   int head = gkv * G + hg;
   const float *ml = part_ml + prow * n_splits * 2;
   float m = -INFINITY;
-  for (int s = 0; s < n_splits; ++s) m = fmaxf(m, ml[2 * s]);
+  for (int s = 0; s < n_splits; ++s)
+    if (ml[2 * s + 1] > 0.f) m = fmaxf(m, ml[2 * s]);
   float wsum = 0.f;
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   for (int s = 0; s < n_splits; ++s) {
@@ -348,39 +346,79 @@ __global__ __launch_bounds__(256) void splitkv_combine_kernel(const float *__res
   *(pc::bf16x4 *)(out + ((size_t)b * T + i) * ((size_t)Hq * D) + (size_t)head * D + dv * 4) = v;
 }
 
+// Fresh V [B*Hkv][T][D] -> 64-key blocks [B*Hkv][ceil(T/64)][D][64] in the key order of the store
+// (see kvstore.hip: blocked_pos), zero filled past T.  One thread per 16 output bytes.
+__global__ __launch_bounds__(256) void v_block_repack_kernel(const __bf16 *__restrict__ v, __bf16 *__restrict__ vb, int T,
+                                                             int D, long total_vec) {
+  long gid = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (gid >= total_vec) return;
+  const int ft = (T + TK - 1) / TK;
+  int chunk = (int)(gid & 7);
+  long r = gid >> 3;
+  int d = (int)(r % D);
+  r /= D;
+  int tile = (int)(r % ft);
+  long bg = r / ft;
+  pc::bf16x8 o;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    int pos = chunk * 8 + e;
+    int t = tile * TK + (pos & ~15) + pc::blocked_key(pos & 15);
+    o[e] = t < T ? v[((size_t)bg * T + t) * D + d] : (__bf16)0.f;
+  }
+  *(pc::bf16x8 *)(vb + gid * 8) = o;
+}
+
 }  // namespace
 
 namespace pc {
 
-pc_status launch_attention(percache_ctx *ctx, int layer, const __bf16 *q, const __bf16 *kf, const __bf16 *vf,
+int choose_splits(int n_cu, long base_wgs, int min_tiles, int cap) {
+  const long slots = 2L * n_cu;  // two workgroups are resident per CU
+  int best = 1;
+  double best_eff = 0.0;
+  for (int ns = 1; ns <= cap; ++ns) {
+    if (ns > 1 && min_tiles / ns < 4) break;  // keep at least 4 tiles per partition
+    long w = base_wgs * ns;
+    double eff = (double)w / (double)(((w + slots - 1) / slots) * slots);
+    if (eff > best_eff + 0.03) { best_eff = eff; best = ns; }
+  }
+  return best;
+}
+
+pc_status launch_v_repack(percache_ctx *ctx, const __bf16 *vf, __bf16 *vf_blk, int batch, int t_fresh, hipStream_t stream) {
+  const percache_config &c = ctx->cfg;
+  const int ft = (t_fresh + TK - 1) / TK;
+  long total_vec = (long)batch * c.n_kv_heads * ft * c.head_dim * (TK / 8);
+  hipLaunchKernelGGL(v_block_repack_kernel, dim3((unsigned)((total_vec + 255) / 256)), dim3(256), 0, stream, vf, vf_blk,
+                     t_fresh, c.head_dim, total_vec);
+  PC_HIP(ctx, hipGetLastError());
+  return PC_OK;
+}
+
+pc_status launch_attention(percache_ctx *ctx, int layer, const __bf16 *q, const __bf16 *kf, const __bf16 *vf_blk,
                            int batch, int t_fresh, const int32_t *table_dev, int tbl_stride, int min_tiles,
                            int n_splits, __bf16 *out, float *part_o, float *part_ml, hipStream_t stream) {
   const percache_config &c = ctx->cfg;
   const int G = c.n_q_heads / c.n_kv_heads, R = G * t_fresh;
   const int q_tiles = (R + QROWS - 1) / QROWS;
-  if (n_splits <= 0) {
-    long base = (long)batch * c.n_kv_heads * q_tiles;
-    long want = 2L * ctx->n_cu;
-    n_splits = (int)((want + base - 1) / base);
-    int cap = min_tiles / 4;  // keep at least 4 tiles per partition
-    if (n_splits > cap) n_splits = cap;
-    if (n_splits < 1) n_splits = 1;
-  }
-  {
-    int cap = max_splits_for(c, ctx->n_cu, batch, t_fresh);
-    if (n_splits > cap) n_splits = cap;
-  }
+  const int cap = max_splits_for(c, ctx->n_cu, batch, t_fresh);
+  if (n_splits <= 0) n_splits = choose_splits(ctx->n_cu, (long)batch * c.n_kv_heads * q_tiles, min_tiles, cap);
+  if (n_splits > cap) n_splits = cap;
   const __bf16 *ks = ctx->k_store + (size_t)layer * ctx->layer_stride;
   const __bf16 *vs = ctx->v_store + (size_t)layer * ctx->layer_stride;
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)c.head_dim);
-  dim3 grid(q_tiles, c.n_kv_heads, batch * n_splits);
+  const int n_groups = batch * c.n_kv_heads * n_splits;
+  dim3 grid((unsigned)(((n_groups + 7) / 8) * 8 * q_tiles));
   prof_begin(ctx, PC_KERNEL_ATTENTION, stream);
   if (c.head_dim == 128)
-    hipLaunchKernelGGL(reuse_attention_kernel<128>, grid, dim3(256), 0, stream, q, kf, vf, ks, vs, table_dev, tbl_stride,
-                       t_fresh, c.n_q_heads, c.n_kv_heads, c.slot_capacity, n_splits, scale_log2e, out, part_o, part_ml);
+    hipLaunchKernelGGL(reuse_attention_kernel<128>, grid, dim3(256), 0, stream, q, kf, vf_blk, ks, vs, table_dev,
+                       tbl_stride, t_fresh, c.n_q_heads, c.n_kv_heads, c.slot_capacity, n_splits, q_tiles, n_groups,
+                       scale_log2e, out, part_o, part_ml);
   else
-    hipLaunchKernelGGL(reuse_attention_kernel<64>, grid, dim3(256), 0, stream, q, kf, vf, ks, vs, table_dev, tbl_stride,
-                       t_fresh, c.n_q_heads, c.n_kv_heads, c.slot_capacity, n_splits, scale_log2e, out, part_o, part_ml);
+    hipLaunchKernelGGL(reuse_attention_kernel<64>, grid, dim3(256), 0, stream, q, kf, vf_blk, ks, vs, table_dev,
+                       tbl_stride, t_fresh, c.n_q_heads, c.n_kv_heads, c.slot_capacity, n_splits, q_tiles, n_groups,
+                       scale_log2e, out, part_o, part_ml);
   prof_end(ctx, PC_KERNEL_ATTENTION, stream);
   PC_HIP(ctx, hipGetLastError());
   if (n_splits > 1) {
