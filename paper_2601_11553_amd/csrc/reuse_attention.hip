@@ -29,7 +29,6 @@ using pc::kTblHeader;
 using pc::u32x4;
 
 constexpr int TK = kKvTile;  // keys per tile
-constexpr int QROWS = 128;   // query rows per workgroup
 constexpr float kLazy = 8.f; // log2 slack before the running max is refreshed
 
 template <int D>
@@ -48,8 +47,9 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 __device__ __forceinline__ float pair_max(float x) { return fmaxf(x, __shfl_xor(x, 32, 64)); }
 __device__ __forceinline__ float pair_sum(float x) { return x + __shfl_xor(x, 32, 64); }
 
-template <int D>
-__global__ __launch_bounds__(256, 2) void reuse_attention_kernel(
+// NW wavefronts per workgroup (32 query rows each), NSTAGE LDS stages of one K tile + one V block.
+template <int D, int NW, int NSTAGE>
+__global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
     const __bf16 *__restrict__ Q, const __bf16 *__restrict__ Kf, const __bf16 *__restrict__ Vf_blk,
     const __bf16 *__restrict__ k_store, const __bf16 *__restrict__ v_store, const int32_t *__restrict__ table,
     int tbl_stride, int T, int Hq, int Hkv, int C, int n_splits, int q_tiles, int n_groups, float scale_log2e,
@@ -57,7 +57,10 @@ __global__ __launch_bounds__(256, 2) void reuse_attention_kernel(
   using L = Lds<D>;
   constexpr int KS = D / 16;  // k-steps of the QK^T contraction
   constexpr int DB = D / 32;  // 32-wide blocks of the head dim (rows of O^T)
-  __shared__ __align__(16) char lds[2 * L::STAGE];
+  constexpr int NT = 64 * NW;      // threads
+  constexpr int QROWS = 32 * NW;   // query rows per workgroup
+  constexpr int AHEAD = NSTAGE - 1;  // tiles in flight ahead of the one being computed
+  __shared__ __align__(16) char lds[NSTAGE * L::STAGE];
 
   // workgroup -> (stream group, q tile): the q tiles of one stream group are consecutive on one XCD
   const int xcd = blockIdx.x & 7, jj = blockIdx.x >> 3;
@@ -122,8 +125,8 @@ __global__ __launch_bounds__(256, 2) void reuse_attention_kernel(
   }
 
   // ---- global -> register -> LDS staging of one tile (K rows as they are, V as a [D][64] block)
-  constexpr int K_PASS = TK * (D / 8) / 256;  // 16-byte loads per thread for the K tile
-  constexpr int V_PASS = D * (TK / 8) / 256;  // same for the V block
+  constexpr int K_PASS = TK * (D / 8) / NT;  // 16-byte loads per thread for the K tile
+  constexpr int V_PASS = D * (TK / 8) / NT;  // same for the V block
   constexpr int TPR = D / 8;                  // threads per key row
   u32x4 rk[K_PASS], rv[V_PASS];
   struct TileDesc { const __bf16 *k, *v; int valid; int t0; bool fresh; };
@@ -145,59 +148,77 @@ __global__ __launch_bounds__(256, 2) void reuse_attention_kernel(
       td.fresh = true;
     }
   };
-  auto advance = [&]() __attribute__((always_inline)) {
-    ++cur_off;
-    if (cur_chunk < n_chunks) {
-      int ntc = (trow[kTblHeader + 2 * cur_chunk + 1] + TK - 1) / TK;
-      if (cur_off >= ntc) {
-        cur_off = 0;
-        ++cur_chunk;
-        while (cur_chunk < n_chunks && trow[kTblHeader + 2 * cur_chunk + 1] == 0) ++cur_chunk;  // unused chunks
+  auto advance = [&](int &chunk, int &off) __attribute__((always_inline)) {
+    ++off;
+    if (chunk < n_chunks) {
+      int ntc = (trow[kTblHeader + 2 * chunk + 1] + TK - 1) / TK;
+      if (off >= ntc) {
+        off = 0;
+        ++chunk;
+        while (chunk < n_chunks && trow[kTblHeader + 2 * chunk + 1] == 0) ++chunk;  // unused chunks
       }
     }
   };
   auto load_tile = [&](const TileDesc &td) __attribute__((always_inline)) {
 #pragma unroll
     for (int p = 0; p < K_PASS; ++p) {
-      int row = min(tid / TPR + p * (256 / TPR), td.valid - 1);
+      int row = min(tid / TPR + p * (NT / TPR), td.valid - 1);
       rk[p] = *(const u32x4 *)(td.k + (size_t)row * D + (tid % TPR) * 8);
     }
 #pragma unroll
-    for (int p = 0; p < V_PASS; ++p) rv[p] = *(const u32x4 *)(td.v + (size_t)(p * 256 + tid) * 8);
+    for (int p = 0; p < V_PASS; ++p) rv[p] = *(const u32x4 *)(td.v + (size_t)(p * NT + tid) * 8);
   };
   auto store_tile = [&](int buf) __attribute__((always_inline)) {
     char *kb = lds + buf * L::STAGE;
     char *vb = kb + L::K_BYTES;
 #pragma unroll
     for (int p = 0; p < K_PASS; ++p) {
-      int row = tid / TPR + p * (256 / TPR);
+      int row = tid / TPR + p * (NT / TPR);
       *(u32x4 *)(kb + row * L::K_ROW + (tid % TPR) * 16) = rk[p];
     }
 #pragma unroll
     for (int p = 0; p < V_PASS; ++p) {
-      int d = (p * 256 + tid) >> 3, chunk = tid & 7;
+      int d = (p * NT + tid) >> 3, chunk = tid & 7;
       *(u32x4 *)(vb + d * L::V_ROW + chunk * 16) = rv[p];
     }
   };
 
-  TileDesc td;
-  if (tile_begin < tile_end) {
-    while (cur_chunk < n_chunks && trow[kTblHeader + 2 * cur_chunk + 1] == 0) ++cur_chunk;
-    describe(cur_chunk, cur_off, td);
-    load_tile(td);
-    store_tile(0);
+  // Pipeline: the tile computed in iteration t sits in stage t % NSTAGE; tiles t+1 .. t+AHEAD-1 are already in
+  // LDS, tile t+AHEAD travels through registers during iteration t and is stored at its end.  One barrier per
+  // tile: it publishes the stores and retires the stage that will be overwritten next.  Two cursors walk the
+  // chunk list: (cur_chunk, cur_off) for the tile being fetched, (cmp_chunk, cmp_off) for the one being computed.
+  while (cur_chunk < n_chunks && trow[kTblHeader + 2 * cur_chunk + 1] == 0) ++cur_chunk;
+  int cmp_chunk = cur_chunk, cmp_off = cur_off;
+  int fetched = tile_begin;  // next tile to fetch
+#pragma unroll
+  for (int k = 0; k < AHEAD; ++k) {
+    if (fetched < tile_end) {
+      TileDesc t0d;
+      describe(cur_chunk, cur_off, t0d);
+      load_tile(t0d);
+      store_tile(k);
+      advance(cur_chunk, cur_off);
+      ++fetched;
+    }
   }
   __syncthreads();
 
+  int stage = 0;  // (tt - tile_begin) % NSTAGE
   for (int tt = tile_begin; tt < tile_end; ++tt) {
-    const int buf = (tt - tile_begin) & 1;
-    const TileDesc cur = td;
-    const bool has_next = tt + 1 < tile_end;
+    const int buf = stage;
+    int in_stage = stage + AHEAD;
+    if (in_stage >= NSTAGE) in_stage -= NSTAGE;
+    const bool has_next = fetched < tile_end;
     if (has_next) {
-      advance();
-      describe(cur_chunk, cur_off, td);
-      load_tile(td);
+      TileDesc nxt;
+      describe(cur_chunk, cur_off, nxt);
+      load_tile(nxt);
+      advance(cur_chunk, cur_off);
+      ++fetched;
     }
+    TileDesc cur;
+    describe(cmp_chunk, cmp_off, cur);
+    advance(cmp_chunk, cmp_off);
     const char *kb = lds + buf * L::STAGE;
     const char *vb = kb + L::K_BYTES;
 
@@ -273,8 +294,9 @@ __global__ __launch_bounds__(256, 2) void reuse_attention_kernel(
         }
     }
 
-    if (has_next) store_tile(buf ^ 1);
+    if (has_next) store_tile(in_stage);
     __syncthreads();
+    stage = stage + 1 == NSTAGE ? 0 : stage + 1;
   }
 
   // ---- finish: combine the two lanes of a row, normalise, write
@@ -373,8 +395,8 @@ __global__ __launch_bounds__(256) void v_block_repack_kernel(const __bf16 *__res
 
 namespace pc {
 
-int choose_splits(int n_cu, long base_wgs, int min_tiles, int cap) {
-  const long slots = 2L * n_cu;  // two workgroups are resident per CU
+int choose_splits(int slots_in, long base_wgs, int min_tiles, int cap) {
+  const long slots = slots_in;  // workgroups resident at once on the whole chip
   int best = 1;
   double best_eff = 0.0;
   for (int ns = 1; ns <= cap; ++ns) {
@@ -401,9 +423,13 @@ pc_status launch_attention(percache_ctx *ctx, int layer, const __bf16 *q, const 
                            int n_splits, __bf16 *out, float *part_o, float *part_ml, hipStream_t stream) {
   const percache_config &c = ctx->cfg;
   const int G = c.n_q_heads / c.n_kv_heads, R = G * t_fresh;
-  const int q_tiles = (R + QROWS - 1) / QROWS;
+  // 8 wavefronts x 32 rows (one workgroup per CU, 3 LDS stages) once a kv head has more than 128 stacked rows,
+  // else 4 wavefronts (two workgroups per CU, 2 stages)
+  const bool wide = R > 128;
+  const int qrows = wide ? 256 : 128;
+  const int q_tiles = (R + qrows - 1) / qrows;
   const int cap = max_splits_for(c, ctx->n_cu, batch, t_fresh);
-  if (n_splits <= 0) n_splits = choose_splits(ctx->n_cu, (long)batch * c.n_kv_heads * q_tiles, min_tiles, cap);
+  if (n_splits <= 0) n_splits = choose_splits(wide ? ctx->n_cu : 2 * ctx->n_cu, (long)batch * c.n_kv_heads * q_tiles, min_tiles, cap);
   if (n_splits > cap) n_splits = cap;
   const __bf16 *ks = ctx->k_store + (size_t)layer * ctx->layer_stride;
   const __bf16 *vs = ctx->v_store + (size_t)layer * ctx->layer_stride;
@@ -411,14 +437,16 @@ pc_status launch_attention(percache_ctx *ctx, int layer, const __bf16 *q, const 
   const int n_groups = batch * c.n_kv_heads * n_splits;
   dim3 grid((unsigned)(((n_groups + 7) / 8) * 8 * q_tiles));
   prof_begin(ctx, PC_KERNEL_ATTENTION, stream);
-  if (c.head_dim == 128)
-    hipLaunchKernelGGL(reuse_attention_kernel<128>, grid, dim3(256), 0, stream, q, kf, vf_blk, ks, vs, table_dev,
-                       tbl_stride, t_fresh, c.n_q_heads, c.n_kv_heads, c.slot_capacity, n_splits, q_tiles, n_groups,
-                       scale_log2e, out, part_o, part_ml);
-  else
-    hipLaunchKernelGGL(reuse_attention_kernel<64>, grid, dim3(256), 0, stream, q, kf, vf_blk, ks, vs, table_dev,
-                       tbl_stride, t_fresh, c.n_q_heads, c.n_kv_heads, c.slot_capacity, n_splits, q_tiles, n_groups,
-                       scale_log2e, out, part_o, part_ml);
+#define PC_ATTN(DD, NWW, NS)                                                                                          \
+  hipLaunchKernelGGL((reuse_attention_kernel<DD, NWW, NS>), grid, dim3(64 * NWW), 0, stream, q, kf, vf_blk, ks, vs,     \
+                     table_dev, tbl_stride, t_fresh, c.n_q_heads, c.n_kv_heads, c.slot_capacity, n_splits, q_tiles,  \
+                     n_groups, scale_log2e, out, part_o, part_ml)
+  if (c.head_dim == 128) {
+    if (wide) PC_ATTN(128, 8, 3); else PC_ATTN(128, 4, 2);
+  } else {
+    if (wide) PC_ATTN(64, 8, 3); else PC_ATTN(64, 4, 2);
+  }
+#undef PC_ATTN
   prof_end(ctx, PC_KERNEL_ATTENTION, stream);
   PC_HIP(ctx, hipGetLastError());
   if (n_splits > 1) {
