@@ -6,13 +6,14 @@
 //
 // Shape of the computation (64-wide wavefronts, bf16 32x32x16 MFMA, fp32 softmax state):
 //   - the G = Hq/Hkv query heads of one kv head are stacked: R = G*T_f rows share every K/V tile;
-//   - a workgroup of 4 wavefronts owns 128 rows, a wavefront 32 rows, and loops over 64-key tiles;
+//   - a workgroup of 4 or 8 wavefronts owns 128 or 256 rows, a wavefront 32 rows, and loops over 64-key tiles;
 //   - scores are computed transposed, S^T = K Q^T, so that a lane's 32 accumulators all belong to ONE
 //     query row: the row max/sum are lane-local plus a single exchange with lane+32, and the bf16
 //     probabilities are already in the B-operand layout of O^T += V^T P^T (no LDS round trip for P);
 //   - V is kept in the store (and handed over for the fresh part) as 64-key blocks [D][64] whose key
 //     order inside each group of 16 is the order the score accumulators deliver them, so K and V tiles
-//     are both staged with plain 16-byte copies and every MFMA operand is one 16-byte LDS read;
+//     are both staged with direct global->LDS loads (no registers, no LDS store instructions) and every
+//     MFMA operand is one 16-byte LDS read from an XOR-swizzled, conflict-free layout;
 //   - the running max is only refreshed when a tile exceeds it by more than 2^8 (probabilities stay
 //     below 256, harmless in bf16/fp32), so the rescale of the output accumulators is almost never run;
 //   - the key axis can be partitioned over workgroups (split-KV); partial (max, sum, output) triples are
@@ -31,14 +32,24 @@ using pc::u32x4;
 constexpr int TK = kKvTile;  // keys per tile
 constexpr float kLazy = 8.f; // log2 slack before the running max is refreshed
 
+// LDS stage = one K tile [TK][D] followed by one V block [D][TK], both unpadded (they are filled by
+// direct global->LDS loads, which write 1 KB per wavefront instruction contiguously).  Bank conflicts are
+// avoided by an XOR swizzle of the 16-byte chunk index inside each row, applied on the global-address side
+// when loading and on the LDS-address side when reading:
+//   rows of 256 bytes (16 chunks): chunk ^= row & 15;   rows of 128 bytes (8 chunks): chunk ^= (row >> 1) & 7.
 template <int D>
 struct Lds {
-  static constexpr int K_ROW = D * 2 + 16;   // bytes per key row (padded: conflict-free 16-byte reads)
-  static constexpr int V_ROW = TK * 2 + 16;  // bytes per V^T row (one head-dim index, TK keys)
+  static constexpr int K_ROW = D * 2;   // bytes per key row
+  static constexpr int V_ROW = TK * 2;  // bytes per V^T row (one head-dim index, TK keys)
   static constexpr int K_BYTES = TK * K_ROW;
   static constexpr int V_BYTES = D * V_ROW;
   static constexpr int STAGE = K_BYTES + V_BYTES;
 };
+template <int ROW_BYTES>
+__device__ __forceinline__ int swz(int row) { return ROW_BYTES == 256 ? (row & 15) : ((row >> 1) & 7); }
+
+// s_waitcnt vmcnt(n) alone (expcnt / lgkmcnt fields left at "no wait")
+#define PC_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xf) | (7 << 4) | (15 << 8) | ((((n) >> 4) & 3) << 14))
 
 // 2^x on the hardware transcendental unit; arguments here are bounded above by kLazy.
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -124,11 +135,33 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
     cur_off = rem;
   }
 
-  // ---- global -> register -> LDS staging of one tile (K rows as they are, V as a [D][64] block)
-  constexpr int K_PASS = TK * (D / 8) / NT;  // 16-byte loads per thread for the K tile
-  constexpr int V_PASS = D * (TK / 8) / NT;  // same for the V block
-  constexpr int TPR = D / 8;                  // threads per key row
-  u32x4 rk[K_PASS], rv[V_PASS];
+  // ---- direct global -> LDS staging of one tile.  Wavefront instruction i writes bytes [1024 i, 1024 i + 1024)
+  // of the K tile (or V block); lane l lands at byte 1024 i + 16 l, i.e. row (1024 i + 16 l) / ROW, physical
+  // chunk ((1024 i + 16 l) % ROW) / 16, and therefore fetches the logical chunk (physical ^ swizzle(row)).
+  static_assert(NSTAGE * L::STAGE <= 160 * 1024, "LDS stages exceed the 160 KB of a CU");
+  constexpr int K_INSTR = L::K_BYTES / 1024 / NW;  // per wavefront
+  constexpr int V_INSTR = L::V_BYTES / 1024 / NW;
+  static_assert(K_INSTR >= 1 && V_INSTR >= 1, "tile too small for this many wavefronts");
+  int k_row[K_INSTR], k_col[K_INSTR], v_goff[V_INSTR];
+#pragma unroll
+  for (int k = 0; k < K_INSTR; ++k) {
+    const int byte = (wave + k * NW) * 1024 + lane * 16;
+    const int row = byte / L::K_ROW, pc = (byte % L::K_ROW) / 16;
+    k_row[k] = row;
+    k_col[k] = (pc ^ swz<L::K_ROW>(row)) * 8;  // element offset inside the row
+  }
+#pragma unroll
+  for (int k = 0; k < V_INSTR; ++k) {
+    const int byte = (wave + k * NW) * 1024 + lane * 16;
+    const int d = byte / L::V_ROW, pc = (byte % L::V_ROW) / 16;
+    v_goff[k] = d * TK + (pc ^ swz<L::V_ROW>(d)) * 8;  // element offset inside the block
+  }
+  // swizzled byte offsets of this lane's MFMA operand reads inside its row
+  int k_rd[KS], v_rd[4];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) k_rd[ks] = ((2 * ks + g2) ^ swz<L::K_ROW>(l32)) * 16;
+#pragma unroll
+  for (int c4 = 0; c4 < 4; ++c4) v_rd[c4] = ((2 * c4 + g2) ^ swz<L::V_ROW>(l32)) * 16;
   struct TileDesc { const __bf16 *k, *v; int valid; int t0; bool fresh; };
   auto describe = [&](int chunk, int off, TileDesc &td) __attribute__((always_inline)) {
     if (chunk < n_chunks) {
@@ -159,34 +192,26 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
       }
     }
   };
-  auto load_tile = [&](const TileDesc &td) __attribute__((always_inline)) {
+  auto fetch_tile = [&](const TileDesc &td, int st) __attribute__((always_inline)) {
+    char *kb = lds + st * L::STAGE;
 #pragma unroll
-    for (int p = 0; p < K_PASS; ++p) {
-      int row = min(tid / TPR + p * (NT / TPR), td.valid - 1);
-      rk[p] = *(const u32x4 *)(td.k + (size_t)row * D + (tid % TPR) * 8);
+    for (int k = 0; k < K_INSTR; ++k) {
+      const int row = min(k_row[k], td.valid - 1);  // rows past a ragged end repeat the last valid row (masked later)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(td.k + (size_t)row * D + k_col[k]),
+                                       (__attribute__((address_space(3))) void *)(kb + (wave + k * NW) * 1024), 16, 0, 0);
     }
 #pragma unroll
-    for (int p = 0; p < V_PASS; ++p) rv[p] = *(const u32x4 *)(td.v + (size_t)(p * NT + tid) * 8);
-  };
-  auto store_tile = [&](int buf) __attribute__((always_inline)) {
-    char *kb = lds + buf * L::STAGE;
-    char *vb = kb + L::K_BYTES;
-#pragma unroll
-    for (int p = 0; p < K_PASS; ++p) {
-      int row = tid / TPR + p * (NT / TPR);
-      *(u32x4 *)(kb + row * L::K_ROW + (tid % TPR) * 16) = rk[p];
-    }
-#pragma unroll
-    for (int p = 0; p < V_PASS; ++p) {
-      int d = (p * NT + tid) >> 3, chunk = tid & 7;
-      *(u32x4 *)(vb + d * L::V_ROW + chunk * 16) = rv[p];
-    }
+    for (int k = 0; k < V_INSTR; ++k)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(td.v + v_goff[k]),
+                                       (__attribute__((address_space(3))) void *)(kb + L::K_BYTES + (wave + k * NW) * 1024), 16, 0, 0);
   };
 
-  // Pipeline: the tile computed in iteration t sits in stage t % NSTAGE; tiles t+1 .. t+AHEAD-1 are already in
-  // LDS, tile t+AHEAD travels through registers during iteration t and is stored at its end.  One barrier per
-  // tile: it publishes the stores and retires the stage that will be overwritten next.  Two cursors walk the
-  // chunk list: (cur_chunk, cur_off) for the tile being fetched, (cmp_chunk, cmp_off) for the one being computed.
+  // Pipeline: the tile computed in iteration t sits in stage t % NSTAGE; the loads of tile t+AHEAD are issued at
+  // the top of iteration t into the stage that iteration t-1 finished reading (the barrier at its end says so).
+  // At the end of iteration t the loads of tile t+1 must have landed: they are the oldest outstanding ones, so
+  // waiting until at most (AHEAD-1) tiles' worth of loads remain is enough; then one barrier publishes them.
+  // Two cursors walk the chunk list: (cur_chunk, cur_off) for the tile being fetched, (cmp_chunk, cmp_off) for
+  // the one being computed.
   while (cur_chunk < n_chunks && trow[kTblHeader + 2 * cur_chunk + 1] == 0) ++cur_chunk;
   int cmp_chunk = cur_chunk, cmp_off = cur_off;
   int fetched = tile_begin;  // next tile to fetch
@@ -195,13 +220,14 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
     if (fetched < tile_end) {
       TileDesc t0d;
       describe(cur_chunk, cur_off, t0d);
-      load_tile(t0d);
-      store_tile(k);
+      fetch_tile(t0d, k);
       advance(cur_chunk, cur_off);
       ++fetched;
     }
   }
-  __syncthreads();
+  PC_WAIT_VMCNT(0);
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
 
   int stage = 0;  // (tt - tile_begin) % NSTAGE
   for (int tt = tile_begin; tt < tile_end; ++tt) {
@@ -212,7 +238,7 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
     if (has_next) {
       TileDesc nxt;
       describe(cur_chunk, cur_off, nxt);
-      load_tile(nxt);
+      fetch_tile(nxt, in_stage);
       advance(cur_chunk, cur_off);
       ++fetched;
     }
@@ -228,10 +254,10 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
     for (int kbk = 0; kbk < 2; ++kbk) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) s_acc[kbk][r] = 0.f;
-      const char *krow = kb + (kbk * 32 + l32) * L::K_ROW + g2 * 16;
+      const char *krow = kb + (kbk * 32 + l32) * L::K_ROW;
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        bf16x8 a = *(const bf16x8 *)(krow + ks * 32);
+        bf16x8 a = *(const bf16x8 *)(krow + k_rd[ks]);
         s_acc[kbk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s_acc[kbk], 0, 0, 0);
       }
     }
@@ -284,18 +310,21 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
     // ---- O^T += V^T P^T
 #pragma unroll
     for (int db = 0; db < DB; ++db) {
-      const char *vrow = vb + (db * 32 + l32) * L::V_ROW + g2 * 16;
+      const char *vrow = vb + (db * 32 + l32) * L::V_ROW;
 #pragma unroll
       for (int kbk = 0; kbk < 2; ++kbk)
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
-          bf16x8 a = *(const bf16x8 *)(vrow + (kbk * 2 + j) * 32);
+          bf16x8 a = *(const bf16x8 *)(vrow + v_rd[kbk * 2 + j]);
           o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[kbk][j], o_acc[db], 0, 0, 0);
         }
     }
 
-    if (has_next) store_tile(in_stage);
-    __syncthreads();
+    // (when nothing was fetched in this iteration fewer tiles are in flight: wait for all of them)
+    if (AHEAD == 1 || !has_next) PC_WAIT_VMCNT(0); else PC_WAIT_VMCNT((AHEAD - 1) * (K_INSTR + V_INSTR));
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
     stage = stage + 1 == NSTAGE ? 0 : stage + 1;
   }
 
@@ -442,9 +471,9 @@ pc_status launch_attention(percache_ctx *ctx, int layer, const __bf16 *q, const 
                      table_dev, tbl_stride, t_fresh, c.n_q_heads, c.n_kv_heads, c.slot_capacity, n_splits, q_tiles,  \
                      n_groups, scale_log2e, out, part_o, part_ml)
   if (c.head_dim == 128) {
-    if (wide) PC_ATTN(128, 8, 3); else PC_ATTN(128, 4, 2);
+    if (wide) PC_ATTN(128, 8, 2); else PC_ATTN(128, 4, 2);
   } else {
-    if (wide) PC_ATTN(64, 8, 3); else PC_ATTN(64, 4, 2);
+    if (wide) PC_ATTN(64, 8, 4); else PC_ATTN(64, 4, 4);
   }
 #undef PC_ATTN
   prof_end(ctx, PC_KERNEL_ATTENTION, stream);
