@@ -84,8 +84,7 @@ def main():
     def step():
         pc.percache_lookup(probes, lw.tau, idx, sim, hit)
         pc.percache_prefill_reuse(0, X, W, w.slot_ids, w.used_len, attn_out=attn, k_fresh_out=kf, v_fresh_out=vf)
-        for b in range(B):
-            pc.percache_kv_put(0, spare[b], kf[b], vf[b], T)
+        pc.percache_kv_put_batch(0, spare, kf, vf, T)
 
     for _ in range(args.warmup):
         step()

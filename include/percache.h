@@ -105,6 +105,11 @@ pc_status percache_kv_put(percache_ctx *ctx, int32_t layer, int32_t slot, const 
 pc_status percache_kv_get(percache_ctx *ctx, int32_t layer, int32_t slot, void *k_out_dev,
                           void *v_out_dev, int32_t *n_tokens_out_host, void *stream);
 pc_status percache_kv_evict(percache_ctx *ctx, int32_t layer, int32_t slot);
+/* percache_kv_put for n chunks in one launch: tensors [n, n_kv_heads, n_tokens, head_dim] (the layout of
+ * percache_prefill_reuse's k_fresh_out / v_fresh_out, so the fresh part of every query of a batch can be
+ * saved at once); chunk i goes to slot slots_host[i].  Slots must be distinct. */
+pc_status percache_kv_put_batch(percache_ctx *ctx, int32_t layer, const int32_t *slots_host, int32_t n,
+                                const void *k_dev, const void *v_dev, int32_t n_tokens, void *stream);
 /* Stored token count of a slot, 0 if empty, negative pc_status on a bad index. */
 int32_t percache_kv_len(const percache_ctx *ctx, int32_t layer, int32_t slot);
 

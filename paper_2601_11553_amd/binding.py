@@ -23,7 +23,7 @@ STATUS_NAMES = {0: "PC_OK", -1: "PC_EINVAL", -2: "PC_ESHAPE", -3: "PC_ESLOT", -4
 EXPORTS = [
     "percache_arena_bytes", "percache_create", "percache_destroy", "percache_last_error",
     "percache_bank_put", "percache_bank_size", "percache_lookup_workspace_bytes", "percache_lookup",
-    "percache_kv_put", "percache_kv_get", "percache_kv_evict", "percache_kv_len",
+    "percache_kv_put", "percache_kv_put_batch", "percache_kv_get", "percache_kv_evict", "percache_kv_len",
     "percache_prefill_workspace_bytes", "percache_prefill_reuse", "percache_qkv_rope", "percache_attention_reuse",
     "percache_profile_enable", "percache_profile_read",
 ]
@@ -69,6 +69,7 @@ def load_library() -> ctypes.CDLL:
         "percache_lookup_workspace_bytes": (_sz, [_vp, _i32]),
         "percache_lookup": (_i32, [_vp, _vp, _i32, ctypes.c_float, _vp, _vp, _vp, _vp, _sz, _vp]),
         "percache_kv_put": (_i32, [_vp, _i32, _i32, _vp, _vp, _i32, _vp]),
+        "percache_kv_put_batch": (_i32, [_vp, _i32, _pi32, _i32, _vp, _vp, _i32, _vp]),
         "percache_kv_get": (_i32, [_vp, _i32, _i32, _vp, _vp, _pi32, _vp]),
         "percache_kv_evict": (_i32, [_vp, _i32, _i32]),
         "percache_kv_len": (_i32, [_vp, _i32, _i32]),
@@ -191,6 +192,12 @@ class Percache:
     def percache_kv_put(self, layer: int, slot: int, k, v, n_tokens: Optional[int] = None):
         n = k.shape[1] if n_tokens is None else n_tokens
         self._check(self.lib.percache_kv_put(self.ctx, layer, slot, _ptr(k), _ptr(v), n, _stream()))
+
+    def percache_kv_put_batch(self, layer: int, slots, k, v, n_tokens: Optional[int] = None):
+        """k, v: [n, Hkv, n_tokens, D]; chunk i is written to slot slots[i] (one launch)."""
+        arr, p = _host_i32(slots)
+        n = k.shape[2] if n_tokens is None else n_tokens
+        self._check(self.lib.percache_kv_put_batch(self.ctx, layer, p, len(arr), _ptr(k), _ptr(v), n, _stream()))
 
     def percache_kv_get(self, layer: int, slot: int):
         import torch

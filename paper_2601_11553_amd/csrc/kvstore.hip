@@ -14,10 +14,24 @@ using pc::kKvTile;
 
 // blockIdx.y == 0: K, Hkv runs of n_tok*D elements copied 16 bytes per lane.
 // blockIdx.y == 1: V, one output 16-byte vector (8 key positions of one head-dim index) per thread and step.
+struct SlotList {
+  int32_t slot[64];
+};
+
 template <bool kToStore>
 __global__ __launch_bounds__(256) void kv_copy_kernel(pc::u32x4 *__restrict__ slot_k, __bf16 *__restrict__ slot_v,
                                                       pc::u32x4 *__restrict__ dense_k, __bf16 *__restrict__ dense_v,
-                                                      int n_heads, int n_tok, int D, int C) {
+                                                      int n_heads, int n_tok, int D, int C, SlotList slots,
+                                                      long slot_stride_elems) {
+  // blockIdx.z selects the chunk: its slot and its dense tensor
+  {
+    const long so = (long)slots.slot[blockIdx.z] * slot_stride_elems;
+    const long dn = (long)blockIdx.z * n_heads * n_tok * D;
+    slot_k += so / 8;
+    slot_v += so;
+    dense_k += dn / 8;
+    dense_v += dn;
+  }
   const long stride = (long)gridDim.x * blockDim.x;
   const long tid0 = (long)blockIdx.x * blockDim.x + threadIdx.x;
   if (blockIdx.y == 0) {
@@ -79,15 +93,18 @@ pc_status check_slot(percache_ctx *ctx, int32_t layer, int32_t slot) {
 }
 
 template <bool kToStore>
-pc_status launch_copy(percache_ctx *ctx, int layer, int slot, void *k_dev, void *v_dev, int n_tokens, hipStream_t stream) {
+pc_status launch_copy(percache_ctx *ctx, int layer, const int32_t *slot_list, int n, void *k_dev, void *v_dev, int n_tokens,
+                      hipStream_t stream) {
   const percache_config &c = ctx->cfg;
-  size_t off = (size_t)layer * ctx->layer_stride + (size_t)slot * ctx->slot_stride;
+  size_t off = (size_t)layer * ctx->layer_stride;
+  SlotList sl;
+  for (int i = 0; i < 64; ++i) sl.slot[i] = i < n ? slot_list[i] : 0;
   long total = (long)c.n_kv_heads * ((n_tokens + kKvTile - 1) / kKvTile) * kKvTile * c.head_dim / 8;
   int blocks = (int)((total + 255) / 256);
   if (blocks > 2048) blocks = 2048;
-  hipLaunchKernelGGL(kv_copy_kernel<kToStore>, dim3(blocks, 2), dim3(256), 0, stream, (pc::u32x4 *)(ctx->k_store + off),
+  hipLaunchKernelGGL(kv_copy_kernel<kToStore>, dim3(blocks, 2, n), dim3(256), 0, stream, (pc::u32x4 *)(ctx->k_store + off),
                      ctx->v_store + off, (pc::u32x4 *)k_dev, (__bf16 *)v_dev, c.n_kv_heads, n_tokens, c.head_dim,
-                     c.slot_capacity);
+                     c.slot_capacity, sl, (long)ctx->slot_stride);
   PC_HIP(ctx, hipGetLastError());
   return PC_OK;
 }
@@ -104,9 +121,34 @@ pc_status percache_kv_put(percache_ctx *ctx, int32_t layer, int32_t slot, const 
   if (((uintptr_t)k_dev | (uintptr_t)v_dev) % 16) return pc::fail(ctx, PC_EINVAL, "k_dev / v_dev must be 16-byte aligned");
   const percache_config &c = ctx->cfg;
   if (n_tokens < 1 || n_tokens > c.slot_capacity) return pc::fail(ctx, PC_ELEN, "n_tokens %d outside [1,%d]", n_tokens, c.slot_capacity);
-  st = launch_copy<true>(ctx, layer, slot, (void *)k_dev, (void *)v_dev, n_tokens, (hipStream_t)stream);
+  st = launch_copy<true>(ctx, layer, &slot, 1, (void *)k_dev, (void *)v_dev, n_tokens, (hipStream_t)stream);
   if (st != PC_OK) return st;
   ctx->slot_len[(size_t)layer * c.n_slots + slot] = n_tokens;
+  return PC_OK;
+}
+
+pc_status percache_kv_put_batch(percache_ctx *ctx, int32_t layer, const int32_t *slots_host, int32_t n, const void *k_dev,
+                                const void *v_dev, int32_t n_tokens, void *stream) {
+  if (!ctx) return PC_EINVAL;
+  if (!slots_host || n < 1) return pc::fail(ctx, PC_EINVAL, "slots_host is NULL or n < 1");
+  if (!k_dev || !v_dev) return pc::fail(ctx, PC_EINVAL, "k_dev / v_dev is NULL");
+  if (((uintptr_t)k_dev | (uintptr_t)v_dev) % 16) return pc::fail(ctx, PC_EINVAL, "k_dev / v_dev must be 16-byte aligned");
+  const percache_config &c = ctx->cfg;
+  if (n_tokens < 1 || n_tokens > c.slot_capacity) return pc::fail(ctx, PC_ELEN, "n_tokens %d outside [1,%d]", n_tokens, c.slot_capacity);
+  for (int i = 0; i < n; ++i) {
+    pc_status st = check_slot(ctx, layer, slots_host[i]);
+    if (st != PC_OK) return st;
+    for (int j = 0; j < i; ++j)
+      if (slots_host[j] == slots_host[i]) return pc::fail(ctx, PC_EINVAL, "slot %d appears twice in the batch", slots_host[i]);
+  }
+  const size_t per_chunk = (size_t)c.n_kv_heads * n_tokens * c.head_dim;
+  for (int i0 = 0; i0 < n; i0 += 64) {
+    int cnt = n - i0 < 64 ? n - i0 : 64;
+    pc_status st = launch_copy<true>(ctx, layer, slots_host + i0, cnt, (void *)((const __bf16 *)k_dev + per_chunk * i0),
+                                     (void *)((const __bf16 *)v_dev + per_chunk * i0), n_tokens, (hipStream_t)stream);
+    if (st != PC_OK) return st;
+  }
+  for (int i = 0; i < n; ++i) ctx->slot_len[(size_t)layer * c.n_slots + slots_host[i]] = n_tokens;
   return PC_OK;
 }
 
@@ -119,7 +161,7 @@ pc_status percache_kv_get(percache_ctx *ctx, int32_t layer, int32_t slot, void *
   const percache_config &c = ctx->cfg;
   int n_tokens = ctx->slot_len[(size_t)layer * c.n_slots + slot];
   if (n_tokens <= 0) return pc::fail(ctx, PC_ESLOT, "slot %d of layer %d is empty", slot, layer);
-  st = launch_copy<false>(ctx, layer, slot, k_out_dev, v_out_dev, n_tokens, (hipStream_t)stream);
+  st = launch_copy<false>(ctx, layer, &slot, 1, k_out_dev, v_out_dev, n_tokens, (hipStream_t)stream);
   if (st != PC_OK) return st;
   if (n_tokens_out_host) *n_tokens_out_host = n_tokens;
   return PC_OK;

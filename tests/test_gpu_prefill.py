@@ -53,6 +53,18 @@ def test_kv_store_round_trip_and_errors():
         torch.cuda.synchronize()
         assert torch.equal(k, k2) and torch.equal(v, v2)
     assert pc.percache_kv_len(1, 0) == 0
+    # several chunks in one launch, then read back one by one
+    kb = bf16(g.standard_normal((3, 2, 70, 64)).astype(np.float32))
+    vb = bf16(g.standard_normal((3, 2, 70, 64)).astype(np.float32))
+    pc.percache_kv_put_batch(1, [4, 0, 2], kb, vb)
+    for i, s in enumerate([4, 0, 2]):
+        k2, v2 = pc.percache_kv_get(1, s)
+        torch.cuda.synchronize()
+        assert torch.equal(kb[i], k2) and torch.equal(vb[i], v2)
+    with pytest.raises(PercacheError) as e:
+        pc.percache_kv_put_batch(1, [1, 1], kb[:2], vb[:2])
+    assert e.value.status == -1
+    pc.percache_kv_evict(1, 0)
     k = bf16(np.zeros((2, 129, 64), np.float32))
     for args, status in [((0, 6, k[:, :8], k[:, :8]), -3), ((2, 0, k[:, :8], k[:, :8]), -3), ((0, 1, k, k), -4)]:
         with pytest.raises(PercacheError) as e:
