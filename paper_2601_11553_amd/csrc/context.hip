@@ -151,7 +151,7 @@ PrefillWs carve_prefill_ws(const percache_config &c, int n_cu, void *base, int32
   w.v_blk = (__bf16 *)take((size_t)batch * c.n_kv_heads * ((t_fresh + kKvTile - 1) / kKvTile) * kKvTile * c.head_dim * 2);
   size_t rows = (size_t)batch * c.n_q_heads * t_fresh;
   w.max_splits = max_splits_for(c, n_cu, batch, t_fresh);
-  w.part_o = (float *)take(rows * w.max_splits * c.head_dim * sizeof(float));
+  w.part_o = (__bf16 *)take(rows * w.max_splits * c.head_dim * 2);
   w.part_ml = (float *)take(rows * w.max_splits * 2 * sizeof(float));
   w.total = off;
   return w;

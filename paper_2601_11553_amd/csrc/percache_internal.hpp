@@ -96,7 +96,7 @@ struct PrefillWs {
   int32_t *table;
   __bf16 *q, *k, *v;
   __bf16 *v_blk;   // fresh V as 64-key blocks [B*Hkv][ceil(T/64)][D][64]
-  float *part_o;   // [rows][splits][D]
+  __bf16 *part_o;  // [rows][splits][D], normalised per split
   float *part_ml;  // [rows][splits][2]
   int max_splits;  // partitions of the key axis the partial buffers can hold
   size_t total;
@@ -119,6 +119,6 @@ pc_status launch_qkv_rope(percache_ctx *ctx, const __bf16 *x, const __bf16 *w, i
 pc_status launch_v_repack(percache_ctx *ctx, const __bf16 *vf, __bf16 *vf_blk, int batch, int t_fresh, hipStream_t stream);
 pc_status launch_attention(percache_ctx *ctx, int layer, const __bf16 *q, const __bf16 *kf, const __bf16 *vf_blk,
                            int batch, int t_fresh, const int32_t *table_dev, int tbl_stride, int max_tiles,
-                           int n_splits, __bf16 *out, float *part_o, float *part_ml, hipStream_t stream);
+                           int n_splits, __bf16 *out, __bf16 *part_o, float *part_ml, hipStream_t stream);
 
 }  // namespace pc

@@ -64,7 +64,7 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
     const __bf16 *__restrict__ Q, const __bf16 *__restrict__ Kf, const __bf16 *__restrict__ Vf_blk,
     const __bf16 *__restrict__ k_store, const __bf16 *__restrict__ v_store, const int32_t *__restrict__ table,
     int tbl_stride, int T, int Hq, int Hkv, int C, int n_splits, int q_tiles, int n_groups, float scale_log2e,
-    __bf16 *__restrict__ out, float *__restrict__ part_o, float *__restrict__ part_ml) {
+    __bf16 *__restrict__ out, __bf16 *__restrict__ part_o, float *__restrict__ part_ml) {
   using L = Lds<D>;
   constexpr int KS = D / 16;  // k-steps of the QK^T contraction
   constexpr int DB = D / 32;  // 32-wide blocks of the head dim (rows of O^T)
@@ -344,14 +344,16 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
       }
   } else {
     const size_t prow = (((size_t)b * Hkv + gkv) * R + my_row) * n_splits + split;
-    float *po = part_o + prow * D;
+    // partial outputs are normalised per split and kept in bf16: they are convex combinations of V rows, and the
+    // merge weights them in fp32, so this costs one extra bf16 rounding and halves the merge traffic
+    __bf16 *po = part_o + prow * D;
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {
-        float4 v = make_float4(o_acc[db][q4 * 4 + 0] * inv, o_acc[db][q4 * 4 + 1] * inv, o_acc[db][q4 * 4 + 2] * inv,
-                               o_acc[db][q4 * 4 + 3] * inv);
-        *(float4 *)(po + db * 32 + q4 * 8 + g2 * 4) = v;
+        pc::bf16x4 v = {(__bf16)(o_acc[db][q4 * 4 + 0] * inv), (__bf16)(o_acc[db][q4 * 4 + 1] * inv),
+                        (__bf16)(o_acc[db][q4 * 4 + 2] * inv), (__bf16)(o_acc[db][q4 * 4 + 3] * inv)};
+        *(pc::bf16x4 *)(po + db * 32 + q4 * 8 + g2 * 4) = v;
       }
     if (g2 == 0) {
       part_ml[prow * 2] = m_ref;
@@ -361,13 +363,13 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
 }
 
 // Merge of the split-KV partials: m = max m_s, w_s = l_s 2^(m_s - m), o = sum w_s o_s / sum w_s.
-// One thread per (row, 4 head-dim elements).
+// One thread per (row, 8 head-dim elements).
 template <int D>
-__global__ __launch_bounds__(256) void splitkv_combine_kernel(const float *__restrict__ part_o,
+__global__ __launch_bounds__(256) void splitkv_combine_kernel(const __bf16 *__restrict__ part_o,
                                                               const float *__restrict__ part_ml, int n_splits, int T,
                                                               int Hq, int Hkv, long total_rows,
                                                               __bf16 *__restrict__ out) {
-  constexpr int VPR = D / 4;
+  constexpr int VPR = D / 8;
   long gid = (long)blockIdx.x * blockDim.x + threadIdx.x;
   long prow = gid / VPR;
   int dv = (int)(gid - prow * VPR);
@@ -383,18 +385,21 @@ __global__ __launch_bounds__(256) void splitkv_combine_kernel(const float *__res
   for (int s = 0; s < n_splits; ++s)
     if (ml[2 * s + 1] > 0.f) m = fmaxf(m, ml[2 * s]);
   float wsum = 0.f;
-  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   for (int s = 0; s < n_splits; ++s) {
     float ms = ml[2 * s], ls = ml[2 * s + 1];
     if (ls <= 0.f) continue;
     float w = ls * exp2f(ms - m);
-    float4 o = *(const float4 *)(part_o + (prow * n_splits + s) * D + dv * 4);
-    acc.x += w * o.x; acc.y += w * o.y; acc.z += w * o.z; acc.w += w * o.w;
+    pc::bf16x8 o = *(const pc::bf16x8 *)(part_o + (prow * n_splits + s) * D + dv * 8);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] += w * (float)o[e];
     wsum += w;
   }
   float inv = wsum > 0.f ? 1.0f / wsum : 0.f;
-  pc::bf16x4 v = {(__bf16)(acc.x * inv), (__bf16)(acc.y * inv), (__bf16)(acc.z * inv), (__bf16)(acc.w * inv)};
-  *(pc::bf16x4 *)(out + ((size_t)b * T + i) * ((size_t)Hq * D) + (size_t)head * D + dv * 4) = v;
+  pc::bf16x8 v;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) v[e] = (__bf16)(acc[e] * inv);
+  *(pc::bf16x8 *)(out + ((size_t)b * T + i) * ((size_t)Hq * D) + (size_t)head * D + dv * 8) = v;
 }
 
 // Fresh V [B*Hkv][T][D] -> 64-key blocks [B*Hkv][ceil(T/64)][D][64] in the key order of the store
@@ -449,7 +454,7 @@ pc_status launch_v_repack(percache_ctx *ctx, const __bf16 *vf, __bf16 *vf_blk, i
 
 pc_status launch_attention(percache_ctx *ctx, int layer, const __bf16 *q, const __bf16 *kf, const __bf16 *vf_blk,
                            int batch, int t_fresh, const int32_t *table_dev, int tbl_stride, int min_tiles,
-                           int n_splits, __bf16 *out, float *part_o, float *part_ml, hipStream_t stream) {
+                           int n_splits, __bf16 *out, __bf16 *part_o, float *part_ml, hipStream_t stream) {
   const percache_config &c = ctx->cfg;
   const int G = c.n_q_heads / c.n_kv_heads, R = G * t_fresh;
   // 8 wavefronts x 32 rows (one workgroup per CU, 3 LDS stages) once a kv head has more than 128 stacked rows,
@@ -480,7 +485,7 @@ pc_status launch_attention(percache_ctx *ctx, int layer, const __bf16 *q, const 
   PC_HIP(ctx, hipGetLastError());
   if (n_splits > 1) {
     long total_rows = (long)batch * c.n_kv_heads * R;
-    long threads = total_rows * (c.head_dim / 4);
+    long threads = total_rows * (c.head_dim / 8);
     int blocks = (int)((threads + 255) / 256);
     if (c.head_dim == 128)
       hipLaunchKernelGGL(splitkv_combine_kernel<128>, dim3(blocks), dim3(256), 0, stream, part_o, part_ml, n_splits,
