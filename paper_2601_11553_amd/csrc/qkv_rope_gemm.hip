@@ -9,15 +9,21 @@
 // x (64 or 128) tokens.  The features are the M side of the MFMA and the tokens the N side, so a lane ends
 // up holding 4 consecutive features of one token per accumulator quad (8-byte stores), and each wavefront
 // owns a feature block together with its rotation partner (m, m + D/2): RoPE needs no cross-lane traffic.
+// Operand tiles (64 k-elements = 128-byte rows) are brought in by direct global->LDS loads into a
+// double-buffered, XOR-swizzled LDS layout (16-byte chunk index ^= (row >> 1) & 7: conflict-free reads).
 #include "percache_internal.hpp"
 
 namespace {
 using pc::bf16x8;
 using pc::f32x16;
 
-constexpr int BK = 64;               // k elements per LDS stage
-constexpr int LDS_ROW = BK * 2 + 16; // bytes per padded LDS row (conflict-free 16-byte reads)
-constexpr int BF = 128;              // features per workgroup
+constexpr int BK = 64;         // k elements per LDS stage
+constexpr int ROW = BK * 2;    // bytes per LDS row
+constexpr int BF = 128;        // features per workgroup
+constexpr int NW = 4;          // wavefronts per workgroup
+
+__device__ __forceinline__ int swz128(int row) { return (row >> 1) & 7; }
+#define PC_WAIT_VMCNT0() __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8))
 
 __device__ __forceinline__ uint2 pack4(float a, float b, float c, float d) {
   pc::bf16x4 v = {(__bf16)a, (__bf16)b, (__bf16)c, (__bf16)d};
@@ -26,14 +32,15 @@ __device__ __forceinline__ uint2 pack4(float a, float b, float c, float d) {
 
 // NTB: 32-token blocks per wavefront (1 -> 64-token tile, 2 -> 128-token tile).
 template <int D, int NTB>
-__global__ __launch_bounds__(256) void qkv_rope_kernel(const __bf16 *__restrict__ X, const __bf16 *__restrict__ W, int M,
-                                                       int H, int t_fresh, int Hq, int Hkv,
-                                                       const int32_t *__restrict__ table, int tbl_stride,
-                                                       const float2 *__restrict__ rope, __bf16 *__restrict__ Q,
-                                                       __bf16 *__restrict__ K, __bf16 *__restrict__ V) {
+__global__ __launch_bounds__(256, 2) void qkv_rope_kernel(const __bf16 *__restrict__ X, const __bf16 *__restrict__ W, int M,
+                                                          int H, int t_fresh, int Hq, int Hkv,
+                                                          const int32_t *__restrict__ table, int tbl_stride,
+                                                          const float2 *__restrict__ rope, __bf16 *__restrict__ Q,
+                                                          __bf16 *__restrict__ K, __bf16 *__restrict__ V) {
   constexpr int BT = 64 * NTB;
-  __shared__ __align__(16) char lds_w[2][BF * LDS_ROW];
-  __shared__ __align__(16) char lds_x[2][BT * LDS_ROW];
+  constexpr int W_BYTES = BF * ROW, X_BYTES = BT * ROW, STAGE = W_BYTES + X_BYTES;
+  constexpr int W_INSTR = W_BYTES / 1024 / NW, X_INSTR = X_BYTES / 1024 / NW;
+  __shared__ __align__(16) char lds[2 * STAGE];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wf = wave & 1, wt = wave >> 1;
@@ -45,27 +52,35 @@ __global__ __launch_bounds__(256) void qkv_rope_kernel(const __bf16 *__restrict_
   const int fb_lo = (D == 128) ? wf : 2 * wf;
   const int fb_hi = (D == 128) ? wf + 2 : 2 * wf + 1;
 
-  // global -> LDS mapping: 8 threads per 128-byte row segment
-  const int ld_row = tid >> 3, ld_col = tid & 7;
-  pc::u32x4 rw[BF / 32], rx[BT / 32];
-  auto load_global = [&](int kt) __attribute__((always_inline)) {
+  // direct global -> LDS loads: wavefront instruction i fills bytes [1024 i, 1024 i + 1024) of a tile, lane l
+  // the 16 bytes at 1024 i + 16 l, i.e. row (8 i + l / 8), physical chunk l % 8 <- logical chunk (l % 8) ^ swz(row)
+  int w_off[W_INSTR], x_off[X_INSTR];
 #pragma unroll
-    for (int p = 0; p < BF / 32; ++p) {
-      int row = f0 + ld_row + 32 * p;
-      rw[p] = *(const pc::u32x4 *)(W + (size_t)row * H + kt * BK + ld_col * 8);
-    }
+  for (int k = 0; k < W_INSTR; ++k) {
+    const int row = (wave + k * NW) * 8 + (lane >> 3);
+    w_off[k] = (f0 + row) * H + (((lane & 7) ^ swz128(row)) * 8);
+  }
 #pragma unroll
-    for (int p = 0; p < BT / 32; ++p) {
-      int row = min(m0 + ld_row + 32 * p, M - 1);
-      rx[p] = *(const pc::u32x4 *)(X + (size_t)row * H + kt * BK + ld_col * 8);
-    }
+  for (int k = 0; k < X_INSTR; ++k) {
+    const int row = (wave + k * NW) * 8 + (lane >> 3);
+    x_off[k] = min(m0 + row, M - 1) * H + (((lane & 7) ^ swz128(row)) * 8);
+  }
+  auto fetch = [&](int kt, int st) __attribute__((always_inline)) {
+    char *base = lds + st * STAGE;
+#pragma unroll
+    for (int k = 0; k < W_INSTR; ++k)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(W + (size_t)w_off[k] + kt * BK),
+                                       (__attribute__((address_space(3))) void *)(base + (wave + k * NW) * 1024), 16, 0, 0);
+#pragma unroll
+    for (int k = 0; k < X_INSTR; ++k)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(X + (size_t)x_off[k] + kt * BK),
+                                       (__attribute__((address_space(3))) void *)(base + W_BYTES + (wave + k * NW) * 1024), 16, 0, 0);
   };
-  auto store_lds = [&](int buf) __attribute__((always_inline)) {
+
+  // swizzled byte offsets of this lane's operand reads inside its row (row & 31 = l32 for every block)
+  int rd[BK / 16];
 #pragma unroll
-    for (int p = 0; p < BF / 32; ++p) *(pc::u32x4 *)(lds_w[buf] + (ld_row + 32 * p) * LDS_ROW + ld_col * 16) = rw[p];
-#pragma unroll
-    for (int p = 0; p < BT / 32; ++p) *(pc::u32x4 *)(lds_x[buf] + (ld_row + 32 * p) * LDS_ROW + ld_col * 16) = rx[p];
-  };
+  for (int ks = 0; ks < BK / 16; ++ks) rd[ks] = ((2 * ks + g) ^ swz128(l32)) * 16;
 
   f32x16 acc[2][NTB];
 #pragma unroll
@@ -76,28 +91,32 @@ __global__ __launch_bounds__(256) void qkv_rope_kernel(const __bf16 *__restrict_
       for (int r = 0; r < 16; ++r) acc[a][t][r] = 0.f;
 
   const int nk = H / BK;
-  load_global(0);
-  store_lds(0);
-  __syncthreads();
+  fetch(0, 0);
+  PC_WAIT_VMCNT0();
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
   for (int kt = 0; kt < nk; ++kt) {
-    const int buf = kt & 1;
-    if (kt + 1 < nk) load_global(kt + 1);
-    const char *wl = lds_w[buf] + (fb_lo * 32 + l32) * LDS_ROW + g * 16;
-    const char *wh = lds_w[buf] + (fb_hi * 32 + l32) * LDS_ROW + g * 16;
-    const char *xb = lds_x[buf] + ((wt * NTB) * 32 + l32) * LDS_ROW + g * 16;
+    const int st = kt & 1;
+    if (kt + 1 < nk) fetch(kt + 1, st ^ 1);
+    const char *wl = lds + st * STAGE + (fb_lo * 32 + l32) * ROW;
+    const char *wh = lds + st * STAGE + (fb_hi * 32 + l32) * ROW;
+    const char *xb = lds + st * STAGE + W_BYTES + ((wt * NTB) * 32 + l32) * ROW;
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 a_lo = *(const bf16x8 *)(wl + ks * 32);
-      bf16x8 a_hi = *(const bf16x8 *)(wh + ks * 32);
+      bf16x8 a_lo = *(const bf16x8 *)(wl + rd[ks]);
+      bf16x8 a_hi = *(const bf16x8 *)(wh + rd[ks]);
 #pragma unroll
       for (int t = 0; t < NTB; ++t) {
-        bf16x8 b = *(const bf16x8 *)(xb + t * 32 * LDS_ROW + ks * 32);
+        bf16x8 b = *(const bf16x8 *)(xb + t * 32 * ROW + rd[ks]);
         acc[0][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_lo, b, acc[0][t], 0, 0, 0);
         acc[1][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi, b, acc[1][t], 0, 0, 0);
       }
     }
-    if (kt + 1 < nk) store_lds(buf ^ 1);
-    __syncthreads();
+    // the next stage's loads must have landed before anyone reads them; the barrier also retires this stage
+    PC_WAIT_VMCNT0();
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
   }
 
   // ---- epilogue: RoPE at position L_pre[b] + i on fp32, one rounding to bf16, head-major stores
@@ -117,7 +136,16 @@ __global__ __launch_bounds__(256) void qkv_rope_kernel(const __bf16 *__restrict_
     const int b = m / t_fresh, i = m - b * t_fresh;
     const int pos = table[(size_t)b * tbl_stride + 1] + i;
     __bf16 *row = dst + (((size_t)b * n_heads + hh) * t_fresh + i) * D;
-    const float2 *cs = rope + (size_t)pos * (D / 2);
+    // all sixteen (cos, sin) pairs of this lane's token first (eight 16-byte loads in flight), then the math
+    float4 cs[4][2];
+    if (rotate) {
+      const float4 *csp = (const float4 *)(rope + (size_t)pos * (D / 2) + m_base + g * 4);
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        cs[q4][0] = csp[q4 * 4];      // pairs mm, mm+1
+        cs[q4][1] = csp[q4 * 4 + 1];  // pairs mm+2, mm+3
+      }
+    }
 #pragma unroll
     for (int q4 = 0; q4 < 4; ++q4) {
       const int mm = m_base + q4 * 8 + g * 4;  // first of 4 consecutive pair indices
@@ -126,9 +154,10 @@ __global__ __launch_bounds__(256) void qkv_rope_kernel(const __bf16 *__restrict_
       for (int e = 0; e < 4; ++e) {
         float a = acc[0][t][q4 * 4 + e], c = acc[1][t][q4 * 4 + e];
         if (rotate) {
-          float2 w = cs[mm + e];
-          lo[e] = a * w.x - c * w.y;
-          hi[e] = c * w.x + a * w.y;
+          const float4 w4 = cs[q4][e >> 1];
+          const float wc = (e & 1) ? w4.z : w4.x, ws = (e & 1) ? w4.w : w4.y;
+          lo[e] = a * wc - c * ws;
+          hi[e] = c * wc + a * ws;
         } else {
           lo[e] = a;
           hi[e] = c;
@@ -153,6 +182,8 @@ pc_status launch_qkv_rope(percache_ctx *ctx, const __bf16 *x, const __bf16 *w, i
   const int M = batch * t_fresh;
   const int F = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
   if (F % BF) return fail(ctx, PC_ESHAPE, "(Hq + 2 Hkv) * D = %d must be a multiple of %d", F, BF);
+  if ((long)F * c.hidden >= (1L << 31) || (long)M * c.hidden >= (1L << 31))
+    return fail(ctx, PC_ESHAPE, "operand larger than 2^31 elements");
   const float2 *rope = (const float2 *)ctx->rope;
   const bool big = M > 64 * 3;  // 128-token tiles once there are enough rows to fill them
   dim3 grid(F / BF, big ? (M + 127) / 128 : (M + 63) / 64);
