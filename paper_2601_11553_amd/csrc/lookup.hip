@@ -11,7 +11,7 @@
 namespace {
 using pc::f16x8;
 using pc::f32x4;
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+using pc::u32x4;
 
 struct Best {
   float s;
@@ -28,11 +28,11 @@ __global__ __launch_bounds__(256) void bank_put_kernel(const _Float16 *__restric
   const int lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= n) return;
-  const uint4 *s = (const uint4 *)(src + (size_t)row * d);
-  uint4 *t = (uint4 *)(dst + (size_t)row * d);
+  const u32x4 *s = (const u32x4 *)(src + (size_t)row * d);
+  u32x4 *t = (u32x4 *)(dst + (size_t)row * d);
   float ss = 0.f;
   for (int v = lane; v < d / 8; v += 64) {
-    uint4 raw = s[v];
+    u32x4 raw = s[v];
     t[v] = raw;
     f16x8 h = __builtin_bit_cast(f16x8, raw);
 #pragma unroll
@@ -44,42 +44,47 @@ __global__ __launch_bounds__(256) void bank_put_kernel(const _Float16 *__restric
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Streaming pass.  Workgroup = 4 wavefronts; workgroup b owns a contiguous range of 16-row blocks, its
-// wavefronts take them round-robin.  For one row block a wavefront issues, per step, one 16-byte load
-// per lane: lane (r = lane%16, g = lane/16) reads elements [32 step + 8 g, +8) of row r, i.e. the four
-// lanes of a row cover 64 contiguous bytes and consecutive steps walk along the row.  The probes of the
-// pass (NPB blocks of 16, zero padded) sit in LDS and are the B operand.
+// Streaming pass.  Workgroup = 4 wavefronts; workgroup b owns a contiguous range of 16-row blocks (at most
+// kMaxBlocksPerWg), its wavefronts take them round-robin.  For one row block a wavefront issues, per step,
+// one 16-byte load per lane: lane (r = lane%16, g = lane/16) reads elements [32 step + 8 g, +8) of row r,
+// i.e. the four lanes of a row cover 64 contiguous bytes and consecutive steps walk along the row.  Loads
+// are grouped in chunks of CS steps; the chunk after the one being multiplied is always in flight (two
+// register sets, all indices compile-time, so the only waits are partial vmcnt waits).  The probes of the
+// pass (NPB blocks of 16, zero padded) and the inverse norms of the workgroup's rows sit in LDS.
 // Result lane layout of the 16x16 product: lane holds probe (lane%16), rows 4*(lane/16) + 0..3.
 // ---------------------------------------------------------------------------------------------------
-constexpr int kChunk = 8;  // k-steps whose loads are in flight together (8 x 16 B per lane)
+constexpr int kMaxBlocksPerWg = 256;  // 4096 rows: bounds the LDS copy of the inverse norms (16 KB)
 
-template <int NPB>
+template <int NPB, int CS>
 __global__ __launch_bounds__(256) void lookup_stream_kernel(const _Float16 *__restrict__ bank,
                                                             const float *__restrict__ inv_norm, int N, int d,
                                                             const _Float16 *__restrict__ probes, int n_probes,
-                                                            Best *__restrict__ partial) {
+                                                            int per_wg, Best *__restrict__ partial) {
   extern __shared__ __align__(16) char smem[];
   const int row_bytes = d * 2 + 64;  // padded probe row in LDS
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r16 = lane & 15, g = lane >> 4;
 
-  // stage probes (zero rows beyond n_probes)
+  const int n_blocks = (N + 15) / 16;
+  const int rb_begin = blockIdx.x * per_wg;
+  const int rb_end = min(n_blocks, rb_begin + per_wg);
+
+  // stage probes (zero rows beyond n_probes) and this workgroup's inverse norms (zero beyond N)
   const int vec_per_row = d / 8;
   for (int v = tid; v < NPB * 16 * vec_per_row; v += 256) {
     int p = v / vec_per_row, c = v - p * vec_per_row;
-    uint4 val = make_uint4(0, 0, 0, 0);
-    if (p < n_probes) val = ((const uint4 *)(probes + (size_t)p * d))[c];
-    *(uint4 *)(smem + (size_t)p * row_bytes + c * 16) = val;
+    u32x4 val = {0, 0, 0, 0};
+    if (p < n_probes) val = ((const u32x4 *)(probes + (size_t)p * d))[c];
+    *(u32x4 *)(smem + (size_t)p * row_bytes + c * 16) = val;
+  }
+  float *inv_lds = (float *)(smem + (size_t)NPB * 16 * row_bytes);
+  for (int r = tid; r < per_wg * 16; r += 256) {
+    int row = rb_begin * 16 + r;
+    inv_lds[r] = row < N ? inv_norm[row] : 0.f;
   }
   __syncthreads();
 
-  const int n_blocks = (N + 15) / 16;
-  const int per_wg = (n_blocks + gridDim.x - 1) / gridDim.x;
-  const int rb_begin = blockIdx.x * per_wg;
-  const int rb_end = min(n_blocks, rb_begin + per_wg);
-  const int steps = d / 32;
-  const int chunks = steps / kChunk > 0 ? steps / kChunk : 1;
-  const int chunk_steps = steps < kChunk ? steps : kChunk;  // d = 64..224 -> fewer steps (d % 256 == 0 otherwise)
+  const int chunks = d / (32 * CS);
 
   float best_s[NPB][4];
   int best_i[NPB][4];
@@ -88,45 +93,41 @@ __global__ __launch_bounds__(256) void lookup_stream_kernel(const _Float16 *__re
 #pragma unroll
     for (int r = 0; r < 4; ++r) { best_s[pb][r] = -INFINITY; best_i[pb][r] = INT_MAX; }
 
-  u32x4 a0[kChunk], a1[kChunk];
-  auto issue = [&](int rb, int chunk, u32x4 (&dst)[kChunk]) __attribute__((always_inline)) {
+  u32x4 a0[CS], a1[CS];
+  auto issue = [&](int rb, int chunk, u32x4 (&dst)[CS]) __attribute__((always_inline)) {
     int row = min(rb * 16 + r16, N - 1);
-    const u32x4 *src = (const u32x4 *)(bank + (size_t)row * d + chunk * (kChunk * 32) + g * 8);
+    const u32x4 *src = (const u32x4 *)(bank + (size_t)row * d + chunk * (CS * 32) + g * 8);
 #pragma unroll
-    for (int s = 0; s < kChunk; ++s)
-      if (s < chunk_steps) dst[s] = __builtin_nontemporal_load(src + s * 4);
+    for (int s = 0; s < CS; ++s) dst[s] = __builtin_nontemporal_load(src + s * 4);
   };
   f32x4 acc[NPB];
   auto clear = [&]() __attribute__((always_inline)) {
 #pragma unroll
     for (int pb = 0; pb < NPB; ++pb) acc[pb] = f32x4{0.f, 0.f, 0.f, 0.f};
   };
-  auto compute = [&](int chunk, const u32x4 (&src)[kChunk]) __attribute__((always_inline)) {
-    const char *pbase = smem + (size_t)r16 * row_bytes + (chunk * kChunk * 32 + g * 8) * 2;
+  auto compute = [&](int chunk, const u32x4 (&src)[CS]) __attribute__((always_inline)) {
+    const char *pbase = smem + (size_t)r16 * row_bytes + (chunk * CS * 32 + g * 8) * 2;
 #pragma unroll
-    for (int s = 0; s < kChunk; ++s) {
-      if (s < chunk_steps) {
-        f16x8 av = __builtin_bit_cast(f16x8, src[s]);
+    for (int s = 0; s < CS; ++s) {
+      f16x8 av = __builtin_bit_cast(f16x8, src[s]);
 #pragma unroll
-        for (int pb = 0; pb < NPB; ++pb) {
-          f16x8 bv = *(const f16x8 *)(pbase + (size_t)pb * 16 * row_bytes + s * 64);
-          acc[pb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, acc[pb], 0, 0, 0);
-        }
+      for (int pb = 0; pb < NPB; ++pb) {
+        f16x8 bv = *(const f16x8 *)(pbase + (size_t)pb * 16 * row_bytes + s * 64);
+        acc[pb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, acc[pb], 0, 0, 0);
       }
     }
   };
   // scale by the rows' inverse norms and keep the running best (strict >: the lowest row wins ties)
   auto epilogue = [&](int rb) __attribute__((always_inline)) {
+    const f32x4 inv4 = *(const f32x4 *)(inv_lds + (rb - rb_begin) * 16 + g * 4);
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      int row = rb * 16 + g * 4 + r;
-      if (row < N) {
-        float inv = inv_norm[row];
+      const int row = rb * 16 + g * 4 + r;
+      const bool ok = row < N;
 #pragma unroll
-        for (int pb = 0; pb < NPB; ++pb) {
-          float s = acc[pb][r] * inv;
-          if (s > best_s[pb][r]) { best_s[pb][r] = s; best_i[pb][r] = row; }
-        }
+      for (int pb = 0; pb < NPB; ++pb) {
+        float s = acc[pb][r] * inv4[r];
+        if (ok && s > best_s[pb][r]) { best_s[pb][r] = s; best_i[pb][r] = row; }
       }
     }
   };
@@ -134,23 +135,29 @@ __global__ __launch_bounds__(256) void lookup_stream_kernel(const _Float16 *__re
     if (++c_ == chunks) { c_ = 0; rb_ += 4; }
   };
 
-  // flat software pipeline over (row block, chunk): one chunk of loads is always in flight ahead
+  // flat software pipeline over (row block, chunk): one chunk of loads is always in flight ahead.  The
+  // prefetch is issued unconditionally (past the end it re-reads the wavefront's last block and is never
+  // used), so the loop body is straight-line code and every wait is an exact partial vmcnt wait.
   int rb = rb_begin + wave, c = 0;
   int prb = rb, pch = 0;
-  if (prb < rb_end) issue(prb, pch, a0);
-  clear();
-  while (rb < rb_end) {
-    advance(prb, pch);
-    if (prb < rb_end) issue(prb, pch, a1);
-    compute(c, a0);
-    if (c == chunks - 1) { epilogue(rb); clear(); }
-    advance(rb, c);
-    if (rb >= rb_end) break;
-    advance(prb, pch);
-    if (prb < rb_end) issue(prb, pch, a0);
-    compute(c, a1);
-    if (c == chunks - 1) { epilogue(rb); clear(); }
-    advance(rb, c);
+  const int rb_last = rb_end - 1;
+  if (rb < rb_end) {
+    issue(prb, pch, a0);
+    clear();
+    while (true) {
+      advance(prb, pch);
+      issue(min(prb, rb_last), pch, a1);
+      compute(c, a0);
+      if (c == chunks - 1) { epilogue(rb); clear(); }
+      advance(rb, c);
+      if (rb >= rb_end) break;
+      advance(prb, pch);
+      issue(min(prb, rb_last), pch, a0);
+      compute(c, a1);
+      if (c == chunks - 1) { epilogue(rb); clear(); }
+      advance(rb, c);
+      if (rb >= rb_end) break;
+    }
   }
 
   // lane-local over r, then the four lanes that share a probe, then the four wavefronts
@@ -193,7 +200,7 @@ __global__ __launch_bounds__(64) void lookup_finalize_kernel(const Best *__restr
                                                              float *__restrict__ sim_out, uint8_t *__restrict__ hit_out) {
   const int p = blockIdx.x, lane = threadIdx.x;
   float ss = 0.f;
-  const uint4 *src = (const uint4 *)(probes + (size_t)p * d);
+  const u32x4 *src = (const u32x4 *)(probes + (size_t)p * d);
   for (int v = lane; v < d / 8; v += 64) {
     f16x8 h = __builtin_bit_cast(f16x8, src[v]);
 #pragma unroll
@@ -227,14 +234,40 @@ __global__ void lookup_empty_kernel(int n, int32_t *idx_out, float *sim_out, uin
 }
 
 constexpr int kPassProbes = 64;
-int stream_grid(const percache_ctx *ctx, int npb, int N) {
-  int per_cu = npb >= 4 ? 1 : (npb == 2 ? 2 : 3);
-  int grid = ctx->n_cu * per_cu;
-  int n_blocks = (N + 15) / 16;
-  int need = (n_blocks + 3) / 4;
-  return grid < need ? grid : (need > 0 ? need : 1);
+
+// Workgroups of one pass and 16-row blocks per workgroup.
+void stream_shape(const percache_ctx *ctx, int npb, int N, int &grid, int &per_wg) {
+  const int per_cu = npb >= 4 ? 1 : (npb == 2 ? 2 : 4);  // bounded by the LDS copy of the probes
+  const int n_blocks = (N + 15) / 16;
+  grid = ctx->n_cu * per_cu;
+  const int need = (n_blocks + 3) / 4;  // at least one block per wavefront
+  if (grid > need) grid = need > 0 ? need : 1;
+  per_wg = (n_blocks + grid - 1) / grid;
+  if (per_wg > kMaxBlocksPerWg) {
+    per_wg = kMaxBlocksPerWg;
+    grid = (n_blocks + per_wg - 1) / per_wg;
+  }
 }
-int max_stream_grid(const percache_ctx *ctx) { return ctx->n_cu * 3; }
+int max_stream_grid(const percache_ctx *ctx) {
+  int by_rows = (ctx->cfg.bank_capacity / 16 + kMaxBlocksPerWg) / kMaxBlocksPerWg;
+  int by_cu = ctx->n_cu * 4;
+  return by_rows > by_cu ? by_rows : by_cu;
+}
+
+template <int NPB, int CS>
+pc_status launch_stream(percache_ctx *ctx, int grid, int per_wg, size_t lds, hipStream_t st, int N, int d,
+                        const _Float16 *pp, int np, Best *partial) {
+  if (lds > 64 * 1024) {
+    static bool big_lds_set = false;  // dynamic LDS above 64 KB must be opted into once per kernel
+    if (!big_lds_set) {
+      PC_HIP(ctx, hipFuncSetAttribute((const void *)lookup_stream_kernel<NPB, CS>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+      big_lds_set = true;
+    }
+  }
+  hipLaunchKernelGGL((lookup_stream_kernel<NPB, CS>), dim3(grid), dim3(256), lds, st, ctx->bank, ctx->bank_inv, N, d, pp, np,
+                     per_wg, partial);
+  return PC_OK;
+}
 
 }  // namespace
 
@@ -287,24 +320,21 @@ pc_status percache_lookup(percache_ctx *ctx, const void *probes_dev, int32_t n_p
   for (int p0 = 0; p0 < n_probes; p0 += kPassProbes) {
     int np = n_probes - p0 < kPassProbes ? n_probes - p0 : kPassProbes;
     int npb = np <= 16 ? 1 : (np <= 32 ? 2 : 4);
-    int grid = stream_grid(ctx, npb, N);
-    size_t lds = (size_t)npb * 16 * (d * 2 + 64);
-    if (lds < 4 * (size_t)npb * 16 * sizeof(Best)) lds = 4 * (size_t)npb * 16 * sizeof(Best);
+    int grid, per_wg;
+    stream_shape(ctx, npb, N, grid, per_wg);
+    size_t lds = (size_t)npb * 16 * (d * 2 + 64) + (size_t)per_wg * 16 * sizeof(float);
     const _Float16 *pp = probes + (size_t)p0 * d;
-    if (npb == 4) {
-      static bool big_lds_set = false;  // dynamic LDS above 64 KB must be opted into once per kernel
-      if (!big_lds_set) {
-        PC_HIP(ctx, hipFuncSetAttribute((const void *)lookup_stream_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-        big_lds_set = true;
-      }
-    }
     pc::prof_begin(ctx, PC_KERNEL_LOOKUP, st);
-    if (npb == 1)
-      hipLaunchKernelGGL(lookup_stream_kernel<1>, dim3(grid), dim3(256), lds, st, ctx->bank, ctx->bank_inv, N, d, pp, np, partial);
-    else if (npb == 2)
-      hipLaunchKernelGGL(lookup_stream_kernel<2>, dim3(grid), dim3(256), lds, st, ctx->bank, ctx->bank_inv, N, d, pp, np, partial);
-    else
-      hipLaunchKernelGGL(lookup_stream_kernel<4>, dim3(grid), dim3(256), lds, st, ctx->bank, ctx->bank_inv, N, d, pp, np, partial);
+    pc_status ls;
+#define PC_STREAM(NPB_)                                                                                        \
+  (d == 64    ? launch_stream<NPB_, 2>(ctx, grid, per_wg, lds, st, N, d, pp, np, partial)                       \
+   : d == 128 ? launch_stream<NPB_, 4>(ctx, grid, per_wg, lds, st, N, d, pp, np, partial)                       \
+              : launch_stream<NPB_, 8>(ctx, grid, per_wg, lds, st, N, d, pp, np, partial))
+    if (npb == 1) ls = PC_STREAM(1);
+    else if (npb == 2) ls = PC_STREAM(2);
+    else ls = PC_STREAM(4);
+#undef PC_STREAM
+    if (ls != PC_OK) return ls;
     pc::prof_end(ctx, PC_KERNEL_LOOKUP, st);
     PC_HIP(ctx, hipGetLastError());
     hipLaunchKernelGGL(lookup_finalize_kernel, dim3(np), dim3(64), 0, st, partial, grid, npb * 16, pp, d, tau,
