@@ -127,9 +127,9 @@ def main():
         return (time.perf_counter() - a) / iters
 
     look = {}
-    for p in (1, 8, 64, 1024):
+    for p in (1, 8, 32, 1024):
         t = time_lookup(probes_all[:p].contiguous())
-        passes = (p + 63) // 64
+        passes = (p + 31) // 32
         look[f"P{p}"] = {"ms": round(t * 1e3, 4), "lookups_per_s": round(p / t, 1),
                          "bank_GBps": round(bank_bytes * passes / t / 1e9, 1)}
 
@@ -162,21 +162,34 @@ def main():
         a = time.perf_counter()
         Qo, Ko, Vo = oracle.qkv_rope(w.X[0], w.Wqkv, w.n_q_heads, w.n_kv_heads, w.head_dim, int(w.l_pre[0]), w.rope_theta)
         t_proj = time.perf_counter() - a
-        rows = np.arange(0, T, T // 16)[:16]
-        si = np.repeat(rows, w.n_q_heads)
-        sh = np.tile(np.arange(w.n_q_heads), len(rows))
-        a = time.perf_counter()
-        oracle.attention_reuse(Qo, Ko, Vo, sk, sv, ids, w.used_len[0], samples=(si, sh))
-        t_attn = time.perf_counter() - a
-        a = time.perf_counter()
-        oracle.lookup(lw.bank, lw.probes[:4], lw.tau)
-        t_look = time.perf_counter() - a
-        per_token = t_proj / T + t_attn / len(rows) + (t_look / 4) / T
+
+        def attn_rows(n):
+            rows = np.unique(np.linspace(0, T - 1, n).astype(np.int64))
+            si = np.repeat(rows, w.n_q_heads)
+            sh = np.tile(np.arange(w.n_q_heads), len(rows))
+            a = time.perf_counter()
+            oracle.attention_reuse(Qo, Ko, Vo, sk, sv, ids, w.used_len[0], samples=(si, sh))
+            return time.perf_counter() - a, len(rows)
+
+        def look_probes(n):
+            a = time.perf_counter()
+            oracle.lookup(lw.bank, lw.probes[:n], lw.tau)
+            return time.perf_counter() - a
+
+        # a short pilot sizes the sample to about 10 s of attention and 5 s of lookup on this host
+        t_pilot, n_pilot = attn_rows(4)
+        n_rows = int(min(T, max(8, 10.0 / max(t_pilot / n_pilot, 1e-6))))
+        t_attn, n_rows = attn_rows(n_rows)
+        t_pilot = look_probes(2)
+        n_look_cpu = int(min(lw.probes.shape[0], max(4, 5.0 / max(t_pilot / 2, 1e-6))))
+        t_look = look_probes(n_look_cpu)
+        per_token = t_proj / T + t_attn / n_rows + (t_look / n_look_cpu) / T
         out["cpu_baseline"] = {
             "value": round(1.0 / per_token, 2), "unit": "tokens/s", "cores": nthreads, "kind": "oracle",
             "sample": f"query 0 of the same workload: projection+RoPE of all {T} fresh tokens ({t_proj:.2f} s), attention of "
-                      f"{len(rows)} token rows x {w.n_q_heads} heads over {int(w.l_pre[0])} cached + fresh keys ({t_attn:.2f} s), "
-                      f"lookup of 4 probes against the {N}-row bank ({t_look:.2f} s); per-token times summed",
+                      f"{n_rows} token rows x {w.n_q_heads} heads over {int(w.l_pre[0])} cached + fresh keys ({t_attn:.2f} s), "
+                      f"lookup of {n_look_cpu} probes against the {N}-row bank ({t_look:.2f} s); per-token times summed "
+                      f"(one lookup per query of {T} fresh tokens)",
         }
     print(json.dumps(out))
     pc.close()

@@ -1,7 +1,7 @@
 // Query-level match (Sec. 4.2.1): cosine top-1 of probe embeddings against every row of the QA bank's
 // embedding matrix, and the hit flag against tau_query.
 //
-// The bank is streamed from HBM exactly once per pass of up to 64 probes.  The dot products run on the
+// The bank is streamed from HBM exactly once per pass of up to 32 probes.  The dot products run on the
 // fp16 matrix cores (16x16x32, fp32 accumulate) only because they perform the cross-lane reduction for
 // free; the kernel is bound by the HBM stream of the bank, not by arithmetic.
 #include <climits>
@@ -45,22 +45,33 @@ __global__ __launch_bounds__(256) void bank_put_kernel(const _Float16 *__restric
 
 // ---------------------------------------------------------------------------------------------------
 // Streaming pass.  Workgroup = 4 wavefronts; workgroup b owns a contiguous range of 16-row blocks (at most
-// kMaxBlocksPerWg), its wavefronts take them round-robin.  For one row block a wavefront issues, per step,
-// one 16-byte load per lane: lane (r = lane%16, g = lane/16) reads elements [32 step + 8 g, +8) of row r,
-// i.e. the four lanes of a row cover 64 contiguous bytes and consecutive steps walk along the row.  Loads
-// are grouped in chunks of CS steps; the chunk after the one being multiplied is always in flight (two
-// register sets, all indices compile-time, so the only waits are partial vmcnt waits).  The probes of the
-// pass (NPB blocks of 16, zero padded) and the inverse norms of the workgroup's rows sit in LDS.
+// kMaxBlocksPerWg), its wavefronts take them round-robin.  Each wavefront streams its row blocks through a
+// PRIVATE ring of LDS stages with direct global->LDS loads: one stage holds 16 rows x CHB bytes (a chunk of
+// CHB/2 elements per row), one load instruction brings 1 KB that is contiguous in memory (whole 128-byte
+// lines, requested once), and NSTG-1 chunks are always in flight per wavefront.  No workgroup barrier is
+// needed in the loop: a ring is written and read by one wavefront only.  The 16-byte chunks of a row are
+// XOR-swizzled inside the stage so that the MFMA operand reads (lane (r = lane%16, g = lane/16) reads
+// elements [32 step + 8 g, +8) of row r) are bank-conflict free.  The probes of the pass (NPB blocks of 16,
+// zero padded) and the inverse norms of the workgroup's rows sit in LDS too.
 // Result lane layout of the 16x16 product: lane holds probe (lane%16), rows 4*(lane/16) + 0..3.
 // ---------------------------------------------------------------------------------------------------
-constexpr int kMaxBlocksPerWg = 256;  // 4096 rows: bounds the LDS copy of the inverse norms (16 KB)
+constexpr int kMaxBlocksPerWg = 128;  // 2048 rows: bounds the LDS copy of the inverse norms (8 KB)
+#define PC_LOOKUP_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xf) | (7 << 4) | (15 << 8) | ((((n) >> 4) & 3) << 14))
 
-template <int NPB, int CS>
+template <int CHB>
+__device__ __forceinline__ int row_swz(int row) { return CHB >= 256 ? (row & 15) : ((row >> 1) & 7); }
+
+template <int NPB, int CHB, int NSTG>
 __global__ __launch_bounds__(256) void lookup_stream_kernel(const _Float16 *__restrict__ bank,
                                                             const float *__restrict__ inv_norm, int N, int d,
                                                             const _Float16 *__restrict__ probes, int n_probes,
-                                                            int per_wg, Best *__restrict__ partial) {
+                                                            int per_wg, int ring_off, Best *__restrict__ partial) {
   extern __shared__ __align__(16) char smem[];
+  constexpr int CS = CHB / 64;           // MFMA k-steps (32 elements) per chunk
+  constexpr int STG = 16 * CHB;          // bytes per stage
+  constexpr int IPS = STG / 1024;        // load instructions per stage
+  constexpr int LPR = CHB / 16;          // lanes (16-byte chunks) per row
+  constexpr int AHEAD = NSTG - 1;
   const int row_bytes = d * 2 + 64;  // padded probe row in LDS
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r16 = lane & 15, g = lane >> 4;
@@ -84,7 +95,8 @@ __global__ __launch_bounds__(256) void lookup_stream_kernel(const _Float16 *__re
   }
   __syncthreads();
 
-  const int chunks = d / (32 * CS);
+  const int chunks = d * 2 / CHB;
+  char *ring = smem + ring_off + wave * (NSTG * STG);
 
   float best_s[NPB][4];
   int best_i[NPB][4];
@@ -93,23 +105,39 @@ __global__ __launch_bounds__(256) void lookup_stream_kernel(const _Float16 *__re
 #pragma unroll
     for (int r = 0; r < 4; ++r) { best_s[pb][r] = -INFINITY; best_i[pb][r] = INT_MAX; }
 
-  u32x4 a0[CS], a1[CS];
-  auto issue = [&](int rb, int chunk, u32x4 (&dst)[CS]) __attribute__((always_inline)) {
-    int row = min(rb * 16 + r16, N - 1);
-    const u32x4 *src = (const u32x4 *)(bank + (size_t)row * d + chunk * (CS * 32) + g * 8);
+  // load instruction i of a stage: lane lands at stage byte 1024 i + 16 lane = (row, physical chunk)
+  int ld_row[IPS], ld_col[IPS];
 #pragma unroll
-    for (int s = 0; s < CS; ++s) dst[s] = __builtin_nontemporal_load(src + s * 4);
+  for (int i = 0; i < IPS; ++i) {
+    const int row = i * (1024 / CHB) + lane / LPR, pc = lane % LPR;
+    ld_row[i] = row;
+    ld_col[i] = (pc ^ row_swz<CHB>(row)) * 8;  // element offset of the logical chunk inside the row's chunk
+  }
+  auto issue = [&](int rb, int chunk, int st) __attribute__((always_inline)) {
+    const _Float16 *base = bank + chunk * (CHB / 2);
+#pragma unroll
+    for (int i = 0; i < IPS; ++i) {
+      const int row = min(rb * 16 + ld_row[i], N - 1);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(base + (size_t)row * d + ld_col[i]),
+                                       (__attribute__((address_space(3))) void *)(ring + st * STG + i * 1024), 16, 0, 0);
+    }
   };
+  // swizzled byte offsets of this lane's operand reads inside a stage
+  int rd_off[CS];
+#pragma unroll
+  for (int s = 0; s < CS; ++s) rd_off[s] = r16 * CHB + (((4 * s + g) ^ row_swz<CHB>(r16)) * 16);
+
   f32x4 acc[NPB];
   auto clear = [&]() __attribute__((always_inline)) {
 #pragma unroll
     for (int pb = 0; pb < NPB; ++pb) acc[pb] = f32x4{0.f, 0.f, 0.f, 0.f};
   };
-  auto compute = [&](int chunk, const u32x4 (&src)[CS]) __attribute__((always_inline)) {
-    const char *pbase = smem + (size_t)r16 * row_bytes + (chunk * CS * 32 + g * 8) * 2;
+  auto compute = [&](int chunk, int st) __attribute__((always_inline)) {
+    const char *pbase = smem + (size_t)r16 * row_bytes + (chunk * (CHB / 2) + g * 8) * 2;
+    const char *abase = ring + st * STG;
 #pragma unroll
     for (int s = 0; s < CS; ++s) {
-      f16x8 av = __builtin_bit_cast(f16x8, src[s]);
+      f16x8 av = *(const f16x8 *)(abase + rd_off[s]);
 #pragma unroll
       for (int pb = 0; pb < NPB; ++pb) {
         f16x8 bv = *(const f16x8 *)(pbase + (size_t)pb * 16 * row_bytes + s * 64);
@@ -135,29 +163,34 @@ __global__ __launch_bounds__(256) void lookup_stream_kernel(const _Float16 *__re
     if (++c_ == chunks) { c_ = 0; rb_ += 4; }
   };
 
-  // flat software pipeline over (row block, chunk): one chunk of loads is always in flight ahead.  The
-  // prefetch is issued unconditionally (past the end it re-reads the wavefront's last block and is never
-  // used), so the loop body is straight-line code and every wait is an exact partial vmcnt wait.
+  // flat pipeline over this wavefront's (row block, chunk) items.  Loads are issued unconditionally (past the
+  // end they re-read the last block into a stage nobody will read), so exactly AHEAD items are outstanding
+  // behind the one about to be multiplied and a partial vmcnt wait is exact.
   int rb = rb_begin + wave, c = 0;
   int prb = rb, pch = 0;
   const int rb_last = rb_end - 1;
   if (rb < rb_end) {
-    issue(prb, pch, a0);
+    int st = 0, ist = 0;
+#pragma unroll
+    for (int k = 0; k < AHEAD; ++k) {
+      issue(min(prb, rb_last), pch, ist);
+      advance(prb, pch);
+      ist = ist + 1 == NSTG ? 0 : ist + 1;
+    }
     clear();
     while (true) {
+      issue(min(prb, rb_last), pch, ist);  // overwrites the stage multiplied in the previous iteration
       advance(prb, pch);
-      issue(min(prb, rb_last), pch, a1);
-      compute(c, a0);
+      ist = ist + 1 == NSTG ? 0 : ist + 1;
+      PC_LOOKUP_WAIT_VMCNT(AHEAD * IPS);
+      asm volatile("" ::: "memory");
+      compute(c, st);
       if (c == chunks - 1) { epilogue(rb); clear(); }
       advance(rb, c);
-      if (rb >= rb_end) break;
-      advance(prb, pch);
-      issue(min(prb, rb_last), pch, a0);
-      compute(c, a1);
-      if (c == chunks - 1) { epilogue(rb); clear(); }
-      advance(rb, c);
+      st = st + 1 == NSTG ? 0 : st + 1;
       if (rb >= rb_end) break;
     }
+    PC_LOOKUP_WAIT_VMCNT(0);
   }
 
   // lane-local over r, then the four lanes that share a probe, then the four wavefronts
@@ -233,39 +266,47 @@ __global__ void lookup_empty_kernel(int n, int32_t *idx_out, float *sim_out, uin
   if (p < n) { idx_out[p] = -1; sim_out[p] = -INFINITY; hit_out[p] = 0; }
 }
 
-constexpr int kPassProbes = 64;
+constexpr int kPassProbes = 32;
 
-// Workgroups of one pass and 16-row blocks per workgroup.
-void stream_shape(const percache_ctx *ctx, int npb, int N, int &grid, int &per_wg) {
-  const int per_cu = npb >= 4 ? 1 : (npb == 2 ? 2 : 4);  // bounded by the LDS copy of the probes
+// LDS bytes of one workgroup: probes, inverse norms, then (1 KB aligned) the four wavefront rings.
+struct StreamShape {
+  int grid, per_wg, nstg, chb, ring_off;
+  size_t lds;
+};
+StreamShape stream_shape(const percache_ctx *ctx, int npb, int N) {
+  const int d = ctx->cfg.emb_dim;
+  StreamShape s;
+  s.chb = d * 2 >= 512 ? 512 : d * 2;
+  s.nstg = npb == 1 ? 3 : 2;
   const int n_blocks = (N + 15) / 16;
-  grid = ctx->n_cu * per_cu;
+  s.grid = ctx->n_cu;  // the rings allow one workgroup per CU
   const int need = (n_blocks + 3) / 4;  // at least one block per wavefront
-  if (grid > need) grid = need > 0 ? need : 1;
-  per_wg = (n_blocks + grid - 1) / grid;
-  if (per_wg > kMaxBlocksPerWg) {
-    per_wg = kMaxBlocksPerWg;
-    grid = (n_blocks + per_wg - 1) / per_wg;
+  if (s.grid > need) s.grid = need > 0 ? need : 1;
+  s.per_wg = (n_blocks + s.grid - 1) / s.grid;
+  if (s.per_wg > kMaxBlocksPerWg) {
+    s.per_wg = kMaxBlocksPerWg;
+    s.grid = (n_blocks + s.per_wg - 1) / s.per_wg;
   }
+  size_t head = (size_t)npb * 16 * (d * 2 + 64) + (size_t)s.per_wg * 16 * sizeof(float);
+  s.ring_off = (int)((head + 1023) / 1024 * 1024);
+  s.lds = s.ring_off + (size_t)4 * s.nstg * 16 * s.chb;
+  return s;
 }
 int max_stream_grid(const percache_ctx *ctx) {
   int by_rows = (ctx->cfg.bank_capacity / 16 + kMaxBlocksPerWg) / kMaxBlocksPerWg;
-  int by_cu = ctx->n_cu * 4;
-  return by_rows > by_cu ? by_rows : by_cu;
+  return by_rows > ctx->n_cu ? by_rows : ctx->n_cu;
 }
 
-template <int NPB, int CS>
-pc_status launch_stream(percache_ctx *ctx, int grid, int per_wg, size_t lds, hipStream_t st, int N, int d,
-                        const _Float16 *pp, int np, Best *partial) {
-  if (lds > 64 * 1024) {
-    static bool big_lds_set = false;  // dynamic LDS above 64 KB must be opted into once per kernel
-    if (!big_lds_set) {
-      PC_HIP(ctx, hipFuncSetAttribute((const void *)lookup_stream_kernel<NPB, CS>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-      big_lds_set = true;
-    }
+template <int NPB, int CHB, int NSTG>
+pc_status launch_stream(percache_ctx *ctx, const StreamShape &sh, hipStream_t st, int N, int d, const _Float16 *pp, int np,
+                        Best *partial) {
+  static bool big_lds_set = false;  // dynamic LDS above 64 KB must be opted into once per kernel
+  if (!big_lds_set) {
+    PC_HIP(ctx, hipFuncSetAttribute((const void *)lookup_stream_kernel<NPB, CHB, NSTG>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+    big_lds_set = true;
   }
-  hipLaunchKernelGGL((lookup_stream_kernel<NPB, CS>), dim3(grid), dim3(256), lds, st, ctx->bank, ctx->bank_inv, N, d, pp, np,
-                     per_wg, partial);
+  hipLaunchKernelGGL((lookup_stream_kernel<NPB, CHB, NSTG>), dim3(sh.grid), dim3(256), sh.lds, st, ctx->bank, ctx->bank_inv, N, d,
+                     pp, np, sh.per_wg, sh.ring_off, partial);
   return PC_OK;
 }
 
@@ -319,21 +360,21 @@ pc_status percache_lookup(percache_ctx *ctx, const void *probes_dev, int32_t n_p
   const _Float16 *probes = (const _Float16 *)probes_dev;
   for (int p0 = 0; p0 < n_probes; p0 += kPassProbes) {
     int np = n_probes - p0 < kPassProbes ? n_probes - p0 : kPassProbes;
-    int npb = np <= 16 ? 1 : (np <= 32 ? 2 : 4);
-    int grid, per_wg;
-    stream_shape(ctx, npb, N, grid, per_wg);
-    size_t lds = (size_t)npb * 16 * (d * 2 + 64) + (size_t)per_wg * 16 * sizeof(float);
+    int npb = np <= 16 ? 1 : 2;
+    StreamShape sh = stream_shape(ctx, npb, N);
+    if (sh.lds > 160 * 1024) return pc::fail(ctx, PC_ESHAPE, "emb_dim %d needs %zu bytes of LDS per workgroup", d, sh.lds);
+    const int grid = sh.grid;
     const _Float16 *pp = probes + (size_t)p0 * d;
     pc::prof_begin(ctx, PC_KERNEL_LOOKUP, st);
     pc_status ls;
-#define PC_STREAM(NPB_)                                                                                        \
-  (d == 64    ? launch_stream<NPB_, 2>(ctx, grid, per_wg, lds, st, N, d, pp, np, partial)                       \
-   : d == 128 ? launch_stream<NPB_, 4>(ctx, grid, per_wg, lds, st, N, d, pp, np, partial)                       \
-              : launch_stream<NPB_, 8>(ctx, grid, per_wg, lds, st, N, d, pp, np, partial))
-    if (npb == 1) ls = PC_STREAM(1);
-    else if (npb == 2) ls = PC_STREAM(2);
-    else ls = PC_STREAM(4);
-#undef PC_STREAM
+    if (npb == 1)
+      ls = sh.chb == 128   ? launch_stream<1, 128, 3>(ctx, sh, st, N, d, pp, np, partial)
+           : sh.chb == 256 ? launch_stream<1, 256, 3>(ctx, sh, st, N, d, pp, np, partial)
+                           : launch_stream<1, 512, 3>(ctx, sh, st, N, d, pp, np, partial);
+    else
+      ls = sh.chb == 128   ? launch_stream<2, 128, 2>(ctx, sh, st, N, d, pp, np, partial)
+           : sh.chb == 256 ? launch_stream<2, 256, 2>(ctx, sh, st, N, d, pp, np, partial)
+                           : launch_stream<2, 512, 2>(ctx, sh, st, N, d, pp, np, partial);
     if (ls != PC_OK) return ls;
     pc::prof_end(ctx, PC_KERNEL_LOOKUP, st);
     PC_HIP(ctx, hipGetLastError());

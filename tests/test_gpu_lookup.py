@@ -49,7 +49,7 @@ def test_config0_lookup():
 
 @pytest.mark.parametrize("n_clusters,per_cluster,n_probes", [(37, 27, 70), (50, 100, 16), (13, 5, 1), (64, 64, 130)])
 def test_clustered_ragged_sizes(n_clusters, per_cluster, n_probes):
-    """Bank sizes that are not multiples of the 16-row block, probe counts across the 64-probe pass."""
+    """Bank sizes that are not multiples of the 16-row block, probe counts across the 32-probe pass."""
     w = wl.lookup_clustered("t", 11, n_clusters, per_cluster, 1024, n_probes, 0.05, 0.02, 0.92, n_exact=3, n_near=3)
     N = w.bank.shape[0]
     pc = _ctx(N + 5, 1024)
@@ -61,6 +61,19 @@ def test_clustered_ragged_sizes(n_clusters, per_cluster, n_probes):
     torch.cuda.synchronize()
     _compare(w.bank, w.probes, w.tau, idx, sim, hit)
     assert hit[-6:].all()
+
+
+@pytest.mark.parametrize("dim,n_probes", [(64, 5), (64, 20), (256, 9), (256, 31), (512, 16), (768, 3), (768, 33)])
+def test_every_embedding_width(dim, n_probes):
+    """Each row-chunk width of the streaming kernel (one chunk per row up to 256 elements, several beyond),
+    with one and two probe blocks, on a bank long enough that every wavefront streams many row blocks."""
+    w = wl.lookup_clustered("w", 100 + dim, 1031, 97, dim, n_probes, 0.05, 0.02, 0.92, n_exact=1, n_near=1)
+    N = w.bank.shape[0]
+    pc = _ctx(N, dim)
+    pc.percache_bank_put(0, f16(w.bank))
+    idx, sim, hit = pc.percache_lookup(f16(w.probes), w.tau)
+    torch.cuda.synchronize()
+    _compare(w.bank, w.probes, w.tau, idx, sim, hit)
 
 
 def test_ties_zero_vectors_and_empty_bank():
