@@ -28,6 +28,21 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
+# HBM bytes per launch of the attention kernel on this workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled
+# by a 1 GiB copy (summary under profiles/).  Valid only for the kernel source the counters were taken with.
+ATTN_TRAFFIC = {"source_sha256_16": "77224e0bdfe1b5c5", "read_bytes": 2 * 307534.0 * 1024, "write_bytes": 55296.0 * 1024}
+
+
+def attention_traffic():
+    import hashlib
+    src = os.path.join(ROOT, "paper_2601_11553_amd", "csrc", "reuse_attention.hip")
+    try:
+        with open(src, "rb") as f:
+            same = hashlib.sha256(f.read()).hexdigest()[:16] == ATTN_TRAFFIC["source_sha256_16"]
+    except OSError:
+        same = False
+    return ATTN_TRAFFIC["read_bytes"] + ATTN_TRAFFIC["write_bytes"] if same else None
+
 
 def attention_flops(B, Hq, D, T, l_pre):
     """Algorithmic flops of the reuse attention: QK^T and PV over the cached keys and the causal fresh part."""
@@ -41,6 +56,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
     ap.add_argument("--bank-rows", type=int, default=200_000)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (a kernel of known traffic to scale HBM byte counters by)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -86,6 +103,12 @@ def main():
         pc.percache_prefill_reuse(0, X, W, w.slot_ids, w.used_len, attn_out=attn, k_fresh_out=kf, v_fresh_out=vf)
         pc.percache_kv_put_batch(0, spare, kf, vf, T)
 
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)   # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -143,7 +166,7 @@ def main():
                    "batch": B, "t_fresh": T, "l_pre": int(w.l_pre[0]), "bank_rows": N},
         "roofline": {"bound": "mfma", "kernel": "reuse_attention_kernel<128>", "achieved": round(attn_tflops, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4),
-                     "traffic": None, "avg_launch_ms": round(attn_ms, 4), "launches": n_attn,
+                     "traffic": attention_traffic(), "avg_launch_ms": round(attn_ms, 4), "launches": n_attn,
                      "algorithmic_flops_per_launch": fl_attn, "kv_stream_GBps": round(kv_bytes / (attn_ms * 1e-3) / 1e9, 1)},
         "breakdown": {
             "qkv_rope": {"avg_launch_ms": round(qkv_ms, 4), "TFLOPs": round(fl_qkv / (qkv_ms * 1e-3) / 1e12, 2),

@@ -43,7 +43,7 @@ typedef enum {
 } pc_status;
 
 /* Immutable shape of one context.  Supported: head_dim 64 or 128; hidden a multiple of 64;
- * n_q_heads a multiple of n_kv_heads; slot_capacity a multiple of 64; emb_dim 64, 128 or a multiple of 256. */
+ * n_q_heads a multiple of n_kv_heads; slot_capacity a multiple of 64; emb_dim a multiple of 64, at most 2048. */
 typedef struct {
   int32_t n_layers;      /* layers of K/V store */
   int32_t hidden;        /* model width H */

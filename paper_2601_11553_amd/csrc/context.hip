@@ -18,8 +18,8 @@ bool config_ok(const percache_config *c, std::string &why) {
   if (c->hidden % 64) return bad("hidden must be a multiple of 64");
   if (c->n_q_heads % c->n_kv_heads) return bad("n_q_heads must be a multiple of n_kv_heads");
   if (c->slot_capacity % 64) return bad("slot_capacity must be a multiple of 64");
-  if (c->bank_capacity > 0 && !(c->emb_dim == 64 || c->emb_dim == 128 || (c->emb_dim >= 256 && c->emb_dim % 256 == 0)))
-    return bad("emb_dim must be 64, 128 or a multiple of 256");
+  if (c->bank_capacity > 0 && (c->emb_dim < 64 || c->emb_dim % 64 || c->emb_dim > 2048))
+    return bad("emb_dim must be a multiple of 64 in [64, 2048]");
   if (!(c->rope_theta > 1.0f)) return bad("rope_theta must exceed 1");
   if (((c->n_q_heads + 2 * c->n_kv_heads) * c->head_dim) % 128) return bad("(n_q_heads + 2 n_kv_heads) * head_dim must be a multiple of 128");
   (void)buf;

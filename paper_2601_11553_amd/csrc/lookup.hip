@@ -269,6 +269,7 @@ __global__ void lookup_empty_kernel(int n, int32_t *idx_out, float *sim_out, uin
 constexpr int kPassProbes = 32;
 
 // LDS bytes of one workgroup: probes, inverse norms, then (1 KB aligned) the four wavefront rings.
+constexpr size_t kMaxLds = 160 * 1024;
 struct StreamShape {
   int grid, per_wg, nstg, chb, ring_off;
   size_t lds;
@@ -276,8 +277,7 @@ struct StreamShape {
 StreamShape stream_shape(const percache_ctx *ctx, int npb, int N) {
   const int d = ctx->cfg.emb_dim;
   StreamShape s;
-  s.chb = d * 2 >= 512 ? 512 : d * 2;
-  s.nstg = npb == 1 ? 3 : 2;
+  s.chb = d * 2 % 512 == 0 ? 512 : d * 2 % 256 == 0 ? 256 : 128;  // widest chunk that divides a row
   const int n_blocks = (N + 15) / 16;
   s.grid = ctx->n_cu;  // the rings allow one workgroup per CU
   const int need = (n_blocks + 3) / 4;  // at least one block per wavefront
@@ -289,6 +289,8 @@ StreamShape stream_shape(const percache_ctx *ctx, int npb, int N) {
   }
   size_t head = (size_t)npb * 16 * (d * 2 + 64) + (size_t)s.per_wg * 16 * sizeof(float);
   s.ring_off = (int)((head + 1023) / 1024 * 1024);
+  // three stages per wavefront for a single probe block if they fit beside the probes, else two
+  s.nstg = npb == 1 && s.ring_off + (size_t)4 * 3 * 16 * s.chb <= kMaxLds ? 3 : 2;
   s.lds = s.ring_off + (size_t)4 * s.nstg * 16 * s.chb;
   return s;
 }
@@ -302,7 +304,7 @@ pc_status launch_stream(percache_ctx *ctx, const StreamShape &sh, hipStream_t st
                         Best *partial) {
   static bool big_lds_set = false;  // dynamic LDS above 64 KB must be opted into once per kernel
   if (!big_lds_set) {
-    PC_HIP(ctx, hipFuncSetAttribute((const void *)lookup_stream_kernel<NPB, CHB, NSTG>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+    PC_HIP(ctx, hipFuncSetAttribute((const void *)lookup_stream_kernel<NPB, CHB, NSTG>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxLds));
     big_lds_set = true;
   }
   hipLaunchKernelGGL((lookup_stream_kernel<NPB, CHB, NSTG>), dim3(sh.grid), dim3(256), sh.lds, st, ctx->bank, ctx->bank_inv, N, d,
@@ -358,19 +360,23 @@ pc_status percache_lookup(percache_ctx *ctx, const void *probes_dev, int32_t n_p
   if ((uintptr_t)workspace_dev % 16) return pc::fail(ctx, PC_EINVAL, "workspace must be 16-byte aligned");
   Best *partial = (Best *)workspace_dev;
   const _Float16 *probes = (const _Float16 *)probes_dev;
-  for (int p0 = 0; p0 < n_probes; p0 += kPassProbes) {
-    int np = n_probes - p0 < kPassProbes ? n_probes - p0 : kPassProbes;
+  // two probe blocks per pass unless their LDS copy leaves no room for the rings (very wide embeddings)
+  const int pass_probes = stream_shape(ctx, 2, N).lds <= kMaxLds ? kPassProbes : 16;
+  for (int p0 = 0; p0 < n_probes; p0 += pass_probes) {
+    int np = n_probes - p0 < pass_probes ? n_probes - p0 : pass_probes;
     int npb = np <= 16 ? 1 : 2;
     StreamShape sh = stream_shape(ctx, npb, N);
-    if (sh.lds > 160 * 1024) return pc::fail(ctx, PC_ESHAPE, "emb_dim %d needs %zu bytes of LDS per workgroup", d, sh.lds);
+    if (sh.lds > kMaxLds) return pc::fail(ctx, PC_ESHAPE, "emb_dim %d needs %zu bytes of LDS per workgroup", d, sh.lds);
     const int grid = sh.grid;
     const _Float16 *pp = probes + (size_t)p0 * d;
     pc::prof_begin(ctx, PC_KERNEL_LOOKUP, st);
     pc_status ls;
-    if (npb == 1)
+    if (npb == 1 && sh.nstg == 3)
       ls = sh.chb == 128   ? launch_stream<1, 128, 3>(ctx, sh, st, N, d, pp, np, partial)
            : sh.chb == 256 ? launch_stream<1, 256, 3>(ctx, sh, st, N, d, pp, np, partial)
                            : launch_stream<1, 512, 3>(ctx, sh, st, N, d, pp, np, partial);
+    else if (npb == 1)
+      ls = launch_stream<1, 512, 2>(ctx, sh, st, N, d, pp, np, partial);  // only the widest rows (512-byte chunks) get here
     else
       ls = sh.chb == 128   ? launch_stream<2, 128, 2>(ctx, sh, st, N, d, pp, np, partial)
            : sh.chb == 256 ? launch_stream<2, 256, 2>(ctx, sh, st, N, d, pp, np, partial)

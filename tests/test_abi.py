@@ -36,7 +36,7 @@ def test_arena_bytes_and_config_validation(lib):
     store = 2 * 16 * 8 * 512 * 128 * 2
     assert n >= store + 1000 * 1024 * 2 + 4096 * 64 * 8 and n % 256 == 0
     assert lib.percache_arena_bytes(None) == 0
-    for field, bad in [("head_dim", 96), ("hidden", 1000), ("n_kv_heads", 3), ("slot_capacity", 100), ("emb_dim", 320),
+    for field, bad in [("head_dim", 96), ("hidden", 1000), ("n_kv_heads", 3), ("slot_capacity", 100), ("emb_dim", 96),
                        ("n_layers", 0), ("rope_theta", 0.5)]:
         c = Config(1, 1024, 16, 8, 128, 16, 512, 4096, 10000.0, 1000, 1024)
         setattr(c, field, bad)

@@ -63,7 +63,7 @@ def test_clustered_ragged_sizes(n_clusters, per_cluster, n_probes):
     assert hit[-6:].all()
 
 
-@pytest.mark.parametrize("dim,n_probes", [(64, 5), (64, 20), (256, 9), (256, 31), (512, 16), (768, 3), (768, 33)])
+@pytest.mark.parametrize("dim,n_probes", [(64, 5), (64, 20), (192, 7), (256, 31), (384, 9), (384, 25), (768, 3), (768, 33), (2048, 20)])
 def test_every_embedding_width(dim, n_probes):
     """Each row-chunk width of the streaming kernel (one chunk per row up to 256 elements, several beyond),
     with one and two probe blocks, on a bank long enough that every wavefront streams many row blocks."""
