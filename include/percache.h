@@ -110,6 +110,12 @@ pc_status percache_kv_evict(percache_ctx *ctx, int32_t layer, int32_t slot);
  * saved at once); chunk i goes to slot slots_host[i].  Slots must be distinct. */
 pc_status percache_kv_put_batch(percache_ctx *ctx, int32_t layer, const int32_t *slots_host, int32_t n,
                                 const void *k_dev, const void *v_dev, int32_t n_tokens, void *stream);
+/* Cache slicer (Sec. 4.1.1, App. B.2): cuts the K/V of one prefilled sequence at chunk boundaries and stores
+ * each piece in a slot of its own.  k_dev, v_dev: [n_kv_heads, seq_len, head_dim] bf16 (post-RoPE K); piece j is
+ * the token range [bounds_host[j], bounds_host[j+1]) (n + 1 bounds; at most slot_capacity tokens per piece) and
+ * goes to slot slots_host[j]; a negative slot id skips the piece.  Slots must be distinct. */
+pc_status percache_kv_slice(percache_ctx *ctx, int32_t layer, const void *k_dev, const void *v_dev, int32_t seq_len,
+                            const int32_t *bounds_host, const int32_t *slots_host, int32_t n, void *stream);
 /* Stored token count of a slot, 0 if empty, negative pc_status on a bad index. */
 int32_t percache_kv_len(const percache_ctx *ctx, int32_t layer, int32_t slot);
 
@@ -163,6 +169,42 @@ pc_status percache_attention_reuse(percache_ctx *ctx, int32_t layer, const void 
                                    const int32_t *used_len_host, const int32_t *n_chunks_host,
                                    int32_t max_chunks, int32_t n_splits, void *attn_out_dev,
                                    void *workspace_dev, size_t workspace_bytes, void *stream);
+
+/* ---------------------------------------------------------------- a stack of layers on the retained rows
+ * (App. B.1).  After the attention module a block goes on as usual, and the next layer crops the cached rows
+ * again, so only the retained (fresh) rows of every layer are ever computed:
+ *   n  = RMSNorm(h; gain1, eps)                    y = x / sqrt(mean(x^2) + eps) * gain
+ *   a  = cache-reusing attention of layer l on n   (percache_prefill_reuse with that layer's wqkv and store)
+ *   h' = h + a wo^T
+ *   h''= h' + (silu(m w_gate^T) * (m w_up^T)) w_down^T,   m = RMSNorm(h'; gain2, eps)
+ * All weights bf16 device pointers, 16-byte aligned; the struct array itself is host memory. */
+typedef struct {
+  const void *gain1;  /* [hidden] */
+  const void *wqkv;   /* [(Hq + 2 Hkv) * D, hidden] */
+  const void *wo;     /* [hidden, Hq * D] */
+  const void *gain2;  /* [hidden] */
+  const void *w_gate; /* [ffn, hidden] */
+  const void *w_up;   /* [ffn, hidden] */
+  const void *w_down; /* [hidden, ffn] */
+} percache_block_weights;
+
+/* Runs layers 0 .. n_layers-1 (layer l reads store layer l; the chunk list is the same for every layer and the
+ * chunks' stored lengths must agree across layers).  hidden must be a multiple of 128, ffn of 64.
+ *   h_in_dev, h_out_dev  [batch, t_fresh, hidden] bf16 (may be the same buffer)
+ *   save_*: optional cache slicer on the way (n_save == 0: off).  The fresh K/V of every layer are cut at
+ *           save_bounds_host[0 .. n_save] (token indices inside the fresh part, the same for every query) and piece
+ *           j of query b is stored in slot save_slots_host[b * n_save + j] of that layer (negative: skipped).
+ *           Save slots must be distinct and must not be read by this call.  With n_chunks == 0 this is the
+ *           population pass: an ordinary prefill that fills the cache.
+ *   workspace_dev        >= percache_stack_workspace_bytes(ctx, batch, t_fresh, max_chunks, ffn), 256-byte aligned */
+size_t percache_stack_workspace_bytes(const percache_ctx *ctx, int32_t batch, int32_t t_fresh, int32_t max_chunks,
+                                      int32_t ffn);
+pc_status percache_stack_reuse(percache_ctx *ctx, const percache_block_weights *layers_host, int32_t n_layers,
+                               int32_t ffn, float eps, const void *h_in_dev, int32_t batch, int32_t t_fresh,
+                               const int32_t *slot_ids_host, const int32_t *used_len_host,
+                               const int32_t *n_chunks_host, int32_t max_chunks, const int32_t *save_bounds_host,
+                               const int32_t *save_slots_host, int32_t n_save, void *h_out_dev, void *workspace_dev,
+                               size_t workspace_bytes, void *stream);
 
 /* ---------------------------------------------------------------- kernel timing
  * With profiling on, the launches of the three main kernels are bracketed by HIP events on the caller's

@@ -24,6 +24,7 @@ EXPORTS = [
     "percache_arena_bytes", "percache_create", "percache_destroy", "percache_last_error",
     "percache_bank_put", "percache_bank_size", "percache_lookup_workspace_bytes", "percache_lookup",
     "percache_kv_put", "percache_kv_put_batch", "percache_kv_get", "percache_kv_evict", "percache_kv_len",
+    "percache_kv_slice", "percache_stack_workspace_bytes", "percache_stack_reuse",
     "percache_prefill_workspace_bytes", "percache_prefill_reuse", "percache_qkv_rope", "percache_attention_reuse",
     "percache_profile_enable", "percache_profile_read",
 ]
@@ -43,6 +44,11 @@ class Config(ctypes.Structure):
         ("slot_capacity", ctypes.c_int32), ("max_pos", ctypes.c_int32), ("rope_theta", ctypes.c_float),
         ("bank_capacity", ctypes.c_int32), ("emb_dim", ctypes.c_int32),
     ]
+
+
+class BlockWeights(ctypes.Structure):
+    """percache_block_weights: device pointers of one block's weights."""
+    _fields_ = [(n, ctypes.c_void_p) for n in ("gain1", "wqkv", "wo", "gain2", "w_gate", "w_up", "w_down")]
 
 
 _lib = None
@@ -77,6 +83,10 @@ def load_library() -> ctypes.CDLL:
         "percache_prefill_reuse": (_i32, [_vp, _i32, _vp, _vp, _i32, _i32, _pi32, _pi32, _pi32, _i32, _vp, _vp, _vp, _vp, _sz, _vp]),
         "percache_qkv_rope": (_i32, [_vp, _vp, _vp, _i32, _i32, _pi32, _pi32, _pi32, _i32, _i32, _vp, _vp, _vp, _vp, _sz, _vp]),
         "percache_attention_reuse": (_i32, [_vp, _i32, _vp, _vp, _vp, _i32, _i32, _pi32, _pi32, _pi32, _i32, _i32, _vp, _vp, _sz, _vp]),
+        "percache_kv_slice": (_i32, [_vp, _i32, _vp, _vp, _i32, _pi32, _pi32, _i32, _vp]),
+        "percache_stack_workspace_bytes": (_sz, [_vp, _i32, _i32, _i32, _i32]),
+        "percache_stack_reuse": (_i32, [_vp, ctypes.POINTER(BlockWeights), _i32, _i32, ctypes.c_float, _vp, _i32, _i32,
+                                        _pi32, _pi32, _pi32, _i32, _pi32, _pi32, _i32, _vp, _vp, _sz, _vp]),
         "percache_profile_enable": (_i32, [_vp, _i32]),
         "percache_profile_read": (_i32, [_vp, _i32, ctypes.POINTER(ctypes.c_float), _pi32]),
     }
@@ -212,6 +222,13 @@ class Percache:
         assert cnt.value == n
         return k, v
 
+    def percache_kv_slice(self, layer: int, k, v, bounds, slots):
+        """k, v: [Hkv, seq_len, D]; piece j = tokens [bounds[j], bounds[j+1]) goes to slot slots[j] (< 0: skipped)."""
+        b, bp = _host_i32(bounds)
+        sl, sp = _host_i32(slots)
+        assert len(b) == len(sl) + 1
+        self._check(self.lib.percache_kv_slice(self.ctx, layer, _ptr(k), _ptr(v), k.shape[1], bp, sp, len(sl), _stream()))
+
     def percache_kv_evict(self, layer: int, slot: int):
         self._check(self.lib.percache_kv_evict(self.ctx, layer, slot))
 
@@ -278,3 +295,29 @@ class Percache:
                                                       t_fresh, ids_p, ul_p, nc_p, max_chunks, n_splits, _ptr(attn_out),
                                                       ws, need, _stream()))
         return attn_out
+
+    # ------------------------------------------------------------------ stack of layers on the retained rows
+    def percache_stack_workspace_bytes(self, batch, t_fresh, max_chunks, ffn) -> int:
+        return self.lib.percache_stack_workspace_bytes(self.ctx, batch, t_fresh, max_chunks, ffn)
+
+    def percache_stack_reuse(self, layers, ffn: int, eps: float, h_in, slot_ids=None, used_len=None, n_chunks=None,
+                             save_bounds=None, save_slots=None, h_out=None):
+        """layers: one dict per layer with the tensors gain1, wqkv, wo, gain2, w_gate, w_up, w_down (bf16, on device)."""
+        import torch
+        batch, t_fresh, _ = h_in.shape
+        keep, ids_p, ul_p, nc_p, max_chunks = self._chunk_args(batch, slot_ids, used_len, n_chunks)
+        arr = (BlockWeights * len(layers))()
+        for i, lw in enumerate(layers):
+            for name, _t in BlockWeights._fields_:
+                setattr(arr[i], name, _ptr(lw[name]))
+        sb, sb_p = _host_i32(save_bounds)
+        n_save = 0 if sb is None else len(sb) - 1
+        ss, ss_p = _host_i32(save_slots, (batch, n_save)) if n_save else (None, None)
+        if h_out is None:
+            h_out = torch.empty_like(h_in)
+        need = self.percache_stack_workspace_bytes(batch, t_fresh, max_chunks, ffn)
+        ws = self._workspace(need)
+        self._check(self.lib.percache_stack_reuse(self.ctx, arr, len(layers), ffn, eps, _ptr(h_in), batch, t_fresh, ids_p,
+                                                  ul_p, nc_p, max_chunks, sb_p, ss_p, n_save, _ptr(h_out), ws, need,
+                                                  _stream()))
+        return h_out

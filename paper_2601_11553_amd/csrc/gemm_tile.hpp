@@ -1,0 +1,125 @@
+// Main loop shared by the projection kernels: Y^T tile = W_tile (128 features) x X_tile^T (64 or 128 tokens),
+// bf16 operands, fp32 accumulation on the 32x32x16 matrix cores.
+//
+// A workgroup of 4 wavefronts computes 128 output features x (64 or 128) tokens.  The features are the M side of
+// the MFMA and the tokens the N side, so a lane ends up holding 4 consecutive features of one token per accumulator
+// quad (8-byte stores into token-major outputs).  Wavefront (wf, wt) owns two 32-feature blocks (fb_lo, fb_hi) --
+// chosen by the caller so that features which must meet in the epilogue (a RoPE pair, a gate/up pair) sit in the
+// same lane -- and the token blocks wt*NTB .. wt*NTB+NTB-1.  Operand tiles (64 k-elements = 128-byte rows) are
+// brought in by direct global->LDS loads into a double-buffered, XOR-swizzled LDS layout (16-byte chunk index
+// ^= (row >> 1) & 7: conflict-free reads).
+#pragma once
+
+#include "percache_internal.hpp"
+
+namespace pc {
+namespace gemm {
+
+constexpr int BK = 64;       // k elements per LDS stage
+constexpr int ROW = BK * 2;  // bytes per LDS row
+constexpr int BF = 128;      // feature rows per workgroup
+constexpr int NW = 4;        // wavefronts per workgroup
+
+template <int NTB>
+struct Shape {
+  static constexpr int BT = 64 * NTB;  // tokens per workgroup
+  static constexpr int W_BYTES = BF * ROW, X_BYTES = BT * ROW, STAGE = W_BYTES + X_BYTES;
+  static constexpr int W_INSTR = W_BYTES / 1024 / NW, X_INSTR = X_BYTES / 1024 / NW;
+  static constexpr int LDS_BYTES = 2 * STAGE;
+};
+
+__device__ __forceinline__ int swz128(int row) { return (row >> 1) & 7; }
+__device__ __forceinline__ void wait_vmcnt0() { __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8)); }
+
+__device__ __forceinline__ uint2 pack4(float a, float b, float c, float d) {
+  bf16x4 v = {(__bf16)a, (__bf16)b, (__bf16)c, (__bf16)d};
+  return __builtin_bit_cast(uint2, v);
+}
+__device__ __forceinline__ void unpack4(uint2 raw, float (&o)[4]) {
+  bf16x4 v = __builtin_bit_cast(bf16x4, raw);
+#pragma unroll
+  for (int e = 0; e < 4; ++e) o[e] = (float)v[e];
+}
+
+// w_row(r): pointer to the K contiguous elements of the weight row that tile row r (0..127) stands for.
+// X: [M, K] row-major, the tile covers token rows m0 .. m0 + BT - 1 (clamped to M - 1 when reading).
+// On return acc[a][t] holds features (a ? fb_hi : fb_lo) * 32 + (r/4)*8 + 4*(lane/32) + r%4 of token
+// m0 + (wt*NTB + t)*32 + lane%32 in element r.
+template <int NTB, class WRow>
+__device__ __forceinline__ void mainloop(char *lds, WRow w_row, const __bf16 *__restrict__ X, int m0, int M, int K,
+                                         int fb_lo, int fb_hi, f32x16 (&acc)[2][NTB]) {
+  using S = Shape<NTB>;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wt = wave >> 1;
+  const int l32 = lane & 31, g = lane >> 5;
+
+  // direct global -> LDS loads: wavefront instruction i fills bytes [1024 i, 1024 i + 1024) of a tile, lane l
+  // the 16 bytes at 1024 i + 16 l, i.e. row (8 i + l / 8), physical chunk l % 8 <- logical chunk (l % 8) ^ swz(row)
+  const __bf16 *w_src[S::W_INSTR];
+  const __bf16 *x_src[S::X_INSTR];
+#pragma unroll
+  for (int k = 0; k < S::W_INSTR; ++k) {
+    const int row = (wave + k * NW) * 8 + (lane >> 3);
+    w_src[k] = w_row(row) + (((lane & 7) ^ swz128(row)) * 8);
+  }
+#pragma unroll
+  for (int k = 0; k < S::X_INSTR; ++k) {
+    const int row = (wave + k * NW) * 8 + (lane >> 3);
+    x_src[k] = X + (size_t)min(m0 + row, M - 1) * K + (((lane & 7) ^ swz128(row)) * 8);
+  }
+  auto fetch = [&](int kt, int st) __attribute__((always_inline)) {
+    char *base = lds + st * S::STAGE;
+#pragma unroll
+    for (int k = 0; k < S::W_INSTR; ++k)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(w_src[k] + kt * BK),
+                                       (__attribute__((address_space(3))) void *)(base + (wave + k * NW) * 1024), 16, 0, 0);
+#pragma unroll
+    for (int k = 0; k < S::X_INSTR; ++k)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(x_src[k] + kt * BK),
+                                       (__attribute__((address_space(3))) void *)(base + S::W_BYTES + (wave + k * NW) * 1024), 16, 0, 0);
+  };
+
+  // swizzled byte offsets of this lane's operand reads inside its row (row & 31 = l32 for every block)
+  int rd[BK / 16];
+#pragma unroll
+  for (int ks = 0; ks < BK / 16; ++ks) rd[ks] = ((2 * ks + g) ^ swz128(l32)) * 16;
+
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int t = 0; t < NTB; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[a][t][r] = 0.f;
+
+  const int nk = K / BK;
+  fetch(0, 0);
+  wait_vmcnt0();
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+  for (int kt = 0; kt < nk; ++kt) {
+    const int st = kt & 1;
+    if (kt + 1 < nk) fetch(kt + 1, st ^ 1);
+    const char *wl = lds + st * S::STAGE + (fb_lo * 32 + l32) * ROW;
+    const char *wh = lds + st * S::STAGE + (fb_hi * 32 + l32) * ROW;
+    const char *xb = lds + st * S::STAGE + S::W_BYTES + ((wt * NTB) * 32 + l32) * ROW;
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      bf16x8 a_lo = *(const bf16x8 *)(wl + rd[ks]);
+      bf16x8 a_hi = *(const bf16x8 *)(wh + rd[ks]);
+#pragma unroll
+      for (int t = 0; t < NTB; ++t) {
+        bf16x8 b = *(const bf16x8 *)(xb + t * 32 * ROW + rd[ks]);
+        acc[0][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_lo, b, acc[0][t], 0, 0, 0);
+        acc[1][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi, b, acc[1][t], 0, 0, 0);
+      }
+    }
+    // the next stage's loads must have landed before anyone reads them; the barrier also retires this stage
+    wait_vmcnt0();
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+  }
+}
+
+}  // namespace gemm
+}  // namespace pc

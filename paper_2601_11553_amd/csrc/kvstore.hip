@@ -22,11 +22,12 @@ template <bool kToStore>
 __global__ __launch_bounds__(256) void kv_copy_kernel(pc::u32x4 *__restrict__ slot_k, __bf16 *__restrict__ slot_v,
                                                       pc::u32x4 *__restrict__ dense_k, __bf16 *__restrict__ dense_v,
                                                       int n_heads, int n_tok, int D, int C, SlotList slots,
-                                                      long slot_stride_elems) {
-  // blockIdx.z selects the chunk: its slot and its dense tensor
+                                                      long slot_stride_elems, long dense_head_stride) {
+  // blockIdx.z selects the chunk: its slot and its dense tensor.  dense_head_stride: elements between the heads of
+  // a dense tensor (n_tok * D when the chunk is a tensor of its own, more when it is a token range of a longer one)
   {
     const long so = (long)slots.slot[blockIdx.z] * slot_stride_elems;
-    const long dn = (long)blockIdx.z * n_heads * n_tok * D;
+    const long dn = (long)blockIdx.z * n_heads * dense_head_stride;
     slot_k += so / 8;
     slot_v += so;
     dense_k += dn / 8;
@@ -41,7 +42,8 @@ __global__ __launch_bounds__(256) void kv_copy_kernel(pc::u32x4 *__restrict__ sl
       int g = (int)(e / run_vec);
       int r = (int)(e - (long)g * run_vec);
       long s = (long)g * slot_head_vec + r;
-      if (kToStore) slot_k[s] = dense_k[e]; else dense_k[e] = slot_k[s];
+      long dd = (long)g * (dense_head_stride / 8) + r;
+      if (kToStore) slot_k[s] = dense_k[dd]; else dense_k[dd] = slot_k[s];
     }
     return;
   }
@@ -61,7 +63,7 @@ __global__ __launch_bounds__(256) void kv_copy_kernel(pc::u32x4 *__restrict__ sl
       for (int k = 0; k < 8; ++k) {
         int pos = chunk * 8 + k;
         int t = tile * kKvTile + (pos & ~15) + pc::blocked_key(pos & 15);
-        o[k] = t < n_tok ? dense_v[((size_t)g * n_tok + t) * D + d] : (__bf16)0.f;
+        o[k] = t < n_tok ? dense_v[(size_t)g * dense_head_stride + (size_t)t * D + d] : (__bf16)0.f;
       }
       *(pc::bf16x8 *)(slot_v + (((size_t)g * C + (size_t)tile * kKvTile) * D) + (size_t)d * kKvTile + chunk * 8) = o;
     }
@@ -80,7 +82,7 @@ __global__ __launch_bounds__(256) void kv_copy_kernel(pc::u32x4 *__restrict__ sl
       pc::bf16x8 o;
 #pragma unroll
       for (int k = 0; k < 8; ++k) o[k] = src[(size_t)(dc * 8 + k) * kKvTile];
-      *(pc::bf16x8 *)(dense_v + ((size_t)g * n_tok + t) * D + dc * 8) = o;
+      *(pc::bf16x8 *)(dense_v + (size_t)g * dense_head_stride + (size_t)t * D + dc * 8) = o;
     }
   }
 }
@@ -94,7 +96,7 @@ pc_status check_slot(percache_ctx *ctx, int32_t layer, int32_t slot) {
 
 template <bool kToStore>
 pc_status launch_copy(percache_ctx *ctx, int layer, const int32_t *slot_list, int n, void *k_dev, void *v_dev, int n_tokens,
-                      hipStream_t stream) {
+                      hipStream_t stream, long dense_head_stride = 0) {
   const percache_config &c = ctx->cfg;
   size_t off = (size_t)layer * ctx->layer_stride;
   SlotList sl;
@@ -104,12 +106,20 @@ pc_status launch_copy(percache_ctx *ctx, int layer, const int32_t *slot_list, in
   if (blocks > 2048) blocks = 2048;
   hipLaunchKernelGGL(kv_copy_kernel<kToStore>, dim3(blocks, 2, n), dim3(256), 0, stream, (pc::u32x4 *)(ctx->k_store + off),
                      ctx->v_store + off, (pc::u32x4 *)k_dev, (__bf16 *)v_dev, c.n_kv_heads, n_tokens, c.head_dim,
-                     c.slot_capacity, sl, (long)ctx->slot_stride);
+                     c.slot_capacity, sl, (long)ctx->slot_stride,
+                     dense_head_stride ? dense_head_stride : (long)n_tokens * c.head_dim);
   PC_HIP(ctx, hipGetLastError());
   return PC_OK;
 }
 
 }  // namespace
+
+namespace pc {
+pc_status launch_kv_store(percache_ctx *ctx, int layer, int slot, const __bf16 *k, const __bf16 *v, int n_tokens,
+                          long dense_head_stride, hipStream_t stream) {
+  return launch_copy<true>(ctx, layer, &slot, 1, (void *)k, (void *)v, n_tokens, stream, dense_head_stride);
+}
+}  // namespace pc
 
 extern "C" {
 

@@ -121,4 +121,9 @@ pc_status launch_attention(percache_ctx *ctx, int layer, const __bf16 *q, const 
                            int batch, int t_fresh, const int32_t *table_dev, int tbl_stride, int max_tiles,
                            int n_splits, __bf16 *out, __bf16 *part_o, float *part_ml, hipStream_t stream);
 
+// Copies n_tokens tokens of a dense [Hkv][.][D] tensor whose heads are dense_head_stride elements apart into a
+// slot (no validation, no slot-table update).
+pc_status launch_kv_store(percache_ctx *ctx, int layer, int slot, const __bf16 *k, const __bf16 *v, int n_tokens,
+                          long dense_head_stride, hipStream_t stream);
+
 }  // namespace pc

@@ -5,30 +5,15 @@
 // query b is L_pre[b] + i: the position counter is advanced by the cached length before the sine/cosine
 // table is read.  q and k are rotated on the fp32 accumulators and rounded to bf16 once.
 //
-// Tiling (64-wide wavefronts, 32x32x16 MFMA): a workgroup of 4 wavefronts computes 128 output features
-// x (64 or 128) tokens.  The features are the M side of the MFMA and the tokens the N side, so a lane ends
-// up holding 4 consecutive features of one token per accumulator quad (8-byte stores), and each wavefront
-// owns a feature block together with its rotation partner (m, m + D/2): RoPE needs no cross-lane traffic.
-// Operand tiles (64 k-elements = 128-byte rows) are brought in by direct global->LDS loads into a
-// double-buffered, XOR-swizzled LDS layout (16-byte chunk index ^= (row >> 1) & 7: conflict-free reads).
-#include "percache_internal.hpp"
+// Tiling: the shared projection main loop (gemm_tile.hpp): a workgroup of 4 wavefronts computes 128 output
+// features x (64 or 128) tokens, and each wavefront owns a feature block together with its rotation partner
+// (m, m + D/2), so RoPE needs no cross-lane traffic.
+#include "gemm_tile.hpp"
 
 namespace {
-using pc::bf16x8;
 using pc::f32x16;
-
-constexpr int BK = 64;         // k elements per LDS stage
-constexpr int ROW = BK * 2;    // bytes per LDS row
-constexpr int BF = 128;        // features per workgroup
-constexpr int NW = 4;          // wavefronts per workgroup
-
-__device__ __forceinline__ int swz128(int row) { return (row >> 1) & 7; }
-#define PC_WAIT_VMCNT0() __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8))
-
-__device__ __forceinline__ uint2 pack4(float a, float b, float c, float d) {
-  pc::bf16x4 v = {(__bf16)a, (__bf16)b, (__bf16)c, (__bf16)d};
-  return __builtin_bit_cast(uint2, v);
-}
+using pc::gemm::BF;
+using pc::gemm::pack4;
 
 // NTB: 32-token blocks per wavefront (1 -> 64-token tile, 2 -> 128-token tile).
 template <int D, int NTB>
@@ -38,11 +23,9 @@ __global__ __launch_bounds__(256, 2) void qkv_rope_kernel(const __bf16 *__restri
                                                           const float2 *__restrict__ rope, __bf16 *__restrict__ Q,
                                                           __bf16 *__restrict__ K, __bf16 *__restrict__ V) {
   constexpr int BT = 64 * NTB;
-  constexpr int W_BYTES = BF * ROW, X_BYTES = BT * ROW, STAGE = W_BYTES + X_BYTES;
-  constexpr int W_INSTR = W_BYTES / 1024 / NW, X_INSTR = X_BYTES / 1024 / NW;
-  __shared__ __align__(16) char lds[2 * STAGE];
+  __shared__ __align__(16) char lds[pc::gemm::Shape<NTB>::LDS_BYTES];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wf = wave & 1, wt = wave >> 1;
   const int l32 = lane & 31, g = lane >> 5;
   const int f0 = blockIdx.x * BF;  // first feature of the tile
@@ -52,72 +35,8 @@ __global__ __launch_bounds__(256, 2) void qkv_rope_kernel(const __bf16 *__restri
   const int fb_lo = (D == 128) ? wf : 2 * wf;
   const int fb_hi = (D == 128) ? wf + 2 : 2 * wf + 1;
 
-  // direct global -> LDS loads: wavefront instruction i fills bytes [1024 i, 1024 i + 1024) of a tile, lane l
-  // the 16 bytes at 1024 i + 16 l, i.e. row (8 i + l / 8), physical chunk l % 8 <- logical chunk (l % 8) ^ swz(row)
-  int w_off[W_INSTR], x_off[X_INSTR];
-#pragma unroll
-  for (int k = 0; k < W_INSTR; ++k) {
-    const int row = (wave + k * NW) * 8 + (lane >> 3);
-    w_off[k] = (f0 + row) * H + (((lane & 7) ^ swz128(row)) * 8);
-  }
-#pragma unroll
-  for (int k = 0; k < X_INSTR; ++k) {
-    const int row = (wave + k * NW) * 8 + (lane >> 3);
-    x_off[k] = min(m0 + row, M - 1) * H + (((lane & 7) ^ swz128(row)) * 8);
-  }
-  auto fetch = [&](int kt, int st) __attribute__((always_inline)) {
-    char *base = lds + st * STAGE;
-#pragma unroll
-    for (int k = 0; k < W_INSTR; ++k)
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(W + (size_t)w_off[k] + kt * BK),
-                                       (__attribute__((address_space(3))) void *)(base + (wave + k * NW) * 1024), 16, 0, 0);
-#pragma unroll
-    for (int k = 0; k < X_INSTR; ++k)
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(X + (size_t)x_off[k] + kt * BK),
-                                       (__attribute__((address_space(3))) void *)(base + W_BYTES + (wave + k * NW) * 1024), 16, 0, 0);
-  };
-
-  // swizzled byte offsets of this lane's operand reads inside its row (row & 31 = l32 for every block)
-  int rd[BK / 16];
-#pragma unroll
-  for (int ks = 0; ks < BK / 16; ++ks) rd[ks] = ((2 * ks + g) ^ swz128(l32)) * 16;
-
   f32x16 acc[2][NTB];
-#pragma unroll
-  for (int a = 0; a < 2; ++a)
-#pragma unroll
-    for (int t = 0; t < NTB; ++t)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[a][t][r] = 0.f;
-
-  const int nk = H / BK;
-  fetch(0, 0);
-  PC_WAIT_VMCNT0();
-  __builtin_amdgcn_s_barrier();
-  asm volatile("" ::: "memory");
-  for (int kt = 0; kt < nk; ++kt) {
-    const int st = kt & 1;
-    if (kt + 1 < nk) fetch(kt + 1, st ^ 1);
-    const char *wl = lds + st * STAGE + (fb_lo * 32 + l32) * ROW;
-    const char *wh = lds + st * STAGE + (fb_hi * 32 + l32) * ROW;
-    const char *xb = lds + st * STAGE + W_BYTES + ((wt * NTB) * 32 + l32) * ROW;
-#pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 a_lo = *(const bf16x8 *)(wl + rd[ks]);
-      bf16x8 a_hi = *(const bf16x8 *)(wh + rd[ks]);
-#pragma unroll
-      for (int t = 0; t < NTB; ++t) {
-        bf16x8 b = *(const bf16x8 *)(xb + t * 32 * ROW + rd[ks]);
-        acc[0][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_lo, b, acc[0][t], 0, 0, 0);
-        acc[1][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi, b, acc[1][t], 0, 0, 0);
-      }
-    }
-    // the next stage's loads must have landed before anyone reads them; the barrier also retires this stage
-    PC_WAIT_VMCNT0();
-    asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-  }
+  pc::gemm::mainloop<NTB>(lds, [&](int row) __attribute__((always_inline)) { return W + (size_t)(f0 + row) * H; }, X, m0, M, H, fb_lo, fb_hi, acc);
 
   // ---- epilogue: RoPE at position L_pre[b] + i on fp32, one rounding to bf16, head-major stores
   const int head = (D == 128) ? blockIdx.x : 2 * blockIdx.x + wf;

@@ -1,0 +1,150 @@
+"""GPU parity of the layer stack on the retained rows (App. B.1) and of the cache slicer (Sec. 4.1.1), through the C ABI.
+
+Hidden states are O(1) and are stored in bf16 between the steps of a block, so the attention tolerance (absolute
+2e-2) does not apply to them; the bar for hidden states is relative: max-abs error <= 2^-6 of the largest reference
+magnitude (a few bf16 roundings of 2^-9 each per layer) and relative Frobenius error <= 1e-2.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2601_11553_amd import workloads as wl
+from paper_2601_11553_amd.binding import Percache, PercacheError
+
+from gpu_util import DEV, bf16, host
+
+pytestmark = pytest.mark.gpu
+EPS = 1e-6
+
+
+def check_hidden(got, ref, what, rel_max=2.0 ** -6, rel_fro=1e-2):
+    got = np.asarray(got, np.float64)
+    ref = np.asarray(ref, np.float64)
+    assert got.shape == ref.shape and np.isfinite(got).all(), what
+    err = np.abs(got - ref)
+    fro = np.linalg.norm(got - ref) / np.linalg.norm(ref)
+    msg = f"{what}: max-abs {err.max():.3e} (|ref| max {np.abs(ref).max():.3e}) rel-fro {fro:.3e}"
+    print(msg, flush=True)
+    assert err.max() <= rel_max * np.abs(ref).max() and fro <= rel_fro, msg
+
+
+def dev_layers(Ws):
+    return [dict(gain1=bf16(W.gain1), wqkv=bf16(W.Wqkv), wo=bf16(W.Wo), gain2=bf16(W.gain2), w_gate=bf16(W.Wgate),
+                 w_up=bf16(W.Wup), w_down=bf16(W.Wdown)) for W in Ws]
+
+
+def oracle_block(h, W, Hq, Hkv, D, theta, sk=None, sv=None, ids=(), used=()):
+    return oracle.block(h, W.gain1, W.Wqkv, Hq, Hkv, D, theta, W.Wo, W.gain2, W.Wgate, W.Wup, W.Wdown, EPS, sk, sv, ids, used)
+
+
+@pytest.mark.parametrize("D,t_fresh,used_last", [(64, 48, 64), (128, 70, 40), (128, 200, 64)])
+def test_one_block_vs_oracle(D, t_fresh, used_last):
+    """One block over two loaded chunks (random K/V) + a ragged fresh part, against the oracle's block."""
+    H, Hq, Hkv, F, C = 256, 4, 2, 448, 64
+    w = wl.make_prefill("blk", 21, "bf16", H, Hq, Hkv, D, 2, t_fresh, 2, C, 6, last_used_len=used_last)
+    Ws = [wl.stack_weights(21, 0, H, Hq, Hkv, D, F)]
+    pc = Percache(n_layers=1, hidden=H, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=D, n_slots=6, slot_capacity=C,
+                  max_pos=w.max_pos, device=DEV)
+    for s in sorted(set(int(x) for x in w.slot_ids.reshape(-1))):
+        k, v = w.slot_kv(s)
+        pc.percache_kv_put(0, s, bf16(k), bf16(v))
+    h_out = pc.percache_stack_reuse(dev_layers(Ws), F, EPS, bf16(w.X), w.slot_ids, w.used_len)
+    torch.cuda.synchronize()
+    for b in range(2):
+        sk, sv, ids = w.compact_store(b)
+        ref, _, _ = oracle_block(w.X[b], Ws[0], Hq, Hkv, D, w.rope_theta, sk, sv, ids, w.used_len[b])
+        check_hidden(host(h_out[b]), ref, f"block D={D} T={t_fresh} query {b}")
+
+
+def test_kv_slice_round_trip_and_errors():
+    Hkv, D, C, T = 2, 64, 64, 150
+    pc = Percache(n_layers=2, hidden=256, n_q_heads=4, n_kv_heads=Hkv, head_dim=D, n_slots=8, slot_capacity=C,
+                  max_pos=256, device=DEV)
+    g = np.random.default_rng(3)
+    k = bf16(g.standard_normal((Hkv, T, D)))
+    v = bf16(g.standard_normal((Hkv, T, D)))
+    bounds, slots = [0, 64, 100, 150], [5, -1, 2]
+    pc.percache_kv_slice(1, k, v, bounds, slots)
+    torch.cuda.synchronize()
+    assert pc.percache_kv_len(1, 5) == 64 and pc.percache_kv_len(1, 2) == 50 and pc.percache_kv_len(0, 5) == 0
+    for lo, hi, s in [(0, 64, 5), (100, 150, 2)]:
+        kk, vv = pc.percache_kv_get(1, s)
+        torch.cuda.synchronize()
+        assert torch.equal(kk, k[:, lo:hi]) and torch.equal(vv, v[:, lo:hi])
+    for bad_bounds, bad_slots, status in [([0, 65, 150], [1, -1], -4), ([0, 64, 151], [1, 2], -4), ([0, 64, 128], [1, 1], -1),
+                                          ([0, 64, 128], [1, 8], -3)]:
+        with pytest.raises(PercacheError) as e:
+            pc.percache_kv_slice(0, k, v, bad_bounds, bad_slots)
+        assert e.value.status == status
+    assert pc.percache_kv_len(0, 1) == 0   # failed calls wrote nothing
+
+
+def test_two_layer_stack_population_then_reuse():
+    """The population pass (ordinary prefill of the whole prompt, K/V sliced into slots on the way) and the reuse pass
+    on the last rows, both against the oracle's two-layer stack; then GPU reuse against GPU full on the same rows."""
+    H, Hq, Hkv, D, F, C, n_c, Tf, L = 256, 4, 2, 64, 448, 64, 3, 40, 2
+    total = n_c * C + Tf
+    h0 = wl.round_bf16(np.random.default_rng(9).standard_normal((total, H)).astype(np.float32))
+    Ws = [wl.stack_weights(9, l, H, Hq, Hkv, D, F) for l in range(L)]
+    layers = dev_layers(Ws)
+    pc = Percache(n_layers=L, hidden=H, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=D, n_slots=8, slot_capacity=C,
+                  max_pos=total, device=DEV)
+    # oracle: full pass, K/V per layer
+    h = h0
+    stores = []
+    for W in Ws:
+        h, K, V = oracle_block(h, W, Hq, Hkv, D, 10000.0)
+        stores.append((np.stack([K[:, c * C:(c + 1) * C] for c in range(n_c)]), np.stack([V[:, c * C:(c + 1) * C] for c in range(n_c)])))
+    ref_full = h
+    # GPU population pass
+    slots = [6, 1, 4]
+    bounds = [c * C for c in range(n_c + 1)] + [total]
+    full = pc.percache_stack_reuse(layers, F, EPS, bf16(h0[None]), save_bounds=bounds, save_slots=[slots + [-1]])
+    torch.cuda.synchronize()
+    check_hidden(host(full[0]), ref_full, "population pass, all rows")
+    for l in range(L):
+        for c, s in enumerate(slots):
+            assert pc.percache_kv_len(l, s) == C
+            kk, vv = pc.percache_kv_get(l, s)
+            torch.cuda.synchronize()
+            check_hidden(host(kk), stores[l][0][c], f"sliced K layer {l} chunk {c}", rel_max=2.0 ** -6)
+            check_hidden(host(vv), stores[l][1][c], f"sliced V layer {l} chunk {c}", rel_max=2.0 ** -6)
+    # GPU reuse pass on the fresh rows, from the GPU-made cache
+    reuse = pc.percache_stack_reuse(layers, F, EPS, bf16(h0[None, n_c * C:]), [slots])
+    torch.cuda.synchronize()
+    check_hidden(host(reuse[0]), ref_full[n_c * C:], "reuse pass vs oracle full recompute")
+    check_hidden(host(reuse[0]), host(full[0, n_c * C:]), "reuse pass vs population pass (GPU)")
+    # error paths: a save slot that the call also reads; differing lengths between layers
+    with pytest.raises(PercacheError) as e:
+        pc.percache_stack_reuse(layers, F, EPS, bf16(h0[None, n_c * C:]), [slots], save_bounds=[0, Tf], save_slots=[[6]])
+    assert e.value.status == -1
+    pc.percache_kv_evict(1, 4)
+    with pytest.raises(PercacheError) as e:
+        pc.percache_stack_reuse(layers, F, EPS, bf16(h0[None, n_c * C:]), [slots])
+    assert e.value.status == -3
+
+
+def test_config2_full_size_reuse_equals_full_recompute():
+    """28-layer Qwen3-0.6B-shaped stack, 8 chunks x 512 cached + 128 fresh tokens.  The GPU's own full prefill of the
+    4224-token prompt fills the cache (slicer); the reuse pass over the last 128 rows must reproduce the full pass's
+    rows.  The oracle checks layer 0 of the full pass on sampled rows (deeper layers are covered at reduced size)."""
+    w = wl.config2(n_slots=16)
+    F, L, C, n_c, Tf = 3072, w.n_layers, w.chunk_tokens, w.n_chunks, w.t_fresh
+    total = n_c * C + Tf
+    h0 = wl.round_bf16(np.random.default_rng(2).standard_normal((total, w.hidden)).astype(np.float32))
+    Ws = [wl.stack_weights(2, l, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, F) for l in range(L)]
+    layers = dev_layers(Ws)
+    pc = Percache(n_layers=L, hidden=w.hidden, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
+                  n_slots=16, slot_capacity=C, max_pos=total, device=DEV)
+    slots = [int(s) for s in w.slot_ids[0]]
+    bounds = [c * C for c in range(n_c + 1)] + [total]
+    h_dev = bf16(h0[None])
+    one = pc.percache_stack_reuse(layers[:1], F, EPS, h_dev)
+    full = pc.percache_stack_reuse(layers, F, EPS, h_dev, save_bounds=bounds, save_slots=[slots + [-1]])
+    reuse = pc.percache_stack_reuse(layers, F, EPS, h_dev[:, n_c * C:].contiguous(), [slots])
+    torch.cuda.synchronize()
+    check_hidden(host(reuse[0]), host(full[0, n_c * C:]), "cfg2: reuse vs full recompute after 28 layers", rel_max=2.0 ** -5, rel_fro=2e-2)
+    # layer 0 of the full pass against the oracle on the first 96 rows (causal: they depend on nothing later)
+    ref, _, _ = oracle_block(h0[:96], Ws[0], w.n_q_heads, w.n_kv_heads, w.head_dim, w.rope_theta)
+    check_hidden(host(one[0, :96]), ref, "cfg2: layer 0 of the full pass, rows 0..95")
