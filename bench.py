@@ -49,6 +49,68 @@ def attention_flops(B, Hq, D, T, l_pre):
     return float(sum(4.0 * Hq * D * T * (lp + (T + 1) / 2.0) for lp in l_pre))
 
 
+def _wall_ms(torch, fn, iters, warmup):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    a = time.perf_counter()
+    for _ in range(iters):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - a) * 1e3 / iters
+
+
+def bench_cfg1(torch, wl, binding, Percache, dev, bf):
+    """One 0.6B-shaped layer, batch 1, 4 x 512 cached + 64 fresh tokens: bound by the K/V stream and launch latency."""
+    w = wl.config1()
+    pc = Percache(n_layers=1, hidden=w.hidden, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
+                  n_slots=w.n_slots, slot_capacity=w.chunk_tokens, max_pos=w.max_pos, rope_theta=w.rope_theta, device=dev)
+    for s_, (k, v) in w.slots_kv(sorted(set(int(x) for x in w.slot_ids.reshape(-1)))).items():
+        pc.percache_kv_put(0, s_, bf(k), bf(v))
+    X, W = bf(w.X), bf(w.Wqkv)
+    out = torch.empty((1, w.t_fresh, w.n_q_heads * w.head_dim), dtype=torch.bfloat16, device=dev)
+    fn = lambda: pc.percache_prefill_reuse(0, X, W, w.slot_ids, w.used_len, attn_out=out)
+    _wall_ms(torch, fn, 20, 10)
+    pc.percache_profile_enable(True)
+    ms = _wall_ms(torch, fn, 100, 0)
+    ms_attn, n_attn = pc.percache_profile_read(binding.KERNEL_ATTENTION)
+    ms_qkv, n_qkv = pc.percache_profile_read(binding.KERNEL_QKV_ROPE)
+    pc.percache_profile_enable(False)
+    pc.close()
+    kv_bytes = float(w.l_pre[0]) * w.n_kv_heads * w.head_dim * 2 * 2
+    w_bytes = float(w.Wqkv.size) * 2
+    return {"ms_per_call": round(ms, 4), "fresh_tokens_per_s": round(w.t_fresh / (ms * 1e-3), 1),
+            "attention_ms": round(ms_attn / n_attn, 4), "kv_stream_GBps": round(kv_bytes / (ms_attn / n_attn * 1e-3) / 1e9, 1),
+            "qkv_rope_ms": round(ms_qkv / n_qkv, 4), "weight_stream_GBps": round(w_bytes / (ms_qkv / n_qkv * 1e-3) / 1e9, 1)}
+
+
+def bench_cfg2(torch, wl, Percache, dev, bf):
+    """28-layer 0.6B-shaped stack: reuse of 8 x 512 cached tokens + 128 fresh rows against the full prefill of all
+    4224 tokens (same kernels, no chunks).  The cache is filled by the full pass itself (slicer)."""
+    w = wl.config2()
+    F, L, C, n_c, Tf = 3072, w.n_layers, w.chunk_tokens, w.n_chunks, w.t_fresh
+    total = n_c * C + Tf
+    pc = Percache(n_layers=L, hidden=w.hidden, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
+                  n_slots=w.n_slots, slot_capacity=C, max_pos=total, rope_theta=w.rope_theta, device=dev)
+    layers = []
+    for l in range(L):
+        W = wl.stack_weights(2, l, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, F)
+        layers.append(dict(gain1=bf(W.gain1), wqkv=bf(W.Wqkv), wo=bf(W.Wo), gain2=bf(W.gain2), w_gate=bf(W.Wgate),
+                           w_up=bf(W.Wup), w_down=bf(W.Wdown)))
+    h0 = bf(np.random.default_rng(2).standard_normal((1, total, w.hidden)).astype(np.float32))
+    slots = [int(x) for x in w.slot_ids[0]]
+    bounds = [c * C for c in range(n_c + 1)] + [total]
+    h_full = torch.empty_like(h0)
+    pc.percache_stack_reuse(layers, F, 1e-6, h0, save_bounds=bounds, save_slots=[slots + [-1]], h_out=h_full)
+    hf = h0[:, n_c * C:].contiguous()
+    h_reuse = torch.empty_like(hf)
+    reuse_ms = _wall_ms(torch, lambda: pc.percache_stack_reuse(layers, F, 1e-6, hf, [slots], h_out=h_reuse), 20, 5)
+    full_ms = _wall_ms(torch, lambda: pc.percache_stack_reuse(layers, F, 1e-6, h0, h_out=h_full), 5, 2)
+    pc.close()
+    return {"reuse_ms": round(reuse_ms, 3), "full_recompute_ms": round(full_ms, 3), "speedup": round(full_ms / reuse_ms, 2),
+            "fresh_tokens_per_s": round(Tf / (reuse_ms * 1e-3), 1), "layers": L, "cached_tokens": n_c * C, "fresh_tokens": Tf}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -56,6 +118,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
     ap.add_argument("--bank-rows", type=int, default=200_000)
+    ap.add_argument("--no-extra", action="store_true", help="skip the config 1 / config 2 side measurements")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (a kernel of known traffic to scale HBM byte counters by)")
     args = ap.parse_args()
@@ -177,6 +240,15 @@ def main():
         },
     }
 
+    # ------------------------------------------------------------------ side measurements: config 1 layer, config 2 stack
+    if not args.no_extra:
+        pc.close()
+        del pc
+        torch.cuda.empty_cache()
+        out["breakdown"]["cfg1_layer"] = bench_cfg1(torch, wl, binding, Percache, dev, bf)
+        out["breakdown"]["cfg2_stack"] = bench_cfg2(torch, wl, Percache, dev, bf)
+        pc = None
+
     # ------------------------------------------------------------------ CPU oracle on a bounded sample
     if not args.no_cpu_baseline:
         import oracle
@@ -212,7 +284,8 @@ def main():
                       f"value = {T} tokens / (prefill seconds per query + lookup seconds per probe)",
         }
     print(json.dumps(out))
-    pc.close()
+    if pc is not None:
+        pc.close()
 
 
 if __name__ == "__main__":
