@@ -122,17 +122,27 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
     for (int r = 0; r < 16; ++r) o_acc[db][r] = 0.f;
   float m_ref = -INFINITY, l_run = 0.f;  // m_ref: reference exponent (scaled, log2 domain)
 
-  // ---- tile cursor over the chunk list
-  int cur_chunk = 0, cur_off = 0;  // chunk index, tile index inside the chunk (or inside the fresh part)
+  // ---- tile cursor over the chunk list.  The chunk's slot id and used length are kept in (scalar) registers and
+  // re-read from the table only when the cursor enters another chunk.
+  struct Cursor { int chunk, off, slot, used; };  // chunk index, tile index inside the chunk (or the fresh part)
+  auto enter_chunk = [&](Cursor &c) __attribute__((always_inline)) {
+    while (c.chunk < n_chunks && trow[kTblHeader + 2 * c.chunk + 1] == 0) ++c.chunk;  // unused chunks
+    if (c.chunk < n_chunks) {
+      c.slot = trow[kTblHeader + 2 * c.chunk];
+      c.used = trow[kTblHeader + 2 * c.chunk + 1];
+    }
+  };
+  Cursor cur = {0, 0, 0, 0};
   {
     int rem = tile_begin;
-    while (cur_chunk < n_chunks) {
-      int ntc = (trow[kTblHeader + 2 * cur_chunk + 1] + TK - 1) / TK;
+    while (cur.chunk < n_chunks) {
+      int ntc = (trow[kTblHeader + 2 * cur.chunk + 1] + TK - 1) / TK;
       if (rem < ntc) break;
       rem -= ntc;
-      ++cur_chunk;
+      ++cur.chunk;
     }
-    cur_off = rem;
+    cur.off = rem;
+    enter_chunk(cur);
   }
 
   // ---- direct global -> LDS staging of one tile.  Wavefront instruction i writes bytes [1024 i, 1024 i + 1024)
@@ -163,33 +173,29 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
 #pragma unroll
   for (int c4 = 0; c4 < 4; ++c4) v_rd[c4] = ((2 * c4 + g2) ^ swz<L::V_ROW>(l32)) * 16;
   struct TileDesc { const __bf16 *k, *v; int valid; int t0; bool fresh; };
-  auto describe = [&](int chunk, int off, TileDesc &td) __attribute__((always_inline)) {
-    if (chunk < n_chunks) {
-      int slot = trow[kTblHeader + 2 * chunk], used = trow[kTblHeader + 2 * chunk + 1];
-      size_t base = (((size_t)slot * Hkv + gkv) * C + (size_t)off * TK) * D;  // same offset in both layouts
+  auto describe = [&](const Cursor &c, TileDesc &td) __attribute__((always_inline)) {
+    if (c.chunk < n_chunks) {
+      size_t base = (((size_t)c.slot * Hkv + gkv) * C + (size_t)c.off * TK) * D;  // same offset in both layouts
       td.k = k_store + base;
       td.v = v_store + base;
-      td.valid = min(TK, used - off * TK);
+      td.valid = min(TK, c.used - c.off * TK);
       td.t0 = 0;
       td.fresh = false;
     } else {
       const int ft = (T + TK - 1) / TK;
-      td.k = Kf + (((size_t)b * Hkv + gkv) * T + (size_t)off * TK) * D;
-      td.v = Vf_blk + (((size_t)b * Hkv + gkv) * ft + off) * (size_t)(TK * D);
-      td.valid = min(TK, T - off * TK);
-      td.t0 = off * TK;
+      td.k = Kf + (((size_t)b * Hkv + gkv) * T + (size_t)c.off * TK) * D;
+      td.v = Vf_blk + (((size_t)b * Hkv + gkv) * ft + c.off) * (size_t)(TK * D);
+      td.valid = min(TK, T - c.off * TK);
+      td.t0 = c.off * TK;
       td.fresh = true;
     }
   };
-  auto advance = [&](int &chunk, int &off) __attribute__((always_inline)) {
-    ++off;
-    if (chunk < n_chunks) {
-      int ntc = (trow[kTblHeader + 2 * chunk + 1] + TK - 1) / TK;
-      if (off >= ntc) {
-        off = 0;
-        ++chunk;
-        while (chunk < n_chunks && trow[kTblHeader + 2 * chunk + 1] == 0) ++chunk;  // unused chunks
-      }
+  auto advance = [&](Cursor &c) __attribute__((always_inline)) {
+    ++c.off;
+    if (c.chunk < n_chunks && c.off * TK >= c.used) {
+      c.off = 0;
+      ++c.chunk;
+      enter_chunk(c);
     }
   };
   auto fetch_tile = [&](const TileDesc &td, int st) __attribute__((always_inline)) {
@@ -210,18 +216,16 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
   // the top of iteration t into the stage that iteration t-1 finished reading (the barrier at its end says so).
   // At the end of iteration t the loads of tile t+1 must have landed: they are the oldest outstanding ones, so
   // waiting until at most (AHEAD-1) tiles' worth of loads remain is enough; then one barrier publishes them.
-  // Two cursors walk the chunk list: (cur_chunk, cur_off) for the tile being fetched, (cmp_chunk, cmp_off) for
-  // the one being computed.
-  while (cur_chunk < n_chunks && trow[kTblHeader + 2 * cur_chunk + 1] == 0) ++cur_chunk;
-  int cmp_chunk = cur_chunk, cmp_off = cur_off;
+  // Two cursors walk the chunk list: cur for the tile being fetched, cmp for the one being computed.
+  Cursor cmp = cur;
   int fetched = tile_begin;  // next tile to fetch
 #pragma unroll
   for (int k = 0; k < AHEAD; ++k) {
     if (fetched < tile_end) {
       TileDesc t0d;
-      describe(cur_chunk, cur_off, t0d);
+      describe(cur, t0d);
       fetch_tile(t0d, k);
-      advance(cur_chunk, cur_off);
+      advance(cur);
       ++fetched;
     }
   }
@@ -237,14 +241,14 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
     const bool has_next = fetched < tile_end;
     if (has_next) {
       TileDesc nxt;
-      describe(cur_chunk, cur_off, nxt);
+      describe(cur, nxt);
       fetch_tile(nxt, in_stage);
-      advance(cur_chunk, cur_off);
+      advance(cur);
       ++fetched;
     }
-    TileDesc cur;
-    describe(cmp_chunk, cmp_off, cur);
-    advance(cmp_chunk, cmp_off);
+    TileDesc td;
+    describe(cmp, td);
+    advance(cmp);
     const char *kb = lds + buf * L::STAGE;
     const char *vb = kb + L::K_BYTES;
 
@@ -263,13 +267,13 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
     }
 
     // ---- mask: only tiles with a ragged end or in the causal part take this path (wave-uniform test)
-    if (cur.valid < TK || cur.fresh) {
+    if (td.valid < TK || td.fresh) {
 #pragma unroll
       for (int kbk = 0; kbk < 2; ++kbk)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           int t = kbk * 32 + (r >> 2) * 8 + g2 * 4 + (r & 3);
-          bool vis = t < cur.valid && (!cur.fresh || cur.t0 + t <= my_i);
+          bool vis = t < td.valid && (!td.fresh || td.t0 + t <= my_i);
           s_acc[kbk][r] = vis ? s_acc[kbk][r] : -INFINITY;
         }
     }
@@ -280,10 +284,11 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
     for (int kbk = 0; kbk < 2; ++kbk)
 #pragma unroll
       for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s_acc[kbk][r]);
-    mx = pair_max(mx);
-    const float mc = mx * scale_log2e;
-    const bool upd = mc > m_ref + kLazy;  // also true for the first finite tile (m_ref = -inf)
-    if (__builtin_amdgcn_ballot_w64(upd) != 0) {
+    // m_ref is common to the two lanes of a row: if neither lane's own keys exceed it by kLazy, nor does the row,
+    // so the common path needs no exchange between the lanes
+    if (__builtin_amdgcn_ballot_w64(mx * scale_log2e > m_ref + kLazy) != 0) {
+      const float mc = pair_max(mx) * scale_log2e;
+      const bool upd = mc > m_ref + kLazy;  // also true for the first finite tile (m_ref = -inf)
       const float alpha = upd ? fast_exp2(m_ref - mc) : 1.0f;  // m_ref = -inf gives 0
       m_ref = upd ? mc : m_ref;
       l_run *= alpha;
