@@ -62,7 +62,7 @@ __global__ __launch_bounds__(256, 2) void linear_residual_kernel(const __bf16 *_
   const int l32 = lane & 31, g = lane >> 5;
   const int f0 = blockIdx.x * BF, m0 = blockIdx.y * BT;
   f32x16 acc[2][NTB];
-  pc::gemm::mainloop<NTB>(lds, [&](int row) __attribute__((always_inline)) { return W + (size_t)(f0 + row) * K; }, A, m0, M,
+  pc::gemm::mainloop<NTB>(lds, [&](int row) __attribute__((always_inline)) { return W + (size_t)(f0 + row) * K; }, A, K, m0, M,
                           K, 2 * wf, 2 * wf + 1, acc);
 #pragma unroll
   for (int t = 0; t < NTB; ++t) {
@@ -99,7 +99,7 @@ __global__ __launch_bounds__(256, 2) void linear_swiglu_kernel(const __bf16 *__r
   const int f0 = blockIdx.x * (BF / 2), m0 = blockIdx.y * BT;
   f32x16 acc[2][NTB];
   pc::gemm::mainloop<NTB>(
-      lds, [&](int row) __attribute__((always_inline)) { return (row < 64 ? Wg : Wu) + (size_t)(f0 + (row & 63)) * K; }, A, m0, M, K,
+      lds, [&](int row) __attribute__((always_inline)) { return (row < 64 ? Wg : Wu) + (size_t)(f0 + (row & 63)) * K; }, A, K, m0, M, K,
       wf, wf + 2, acc);
 #pragma unroll
   for (int t = 0; t < NTB; ++t) {
@@ -117,6 +117,109 @@ __global__ __launch_bounds__(256, 2) void linear_swiglu_kernel(const __bf16 *__r
       if (ok) *(uint2 *)(Y + (size_t)m * F + f0 + wf * 32 + q4 * 8 + g * 4) = pack4(o[0], o[1], o[2], o[3]);
     }
   }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Few token rows (one or two token tiles): the projections are bound by the stream of the weights, and N/128
+// workgroups cannot pull it.  The contraction is therefore cut into n_k slices computed by separate workgroups:
+//   P[s][m][n] = sum over k in slice s of A[m][k] W[n][k]     (fp32, [n_k][M][N])
+// and a small second kernel adds the slices in a fixed order (deterministic) and applies the epilogue.
+// The weight rows may come from two matrices (rows >= n_split from W1): gate and up projections in one launch.
+// ---------------------------------------------------------------------------------------------------
+template <int NTB>
+__global__ __launch_bounds__(256, 2) void splitk_partial_kernel(const __bf16 *__restrict__ A, int lda,
+                                                                const __bf16 *__restrict__ W0, const __bf16 *__restrict__ W1,
+                                                                int n_split, int ldw, float *__restrict__ P, int M, int N,
+                                                                int k_slice) {
+  constexpr int BT = 64 * NTB;
+  __shared__ __align__(16) char lds[pc::gemm::Shape<NTB>::LDS_BYTES];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wf = wave & 1, wt = wave >> 1;
+  const int l32 = lane & 31, g = lane >> 5;
+  const int f0 = blockIdx.x * BF, m0 = blockIdx.z * BT;
+  const int k0 = blockIdx.y * k_slice;
+  f32x16 acc[2][NTB];
+  pc::gemm::mainloop<NTB>(
+      lds,
+      [&](int row) __attribute__((always_inline)) {
+        const int n = f0 + row;
+        return (n < n_split ? W0 + (size_t)n * ldw : W1 + (size_t)(n - n_split) * ldw) + k0;
+      },
+      A + k0, lda, m0, M, k_slice, 2 * wf, 2 * wf + 1, acc);
+  float *Ps = P + (size_t)blockIdx.y * M * N;
+#pragma unroll
+  for (int t = 0; t < NTB; ++t) {
+    const int m_raw = m0 + (wt * NTB + t) * 32 + l32;
+    const bool ok = m_raw < M;
+    const int m = ok ? m_raw : M - 1;
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const float4 v = {acc[a][t][q4 * 4 + 0], acc[a][t][q4 * 4 + 1], acc[a][t][q4 * 4 + 2], acc[a][t][q4 * 4 + 3]};
+        if (ok) *(float4 *)(Ps + (size_t)m * N + f0 + (2 * wf + a) * 32 + q4 * 8 + g * 4) = v;
+      }
+  }
+}
+
+// y = sum of slices + residual (rounded to bf16), and optionally n = RMSNorm(y) * gain on the rounded values.
+// One workgroup per row, four columns per thread and pass.
+__global__ __launch_bounds__(256) void reduce_residual_norm_kernel(const float *__restrict__ P, int n_k, int M, int N,
+                                                                   const __bf16 *__restrict__ R, __bf16 *__restrict__ Y,
+                                                                   const __bf16 *__restrict__ gain, __bf16 *__restrict__ Yn,
+                                                                   float eps) {
+  __shared__ float red[4];
+  const int row = blockIdx.x, tid = threadIdx.x;
+  const size_t slice = (size_t)M * N;
+  float ss = 0.f;
+  for (int c = tid * 4; c < N; c += 1024) {
+    const size_t at = (size_t)row * N + c;
+    float4 sum = *(const float4 *)(P + at);
+#pragma unroll 4
+    for (int s = 1; s < n_k; ++s) {
+      const float4 v = *(const float4 *)(P + s * slice + at);
+      sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+    }
+    float res[4];
+    unpack4(*(const uint2 *)(R + at), res);
+    const uint2 packed = pack4(sum.x + res[0], sum.y + res[1], sum.z + res[2], sum.w + res[3]);
+    *(uint2 *)(Y + at) = packed;
+    float y[4];
+    unpack4(packed, y);
+    ss += y[0] * y[0] + y[1] * y[1] + y[2] * y[2] + y[3] * y[3];
+  }
+  if (!gain) return;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
+  if ((tid & 63) == 0) red[tid >> 6] = ss;
+  __syncthreads();
+  const float r = 1.0f / sqrtf((red[0] + red[1] + red[2] + red[3]) / (float)N + eps);
+  for (int c = tid * 4; c < N; c += 1024) {
+    const size_t at = (size_t)row * N + c;
+    float y[4], gq[4];
+    unpack4(*(const uint2 *)(Y + at), y);  // this thread's own stores
+    unpack4(*(const uint2 *)(gain + c), gq);
+    *(uint2 *)(Yn + at) = pack4(y[0] * r * gq[0], y[1] * r * gq[1], y[2] * r * gq[2], y[3] * r * gq[3]);
+  }
+}
+
+// act[m][f] = silu(sum of gate slices) * (sum of up slices); slices are [n_k][M][2F] with the up half at column F.
+__global__ __launch_bounds__(256) void reduce_swiglu_kernel(const float *__restrict__ P, int n_k, int M, int F,
+                                                            __bf16 *__restrict__ Y) {
+  const long gid = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  const int per_row = F / 4;
+  if (gid >= (long)M * per_row) return;
+  const int m = (int)(gid / per_row), f = (int)(gid - (long)m * per_row) * 4;
+  const size_t slice = (size_t)M * 2 * F, at = (size_t)m * 2 * F + f;
+  float4 gt = *(const float4 *)(P + at), up = *(const float4 *)(P + at + F);
+#pragma unroll 4
+  for (int s = 1; s < n_k; ++s) {
+    const float4 a = *(const float4 *)(P + s * slice + at), b = *(const float4 *)(P + s * slice + at + F);
+    gt.x += a.x; gt.y += a.y; gt.z += a.z; gt.w += a.w;
+    up.x += b.x; up.y += b.y; up.z += b.z; up.w += b.w;
+  }
+  *(uint2 *)(Y + (size_t)m * F + f) = pack4(gt.x / (1.0f + __expf(-gt.x)) * up.x, gt.y / (1.0f + __expf(-gt.y)) * up.y,
+                                            gt.z / (1.0f + __expf(-gt.z)) * up.z, gt.w / (1.0f + __expf(-gt.w)) * up.w);
 }
 
 bool aligned16(const void *p) { return ((uintptr_t)p % 16) == 0; }
@@ -146,6 +249,19 @@ pc_status launch_linear_swiglu(percache_ctx *ctx, const __bf16 *a, const __bf16 
   return PC_OK;
 }
 
+pc_status launch_reduce_residual_norm(percache_ctx *ctx, const float *part, int n_k, int M, int N, const __bf16 *res, __bf16 *y,
+                                      const __bf16 *gain, __bf16 *yn, float eps, hipStream_t s) {
+  hipLaunchKernelGGL(reduce_residual_norm_kernel, dim3(M), dim3(256), 0, s, part, n_k, M, N, res, y, gain, yn, eps);
+  PC_HIP(ctx, hipGetLastError());
+  return PC_OK;
+}
+pc_status launch_reduce_swiglu(percache_ctx *ctx, const float *part, int n_k, int M, int F, __bf16 *y, hipStream_t s) {
+  const long threads = (long)M * (F / 4);
+  hipLaunchKernelGGL(reduce_swiglu_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, part, n_k, M, F, y);
+  PC_HIP(ctx, hipGetLastError());
+  return PC_OK;
+}
+
 // Workspace of the stack call: the prefill workspace followed by the block's own activations.
 struct StackWs {
   pc::PrefillWs pf;
@@ -153,6 +269,7 @@ struct StackWs {
   __bf16 *attn;    // [M, Hq*D]
   __bf16 *mid;     // [M, H]
   __bf16 *act;     // [M, F]
+  float *part;     // split-k slices of the block projections (few token rows only)
   size_t total;
 };
 StackWs carve_stack_ws(const percache_ctx *ctx, void *base, int batch, int t_fresh, int max_chunks, int ffn) {
@@ -167,11 +284,41 @@ StackWs carve_stack_ws(const percache_ctx *ctx, void *base, int batch, int t_fre
   w.attn = take(M * c.n_q_heads * c.head_dim * 2);
   w.mid = take(M * c.hidden * 2);
   w.act = take(M * ffn * 2);
+  const size_t widest = (size_t)(2 * ffn > c.hidden ? 2 * ffn : c.hidden);
+  w.part = (float *)take(pc::splitk_applies((int)M) ? (size_t)pc::kMaxSplitK * M * widest * sizeof(float) : 0);
   w.total = off;
   return w;
 }
 
 }  // namespace
+
+namespace pc {
+
+// Largest number of slices that divides the k steps, leaves every workgroup at least two of them and keeps the
+// launch within two workgroups per CU.
+int choose_split_k(int n_cu, int n_tiles, int k_steps) {
+  int best = 1;
+  for (int d = 1; d <= kMaxSplitK; ++d)
+    if (k_steps % d == 0 && k_steps / d >= 2 && (long)n_tiles * d <= 2L * n_cu) best = d;
+  return best;
+}
+
+pc_status launch_splitk_partial(percache_ctx *ctx, const __bf16 *a, int lda, const __bf16 *w0, const __bf16 *w1, int n_split,
+                                int ldw, float *part, int M, int N, int K, int n_k, hipStream_t stream) {
+  if (N % BF || n_split % BF || K % (pc::gemm::BK * n_k)) return fail(ctx, PC_ESHAPE, "split-k projection: N %d, K %d, slices %d", N, K, n_k);
+  const int k_slice = K / n_k;
+  if (M > 64) {
+    dim3 grid(N / BF, n_k, (M + 127) / 128);
+    hipLaunchKernelGGL(splitk_partial_kernel<2>, grid, dim3(256), 0, stream, a, lda, w0, w1, n_split, ldw, part, M, N, k_slice);
+  } else {
+    dim3 grid(N / BF, n_k, 1);
+    hipLaunchKernelGGL(splitk_partial_kernel<1>, grid, dim3(256), 0, stream, a, lda, w0, w1, n_split, ldw, part, M, N, k_slice);
+  }
+  PC_HIP(ctx, hipGetLastError());
+  return PC_OK;
+}
+
+}  // namespace pc
 
 extern "C" {
 
@@ -275,8 +422,11 @@ pc_status percache_stack_reuse(percache_ctx *ctx, const percache_block_weights *
   for (int l = 0; l < n_layers; ++l) {
     const percache_block_weights &w = layers_host[l];
 #define PC_TRY(call) do { st = (call); if (st != PC_OK) return st; } while (0)
-    PC_TRY(launch_rmsnorm(ctx, h_cur, (const __bf16 *)w.gain1, ws.normed, (int)M, H, eps, s));
-    PC_TRY(pc::launch_qkv_rope(ctx, ws.normed, (const __bf16 *)w.wqkv, batch, t_fresh, ws.pf.table, stride, ws.pf.q, ws.pf.k, ws.pf.v, s));
+    // few token rows: split-k projections, whose reduce kernels also apply the residual and the next RMSNorm
+    const bool skinny = pc::splitk_applies(M) && ffn % BF == 0;
+    if (!skinny || l == 0) PC_TRY(launch_rmsnorm(ctx, h_cur, (const __bf16 *)w.gain1, ws.normed, (int)M, H, eps, s));
+    PC_TRY(pc::launch_qkv_rope(ctx, ws.normed, (const __bf16 *)w.wqkv, batch, t_fresh, ws.pf.table, stride, ws.pf.q, ws.pf.k, ws.pf.v, s,
+                               skinny ? ws.pf.gemm_part : nullptr));
     PC_TRY(pc::launch_v_repack(ctx, ws.pf.v, ws.pf.v_blk, batch, t_fresh, s));
     PC_TRY(pc::launch_attention(ctx, l, ws.pf.q, ws.pf.k, ws.pf.v_blk, batch, t_fresh, ws.pf.table, stride, min_tiles, 0, ws.attn,
                                 ws.pf.part_o, ws.pf.part_ml, s));
@@ -289,10 +439,24 @@ pc_status percache_stack_reuse(percache_ctx *ctx, const percache_block_weights *
         PC_TRY(pc::launch_kv_store(ctx, l, slot, ws.pf.k + at, ws.pf.v + at, cnt, (long)t_fresh * c.head_dim, s));
         ctx->slot_len[(size_t)l * c.n_slots + slot] = cnt;
       }
-    PC_TRY(launch_linear_residual(ctx, ws.attn, (const __bf16 *)w.wo, h_cur, ws.mid, (int)M, H, A, s));
-    PC_TRY(launch_rmsnorm(ctx, ws.mid, (const __bf16 *)w.gain2, ws.normed, (int)M, H, eps, s));
-    PC_TRY(launch_linear_swiglu(ctx, ws.normed, (const __bf16 *)w.w_gate, (const __bf16 *)w.w_up, ws.act, (int)M, ffn, H, s));
-    PC_TRY(launch_linear_residual(ctx, ws.act, (const __bf16 *)w.w_down, ws.mid, h_out, (int)M, H, ffn, s));
+    if (skinny) {
+      const int m_tiles = M > 128 ? 2 : 1;
+      const __bf16 *next_gain = l + 1 < n_layers ? (const __bf16 *)layers_host[l + 1].gain1 : nullptr;
+      int nk = pc::choose_split_k(ctx->n_cu, H / BF * m_tiles, A / pc::gemm::BK);
+      PC_TRY(pc::launch_splitk_partial(ctx, ws.attn, A, (const __bf16 *)w.wo, (const __bf16 *)w.wo, H, A, ws.part, (int)M, H, A, nk, s));
+      PC_TRY(launch_reduce_residual_norm(ctx, ws.part, nk, (int)M, H, h_cur, ws.mid, (const __bf16 *)w.gain2, ws.normed, eps, s));
+      nk = pc::choose_split_k(ctx->n_cu, 2 * ffn / BF * m_tiles, H / pc::gemm::BK);
+      PC_TRY(pc::launch_splitk_partial(ctx, ws.normed, H, (const __bf16 *)w.w_gate, (const __bf16 *)w.w_up, ffn, H, ws.part, (int)M, 2 * ffn, H, nk, s));
+      PC_TRY(launch_reduce_swiglu(ctx, ws.part, nk, (int)M, ffn, ws.act, s));
+      nk = pc::choose_split_k(ctx->n_cu, H / BF * m_tiles, ffn / pc::gemm::BK);
+      PC_TRY(pc::launch_splitk_partial(ctx, ws.act, ffn, (const __bf16 *)w.w_down, (const __bf16 *)w.w_down, H, ffn, ws.part, (int)M, H, ffn, nk, s));
+      PC_TRY(launch_reduce_residual_norm(ctx, ws.part, nk, (int)M, H, ws.mid, h_out, next_gain, ws.normed, eps, s));
+    } else {
+      PC_TRY(launch_linear_residual(ctx, ws.attn, (const __bf16 *)w.wo, h_cur, ws.mid, (int)M, H, A, s));
+      PC_TRY(launch_rmsnorm(ctx, ws.mid, (const __bf16 *)w.gain2, ws.normed, (int)M, H, eps, s));
+      PC_TRY(launch_linear_swiglu(ctx, ws.normed, (const __bf16 *)w.w_gate, (const __bf16 *)w.w_up, ws.act, (int)M, ffn, H, s));
+      PC_TRY(launch_linear_residual(ctx, ws.act, (const __bf16 *)w.w_down, ws.mid, h_out, (int)M, H, ffn, s));
+    }
 #undef PC_TRY
     h_cur = h_out;
   }

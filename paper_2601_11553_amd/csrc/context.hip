@@ -149,6 +149,8 @@ PrefillWs carve_prefill_ws(const percache_config &c, int n_cu, void *base, int32
   w.k = (__bf16 *)take(kn * 2);
   w.v = (__bf16 *)take(kn * 2);
   w.v_blk = (__bf16 *)take((size_t)batch * c.n_kv_heads * ((t_fresh + kKvTile - 1) / kKvTile) * kKvTile * c.head_dim * 2);
+  const size_t M = (size_t)batch * t_fresh;
+  w.gemm_part = (float *)take(splitk_applies((long)M) ? (size_t)kMaxSplitK * M * (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim * sizeof(float) : 0);
   size_t rows = (size_t)batch * c.n_q_heads * t_fresh;
   w.max_splits = max_splits_for(c, n_cu, batch, t_fresh);
   w.part_o = (__bf16 *)take(rows * w.max_splits * c.head_dim * 2);

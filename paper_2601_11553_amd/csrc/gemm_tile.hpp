@@ -41,12 +41,14 @@ __device__ __forceinline__ void unpack4(uint2 raw, float (&o)[4]) {
   for (int e = 0; e < 4; ++e) o[e] = (float)v[e];
 }
 
-// w_row(r): pointer to the K contiguous elements of the weight row that tile row r (0..127) stands for.
-// X: [M, K] row-major, the tile covers token rows m0 .. m0 + BT - 1 (clamped to M - 1 when reading).
+// w_row(r): pointer to the first of the K contiguous elements of the weight row that tile row r (0..127) stands
+// for (already advanced to the start of the k range when only a slice of the contraction is computed).
+// X: token rows of ldx elements, pointing at the first element of the k range; the tile covers token rows
+// m0 .. m0 + BT - 1 (clamped to M - 1 when reading); K elements are contracted.
 // On return acc[a][t] holds features (a ? fb_hi : fb_lo) * 32 + (r/4)*8 + 4*(lane/32) + r%4 of token
 // m0 + (wt*NTB + t)*32 + lane%32 in element r.
 template <int NTB, class WRow>
-__device__ __forceinline__ void mainloop(char *lds, WRow w_row, const __bf16 *__restrict__ X, int m0, int M, int K,
+__device__ __forceinline__ void mainloop(char *lds, WRow w_row, const __bf16 *__restrict__ X, int ldx, int m0, int M, int K,
                                          int fb_lo, int fb_hi, f32x16 (&acc)[2][NTB]) {
   using S = Shape<NTB>;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -65,7 +67,7 @@ __device__ __forceinline__ void mainloop(char *lds, WRow w_row, const __bf16 *__
 #pragma unroll
   for (int k = 0; k < S::X_INSTR; ++k) {
     const int row = (wave + k * NW) * 8 + (lane >> 3);
-    x_src[k] = X + (size_t)min(m0 + row, M - 1) * K + (((lane & 7) ^ swz128(row)) * 8);
+    x_src[k] = X + (size_t)min(m0 + row, M - 1) * ldx + (((lane & 7) ^ swz128(row)) * 8);
   }
   auto fetch = [&](int kt, int st) __attribute__((always_inline)) {
     char *base = lds + st * S::STAGE;

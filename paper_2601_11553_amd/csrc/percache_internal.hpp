@@ -96,6 +96,7 @@ struct PrefillWs {
   int32_t *table;
   __bf16 *q, *k, *v;
   __bf16 *v_blk;   // fresh V as 64-key blocks [B*Hkv][ceil(T/64)][D][64]
+  float *gemm_part;  // split-k slices of the QKV projection (few token rows only), else unused
   __bf16 *part_o;  // [rows][splits][D], normalised per split
   float *part_ml;  // [rows][splits][2]
   int max_splits;  // partitions of the key axis the partial buffers can hold
@@ -113,9 +114,18 @@ void prof_begin(percache_ctx *ctx, int kind, hipStream_t stream);
 void prof_end(percache_ctx *ctx, int kind, hipStream_t stream);
 
 // kernel launchers (defined in the .hip files)
+// gemm_part: workspace for the split-k path (nullptr: always the single-pass kernel)
 pc_status launch_qkv_rope(percache_ctx *ctx, const __bf16 *x, const __bf16 *w, int batch, int t_fresh,
                           const int32_t *table_dev, int tbl_stride, __bf16 *q, __bf16 *k, __bf16 *v,
-                          hipStream_t stream);
+                          hipStream_t stream, float *gemm_part = nullptr);
+
+// Split-k projections for few token rows (see block.hip).  P[s][m][n] = sum over slice s of A[m][k] W[n][k];
+// weight rows >= n_split come from w1.  Returns the number of slices written (chosen by choose_split_k).
+constexpr int kMaxSplitK = 16;
+inline bool splitk_applies(long M) { return M <= 192; }
+int choose_split_k(int n_cu, int n_tiles, int k_steps);
+pc_status launch_splitk_partial(percache_ctx *ctx, const __bf16 *a, int lda, const __bf16 *w0, const __bf16 *w1, int n_split,
+                                int ldw, float *part, int M, int N, int K, int n_k, hipStream_t stream);
 pc_status launch_v_repack(percache_ctx *ctx, const __bf16 *vf, __bf16 *vf_blk, int batch, int t_fresh, hipStream_t stream);
 pc_status launch_attention(percache_ctx *ctx, int layer, const __bf16 *q, const __bf16 *kf, const __bf16 *vf_blk,
                            int batch, int t_fresh, const int32_t *table_dev, int tbl_stride, int max_tiles,

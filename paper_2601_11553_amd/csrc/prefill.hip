@@ -62,7 +62,7 @@ pc_status percache_qkv_rope(percache_ctx *ctx, const void *x_fresh_dev, const vo
   st = pc::upload_table(ctx, rows, p.ws.table, s);
   if (st != PC_OK) return st;
   return pc::launch_qkv_rope(ctx, (const __bf16 *)x_fresh_dev, (const __bf16 *)wqkv_dev, batch, t_fresh, p.ws.table,
-                             p.tbl_stride, (__bf16 *)q_out_dev, (__bf16 *)k_fresh_out_dev, (__bf16 *)v_fresh_out_dev, s);
+                             p.tbl_stride, (__bf16 *)q_out_dev, (__bf16 *)k_fresh_out_dev, (__bf16 *)v_fresh_out_dev, s, p.ws.gemm_part);
 }
 
 pc_status percache_attention_reuse(percache_ctx *ctx, int32_t layer, const void *q_dev, const void *k_fresh_dev,
@@ -114,7 +114,7 @@ pc_status percache_prefill_reuse(percache_ctx *ctx, int32_t layer, const void *x
   __bf16 *kf = k_fresh_out_dev ? (__bf16 *)k_fresh_out_dev : p.ws.k;
   __bf16 *vf = v_fresh_out_dev ? (__bf16 *)v_fresh_out_dev : p.ws.v;
   st = pc::launch_qkv_rope(ctx, (const __bf16 *)x_fresh_dev, (const __bf16 *)wqkv_dev, batch, t_fresh, p.ws.table,
-                           p.tbl_stride, p.ws.q, kf, vf, s);
+                           p.tbl_stride, p.ws.q, kf, vf, s, p.ws.gemm_part);
   if (st != PC_OK) return st;
   st = pc::launch_v_repack(ctx, vf, p.ws.v_blk, batch, t_fresh, s);
   if (st != PC_OK) return st;

@@ -36,7 +36,7 @@ __global__ __launch_bounds__(256, 2) void qkv_rope_kernel(const __bf16 *__restri
   const int fb_hi = (D == 128) ? wf + 2 : 2 * wf + 1;
 
   f32x16 acc[2][NTB];
-  pc::gemm::mainloop<NTB>(lds, [&](int row) __attribute__((always_inline)) { return W + (size_t)(f0 + row) * H; }, X, m0, M, H, fb_lo, fb_hi, acc);
+  pc::gemm::mainloop<NTB>(lds, [&](int row) __attribute__((always_inline)) { return W + (size_t)(f0 + row) * H; }, X, H, m0, M, H, fb_lo, fb_hi, acc);
 
   // ---- epilogue: RoPE at position L_pre[b] + i on fp32, one rounding to bf16, head-major stores
   const int head = (D == 128) ? blockIdx.x : 2 * blockIdx.x + wf;
@@ -90,13 +90,61 @@ __global__ __launch_bounds__(256, 2) void qkv_rope_kernel(const __bf16 *__restri
   }
 }
 
+// Epilogue of the split-k path (few token rows): adds the fp32 slices P[s][m][f] in a fixed order, rotates q and k
+// exactly as above, rounds once.  One thread per (token, head, 4 consecutive rotation pairs).
+template <int D>
+__global__ __launch_bounds__(256) void reduce_rope_kernel(const float *__restrict__ P, int n_k, int M, int F, int t_fresh, int Hq,
+                                                          int Hkv, const int32_t *__restrict__ table, int tbl_stride,
+                                                          const float2 *__restrict__ rope, __bf16 *__restrict__ Q,
+                                                          __bf16 *__restrict__ K, __bf16 *__restrict__ V) {
+  constexpr int QUADS = D / 8;
+  const long gid = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  const int n_heads_all = Hq + 2 * Hkv;
+  if (gid >= (long)M * n_heads_all * QUADS) return;
+  const int j = (int)(gid % QUADS);
+  const long r = gid / QUADS;
+  const int head = (int)(r % n_heads_all), m = (int)(r / n_heads_all);
+  const int mm = 4 * j;
+  const size_t slice = (size_t)M * F, at = (size_t)m * F + (size_t)head * D + mm;
+  float4 lo = *(const float4 *)(P + at), hi = *(const float4 *)(P + at + D / 2);
+#pragma unroll 4
+  for (int s = 1; s < n_k; ++s) {
+    const float4 a = *(const float4 *)(P + s * slice + at), c = *(const float4 *)(P + s * slice + at + D / 2);
+    lo.x += a.x; lo.y += a.y; lo.z += a.z; lo.w += a.w;
+    hi.x += c.x; hi.y += c.y; hi.z += c.z; hi.w += c.w;
+  }
+  const int b = m / t_fresh, i = m - b * t_fresh;
+  __bf16 *dst;
+  int hh, n_heads;
+  bool rotate = true;
+  if (head < Hq) { dst = Q; hh = head; n_heads = Hq; }
+  else if (head < Hq + Hkv) { dst = K; hh = head - Hq; n_heads = Hkv; }
+  else { dst = V; hh = head - Hq - Hkv; n_heads = Hkv; rotate = false; }
+  float l4[4] = {lo.x, lo.y, lo.z, lo.w}, h4[4] = {hi.x, hi.y, hi.z, hi.w};
+  if (rotate) {
+    const int pos = table[(size_t)b * tbl_stride + 1] + i;
+    const float4 *csp = (const float4 *)(rope + (size_t)pos * (D / 2) + mm);
+    const float4 c01 = csp[0], c23 = csp[1];  // (cos, sin) of pairs mm, mm+1 and mm+2, mm+3
+    const float wc[4] = {c01.x, c01.z, c23.x, c23.z}, wsn[4] = {c01.y, c01.w, c23.y, c23.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float a = l4[e], c = h4[e];
+      l4[e] = a * wc[e] - c * wsn[e];
+      h4[e] = c * wc[e] + a * wsn[e];
+    }
+  }
+  __bf16 *row = dst + (((size_t)b * n_heads + hh) * t_fresh + i) * D;
+  *(uint2 *)(row + mm) = pack4(l4[0], l4[1], l4[2], l4[3]);
+  *(uint2 *)(row + mm + D / 2) = pack4(h4[0], h4[1], h4[2], h4[3]);
+}
+
 }  // namespace
 
 namespace pc {
 
 pc_status launch_qkv_rope(percache_ctx *ctx, const __bf16 *x, const __bf16 *w, int batch, int t_fresh,
                           const int32_t *table_dev, int tbl_stride, __bf16 *q, __bf16 *k, __bf16 *v,
-                          hipStream_t stream) {
+                          hipStream_t stream, float *gemm_part) {
   const percache_config &c = ctx->cfg;
   const int M = batch * t_fresh;
   const int F = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
@@ -104,6 +152,24 @@ pc_status launch_qkv_rope(percache_ctx *ctx, const __bf16 *x, const __bf16 *w, i
   if ((long)F * c.hidden >= (1L << 31) || (long)M * c.hidden >= (1L << 31))
     return fail(ctx, PC_ESHAPE, "operand larger than 2^31 elements");
   const float2 *rope = (const float2 *)ctx->rope;
+  if (gemm_part && splitk_applies(M)) {
+    // few token rows: weight-stream bound, contraction cut into slices (see block.hip)
+    const int nk = choose_split_k(ctx->n_cu, F / BF * (M > 128 ? 2 : 1), c.hidden / pc::gemm::BK);
+    prof_begin(ctx, PC_KERNEL_QKV_ROPE, stream);
+    pc_status st = launch_splitk_partial(ctx, x, c.hidden, w, w, F, c.hidden, gemm_part, M, F, c.hidden, nk, stream);
+    if (st != PC_OK) return st;
+    const long threads = (long)M * (c.n_q_heads + 2 * c.n_kv_heads) * (c.head_dim / 8);
+    const dim3 rgrid((unsigned)((threads + 255) / 256));
+    if (c.head_dim == 128)
+      hipLaunchKernelGGL(reduce_rope_kernel<128>, rgrid, dim3(256), 0, stream, gemm_part, nk, M, F, t_fresh, c.n_q_heads,
+                         c.n_kv_heads, table_dev, tbl_stride, rope, q, k, v);
+    else
+      hipLaunchKernelGGL(reduce_rope_kernel<64>, rgrid, dim3(256), 0, stream, gemm_part, nk, M, F, t_fresh, c.n_q_heads,
+                         c.n_kv_heads, table_dev, tbl_stride, rope, q, k, v);
+    prof_end(ctx, PC_KERNEL_QKV_ROPE, stream);
+    PC_HIP(ctx, hipGetLastError());
+    return PC_OK;
+  }
   const bool big = M > 64 * 3;  // 128-token tiles once there are enough rows to fill them
   dim3 grid(F / BF, big ? (M + 127) / 128 : (M + 63) / 64);
 #define PC_LAUNCH(DD, NN)                                                                                          \

@@ -387,15 +387,16 @@ __global__ __launch_bounds__(256) void splitkv_combine_kernel(const __bf16 *__re
   int head = gkv * G + hg;
   const float *ml = part_ml + prow * n_splits * 2;
   float m = -INFINITY;
-  for (int s = 0; s < n_splits; ++s)
-    if (ml[2 * s + 1] > 0.f) m = fmaxf(m, ml[2 * s]);
+#pragma unroll 4
+  for (int s = 0; s < n_splits; ++s) m = fmaxf(m, ml[2 * s + 1] > 0.f ? ml[2 * s] : -INFINITY);
   float wsum = 0.f;
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  const __bf16 *po = part_o + prow * n_splits * D + dv * 8;
+#pragma unroll 4
   for (int s = 0; s < n_splits; ++s) {
-    float ms = ml[2 * s], ls = ml[2 * s + 1];
-    if (ls <= 0.f) continue;
-    float w = ls * exp2f(ms - m);
-    pc::bf16x8 o = *(const pc::bf16x8 *)(part_o + (prow * n_splits + s) * D + dv * 8);
+    const float ms = ml[2 * s], ls = ml[2 * s + 1];
+    const float w = ls > 0.f ? ls * exp2f(ms - m) : 0.f;  // an empty partition has weight 0 (its output row is 0)
+    pc::bf16x8 o = *(const pc::bf16x8 *)(po + (size_t)s * D);
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] += w * (float)o[e];
     wsum += w;
