@@ -170,6 +170,36 @@ pc_status percache_attention_reuse(percache_ctx *ctx, int32_t layer, const void 
                                    int32_t max_chunks, int32_t n_splits, void *attn_out_dev,
                                    void *workspace_dev, size_t workspace_bytes, void *stream);
 
+/* ---------------------------------------------------------------- cache index (Sec. 4.1.1, Sec. 4.2.2, App. B.2)
+ * Host-side prefix tree over knowledge chunks that hands out slot ids of the K/V store; no device work.  A node is
+ * one chunk (keyed by its text), a path from the root the chunk list of one query.  The same slot id is meant to
+ * be used in every layer of the store.
+ *   create: n_slots slots; the stored chunks may take at most byte_limit bytes at bytes_per_token bytes per token
+ *           (all layers together); a matched chain is used without the last tail_discard_tokens tokens of its final
+ *           chunk (App. B.2).  NULL on a bad argument.
+ *   match:  longest chain root -> chunk 0 -> chunk 1 ... present in the tree; returns its length m (0..n), writes
+ *           slots_out[0..m) and used_len_out[0..m) (the stored token counts, the last one shortened by the tail
+ *           discard) and counts one retrieval on each matched node.
+ *   insert: stores the chain of n chunks (chunk_tokens[i] tokens each).  Returns the number s of leading chunks
+ *           shared with the tree (their slots are in slots_out, is_new_out = 0: nothing to fill); chunks s..n-1 get
+ *           fresh slots (is_new_out = 1) that the caller must fill, e.g. with percache_kv_slice.  Sharing stops one
+ *           node before the end of the common prefix (App. B.2), unless the whole chain is already stored.  When
+ *           the byte limit or the slot count requires it, least-frequently-retrieved leaves are evicted first
+ *           (ties: least recently used); their slots are listed in evicted_out[0..*n_evicted_out) -- the caller
+ *           clears them with percache_kv_evict in every layer -- and this list is final even when the call then
+ *           fails with PC_ENOMEM (chain larger than the limits allow).  evicted_cap must be at least n_slots. */
+typedef struct percache_tree percache_tree;
+percache_tree *percache_tree_create(int32_t n_slots, int64_t byte_limit, int64_t bytes_per_token,
+                                    int32_t tail_discard_tokens);
+void percache_tree_destroy(percache_tree *tree);
+int32_t percache_tree_match(percache_tree *tree, const char *const *chunk_texts, int32_t n, int32_t *slots_out,
+                            int32_t *used_len_out);
+int32_t percache_tree_insert(percache_tree *tree, const char *const *chunk_texts, const int32_t *chunk_tokens,
+                             int32_t n, int32_t *slots_out, uint8_t *is_new_out, int32_t *evicted_out,
+                             int32_t evicted_cap, int32_t *n_evicted_out);
+int32_t percache_tree_nodes(const percache_tree *tree);
+int64_t percache_tree_bytes(const percache_tree *tree);
+
 /* ---------------------------------------------------------------- a stack of layers on the retained rows
  * (App. B.1).  After the attention module a block goes on as usual, and the next layer crops the cached rows
  * again, so only the retained (fresh) rows of every layer are ever computed:

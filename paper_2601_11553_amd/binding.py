@@ -25,6 +25,8 @@ EXPORTS = [
     "percache_bank_put", "percache_bank_size", "percache_lookup_workspace_bytes", "percache_lookup",
     "percache_kv_put", "percache_kv_put_batch", "percache_kv_get", "percache_kv_evict", "percache_kv_len",
     "percache_kv_slice", "percache_stack_workspace_bytes", "percache_stack_reuse",
+    "percache_tree_create", "percache_tree_destroy", "percache_tree_match", "percache_tree_insert",
+    "percache_tree_nodes", "percache_tree_bytes",
     "percache_prefill_workspace_bytes", "percache_prefill_reuse", "percache_qkv_rope", "percache_attention_reuse",
     "percache_profile_enable", "percache_profile_read",
 ]
@@ -87,6 +89,13 @@ def load_library() -> ctypes.CDLL:
         "percache_stack_workspace_bytes": (_sz, [_vp, _i32, _i32, _i32, _i32]),
         "percache_stack_reuse": (_i32, [_vp, ctypes.POINTER(BlockWeights), _i32, _i32, ctypes.c_float, _vp, _i32, _i32,
                                         _pi32, _pi32, _pi32, _i32, _pi32, _pi32, _i32, _vp, _vp, _sz, _vp]),
+        "percache_tree_create": (_vp, [_i32, ctypes.c_int64, ctypes.c_int64, _i32]),
+        "percache_tree_destroy": (None, [_vp]),
+        "percache_tree_match": (_i32, [_vp, ctypes.POINTER(ctypes.c_char_p), _i32, _pi32, _pi32]),
+        "percache_tree_insert": (_i32, [_vp, ctypes.POINTER(ctypes.c_char_p), _pi32, _i32, _pi32, ctypes.POINTER(ctypes.c_uint8),
+                                        _pi32, _i32, _pi32]),
+        "percache_tree_nodes": (_i32, [_vp]),
+        "percache_tree_bytes": (ctypes.c_int64, [_vp]),
         "percache_profile_enable": (_i32, [_vp, _i32]),
         "percache_profile_read": (_i32, [_vp, _i32, ctypes.POINTER(ctypes.c_float), _pi32]),
     }
@@ -321,3 +330,62 @@ class Percache:
                                                   ul_p, nc_p, max_chunks, sb_p, ss_p, n_save, _ptr(h_out), ws, need,
                                                   _stream()))
         return h_out
+
+
+class CacheTree:
+    """Host-side chunk prefix tree with LFU eviction (percache_tree_*): marshalling only."""
+
+    def __init__(self, n_slots: int, byte_limit: int, bytes_per_token: int, tail_discard_tokens: int = 0):
+        self.lib = load_library()
+        self.n_slots = n_slots
+        self.t = self.lib.percache_tree_create(n_slots, byte_limit, bytes_per_token, tail_discard_tokens)
+        if not self.t:
+            raise PercacheError(-1, "percache_tree_create: bad argument")
+
+    def close(self):
+        if getattr(self, "t", None):
+            self.lib.percache_tree_destroy(self.t)
+            self.t = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @staticmethod
+    def _texts(chunks):
+        arr = (ctypes.c_char_p * len(chunks))(*[c.encode() if isinstance(c, str) else bytes(c) for c in chunks])
+        return arr
+
+    def percache_tree_match(self, chunks):
+        """Returns (slots, used_len) of the longest stored chain that is a prefix of ``chunks``."""
+        n = len(chunks)
+        slots = (ctypes.c_int32 * max(n, 1))()
+        used = (ctypes.c_int32 * max(n, 1))()
+        m = self.lib.percache_tree_match(self.t, self._texts(chunks), n, slots, used)
+        if m < 0:
+            raise PercacheError(m, "percache_tree_match")
+        return list(slots[:m]), list(used[:m])
+
+    def percache_tree_insert(self, chunks, tokens):
+        """Returns (n_shared, slots, is_new, evicted_slots)."""
+        n = len(chunks)
+        slots = (ctypes.c_int32 * n)()
+        new = (ctypes.c_uint8 * n)()
+        ev = (ctypes.c_int32 * self.n_slots)()
+        n_ev = ctypes.c_int32(0)
+        tok = (ctypes.c_int32 * n)(*[int(x) for x in tokens])
+        s = self.lib.percache_tree_insert(self.t, self._texts(chunks), tok, n, slots, new, ev, self.n_slots, ctypes.byref(n_ev))
+        evicted = list(ev[:n_ev.value])
+        if s < 0:
+            err = PercacheError(s, "percache_tree_insert")
+            err.evicted = evicted
+            raise err
+        return s, list(slots), [bool(x) for x in new], evicted
+
+    def percache_tree_nodes(self) -> int:
+        return self.lib.percache_tree_nodes(self.t)
+
+    def percache_tree_bytes(self) -> int:
+        return self.lib.percache_tree_bytes(self.t)
