@@ -93,6 +93,15 @@ pc_status percache_lookup(percache_ctx *ctx, const void *probes_dev, int32_t n_p
                           int32_t *idx_out_dev, float *sim_out_dev, uint8_t *hit_out_dev,
                           void *workspace_dev, size_t workspace_bytes, void *stream);
 
+/* The k best rows per probe instead of the best one (1 <= k <= 8): the ranking that cache refresh (Sec. 4.1.3,
+ * "top-k_refresh") and dense retrieval over chunk embeddings need.  Same similarity, same tie rule (equal
+ * similarities: lower row first), sorted best first.
+ *   idx_out_dev int32[n_probes * k], sim_out_dev float[n_probes * k]; entries beyond the bank size: idx -1, sim -inf.
+ * Same workspace as percache_lookup. */
+pc_status percache_lookup_topk(percache_ctx *ctx, const void *probes_dev, int32_t n_probes, int32_t k,
+                               int32_t *idx_out_dev, float *sim_out_dev, void *workspace_dev,
+                               size_t workspace_bytes, void *stream);
+
 /* ---------------------------------------------------------------- K/V store (Sec. 4.1.1)
  * One slot holds one knowledge chunk's K and V for one layer, as collected from the attention
  * module during a prefill (K already rotated at the positions it had then).

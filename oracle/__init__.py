@@ -96,6 +96,31 @@ def similarities(E, probe) -> np.ndarray:
     return out
 
 
+def lookup_topk(E, probes, k: int):
+    """The k most similar bank rows of each probe, best first; equal similarities: lower row first (the ranking
+    behind cache refresh, Sec. 4.1.3, and dense retrieval).  The definition written out: all N cosine
+    similarities, then a stable sort.  Returns (idx [P, k] int32 with -1 past the bank size, sim [P, k] float32 with
+    -inf there, next [P] float32 = similarity ranked k+1, for judging near-ties)."""
+    E = _f(E)
+    probes = _f(probes)
+    P = probes.shape[0]
+    N = E.shape[0]
+    idx = np.full((P, k), -1, np.int32)
+    sim = np.full((P, k), -np.inf, np.float32)
+    nxt = np.full(P, -np.inf, np.float32)
+    for p in range(P):
+        if N == 0:
+            continue
+        s = similarities(E, probes[p])
+        order = np.argsort(-s.astype(np.float64), kind="stable")
+        m = min(k, N)
+        idx[p, :m] = order[:m]
+        sim[p, :m] = s[order[:m]]
+        if N > k:
+            nxt[p] = s[order[k]]
+    return idx, sim, nxt
+
+
 def rope(u, pos: int, theta: float) -> np.ndarray:
     """RoPE of one head vector at absolute position ``pos`` (App. B.1)."""
     u = _f(u).copy()

@@ -23,6 +23,7 @@ STATUS_NAMES = {0: "PC_OK", -1: "PC_EINVAL", -2: "PC_ESHAPE", -3: "PC_ESLOT", -4
 EXPORTS = [
     "percache_arena_bytes", "percache_create", "percache_destroy", "percache_last_error",
     "percache_bank_put", "percache_bank_size", "percache_lookup_workspace_bytes", "percache_lookup",
+    "percache_lookup_topk",
     "percache_kv_put", "percache_kv_put_batch", "percache_kv_get", "percache_kv_evict", "percache_kv_len",
     "percache_kv_slice", "percache_stack_workspace_bytes", "percache_stack_reuse",
     "percache_tree_create", "percache_tree_destroy", "percache_tree_match", "percache_tree_insert",
@@ -76,6 +77,7 @@ def load_library() -> ctypes.CDLL:
         "percache_bank_size": (_i32, [_vp]),
         "percache_lookup_workspace_bytes": (_sz, [_vp, _i32]),
         "percache_lookup": (_i32, [_vp, _vp, _i32, ctypes.c_float, _vp, _vp, _vp, _vp, _sz, _vp]),
+        "percache_lookup_topk": (_i32, [_vp, _vp, _i32, _i32, _vp, _vp, _vp, _sz, _vp]),
         "percache_kv_put": (_i32, [_vp, _i32, _i32, _vp, _vp, _i32, _vp]),
         "percache_kv_put_batch": (_i32, [_vp, _i32, _pi32, _i32, _vp, _vp, _i32, _vp]),
         "percache_kv_get": (_i32, [_vp, _i32, _i32, _vp, _vp, _pi32, _vp]),
@@ -206,6 +208,19 @@ class Percache:
         self._check(self.lib.percache_lookup(self.ctx, _ptr(probes), n, tau, _ptr(idx_out), _ptr(sim_out),
                                              _ptr(hit_out), ws, need, _stream()))
         return idx_out, sim_out, hit_out
+
+    def percache_lookup_topk(self, probes, k: int):
+        """(idx [P, k] int32, sim [P, k] float32): the k best bank rows per probe, best first."""
+        import torch
+        n = probes.shape[0]
+        idx_out = torch.empty((n, k), dtype=torch.int32, device=self.device)
+        sim_out = torch.empty((n, k), dtype=torch.float32, device=self.device)
+        need = self.lib.percache_lookup_workspace_bytes(self.ctx, n)
+        if self._lookup_ws is None or self._lookup_ws.numel() < need + 256:
+            self._lookup_ws = torch.empty(need + 256, dtype=torch.uint8, device=self.device)
+        ws = (self._lookup_ws.data_ptr() + 255) // 256 * 256
+        self._check(self.lib.percache_lookup_topk(self.ctx, _ptr(probes), n, k, _ptr(idx_out), _ptr(sim_out), ws, need, _stream()))
+        return idx_out, sim_out
 
     # ------------------------------------------------------------------ K/V store
     def percache_kv_put(self, layer: int, slot: int, k, v, n_tokens: Optional[int] = None):

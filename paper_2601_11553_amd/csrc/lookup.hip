@@ -5,6 +5,7 @@
 // fp16 matrix cores (16x16x32, fp32 accumulate) only because they perform the cross-lane reduction for
 // free; the kernel is bound by the HBM stream of the bank, not by arithmetic.
 #include <climits>
+#include <cmath>
 
 #include "percache_internal.hpp"
 
@@ -18,6 +19,36 @@ struct Best {
   int idx;
 };
 __device__ __forceinline__ bool better(float s1, int i1, float s2, int i2) { return s1 > s2 || (s1 == s2 && i1 < i2); }
+
+// Sorted list of the K best (similarity, row) pairs, best first; ties go to the lower row.
+template <int K>
+struct TopK {
+  float s[K];
+  int i[K];
+  __device__ __forceinline__ void clear() {
+#pragma unroll
+    for (int j = 0; j < K; ++j) { s[j] = -INFINITY; i[j] = INT_MAX; }
+  }
+  __device__ __forceinline__ void insert(float cs, int ci) {
+    if (!better(cs, ci, s[K - 1], i[K - 1])) return;
+    s[K - 1] = cs;
+    i[K - 1] = ci;
+#pragma unroll
+    for (int j = K - 1; j > 0; --j) {
+      const bool up = better(s[j], i[j], s[j - 1], i[j - 1]);
+      const float ts = s[j]; const int ti = i[j];
+      s[j] = up ? s[j - 1] : ts;   i[j] = up ? i[j - 1] : ti;
+      s[j - 1] = up ? ts : s[j - 1]; i[j - 1] = up ? ti : i[j - 1];
+    }
+  }
+  // drops the head if this list owns it
+  __device__ __forceinline__ void pop_if(bool mine) {
+#pragma unroll
+    for (int j = 0; j < K - 1; ++j) { s[j] = mine ? s[j + 1] : s[j]; i[j] = mine ? i[j + 1] : i[j]; }
+    s[K - 1] = mine ? -INFINITY : s[K - 1];
+    i[K - 1] = mine ? INT_MAX : i[K - 1];
+  }
+};
 
 // ---------------------------------------------------------------------------------------------------
 // Inverse L2 norms of newly written bank rows; one wavefront per row.  Also copies the rows into the
@@ -61,7 +92,7 @@ constexpr int kMaxBlocksPerWg = 128;  // 2048 rows: bounds the LDS copy of the i
 template <int CHB>
 __device__ __forceinline__ int row_swz(int row) { return CHB >= 256 ? (row & 15) : ((row >> 1) & 7); }
 
-template <int NPB, int CHB, int NSTG>
+template <int NPB, int CHB, int NSTG, int K>
 __global__ __launch_bounds__(256) void lookup_stream_kernel(const _Float16 *__restrict__ bank,
                                                             const float *__restrict__ inv_norm, int N, int d,
                                                             const _Float16 *__restrict__ probes, int n_probes,
@@ -98,12 +129,9 @@ __global__ __launch_bounds__(256) void lookup_stream_kernel(const _Float16 *__re
   const int chunks = d * 2 / CHB;
   char *ring = smem + ring_off + wave * (NSTG * STG);
 
-  float best_s[NPB][4];
-  int best_i[NPB][4];
+  TopK<K> best[NPB];  // this lane's best rows for probe pb*16 + r16
 #pragma unroll
-  for (int pb = 0; pb < NPB; ++pb)
-#pragma unroll
-    for (int r = 0; r < 4; ++r) { best_s[pb][r] = -INFINITY; best_i[pb][r] = INT_MAX; }
+  for (int pb = 0; pb < NPB; ++pb) best[pb].clear();
 
   // load instruction i of a stage: lane lands at stage byte 1024 i + 16 lane = (row, physical chunk)
   int ld_row[IPS], ld_col[IPS];
@@ -145,7 +173,7 @@ __global__ __launch_bounds__(256) void lookup_stream_kernel(const _Float16 *__re
       }
     }
   };
-  // scale by the rows' inverse norms and keep the running best (strict >: the lowest row wins ties)
+  // scale by the rows' inverse norms and keep the running best list (the lowest row wins ties)
   auto epilogue = [&](int rb) __attribute__((always_inline)) {
     const f32x4 inv4 = *(const f32x4 *)(inv_lds + (rb - rb_begin) * 16 + g * 4);
 #pragma unroll
@@ -154,8 +182,8 @@ __global__ __launch_bounds__(256) void lookup_stream_kernel(const _Float16 *__re
       const bool ok = row < N;
 #pragma unroll
       for (int pb = 0; pb < NPB; ++pb) {
-        float s = acc[pb][r] * inv4[r];
-        if (ok && s > best_s[pb][r]) { best_s[pb][r] = s; best_i[pb][r] = row; }
+        const float s = acc[pb][r] * inv4[r];
+        if (ok) best[pb].insert(s, row);
       }
     }
   };
@@ -193,43 +221,52 @@ __global__ __launch_bounds__(256) void lookup_stream_kernel(const _Float16 *__re
     PC_LOOKUP_WAIT_VMCNT(0);
   }
 
-  // lane-local over r, then the four lanes that share a probe, then the four wavefronts
+  // the four lanes that share a probe (K rounds of "best head wins and is popped"), then the four wavefronts
   __syncthreads();  // probes no longer needed: reuse LDS for the cross-wave step
-  Best *red = (Best *)smem;  // [4 waves][NPB*16]
+  Best *red = (Best *)smem;  // [4 waves][NPB*16][K]
 #pragma unroll
   for (int pb = 0; pb < NPB; ++pb) {
-    float s = best_s[pb][0];
-    int i = best_i[pb][0];
 #pragma unroll
-    for (int r = 1; r < 4; ++r)
-      if (better(best_s[pb][r], best_i[pb][r], s, i)) { s = best_s[pb][r]; i = best_i[pb][r]; }
+    for (int j = 0; j < K; ++j) {
+      float s = best[pb].s[0];
+      int i = best[pb].i[0];
 #pragma unroll
-    for (int o = 16; o < 64; o <<= 1) {
-      float s2 = __shfl_xor(s, o, 64);
-      int i2 = __shfl_xor(i, o, 64);
-      if (better(s2, i2, s, i)) { s = s2; i = i2; }
+      for (int o = 16; o < 64; o <<= 1) {
+        float s2 = __shfl_xor(s, o, 64);
+        int i2 = __shfl_xor(i, o, 64);
+        if (better(s2, i2, s, i)) { s = s2; i = i2; }
+      }
+      best[pb].pop_if(i != INT_MAX && best[pb].i[0] == i);  // rows are unique: at most one lane owns the winner
+      if (g == 0) red[(wave * (NPB * 16) + pb * 16 + r16) * K + j] = Best{s, i};
     }
-    if (g == 0) red[wave * (NPB * 16) + pb * 16 + r16] = Best{s, i};
   }
   __syncthreads();
   if (tid < NPB * 16) {
-    Best b = red[tid];
+    int head[4] = {0, 0, 0, 0};
+    for (int j = 0; j < K; ++j) {
+      Best b = Best{-INFINITY, INT_MAX};
+      int from = -1;
 #pragma unroll
-    for (int w = 1; w < 4; ++w) {
-      Best o = red[w * (NPB * 16) + tid];
-      if (better(o.s, o.idx, b.s, b.idx)) b = o;
+      for (int w = 0; w < 4; ++w) {
+        if (head[w] >= K) continue;
+        Best o = red[(w * (NPB * 16) + tid) * K + head[w]];
+        if (o.idx != INT_MAX && better(o.s, o.idx, b.s, b.idx)) { b = o; from = w; }
+      }
+#pragma unroll
+      for (int w = 0; w < 4; ++w) head[w] += (w == from);
+      partial[((size_t)blockIdx.x * (NPB * 16) + tid) * K + j] = b;
     }
-    partial[(size_t)blockIdx.x * (NPB * 16) + tid] = b;
   }
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Per probe: merge the workgroup partials, divide by the probe's norm, compare with tau.
-// One workgroup (one wavefront) per probe.
+// Per probe: merge the workgroup partial lists, divide by the probe's norm, compare the best with tau.
+// One workgroup (one wavefront) per probe; k <= K entries are written per probe.
 // ---------------------------------------------------------------------------------------------------
+template <int K>
 __global__ __launch_bounds__(64) void lookup_finalize_kernel(const Best *__restrict__ partial, int n_partials,
                                                              int partial_stride, const _Float16 *__restrict__ probes,
-                                                             int d, float tau, int32_t *__restrict__ idx_out,
+                                                             int d, float tau, int k, int32_t *__restrict__ idx_out,
                                                              float *__restrict__ sim_out, uint8_t *__restrict__ hit_out) {
   const int p = blockIdx.x, lane = threadIdx.x;
   float ss = 0.f;
@@ -239,31 +276,42 @@ __global__ __launch_bounds__(64) void lookup_finalize_kernel(const Best *__restr
 #pragma unroll
     for (int e = 0; e < 8; ++e) ss += (float)h[e] * (float)h[e];
   }
-  float s = -INFINITY;
-  int i = INT_MAX;
-  for (int w = lane; w < n_partials; w += 64) {
-    Best b = partial[(size_t)w * partial_stride + p];
-    if (better(b.s, b.idx, s, i)) { s = b.s; i = b.idx; }
-  }
 #pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    ss += __shfl_xor(ss, o, 64);
-    float s2 = __shfl_xor(s, o, 64);
-    int i2 = __shfl_xor(i, o, 64);
-    if (better(s2, i2, s, i)) { s = s2; i = i2; }
+  for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
+  const float inv = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
+  TopK<K> mine;
+  mine.clear();
+  for (int w = lane; w < n_partials; w += 64) {
+    const Best *lst = partial + ((size_t)w * partial_stride + p) * K;
+#pragma unroll
+    for (int j = 0; j < K; ++j) {
+      Best b = lst[j];
+      if (b.idx != INT_MAX) mine.insert(b.s, b.idx);
+    }
   }
-  if (lane == 0) {
-    float inv = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
-    float sim = s * inv;
-    idx_out[p] = i;
-    sim_out[p] = sim;
-    hit_out[p] = sim > tau ? 1 : 0;
+  for (int j = 0; j < k; ++j) {
+    float s = mine.s[0];
+    int i = mine.i[0];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      float s2 = __shfl_xor(s, o, 64);
+      int i2 = __shfl_xor(i, o, 64);
+      if (better(s2, i2, s, i)) { s = s2; i = i2; }
+    }
+    mine.pop_if(i != INT_MAX && mine.i[0] == i);
+    if (lane == 0) {
+      const float sim = i == INT_MAX ? -INFINITY : s * inv;
+      idx_out[(size_t)p * k + j] = i == INT_MAX ? -1 : i;
+      sim_out[(size_t)p * k + j] = sim;
+      if (hit_out && j == 0) hit_out[p] = sim > tau ? 1 : 0;
+    }
   }
 }
 
-__global__ void lookup_empty_kernel(int n, int32_t *idx_out, float *sim_out, uint8_t *hit_out) {
+__global__ void lookup_empty_kernel(int n_out, int n_probes, int32_t *idx_out, float *sim_out, uint8_t *hit_out) {
   int p = blockIdx.x * blockDim.x + threadIdx.x;
-  if (p < n) { idx_out[p] = -1; sim_out[p] = -INFINITY; hit_out[p] = 0; }
+  if (p < n_out) { idx_out[p] = -1; sim_out[p] = -INFINITY; }
+  if (hit_out && p < n_probes) hit_out[p] = 0;
 }
 
 constexpr int kPassProbes = 32;
@@ -299,16 +347,81 @@ int max_stream_grid(const percache_ctx *ctx) {
   return by_rows > ctx->n_cu ? by_rows : ctx->n_cu;
 }
 
-template <int NPB, int CHB, int NSTG>
+constexpr int kMaxTopK = 8;
+
+template <int NPB, int CHB, int NSTG, int K>
 pc_status launch_stream(percache_ctx *ctx, const StreamShape &sh, hipStream_t st, int N, int d, const _Float16 *pp, int np,
                         Best *partial) {
   static bool big_lds_set = false;  // dynamic LDS above 64 KB must be opted into once per kernel
   if (!big_lds_set) {
-    PC_HIP(ctx, hipFuncSetAttribute((const void *)lookup_stream_kernel<NPB, CHB, NSTG>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxLds));
+    PC_HIP(ctx, hipFuncSetAttribute((const void *)lookup_stream_kernel<NPB, CHB, NSTG, K>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxLds));
     big_lds_set = true;
   }
-  hipLaunchKernelGGL((lookup_stream_kernel<NPB, CHB, NSTG>), dim3(sh.grid), dim3(256), sh.lds, st, ctx->bank, ctx->bank_inv, N, d,
+  hipLaunchKernelGGL((lookup_stream_kernel<NPB, CHB, NSTG, K>), dim3(sh.grid), dim3(256), sh.lds, st, ctx->bank, ctx->bank_inv, N, d,
                      pp, np, sh.per_wg, sh.ring_off, partial);
+  return PC_OK;
+}
+
+template <int K>
+pc_status launch_pass(percache_ctx *ctx, const StreamShape &sh, int npb, hipStream_t st, int N, int d, const _Float16 *pp, int np,
+                      Best *partial) {
+  if (npb == 1 && sh.nstg == 3)
+    return sh.chb == 128   ? launch_stream<1, 128, 3, K>(ctx, sh, st, N, d, pp, np, partial)
+           : sh.chb == 256 ? launch_stream<1, 256, 3, K>(ctx, sh, st, N, d, pp, np, partial)
+                           : launch_stream<1, 512, 3, K>(ctx, sh, st, N, d, pp, np, partial);
+  if (npb == 1) return launch_stream<1, 512, 2, K>(ctx, sh, st, N, d, pp, np, partial);  // only the widest rows (512-byte chunks) get here
+  return sh.chb == 128   ? launch_stream<2, 128, 2, K>(ctx, sh, st, N, d, pp, np, partial)
+         : sh.chb == 256 ? launch_stream<2, 256, 2, K>(ctx, sh, st, N, d, pp, np, partial)
+                         : launch_stream<2, 512, 2, K>(ctx, sh, st, N, d, pp, np, partial);
+}
+
+// k best rows per probe (k == 1: the query-level match with its hit flag; hit_out may be null otherwise)
+pc_status run_lookup(percache_ctx *ctx, const void *probes_dev, int32_t n_probes, float tau, int k, int32_t *idx_out_dev,
+                     float *sim_out_dev, uint8_t *hit_out_dev, void *workspace_dev, size_t workspace_bytes, void *stream) {
+  if (!ctx) return PC_EINVAL;
+  const percache_config &c = ctx->cfg;
+  if (c.bank_capacity <= 0) return pc::fail(ctx, PC_ESHAPE, "context was created without a bank");
+  if (n_probes < 0) return pc::fail(ctx, PC_EINVAL, "n_probes is negative");
+  if (k < 1 || k > kMaxTopK) return pc::fail(ctx, PC_ESHAPE, "k = %d outside [1,%d]", k, kMaxTopK);
+  if (n_probes == 0) return PC_OK;
+  if (!probes_dev || !idx_out_dev || !sim_out_dev || (k == 1 && !hit_out_dev)) return pc::fail(ctx, PC_EINVAL, "NULL probe or output pointer");
+  if ((uintptr_t)probes_dev % 16) return pc::fail(ctx, PC_EINVAL, "probes_dev must be 16-byte aligned");
+  if (!(tau == tau)) return pc::fail(ctx, PC_EINVAL, "tau is NaN");
+  hipStream_t st = (hipStream_t)stream;
+  const int N = ctx->bank_size, d = c.emb_dim;
+  if (N == 0) {
+    const int n_out = n_probes * k;
+    hipLaunchKernelGGL(lookup_empty_kernel, dim3((n_out + 255) / 256), dim3(256), 0, st, n_out, n_probes, idx_out_dev, sim_out_dev, hit_out_dev);
+    PC_HIP(ctx, hipGetLastError());
+    return PC_OK;
+  }
+  const size_t need = percache_lookup_workspace_bytes(ctx, n_probes);
+  if (!workspace_dev || workspace_bytes < need) return pc::fail(ctx, PC_ENOMEM, "lookup workspace has %zu bytes, need %zu", workspace_bytes, need);
+  if ((uintptr_t)workspace_dev % 16) return pc::fail(ctx, PC_EINVAL, "workspace must be 16-byte aligned");
+  Best *partial = (Best *)workspace_dev;
+  const _Float16 *probes = (const _Float16 *)probes_dev;
+  // two probe blocks per pass unless their LDS copy leaves no room for the rings (very wide embeddings)
+  const int pass_probes = stream_shape(ctx, 2, N).lds <= kMaxLds ? kPassProbes : 16;
+  for (int p0 = 0; p0 < n_probes; p0 += pass_probes) {
+    int np = n_probes - p0 < pass_probes ? n_probes - p0 : pass_probes;
+    int npb = np <= 16 ? 1 : 2;
+    StreamShape sh = stream_shape(ctx, npb, N);
+    if (sh.lds > kMaxLds) return pc::fail(ctx, PC_ESHAPE, "emb_dim %d needs %zu bytes of LDS per workgroup", d, sh.lds);
+    const _Float16 *pp = probes + (size_t)p0 * d;
+    pc::prof_begin(ctx, PC_KERNEL_LOOKUP, st);
+    pc_status ls = k == 1 ? launch_pass<1>(ctx, sh, npb, st, N, d, pp, np, partial) : launch_pass<kMaxTopK>(ctx, sh, npb, st, N, d, pp, np, partial);
+    if (ls != PC_OK) return ls;
+    pc::prof_end(ctx, PC_KERNEL_LOOKUP, st);
+    PC_HIP(ctx, hipGetLastError());
+    uint8_t *hit = hit_out_dev ? hit_out_dev + p0 : nullptr;
+    if (k == 1)
+      hipLaunchKernelGGL(lookup_finalize_kernel<1>, dim3(np), dim3(64), 0, st, partial, sh.grid, npb * 16, pp, d, tau, 1,
+                         idx_out_dev + p0, sim_out_dev + p0, hit);
+    else
+      hipLaunchKernelGGL(lookup_finalize_kernel<kMaxTopK>, dim3(np), dim3(64), 0, st, partial, sh.grid, npb * 16, pp, d, tau, k,
+                         idx_out_dev + (size_t)p0 * k, sim_out_dev + (size_t)p0 * k, hit);
+    PC_HIP(ctx, hipGetLastError());
+  }
   return PC_OK;
 }
 
@@ -334,61 +447,18 @@ pc_status percache_bank_put(percache_ctx *ctx, int32_t index, const void *emb_de
 
 size_t percache_lookup_workspace_bytes(const percache_ctx *ctx, int32_t n_probes) {
   if (!ctx || n_probes < 0) return 0;
-  return pc::align_up((size_t)max_stream_grid(ctx) * kPassProbes * sizeof(Best));
+  return pc::align_up((size_t)max_stream_grid(ctx) * kPassProbes * kMaxTopK * sizeof(Best));
 }
 
 pc_status percache_lookup(percache_ctx *ctx, const void *probes_dev, int32_t n_probes, float tau, int32_t *idx_out_dev,
                           float *sim_out_dev, uint8_t *hit_out_dev, void *workspace_dev, size_t workspace_bytes,
                           void *stream) {
-  if (!ctx) return PC_EINVAL;
-  const percache_config &c = ctx->cfg;
-  if (c.bank_capacity <= 0) return pc::fail(ctx, PC_ESHAPE, "context was created without a bank");
-  if (n_probes < 0) return pc::fail(ctx, PC_EINVAL, "n_probes is negative");
-  if (n_probes == 0) return PC_OK;
-  if (!probes_dev || !idx_out_dev || !sim_out_dev || !hit_out_dev) return pc::fail(ctx, PC_EINVAL, "NULL probe or output pointer");
-  if ((uintptr_t)probes_dev % 16) return pc::fail(ctx, PC_EINVAL, "probes_dev must be 16-byte aligned");
-  if (!(tau == tau)) return pc::fail(ctx, PC_EINVAL, "tau is NaN");
-  hipStream_t st = (hipStream_t)stream;
-  const int N = ctx->bank_size, d = c.emb_dim;
-  if (N == 0) {
-    hipLaunchKernelGGL(lookup_empty_kernel, dim3((n_probes + 255) / 256), dim3(256), 0, st, n_probes, idx_out_dev, sim_out_dev, hit_out_dev);
-    PC_HIP(ctx, hipGetLastError());
-    return PC_OK;
-  }
-  if (!workspace_dev || workspace_bytes < percache_lookup_workspace_bytes(ctx, n_probes))
-    return pc::fail(ctx, PC_ENOMEM, "lookup workspace has %zu bytes, need %zu", workspace_bytes, percache_lookup_workspace_bytes(ctx, n_probes));
-  if ((uintptr_t)workspace_dev % 16) return pc::fail(ctx, PC_EINVAL, "workspace must be 16-byte aligned");
-  Best *partial = (Best *)workspace_dev;
-  const _Float16 *probes = (const _Float16 *)probes_dev;
-  // two probe blocks per pass unless their LDS copy leaves no room for the rings (very wide embeddings)
-  const int pass_probes = stream_shape(ctx, 2, N).lds <= kMaxLds ? kPassProbes : 16;
-  for (int p0 = 0; p0 < n_probes; p0 += pass_probes) {
-    int np = n_probes - p0 < pass_probes ? n_probes - p0 : pass_probes;
-    int npb = np <= 16 ? 1 : 2;
-    StreamShape sh = stream_shape(ctx, npb, N);
-    if (sh.lds > kMaxLds) return pc::fail(ctx, PC_ESHAPE, "emb_dim %d needs %zu bytes of LDS per workgroup", d, sh.lds);
-    const int grid = sh.grid;
-    const _Float16 *pp = probes + (size_t)p0 * d;
-    pc::prof_begin(ctx, PC_KERNEL_LOOKUP, st);
-    pc_status ls;
-    if (npb == 1 && sh.nstg == 3)
-      ls = sh.chb == 128   ? launch_stream<1, 128, 3>(ctx, sh, st, N, d, pp, np, partial)
-           : sh.chb == 256 ? launch_stream<1, 256, 3>(ctx, sh, st, N, d, pp, np, partial)
-                           : launch_stream<1, 512, 3>(ctx, sh, st, N, d, pp, np, partial);
-    else if (npb == 1)
-      ls = launch_stream<1, 512, 2>(ctx, sh, st, N, d, pp, np, partial);  // only the widest rows (512-byte chunks) get here
-    else
-      ls = sh.chb == 128   ? launch_stream<2, 128, 2>(ctx, sh, st, N, d, pp, np, partial)
-           : sh.chb == 256 ? launch_stream<2, 256, 2>(ctx, sh, st, N, d, pp, np, partial)
-                           : launch_stream<2, 512, 2>(ctx, sh, st, N, d, pp, np, partial);
-    if (ls != PC_OK) return ls;
-    pc::prof_end(ctx, PC_KERNEL_LOOKUP, st);
-    PC_HIP(ctx, hipGetLastError());
-    hipLaunchKernelGGL(lookup_finalize_kernel, dim3(np), dim3(64), 0, st, partial, grid, npb * 16, pp, d, tau,
-                       idx_out_dev + p0, sim_out_dev + p0, hit_out_dev + p0);
-    PC_HIP(ctx, hipGetLastError());
-  }
-  return PC_OK;
+  return run_lookup(ctx, probes_dev, n_probes, tau, 1, idx_out_dev, sim_out_dev, hit_out_dev, workspace_dev, workspace_bytes, stream);
+}
+
+pc_status percache_lookup_topk(percache_ctx *ctx, const void *probes_dev, int32_t n_probes, int32_t k, int32_t *idx_out_dev,
+                               float *sim_out_dev, void *workspace_dev, size_t workspace_bytes, void *stream) {
+  return run_lookup(ctx, probes_dev, n_probes, 0.f, k, idx_out_dev, sim_out_dev, nullptr, workspace_dev, workspace_bytes, stream);
 }
 
 }  // extern "C"

@@ -149,3 +149,62 @@ def test_config3_full_size_sampled_probes():
     copies = w.source[:1024] >= 0
     assert np.array_equal(idx_h[:1024][copies], w.source[:1024][copies])   # perturbed copies find their source
     assert hit_h[1024:].all() and np.array_equal(idx_h[1024:], w.source[1024:])
+
+
+def _compare_topk(bank, probes, k, idx, sim):
+    o_idx, o_sim, o_next = oracle.lookup_topk(bank, probes, k)
+    idx, sim = idx.cpu().numpy(), sim.cpu().numpy()
+    fin = np.isfinite(o_sim)
+    assert np.array_equal(np.isfinite(sim), fin) and np.array_equal(idx[~fin], o_idx[~fin])
+    assert np.abs(sim[fin] - o_sim[fin]).max() < 2e-5
+    n_loose = 0
+    for p in range(probes.shape[0]):
+        assert len(set(idx[p][fin[p]])) == int(fin[p].sum())                      # no row twice
+        ranked = np.concatenate([o_sim[p], [o_next[p]]])
+        s_all = None
+        for j in range(k):
+            if not fin[p, j]:
+                continue
+            clear = (j == 0 or ranked[j - 1] - ranked[j] >= 1e-4) and ranked[j] - ranked[j + 1] >= 1e-4
+            if clear:
+                assert idx[p, j] == o_idx[p, j], (p, j)
+            else:                                                                   # near-tie: any row that close is right
+                if s_all is None:
+                    s_all = oracle.similarities(bank, probes[p])
+                assert abs(s_all[idx[p, j]] - o_sim[p, j]) < 1e-4, (p, j)
+                n_loose += 1
+    return n_loose
+
+
+@pytest.mark.parametrize("dim,n_probes,k", [(1024, 40, 8), (1024, 3, 3), (128, 17, 5), (384, 33, 2), (64, 5, 8)])
+def test_topk_vs_oracle(dim, n_probes, k):
+    w = wl.lookup_clustered("k", 300 + dim, 523, 41, dim, n_probes, 0.05, 0.02, 0.92, n_exact=1, n_near=1)
+    pc = _ctx(w.bank.shape[0], dim)
+    pc.percache_bank_put(0, f16(w.bank))
+    idx, sim = pc.percache_lookup_topk(f16(w.probes), k)
+    i1, s1, _ = pc.percache_lookup(f16(w.probes), w.tau)
+    torch.cuda.synchronize()
+    loose = _compare_topk(w.bank, w.probes, k, idx, sim)
+    assert torch.equal(idx[:, 0], i1) and torch.equal(sim[:, 0], s1)              # rank 1 is the query-level match
+    print(f"top-{k}: {loose} near-tie entries judged by similarity", flush=True)
+
+
+def test_topk_ties_small_bank_and_errors():
+    d = 128
+    g = np.random.default_rng(12)
+    bank = wl.round_f16(g.standard_normal((5, d)).astype(np.float32))
+    bank[3] = bank[1] * 2.0
+    probes = np.stack([bank[1], bank[4]])
+    pc = _ctx(16, d)
+    idx, sim = pc.percache_lookup_topk(f16(probes), 4)
+    torch.cuda.synchronize()
+    assert (idx == -1).all().item() and torch.isneginf(sim).all().item()           # empty bank
+    pc.percache_bank_put(0, f16(bank))
+    idx, sim = pc.percache_lookup_topk(f16(probes), 8)
+    torch.cuda.synchronize()
+    assert idx[0, :2].tolist() == [1, 3] and (idx[:, 5:] == -1).all().item() and torch.isneginf(sim[:, 5:]).all().item()
+    o_idx, o_sim, _ = oracle.lookup_topk(bank, probes, 8)
+    assert np.array_equal(idx.cpu().numpy(), o_idx)
+    with pytest.raises(PercacheError) as e:
+        pc.percache_lookup_topk(f16(probes), 9)
+    assert e.value.status == -2

@@ -88,3 +88,26 @@ def test_clustered_recipe_statistics_small():
     assert hit[64:].all() and np.array_equal(idx[64:], w.source[64:])
     assert np.all(np.abs(sim[64:68] - 1.0) < 1e-3)  # exact copies of fp16 rows
     assert np.all(np.abs(sim - w.tau) > 1e-3)      # threshold comparison is never marginal
+
+
+def test_topk_pins():
+    """k = 1 is the query-level match; against a float64 numpy ranking; sorted, distinct, lower row first on ties."""
+    g = np.random.default_rng(8)
+    E = g.standard_normal((200, 24)).astype(np.float32)
+    E[50] = E[17] * 3.0          # same direction: exact tie in cosine
+    E[120] = 0.0
+    P = np.concatenate([g.standard_normal((6, 24)).astype(np.float32), E[17:18]])
+    i1, s1, _, _ = oracle.lookup(E, P, 0.5)
+    ik, sk, nxt = oracle.lookup_topk(E, P, 5)
+    assert np.array_equal(ik[:, 0], i1) and np.allclose(sk[:, 0], s1, atol=1e-7)
+    En = E.astype(np.float64)
+    nrm = np.linalg.norm(En, axis=1)
+    for p in range(P.shape[0]):
+        q = P[p].astype(np.float64)
+        cos = np.where(nrm > 0, En @ q / np.where(nrm > 0, nrm, 1) / np.linalg.norm(q), 0.0)
+        top = np.sort(cos)[::-1][:6]
+        assert np.allclose(sk[p], top[:5], atol=1e-6) and abs(nxt[p] - top[5]) < 1e-6
+        assert len(set(ik[p])) == 5 and np.all(np.diff(sk[p]) <= 0)
+    assert list(ik[6, :2]) == [17, 50]                                   # tie: lower row first
+    ik2, sk2, nxt2 = oracle.lookup_topk(E[:3], P[:2], 5)                 # k beyond the bank
+    assert np.all(ik2[:, 3:] == -1) and np.all(np.isneginf(sk2[:, 3:])) and np.all(np.isneginf(nxt2))
