@@ -102,6 +102,19 @@ pc_status percache_lookup_topk(percache_ctx *ctx, const void *probes_dev, int32_
                                int32_t *idx_out_dev, float *sim_out_dev, void *workspace_dev,
                                size_t workspace_bytes, void *stream);
 
+/* Cache refresh scan (Sec. 4.1.3): new chunks have been added to the knowledge bank; a stored query's answer is
+ * outdated if one of them ranks in that query's top-k_refresh.  With the bank holding the STORED QUERY embeddings
+ * and kth_sim_dev[j] the similarity of query j's current k-th ranked chunk (percache_lookup_topk over the chunk
+ * embeddings gives it), one pass over the bank per 32 new chunks computes for every bank row j
+ *   best_sim[j] = max over new chunks c of cos(e_j, c),  best_new[j] = the lowest c attaining it,
+ *   stale[j]    = best_sim[j] > kth_sim[j].
+ *   new_emb_dev [n_new, d] fp16;  kth_sim_dev, best_sim_out_dev float[bank size];  best_new_out_dev int32[bank size];
+ *   stale_out_dev uint8[bank size];  workspace as for percache_lookup (it also bounds n_new: 4 bytes per new row). */
+pc_status percache_bank_refresh_scan(percache_ctx *ctx, const void *new_emb_dev, int32_t n_new,
+                                     const float *kth_sim_dev, float *best_sim_out_dev, int32_t *best_new_out_dev,
+                                     uint8_t *stale_out_dev, void *workspace_dev, size_t workspace_bytes,
+                                     void *stream);
+
 /* ---------------------------------------------------------------- K/V store (Sec. 4.1.1)
  * One slot holds one knowledge chunk's K and V for one layer, as collected from the attention
  * module during a prefill (K already rotated at the positions it had then).

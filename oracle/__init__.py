@@ -121,6 +121,24 @@ def lookup_topk(E, probes, k: int):
     return idx, sim, nxt
 
 
+def refresh_scan(E, new, kth):
+    """Cache refresh (Sec. 4.1.3) for bank rows E (stored query embeddings) against newly added chunk embeddings:
+    per row the best cosine similarity over the new chunks, the lowest chunk attaining it, and whether it exceeds
+    the row's current k-th best similarity ``kth`` (then a new chunk enters that query's top-k).  By definition,
+    row by row.  Returns (best_sim [N] float32, best_new [N] int32, stale [N] uint8)."""
+    E = _f(E)
+    new = _f(new)
+    kth = np.asarray(kth, np.float32)
+    N = E.shape[0]
+    best_sim = np.empty(N, np.float32)
+    best_new = np.empty(N, np.int32)
+    for j in range(N):
+        s = similarities(new, E[j])
+        c = int(np.argmax(s))          # first maximum = lowest index
+        best_sim[j], best_new[j] = s[c], c
+    return best_sim, best_new, (best_sim > kth).astype(np.uint8)
+
+
 def rope(u, pos: int, theta: float) -> np.ndarray:
     """RoPE of one head vector at absolute position ``pos`` (App. B.1)."""
     u = _f(u).copy()

@@ -23,7 +23,7 @@ STATUS_NAMES = {0: "PC_OK", -1: "PC_EINVAL", -2: "PC_ESHAPE", -3: "PC_ESLOT", -4
 EXPORTS = [
     "percache_arena_bytes", "percache_create", "percache_destroy", "percache_last_error",
     "percache_bank_put", "percache_bank_size", "percache_lookup_workspace_bytes", "percache_lookup",
-    "percache_lookup_topk",
+    "percache_lookup_topk", "percache_bank_refresh_scan",
     "percache_kv_put", "percache_kv_put_batch", "percache_kv_get", "percache_kv_evict", "percache_kv_len",
     "percache_kv_slice", "percache_stack_workspace_bytes", "percache_stack_reuse",
     "percache_tree_create", "percache_tree_destroy", "percache_tree_match", "percache_tree_insert",
@@ -78,6 +78,7 @@ def load_library() -> ctypes.CDLL:
         "percache_lookup_workspace_bytes": (_sz, [_vp, _i32]),
         "percache_lookup": (_i32, [_vp, _vp, _i32, ctypes.c_float, _vp, _vp, _vp, _vp, _sz, _vp]),
         "percache_lookup_topk": (_i32, [_vp, _vp, _i32, _i32, _vp, _vp, _vp, _sz, _vp]),
+        "percache_bank_refresh_scan": (_i32, [_vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
         "percache_kv_put": (_i32, [_vp, _i32, _i32, _vp, _vp, _i32, _vp]),
         "percache_kv_put_batch": (_i32, [_vp, _i32, _pi32, _i32, _vp, _vp, _i32, _vp]),
         "percache_kv_get": (_i32, [_vp, _i32, _i32, _vp, _vp, _pi32, _vp]),
@@ -221,6 +222,21 @@ class Percache:
         ws = (self._lookup_ws.data_ptr() + 255) // 256 * 256
         self._check(self.lib.percache_lookup_topk(self.ctx, _ptr(probes), n, k, _ptr(idx_out), _ptr(sim_out), ws, need, _stream()))
         return idx_out, sim_out
+
+    def percache_bank_refresh_scan(self, new_emb, kth_sim):
+        """(best_sim [N] float32, best_new [N] int32, stale [N] uint8) for the N bank rows against the new rows."""
+        import torch
+        n_new, N = new_emb.shape[0], self.percache_bank_size()
+        best_sim = torch.empty(N, dtype=torch.float32, device=self.device)
+        best_new = torch.empty(N, dtype=torch.int32, device=self.device)
+        stale = torch.empty(N, dtype=torch.uint8, device=self.device)
+        need = self.lib.percache_lookup_workspace_bytes(self.ctx, n_new)
+        if self._lookup_ws is None or self._lookup_ws.numel() < need + 256:
+            self._lookup_ws = torch.empty(need + 256, dtype=torch.uint8, device=self.device)
+        ws = (self._lookup_ws.data_ptr() + 255) // 256 * 256
+        self._check(self.lib.percache_bank_refresh_scan(self.ctx, _ptr(new_emb), n_new, _ptr(kth_sim), _ptr(best_sim),
+                                                        _ptr(best_new), _ptr(stale), ws, need, _stream()))
+        return best_sim, best_new, stale
 
     # ------------------------------------------------------------------ K/V store
     def percache_kv_put(self, layer: int, slot: int, k, v, n_tokens: Optional[int] = None):

@@ -92,11 +92,23 @@ constexpr int kMaxBlocksPerWg = 128;  // 2048 rows: bounds the LDS copy of the i
 template <int CHB>
 __device__ __forceinline__ int row_swz(int row) { return CHB >= 256 ? (row & 15) : ((row >> 1) & 7); }
 
+// Arguments of the per-row mode (K == 0): instead of the best rows per probe, the best PROBE per bank row is
+// written (cache refresh, Sec. 4.1.3: does any new chunk enter a stored query's top-k?).
+struct RowScan {
+  const float *probe_inv;  // [n_probes] inverse norms of the probes
+  const float *kth;        // [N] similarity a new chunk must exceed for row j (the row's current k-th best)
+  float *best_sim;         // [N] out: best similarity over all new chunks so far
+  int32_t *best_new;       // [N] out: index of that chunk
+  uint8_t *stale;          // [N] out: best_sim > kth
+  int p0;                  // index of this pass's first probe
+  int first;               // 1: first pass (outputs are overwritten), 0: merged with the previous passes
+};
+
 template <int NPB, int CHB, int NSTG, int K>
 __global__ __launch_bounds__(256) void lookup_stream_kernel(const _Float16 *__restrict__ bank,
                                                             const float *__restrict__ inv_norm, int N, int d,
                                                             const _Float16 *__restrict__ probes, int n_probes,
-                                                            int per_wg, int ring_off, Best *__restrict__ partial) {
+                                                            int per_wg, int ring_off, Best *__restrict__ partial, RowScan rs) {
   extern __shared__ __align__(16) char smem[];
   constexpr int CS = CHB / 64;           // MFMA k-steps (32 elements) per chunk
   constexpr int STG = 16 * CHB;          // bytes per stage
@@ -129,9 +141,13 @@ __global__ __launch_bounds__(256) void lookup_stream_kernel(const _Float16 *__re
   const int chunks = d * 2 / CHB;
   char *ring = smem + ring_off + wave * (NSTG * STG);
 
-  TopK<K> best[NPB];  // this lane's best rows for probe pb*16 + r16
+  constexpr int KL = K > 0 ? K : 1;
+  TopK<KL> best[NPB];  // this lane's best rows for probe pb*16 + r16
 #pragma unroll
   for (int pb = 0; pb < NPB; ++pb) best[pb].clear();
+  float pinv[NPB];     // per-row mode: inverse norm of this lane's probes (-inf marks padding probes)
+#pragma unroll
+  for (int pb = 0; pb < NPB; ++pb) pinv[pb] = (K == 0 && pb * 16 + r16 < n_probes) ? rs.probe_inv[pb * 16 + r16] : -INFINITY;
 
   // load instruction i of a stage: lane lands at stage byte 1024 i + 16 lane = (row, physical chunk)
   int ld_row[IPS], ld_col[IPS];
@@ -180,10 +196,33 @@ __global__ __launch_bounds__(256) void lookup_stream_kernel(const _Float16 *__re
     for (int r = 0; r < 4; ++r) {
       const int row = rb * 16 + g * 4 + r;
       const bool ok = row < N;
+      if (K > 0) {
 #pragma unroll
-      for (int pb = 0; pb < NPB; ++pb) {
-        const float s = acc[pb][r] * inv4[r];
-        if (ok) best[pb].insert(s, row);
+        for (int pb = 0; pb < NPB; ++pb) {
+          const float s = acc[pb][r] * inv4[r];
+          if (ok) best[pb].insert(s, row);
+        }
+      } else {
+        // best probe of this row: this lane's probes first, then the 16 lanes that hold the row (lowest probe wins ties)
+        float s = -INFINITY;
+        int pi = INT_MAX;
+#pragma unroll
+        for (int pb = 0; pb < NPB; ++pb) {
+          const float c = pinv[pb] == -INFINITY ? -INFINITY : acc[pb][r] * inv4[r] * pinv[pb];
+          if (better(c, rs.p0 + pb * 16 + r16, s, pi)) { s = c; pi = rs.p0 + pb * 16 + r16; }
+        }
+#pragma unroll
+        for (int o = 1; o < 16; o <<= 1) {
+          const float s2 = __shfl_xor(s, o, 64);
+          const int p2 = __shfl_xor(pi, o, 64);
+          if (better(s2, p2, s, pi)) { s = s2; pi = p2; }
+        }
+        if (ok && r16 == 0) {
+          if (!rs.first && !better(s, pi, rs.best_sim[row], rs.best_new[row])) { s = rs.best_sim[row]; pi = rs.best_new[row]; }
+          rs.best_sim[row] = s;
+          rs.best_new[row] = pi;
+          rs.stale[row] = s > rs.kth[row] ? 1 : 0;
+        }
       }
     }
   };
@@ -221,13 +260,14 @@ __global__ __launch_bounds__(256) void lookup_stream_kernel(const _Float16 *__re
     PC_LOOKUP_WAIT_VMCNT(0);
   }
 
+  if (K == 0) return;  // per-row mode: everything has been written
   // the four lanes that share a probe (K rounds of "best head wins and is popped"), then the four wavefronts
   __syncthreads();  // probes no longer needed: reuse LDS for the cross-wave step
-  Best *red = (Best *)smem;  // [4 waves][NPB*16][K]
+  Best *red = (Best *)smem;  // [4 waves][NPB*16][KL]
 #pragma unroll
   for (int pb = 0; pb < NPB; ++pb) {
 #pragma unroll
-    for (int j = 0; j < K; ++j) {
+    for (int j = 0; j < KL; ++j) {
       float s = best[pb].s[0];
       int i = best[pb].i[0];
 #pragma unroll
@@ -237,24 +277,24 @@ __global__ __launch_bounds__(256) void lookup_stream_kernel(const _Float16 *__re
         if (better(s2, i2, s, i)) { s = s2; i = i2; }
       }
       best[pb].pop_if(i != INT_MAX && best[pb].i[0] == i);  // rows are unique: at most one lane owns the winner
-      if (g == 0) red[(wave * (NPB * 16) + pb * 16 + r16) * K + j] = Best{s, i};
+      if (g == 0) red[(wave * (NPB * 16) + pb * 16 + r16) * KL + j] = Best{s, i};
     }
   }
   __syncthreads();
   if (tid < NPB * 16) {
     int head[4] = {0, 0, 0, 0};
-    for (int j = 0; j < K; ++j) {
+    for (int j = 0; j < KL; ++j) {
       Best b = Best{-INFINITY, INT_MAX};
       int from = -1;
 #pragma unroll
       for (int w = 0; w < 4; ++w) {
-        if (head[w] >= K) continue;
-        Best o = red[(w * (NPB * 16) + tid) * K + head[w]];
+        if (head[w] >= KL) continue;
+        Best o = red[(w * (NPB * 16) + tid) * KL + head[w]];
         if (o.idx != INT_MAX && better(o.s, o.idx, b.s, b.idx)) { b = o; from = w; }
       }
 #pragma unroll
       for (int w = 0; w < 4; ++w) head[w] += (w == from);
-      partial[((size_t)blockIdx.x * (NPB * 16) + tid) * K + j] = b;
+      partial[((size_t)blockIdx.x * (NPB * 16) + tid) * KL + j] = b;
     }
   }
 }
@@ -308,6 +348,23 @@ __global__ __launch_bounds__(64) void lookup_finalize_kernel(const Best *__restr
   }
 }
 
+// inverse L2 norms of n embedding rows (0 for a zero row); one wavefront per row
+__global__ __launch_bounds__(256) void inv_norm_kernel(const _Float16 *__restrict__ src, float *__restrict__ inv_norm, int n, int d) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= n) return;
+  const u32x4 *s = (const u32x4 *)(src + (size_t)row * d);
+  float ss = 0.f;
+  for (int v = lane; v < d / 8; v += 64) {
+    f16x8 h = __builtin_bit_cast(f16x8, s[v]);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ss += (float)h[e] * (float)h[e];
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
+  if (lane == 0) inv_norm[row] = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
+}
+
 __global__ void lookup_empty_kernel(int n_out, int n_probes, int32_t *idx_out, float *sim_out, uint8_t *hit_out) {
   int p = blockIdx.x * blockDim.x + threadIdx.x;
   if (p < n_out) { idx_out[p] = -1; sim_out[p] = -INFINITY; }
@@ -351,28 +408,28 @@ constexpr int kMaxTopK = 8;
 
 template <int NPB, int CHB, int NSTG, int K>
 pc_status launch_stream(percache_ctx *ctx, const StreamShape &sh, hipStream_t st, int N, int d, const _Float16 *pp, int np,
-                        Best *partial) {
+                        Best *partial, const RowScan &rs) {
   static bool big_lds_set = false;  // dynamic LDS above 64 KB must be opted into once per kernel
   if (!big_lds_set) {
     PC_HIP(ctx, hipFuncSetAttribute((const void *)lookup_stream_kernel<NPB, CHB, NSTG, K>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxLds));
     big_lds_set = true;
   }
   hipLaunchKernelGGL((lookup_stream_kernel<NPB, CHB, NSTG, K>), dim3(sh.grid), dim3(256), sh.lds, st, ctx->bank, ctx->bank_inv, N, d,
-                     pp, np, sh.per_wg, sh.ring_off, partial);
+                     pp, np, sh.per_wg, sh.ring_off, partial, rs);
   return PC_OK;
 }
 
 template <int K>
 pc_status launch_pass(percache_ctx *ctx, const StreamShape &sh, int npb, hipStream_t st, int N, int d, const _Float16 *pp, int np,
-                      Best *partial) {
+                      Best *partial, const RowScan &rs = RowScan{}) {
   if (npb == 1 && sh.nstg == 3)
-    return sh.chb == 128   ? launch_stream<1, 128, 3, K>(ctx, sh, st, N, d, pp, np, partial)
-           : sh.chb == 256 ? launch_stream<1, 256, 3, K>(ctx, sh, st, N, d, pp, np, partial)
-                           : launch_stream<1, 512, 3, K>(ctx, sh, st, N, d, pp, np, partial);
-  if (npb == 1) return launch_stream<1, 512, 2, K>(ctx, sh, st, N, d, pp, np, partial);  // only the widest rows (512-byte chunks) get here
-  return sh.chb == 128   ? launch_stream<2, 128, 2, K>(ctx, sh, st, N, d, pp, np, partial)
-         : sh.chb == 256 ? launch_stream<2, 256, 2, K>(ctx, sh, st, N, d, pp, np, partial)
-                         : launch_stream<2, 512, 2, K>(ctx, sh, st, N, d, pp, np, partial);
+    return sh.chb == 128   ? launch_stream<1, 128, 3, K>(ctx, sh, st, N, d, pp, np, partial, rs)
+           : sh.chb == 256 ? launch_stream<1, 256, 3, K>(ctx, sh, st, N, d, pp, np, partial, rs)
+                           : launch_stream<1, 512, 3, K>(ctx, sh, st, N, d, pp, np, partial, rs);
+  if (npb == 1) return launch_stream<1, 512, 2, K>(ctx, sh, st, N, d, pp, np, partial, rs);  // only the widest rows (512-byte chunks) get here
+  return sh.chb == 128   ? launch_stream<2, 128, 2, K>(ctx, sh, st, N, d, pp, np, partial, rs)
+         : sh.chb == 256 ? launch_stream<2, 256, 2, K>(ctx, sh, st, N, d, pp, np, partial, rs)
+                         : launch_stream<2, 512, 2, K>(ctx, sh, st, N, d, pp, np, partial, rs);
 }
 
 // k best rows per probe (k == 1: the query-level match with its hit flag; hit_out may be null otherwise)
@@ -454,6 +511,40 @@ pc_status percache_lookup(percache_ctx *ctx, const void *probes_dev, int32_t n_p
                           float *sim_out_dev, uint8_t *hit_out_dev, void *workspace_dev, size_t workspace_bytes,
                           void *stream) {
   return run_lookup(ctx, probes_dev, n_probes, tau, 1, idx_out_dev, sim_out_dev, hit_out_dev, workspace_dev, workspace_bytes, stream);
+}
+
+pc_status percache_bank_refresh_scan(percache_ctx *ctx, const void *new_emb_dev, int32_t n_new, const float *kth_sim_dev,
+                                     float *best_sim_out_dev, int32_t *best_new_out_dev, uint8_t *stale_out_dev,
+                                     void *workspace_dev, size_t workspace_bytes, void *stream) {
+  if (!ctx) return PC_EINVAL;
+  const percache_config &c = ctx->cfg;
+  if (c.bank_capacity <= 0) return pc::fail(ctx, PC_ESHAPE, "context was created without a bank");
+  if (n_new < 1) return pc::fail(ctx, PC_EINVAL, "n_new must be positive");
+  if (!new_emb_dev || !kth_sim_dev || !best_sim_out_dev || !best_new_out_dev || !stale_out_dev) return pc::fail(ctx, PC_EINVAL, "NULL pointer");
+  if ((uintptr_t)new_emb_dev % 16) return pc::fail(ctx, PC_EINVAL, "new_emb_dev must be 16-byte aligned");
+  const int N = ctx->bank_size, d = c.emb_dim;
+  if (N == 0) return PC_OK;  // nothing to mark
+  const size_t need = percache_lookup_workspace_bytes(ctx, n_new);
+  if (!workspace_dev || workspace_bytes < need || (size_t)n_new * sizeof(float) > need)
+    return pc::fail(ctx, PC_ENOMEM, "workspace has %zu bytes, need %zu (and at most %zu new rows per call)", workspace_bytes, need, need / sizeof(float));
+  if ((uintptr_t)workspace_dev % 16) return pc::fail(ctx, PC_EINVAL, "workspace must be 16-byte aligned");
+  hipStream_t st = (hipStream_t)stream;
+  float *probe_inv = (float *)workspace_dev;
+  const _Float16 *probes = (const _Float16 *)new_emb_dev;
+  hipLaunchKernelGGL(inv_norm_kernel, dim3((n_new + 3) / 4), dim3(256), 0, st, probes, probe_inv, n_new, d);
+  PC_HIP(ctx, hipGetLastError());
+  const int pass_probes = stream_shape(ctx, 2, N).lds <= kMaxLds ? kPassProbes : 16;
+  for (int p0 = 0; p0 < n_new; p0 += pass_probes) {
+    const int np = n_new - p0 < pass_probes ? n_new - p0 : pass_probes;
+    const int npb = np <= 16 ? 1 : 2;
+    StreamShape sh = stream_shape(ctx, npb, N);
+    if (sh.lds > kMaxLds) return pc::fail(ctx, PC_ESHAPE, "emb_dim %d needs %zu bytes of LDS per workgroup", d, sh.lds);
+    RowScan rs{probe_inv + p0, kth_sim_dev, best_sim_out_dev, best_new_out_dev, stale_out_dev, p0, p0 == 0 ? 1 : 0};
+    pc_status ls = launch_pass<0>(ctx, sh, npb, st, N, d, probes + (size_t)p0 * d, np, nullptr, rs);
+    if (ls != PC_OK) return ls;
+    PC_HIP(ctx, hipGetLastError());
+  }
+  return PC_OK;
 }
 
 pc_status percache_lookup_topk(percache_ctx *ctx, const void *probes_dev, int32_t n_probes, int32_t k, int32_t *idx_out_dev,

@@ -208,3 +208,35 @@ def test_topk_ties_small_bank_and_errors():
     with pytest.raises(PercacheError) as e:
         pc.percache_lookup_topk(f16(probes), 9)
     assert e.value.status == -2
+
+
+@pytest.mark.parametrize("dim,n_new", [(1024, 5), (1024, 70), (128, 33)])
+def test_refresh_scan_vs_oracle(dim, n_new):
+    """Cache refresh (Sec. 4.1.3): stored queries in the bank, thresholds from a top-k over the chunk embeddings (GPU),
+    new chunks scanned; against the oracle's row-by-row definition, and against a direct re-ranking."""
+    k = 3
+    wq = wl.lookup_clustered("q", 500 + dim, 97, 53, dim, 4, 0.05, 0.02, 0.92)       # bank rows = stored queries
+    wc = wl.lookup_clustered("c", 600 + dim, 97, 31, dim, 4, 0.05, 0.02, 0.92)       # bank rows = knowledge chunks
+    g = np.random.default_rng(dim + n_new)
+    pick = g.integers(0, wq.bank.shape[0], size=n_new)
+    new = wl.round_f16(wq.bank[pick] + 0.03 * g.standard_normal((n_new, dim)).astype(np.float32))
+    chunks_ctx = _ctx(wc.bank.shape[0], dim)
+    chunks_ctx.percache_bank_put(0, f16(wc.bank))
+    _, sk = chunks_ctx.percache_lookup_topk(f16(wq.bank), k)                          # each stored query's best chunks
+    kth = sk[:, k - 1].contiguous()
+    qctx = _ctx(wq.bank.shape[0], dim)
+    qctx.percache_bank_put(0, f16(wq.bank))
+    best_sim, best_new, stale = qctx.percache_bank_refresh_scan(f16(new), kth)
+    torch.cuda.synchronize()
+    o_sim, o_new, o_stale = oracle.refresh_scan(wq.bank, new, kth.cpu().numpy())
+    bs, bn, st = best_sim.cpu().numpy(), best_new.cpu().numpy(), stale.cpu().numpy()
+    assert np.abs(bs - o_sim).max() < 2e-5
+    loose = 0
+    for j in np.nonzero(bn != o_new)[0]:                                              # only near-ties may differ
+        s = oracle.similarities(new, wq.bank[j])
+        assert o_sim[j] - s[bn[j]] < 1e-4
+        loose += 1
+    margin = np.abs(o_sim - kth.cpu().numpy()) > 1e-4
+    assert np.array_equal(st[margin], o_stale[margin])
+    assert st[pick].all()                                                             # a near copy of a query enters its top-k
+    print(f"refresh scan: {int(st.sum())}/{st.size} stored queries outdated, {loose} near-tie indices", flush=True)

@@ -111,3 +111,23 @@ def test_topk_pins():
     assert list(ik[6, :2]) == [17, 50]                                   # tie: lower row first
     ik2, sk2, nxt2 = oracle.lookup_topk(E[:3], P[:2], 5)                 # k beyond the bank
     assert np.all(ik2[:, 3:] == -1) and np.all(np.isneginf(sk2[:, 3:])) and np.all(np.isneginf(nxt2))
+
+
+def test_refresh_scan_marks_exactly_the_queries_whose_topk_changes():
+    """Sec. 4.1.3 stated directly: re-rank every stored query against old + new chunks; a query is outdated iff a new
+    chunk is among its k best.  The scan (threshold = old k-th similarity) must mark the same queries."""
+    g = np.random.default_rng(21)
+    d, k = 32, 3
+    chunks = g.standard_normal((150, d)).astype(np.float32)
+    queries = g.standard_normal((90, d)).astype(np.float32)
+    new = np.concatenate([g.standard_normal((5, d)), queries[[4, 40]] + 0.05 * g.standard_normal((2, d))]).astype(np.float32)
+    _, sk, _ = oracle.lookup_topk(chunks, queries, k)
+    best_sim, best_new, stale = oracle.refresh_scan(queries, new, sk[:, k - 1])
+    idx_all, _, _ = oracle.lookup_topk(np.concatenate([chunks, new]), queries, k)
+    entered = (idx_all >= chunks.shape[0]).any(axis=1)
+    assert np.array_equal(stale.astype(bool), entered) and stale[4] and stale[40] and 2 <= stale.sum() < 60
+    # float64 numpy for the maxima
+    cn = new / np.linalg.norm(new, axis=1, keepdims=True)
+    qn = queries / np.linalg.norm(queries, axis=1, keepdims=True)
+    cos = qn.astype(np.float64) @ cn.astype(np.float64).T
+    assert np.array_equal(best_new, cos.argmax(axis=1)) and np.allclose(best_sim, cos.max(axis=1), atol=1e-6)
