@@ -219,6 +219,20 @@ def main():
         look[f"P{p}"] = {"ms": round(t * 1e3, 4), "lookups_per_s": round(p / t, 1),
                          "bank_GBps": round(bank_bytes * passes / t / 1e9, 1)}
 
+    # ------------------------------------------------------------------ one decoding step of the same layer
+    # (one new token per query over the 16 reused chunks + the 256-token prompt slot written by the step above)
+    x1 = X[:, :1].contiguous()
+    ids1 = np.concatenate([w.slot_ids, np.asarray(spare, np.int32)[:, None]], axis=1)
+    attn1 = torch.empty((B, 1, w.n_q_heads * w.head_dim), dtype=torch.bfloat16, device=dev)
+    dec = lambda: pc.percache_prefill_reuse(0, x1, W, ids1, None, attn_out=attn1)
+    _wall_ms(torch, dec, 10, 5)
+    pc.percache_profile_enable(True)
+    dec_ms = _wall_ms(torch, dec, 50, 0)
+    dec_attn_ms, dec_n = pc.percache_profile_read(binding.KERNEL_ATTENTION)
+    pc.percache_profile_read(binding.KERNEL_QKV_ROPE)
+    pc.percache_profile_enable(False)
+    dec_bytes = float(B) * (w.l_pre[0] + T) * w.n_kv_heads * w.head_dim * 2 * 2
+
     out = {
         "metric": "fresh tokens/sec of cache-reuse prefill", "value": round(tokens_per_s, 1), "unit": "tokens/s",
         "n_gpus": 1, "steps": K_steps, "warmup": args.warmup, "ms_per_step": round(ms_step, 4),
@@ -237,6 +251,9 @@ def main():
             "lookup_in_step": {"avg_pass_ms": round(look_ms, 4), "bank_GBps": round(bank_bytes / (look_ms * 1e-3) / 1e9, 1),
                                "frac_of_hbm_peak": round(bank_bytes / (look_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)},
             "lookup_alone": look,
+            "decode_step_layer": {"ms_per_call": round(dec_ms, 4), "attention_ms": round(dec_attn_ms / max(dec_n, 1), 4),
+                                  "kv_stream_GBps": round(dec_bytes / (dec_attn_ms / max(dec_n, 1) * 1e-3) / 1e9, 1),
+                                  "keys_per_query": int(w.l_pre[0] + T), "batch": B},
         },
     }
 

@@ -132,6 +132,10 @@ pc_status percache_kv_evict(percache_ctx *ctx, int32_t layer, int32_t slot);
  * saved at once); chunk i goes to slot slots_host[i].  Slots must be distinct. */
 pc_status percache_kv_put_batch(percache_ctx *ctx, int32_t layer, const int32_t *slots_host, int32_t n,
                                 const void *k_dev, const void *v_dev, int32_t n_tokens, void *stream);
+/* Appends n_tokens tokens ([n_kv_heads, n_tokens, head_dim] bf16 each) behind the tokens a slot already holds (an
+ * empty slot is allowed): the decoding stage grows a sequence's own K/V token by token (Sec. 2.1). */
+pc_status percache_kv_append(percache_ctx *ctx, int32_t layer, int32_t slot, const void *k_dev, const void *v_dev,
+                             int32_t n_tokens, void *stream);
 /* Cache slicer (Sec. 4.1.1, App. B.2): cuts the K/V of one prefilled sequence at chunk boundaries and stores
  * each piece in a slot of its own.  k_dev, v_dev: [n_kv_heads, seq_len, head_dim] bf16 (post-RoPE K); piece j is
  * the token range [bounds_host[j], bounds_host[j+1]) (n + 1 bounds; at most slot_capacity tokens per piece) and
@@ -257,6 +261,18 @@ pc_status percache_stack_reuse(percache_ctx *ctx, const percache_block_weights *
                                const int32_t *n_chunks_host, int32_t max_chunks, const int32_t *save_bounds_host,
                                const int32_t *save_slots_host, int32_t n_save, void *h_out_dev, void *workspace_dev,
                                size_t workspace_bytes, void *stream);
+
+/* Decoding step (Sec. 2.1: after prefill the model emits one token at a time, each attending to everything before
+ * it): percache_stack_reuse for n_new >= 1 new tokens per query (h_in_dev [batch, n_new, hidden]) whose chunk
+ * list names everything already stored -- the reused knowledge chunks, then the slots that hold the prompt's own
+ * K/V and the tokens generated so far -- and whose new K/V are APPENDED, layer by layer, to slot
+ * append_slots_host[b] (negative: not stored).  That slot may be (and usually is) the last one of the query's own
+ * chunk list: it is read with its old length and grows afterwards.  Same workspace as percache_stack_reuse. */
+pc_status percache_stack_decode(percache_ctx *ctx, const percache_block_weights *layers_host, int32_t n_layers,
+                                int32_t ffn, float eps, const void *h_in_dev, int32_t batch, int32_t n_new,
+                                const int32_t *slot_ids_host, const int32_t *used_len_host,
+                                const int32_t *n_chunks_host, int32_t max_chunks, const int32_t *append_slots_host,
+                                void *h_out_dev, void *workspace_dev, size_t workspace_bytes, void *stream);
 
 /* ---------------------------------------------------------------- kernel timing
  * With profiling on, the launches of the three main kernels are bracketed by HIP events on the caller's

@@ -25,7 +25,8 @@ EXPORTS = [
     "percache_bank_put", "percache_bank_size", "percache_lookup_workspace_bytes", "percache_lookup",
     "percache_lookup_topk", "percache_bank_refresh_scan",
     "percache_kv_put", "percache_kv_put_batch", "percache_kv_get", "percache_kv_evict", "percache_kv_len",
-    "percache_kv_slice", "percache_stack_workspace_bytes", "percache_stack_reuse",
+    "percache_kv_slice", "percache_kv_append", "percache_stack_workspace_bytes", "percache_stack_reuse",
+    "percache_stack_decode",
     "percache_tree_create", "percache_tree_destroy", "percache_tree_match", "percache_tree_insert",
     "percache_tree_nodes", "percache_tree_bytes",
     "percache_prefill_workspace_bytes", "percache_prefill_reuse", "percache_qkv_rope", "percache_attention_reuse",
@@ -89,6 +90,9 @@ def load_library() -> ctypes.CDLL:
         "percache_qkv_rope": (_i32, [_vp, _vp, _vp, _i32, _i32, _pi32, _pi32, _pi32, _i32, _i32, _vp, _vp, _vp, _vp, _sz, _vp]),
         "percache_attention_reuse": (_i32, [_vp, _i32, _vp, _vp, _vp, _i32, _i32, _pi32, _pi32, _pi32, _i32, _i32, _vp, _vp, _sz, _vp]),
         "percache_kv_slice": (_i32, [_vp, _i32, _vp, _vp, _i32, _pi32, _pi32, _i32, _vp]),
+        "percache_kv_append": (_i32, [_vp, _i32, _i32, _vp, _vp, _i32, _vp]),
+        "percache_stack_decode": (_i32, [_vp, ctypes.POINTER(BlockWeights), _i32, _i32, ctypes.c_float, _vp, _i32, _i32,
+                                         _pi32, _pi32, _pi32, _i32, _pi32, _vp, _vp, _sz, _vp]),
         "percache_stack_workspace_bytes": (_sz, [_vp, _i32, _i32, _i32, _i32]),
         "percache_stack_reuse": (_i32, [_vp, ctypes.POINTER(BlockWeights), _i32, _i32, ctypes.c_float, _vp, _i32, _i32,
                                         _pi32, _pi32, _pi32, _i32, _pi32, _pi32, _i32, _vp, _vp, _sz, _vp]),
@@ -269,6 +273,9 @@ class Percache:
         assert len(b) == len(sl) + 1
         self._check(self.lib.percache_kv_slice(self.ctx, layer, _ptr(k), _ptr(v), k.shape[1], bp, sp, len(sl), _stream()))
 
+    def percache_kv_append(self, layer: int, slot: int, k, v):
+        self._check(self.lib.percache_kv_append(self.ctx, layer, slot, _ptr(k), _ptr(v), k.shape[1], _stream()))
+
     def percache_kv_evict(self, layer: int, slot: int):
         self._check(self.lib.percache_kv_evict(self.ctx, layer, slot))
 
@@ -340,16 +347,21 @@ class Percache:
     def percache_stack_workspace_bytes(self, batch, t_fresh, max_chunks, ffn) -> int:
         return self.lib.percache_stack_workspace_bytes(self.ctx, batch, t_fresh, max_chunks, ffn)
 
+    @staticmethod
+    def _weights(layers):
+        arr = (BlockWeights * len(layers))()
+        for i, lw in enumerate(layers):
+            for name, _t in BlockWeights._fields_:
+                setattr(arr[i], name, _ptr(lw[name]))
+        return arr
+
     def percache_stack_reuse(self, layers, ffn: int, eps: float, h_in, slot_ids=None, used_len=None, n_chunks=None,
                              save_bounds=None, save_slots=None, h_out=None):
         """layers: one dict per layer with the tensors gain1, wqkv, wo, gain2, w_gate, w_up, w_down (bf16, on device)."""
         import torch
         batch, t_fresh, _ = h_in.shape
         keep, ids_p, ul_p, nc_p, max_chunks = self._chunk_args(batch, slot_ids, used_len, n_chunks)
-        arr = (BlockWeights * len(layers))()
-        for i, lw in enumerate(layers):
-            for name, _t in BlockWeights._fields_:
-                setattr(arr[i], name, _ptr(lw[name]))
+        arr = self._weights(layers)
         sb, sb_p = _host_i32(save_bounds)
         n_save = 0 if sb is None else len(sb) - 1
         ss, ss_p = _host_i32(save_slots, (batch, n_save)) if n_save else (None, None)
@@ -360,6 +372,22 @@ class Percache:
         self._check(self.lib.percache_stack_reuse(self.ctx, arr, len(layers), ffn, eps, _ptr(h_in), batch, t_fresh, ids_p,
                                                   ul_p, nc_p, max_chunks, sb_p, ss_p, n_save, _ptr(h_out), ws, need,
                                                   _stream()))
+        return h_out
+
+    def percache_stack_decode(self, layers, ffn: int, eps: float, h_in, slot_ids, append_slots, used_len=None, n_chunks=None,
+                              h_out=None):
+        """One decoding step for [batch, n_new, hidden] new rows; their K/V are appended to append_slots[b]."""
+        import torch
+        batch, n_new, _ = h_in.shape
+        keep, ids_p, ul_p, nc_p, max_chunks = self._chunk_args(batch, slot_ids, used_len, n_chunks)
+        arr = self._weights(layers)
+        ap, ap_p = _host_i32(append_slots, (batch,))
+        if h_out is None:
+            h_out = torch.empty_like(h_in)
+        need = self.percache_stack_workspace_bytes(batch, n_new, max_chunks, ffn)
+        ws = self._workspace(need)
+        self._check(self.lib.percache_stack_decode(self.ctx, arr, len(layers), ffn, eps, _ptr(h_in), batch, n_new, ids_p, ul_p,
+                                                   nc_p, max_chunks, ap_p, _ptr(h_out), ws, need, _stream()))
         return h_out
 
 

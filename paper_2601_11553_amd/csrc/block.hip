@@ -356,13 +356,29 @@ size_t percache_stack_workspace_bytes(const percache_ctx *ctx, int32_t batch, in
   return carve_stack_ws(ctx, nullptr, batch, t_fresh, max_chunks, ffn).total;
 }
 
-pc_status percache_stack_reuse(percache_ctx *ctx, const percache_block_weights *layers_host, int32_t n_layers, int32_t ffn,
-                               float eps, const void *h_in_dev, int32_t batch, int32_t t_fresh,
-                               const int32_t *slot_ids_host, const int32_t *used_len_host, const int32_t *n_chunks_host,
-                               int32_t max_chunks, const int32_t *save_bounds_host, const int32_t *save_slots_host,
-                               int32_t n_save, void *h_out_dev, void *workspace_dev, size_t workspace_bytes, void *stream) {
+static pc_status run_stack(percache_ctx *ctx, const percache_block_weights *layers_host, int32_t n_layers, int32_t ffn,
+                           float eps, const void *h_in_dev, int32_t batch, int32_t t_fresh,
+                           const int32_t *slot_ids_host, const int32_t *used_len_host, const int32_t *n_chunks_host,
+                           int32_t max_chunks, const int32_t *save_bounds_host, const int32_t *save_slots_host,
+                           int32_t n_save, const int32_t *append_slots_host, void *h_out_dev, void *workspace_dev,
+                           size_t workspace_bytes, void *stream) {
   if (!ctx) return PC_EINVAL;
   const percache_config &c = ctx->cfg;
+  if (append_slots_host && batch >= 1 && t_fresh >= 1) {
+    for (int b = 0; b < batch; ++b) {
+      const int slot = append_slots_host[b];
+      if (slot < 0) continue;
+      if (slot >= c.n_slots) return pc::fail(ctx, PC_ESLOT, "append slot %d out of range [0,%d)", slot, c.n_slots);
+      for (int bb = 0; bb < b; ++bb)
+        if (append_slots_host[bb] == slot) return pc::fail(ctx, PC_EINVAL, "append slot %d appears twice", slot);
+      for (int l = 0; l < n_layers && l < c.n_layers; ++l) {
+        const int have = ctx->slot_len[(size_t)l * c.n_slots + slot];
+        if (have != ctx->slot_len[slot]) return pc::fail(ctx, PC_ELEN, "append slot %d holds different lengths in layers 0 and %d", slot, l);
+        if (have + t_fresh > c.slot_capacity)
+          return pc::fail(ctx, PC_ELEN, "append slot %d holds %d tokens: %d more do not fit the capacity %d", slot, have, t_fresh, c.slot_capacity);
+      }
+    }
+  }
   if (!layers_host || !h_in_dev || !h_out_dev) return pc::fail(ctx, PC_EINVAL, "NULL pointer");
   if (n_layers < 1 || n_layers > c.n_layers) return pc::fail(ctx, PC_ESHAPE, "n_layers %d outside [1,%d]", n_layers, c.n_layers);
   if (ffn < 64 || ffn % 64) return pc::fail(ctx, PC_ESHAPE, "ffn %d must be a positive multiple of 64", ffn);
@@ -439,6 +455,15 @@ pc_status percache_stack_reuse(percache_ctx *ctx, const percache_block_weights *
         PC_TRY(pc::launch_kv_store(ctx, l, slot, ws.pf.k + at, ws.pf.v + at, cnt, (long)t_fresh * c.head_dim, s));
         ctx->slot_len[(size_t)l * c.n_slots + slot] = cnt;
       }
+    for (int b = 0; b < batch && append_slots_host; ++b) {
+      // after the attention launch in stream order: the keys it gathered from this slot are the older ones
+      const int slot = append_slots_host[b];
+      if (slot < 0) continue;
+      const int have = ctx->slot_len[(size_t)l * c.n_slots + slot];
+      const size_t at = (size_t)b * c.n_kv_heads * t_fresh * c.head_dim;
+      PC_TRY(pc::launch_kv_append(ctx, l, slot, ws.pf.k + at, ws.pf.v + at, have, t_fresh, (long)t_fresh * c.head_dim, s));
+      ctx->slot_len[(size_t)l * c.n_slots + slot] = have + t_fresh;
+    }
     if (skinny) {
       const int m_tiles = M > 128 ? 2 : 1;
       const __bf16 *next_gain = l + 1 < n_layers ? (const __bf16 *)layers_host[l + 1].gain1 : nullptr;
@@ -461,6 +486,26 @@ pc_status percache_stack_reuse(percache_ctx *ctx, const percache_block_weights *
     h_cur = h_out;
   }
   return PC_OK;
+}
+
+pc_status percache_stack_reuse(percache_ctx *ctx, const percache_block_weights *layers_host, int32_t n_layers, int32_t ffn,
+                               float eps, const void *h_in_dev, int32_t batch, int32_t t_fresh,
+                               const int32_t *slot_ids_host, const int32_t *used_len_host, const int32_t *n_chunks_host,
+                               int32_t max_chunks, const int32_t *save_bounds_host, const int32_t *save_slots_host,
+                               int32_t n_save, void *h_out_dev, void *workspace_dev, size_t workspace_bytes, void *stream) {
+  return run_stack(ctx, layers_host, n_layers, ffn, eps, h_in_dev, batch, t_fresh, slot_ids_host, used_len_host, n_chunks_host,
+                   max_chunks, save_bounds_host, save_slots_host, n_save, nullptr, h_out_dev, workspace_dev, workspace_bytes, stream);
+}
+
+pc_status percache_stack_decode(percache_ctx *ctx, const percache_block_weights *layers_host, int32_t n_layers, int32_t ffn,
+                                float eps, const void *h_in_dev, int32_t batch, int32_t n_new,
+                                const int32_t *slot_ids_host, const int32_t *used_len_host, const int32_t *n_chunks_host,
+                                int32_t max_chunks, const int32_t *append_slots_host, void *h_out_dev, void *workspace_dev,
+                                size_t workspace_bytes, void *stream) {
+  if (!ctx) return PC_EINVAL;
+  if (!append_slots_host) return pc::fail(ctx, PC_EINVAL, "append_slots_host is NULL");
+  return run_stack(ctx, layers_host, n_layers, ffn, eps, h_in_dev, batch, n_new, slot_ids_host, used_len_host, n_chunks_host,
+                   max_chunks, nullptr, nullptr, 0, append_slots_host, h_out_dev, workspace_dev, workspace_bytes, stream);
 }
 
 }  // extern "C"

@@ -87,6 +87,37 @@ __global__ __launch_bounds__(256) void kv_copy_kernel(pc::u32x4 *__restrict__ sl
   }
 }
 
+// Appends n_new tokens behind the `off` tokens a slot already holds.  K: rows copied to their place.  V: every
+// position of the 64-key blocks that receive a token is rewritten from `off` on -- the new tokens, then zeros, so
+// that the padding of the last block stays finite (masked probabilities multiply it).
+__global__ __launch_bounds__(256) void kv_append_kernel(__bf16 *__restrict__ slot_k, __bf16 *__restrict__ slot_v,
+                                                        const __bf16 *__restrict__ k_new, const __bf16 *__restrict__ v_new,
+                                                        int n_heads, int off, int n_new, int D, int C, long new_head_stride) {
+  const int tile0 = off / kKvTile, n_tiles = (off + n_new + kKvTile - 1) / kKvTile - tile0;
+  const long stride = (long)gridDim.x * blockDim.x;
+  const long tid0 = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  const long total_k = (long)n_heads * n_new * D;
+  for (long e = tid0; e < total_k; e += stride) {
+    const int dd = (int)(e % D);
+    const long r = e / D;
+    const int t = (int)(r % n_new), g = (int)(r / n_new);
+    slot_k[((size_t)g * C + off + t) * D + dd] = k_new[(size_t)g * new_head_stride + (size_t)t * D + dd];
+  }
+  const long total_v = (long)n_heads * n_tiles * D * kKvTile;
+  for (long e = tid0; e < total_v; e += stride) {
+    const int p = (int)(e % kKvTile);  // physical position inside the block
+    long r = e / kKvTile;
+    const int dd = (int)(r % D);
+    r /= D;
+    const int tile = tile0 + (int)(r % n_tiles), g = (int)(r / n_tiles);
+    const int t_abs = tile * kKvTile + (p & ~15) + pc::blocked_key(p & 15);
+    if (t_abs < off) continue;  // older tokens stay
+    const int t = t_abs - off;
+    const __bf16 val = t < n_new ? v_new[(size_t)g * new_head_stride + (size_t)t * D + dd] : (__bf16)0.f;
+    slot_v[((size_t)g * C + (size_t)tile * kKvTile) * D + (size_t)dd * kKvTile + p] = val;
+  }
+}
+
 pc_status check_slot(percache_ctx *ctx, int32_t layer, int32_t slot) {
   if (!ctx) return PC_EINVAL;
   if (layer < 0 || layer >= ctx->cfg.n_layers) return pc::fail(ctx, PC_ESLOT, "layer %d out of range [0,%d)", layer, ctx->cfg.n_layers);
@@ -119,9 +150,37 @@ pc_status launch_kv_store(percache_ctx *ctx, int layer, int slot, const __bf16 *
                           long dense_head_stride, hipStream_t stream) {
   return launch_copy<true>(ctx, layer, &slot, 1, (void *)k, (void *)v, n_tokens, stream, dense_head_stride);
 }
+pc_status launch_kv_append(percache_ctx *ctx, int layer, int slot, const __bf16 *k, const __bf16 *v, int off, int n_tokens,
+                           long new_head_stride, hipStream_t stream) {
+  const percache_config &c = ctx->cfg;
+  const size_t at = (size_t)layer * ctx->layer_stride + (size_t)slot * ctx->slot_stride;
+  const long work = (long)c.n_kv_heads * c.head_dim * ((n_tokens + kKvTile - 1) / kKvTile + 1) * kKvTile;
+  int blocks = (int)((work + 255) / 256);
+  if (blocks > 1024) blocks = 1024;
+  hipLaunchKernelGGL(kv_append_kernel, dim3(blocks), dim3(256), 0, stream, ctx->k_store + at, ctx->v_store + at, k, v,
+                     c.n_kv_heads, off, n_tokens, c.head_dim, c.slot_capacity, new_head_stride);
+  PC_HIP(ctx, hipGetLastError());
+  return PC_OK;
+}
 }  // namespace pc
 
 extern "C" {
+
+pc_status percache_kv_append(percache_ctx *ctx, int32_t layer, int32_t slot, const void *k_dev, const void *v_dev,
+                             int32_t n_tokens, void *stream) {
+  pc_status st = check_slot(ctx, layer, slot);
+  if (st != PC_OK) return st;
+  if (!k_dev || !v_dev) return pc::fail(ctx, PC_EINVAL, "k_dev / v_dev is NULL");
+  const percache_config &c = ctx->cfg;
+  const int have = ctx->slot_len[(size_t)layer * c.n_slots + slot];
+  if (n_tokens < 1 || have + n_tokens > c.slot_capacity)
+    return pc::fail(ctx, PC_ELEN, "slot %d holds %d tokens: %d more do not fit the capacity %d", slot, have, n_tokens, c.slot_capacity);
+  st = pc::launch_kv_append(ctx, layer, slot, (const __bf16 *)k_dev, (const __bf16 *)v_dev, have, n_tokens,
+                            (long)n_tokens * c.head_dim, (hipStream_t)stream);
+  if (st != PC_OK) return st;
+  ctx->slot_len[(size_t)layer * c.n_slots + slot] = have + n_tokens;
+  return PC_OK;
+}
 
 pc_status percache_kv_put(percache_ctx *ctx, int32_t layer, int32_t slot, const void *k_dev, const void *v_dev,
                           int32_t n_tokens, void *stream) {

@@ -136,4 +136,8 @@ pc_status launch_attention(percache_ctx *ctx, int layer, const __bf16 *q, const 
 pc_status launch_kv_store(percache_ctx *ctx, int layer, int slot, const __bf16 *k, const __bf16 *v, int n_tokens,
                           long dense_head_stride, hipStream_t stream);
 
+// Appends n_tokens tokens behind the `off` tokens a slot holds (no validation, no slot-table update).
+pc_status launch_kv_append(percache_ctx *ctx, int layer, int slot, const __bf16 *k, const __bf16 *v, int off, int n_tokens,
+                           long new_head_stride, hipStream_t stream);
+
 }  // namespace pc
