@@ -143,7 +143,7 @@ def main():
     B, T = w.batch, w.t_fresh
     n_spare = B
     pc = Percache(n_layers=1, hidden=w.hidden, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
-                  n_slots=w.n_slots + n_spare, slot_capacity=w.chunk_tokens, max_pos=w.max_pos, rope_theta=w.rope_theta,
+                  n_slots=w.n_slots + n_spare, slot_capacity=w.chunk_tokens, max_pos=w.max_pos + 64, rope_theta=w.rope_theta,
                   bank_capacity=N, emb_dim=d, device=dev)
     bf = lambda a: torch.from_numpy(np.ascontiguousarray(a, np.float32)).to(dev, torch.bfloat16)
     used_slots = sorted(set(int(s) for s in w.slot_ids.reshape(-1)))
