@@ -30,7 +30,8 @@ using pc::kTblHeader;
 using pc::u32x4;
 
 constexpr int TK = kKvTile;  // keys per tile
-constexpr float kLazy = 8.f; // log2 slack before the running max is refreshed
+constexpr float kLazy = 8.f; // log2 slack before the reference exponent is refreshed
+constexpr float kSumLimit = 32.f * 256.f;  // 32 probabilities of a lane and tile, each at most 2^kLazy
 
 // LDS stage = one K tile [TK][D] followed by one V block [D][TK], both unpadded (they are filled by
 // direct global->LDS loads, which write 1 KB per wavefront instruction contiguously).  Bank conflicts are
@@ -278,17 +279,44 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
         }
     }
 
-    // ---- online softmax in the log2 domain with a lazily refreshed reference exponent
-    float mx = s_acc[0][0];
+    // ---- online softmax in the log2 domain with a lazily refreshed reference exponent.  Common path: the
+    // probabilities are taken against the current reference and only their sum is looked at -- a probability above
+    // 2^kLazy shows up there, so no row maximum is needed.  The row sum is taken over the bf16-rounded
+    // probabilities (the very values the PV product uses), two per instruction.
+    bf16x8 pf[2][2];
+    auto exponentials = [&](float neg_m) __attribute__((always_inline)) {
+      typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+      const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+      float sum = 0.f;
 #pragma unroll
-    for (int kbk = 0; kbk < 2; ++kbk)
+      for (int kbk = 0; kbk < 2; ++kbk)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s_acc[kbk][r]);
-    // m_ref is common to the two lanes of a row: if neither lane's own keys exceed it by kLazy, nor does the row,
-    // so the common path needs no exchange between the lanes
-    if (__builtin_amdgcn_ballot_w64(mx * scale_log2e > m_ref + kLazy) != 0) {
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int e = 0; e < 8; e += 2) {
+            const float p0 = fast_exp2(__builtin_fmaf(s_acc[kbk][j * 8 + e], scale_log2e, neg_m));
+            const float p1 = fast_exp2(__builtin_fmaf(s_acc[kbk][j * 8 + e + 1], scale_log2e, neg_m));
+            const bf16x2 pr = {(__bf16)p0, (__bf16)p1};
+            pf[kbk][j][e] = pr[0];
+            pf[kbk][j][e + 1] = pr[1];
+            sum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, sum, false);
+          }
+      return sum;
+    };
+    float psum = 0.f;
+    bool refresh = __builtin_amdgcn_ballot_w64(m_ref == -INFINITY) != 0;  // a row that has seen no key yet
+    if (!refresh) {
+      psum = exponentials(-m_ref);
+      refresh = __builtin_amdgcn_ballot_w64(!(psum <= kSumLimit)) != 0;   // also catches inf / nan
+    }
+    if (refresh) {  // rare: row maxima, exchange between the two lanes of a row, rescale, probabilities again
+      float mx = s_acc[0][0];
+#pragma unroll
+      for (int kbk = 0; kbk < 2; ++kbk)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s_acc[kbk][r]);
       const float mc = pair_max(mx) * scale_log2e;
-      const bool upd = mc > m_ref + kLazy;  // also true for the first finite tile (m_ref = -inf)
+      const bool upd = mc > m_ref;  // (false for a row whose keys are all masked: mc = -inf)
       const float alpha = upd ? fast_exp2(m_ref - mc) : 1.0f;  // m_ref = -inf gives 0
       m_ref = upd ? mc : m_ref;
       l_run *= alpha;
@@ -296,20 +324,8 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
       for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int r = 0; r < 16; ++r) o_acc[db][r] *= alpha;
+      psum = exponentials((m_ref == -INFINITY) ? 0.f : -m_ref);
     }
-    const float neg_m = (m_ref == -INFINITY) ? 0.f : -m_ref;
-    float psum = 0.f;
-    bf16x8 pf[2][2];
-#pragma unroll
-    for (int kbk = 0; kbk < 2; ++kbk)
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          float p = fast_exp2(__builtin_fmaf(s_acc[kbk][j * 8 + e], scale_log2e, neg_m));
-          psum += p;
-          pf[kbk][j][e] = (__bf16)p;
-        }
     l_run += psum;
 
     // ---- O^T += V^T P^T
