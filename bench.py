@@ -215,9 +215,13 @@ def main():
     look = {}
     for p in (1, 8, 32, 1024):
         t = time_lookup(probes_all[:p].contiguous())
-        passes = (p + 31) // 32
-        look[f"P{p}"] = {"ms": round(t * 1e3, 4), "lookups_per_s": round(p / t, 1),
-                         "bank_GBps": round(bank_bytes * passes / t / 1e9, 1)}
+        if p <= 32:   # one streaming pass of the bank: HBM bound
+            look[f"P{p}"] = {"ms": round(t * 1e3, 4), "lookups_per_s": round(p / t, 1), "bound": "hbm",
+                             "bank_GBps": round(bank_bytes / t / 1e9, 1), "frac_of_hbm_peak": round(bank_bytes / t / 1e9 / PEAK_HBM_GBS, 4)}
+        else:         # matrix-product kernel: fp16 MFMA bound (2 N d flop per probe)
+            tf = 2.0 * N * d * p / t / 1e12
+            look[f"P{p}"] = {"ms": round(t * 1e3, 4), "lookups_per_s": round(p / t, 1), "bound": "mfma", "TFLOPs": round(tf, 1),
+                             "frac_of_fp16_peak": round(tf / PEAK_BF16_TFLOPS, 4)}
 
     # ------------------------------------------------------------------ one decoding step of the same layer
     # (one new token per query over the 16 reused chunks + the 256-token prompt slot written by the step above)

@@ -1,5 +1,5 @@
 // Main loop shared by the projection kernels: Y^T tile = W_tile (128 features) x X_tile^T (64 or 128 tokens),
-// bf16 operands, fp32 accumulation on the 32x32x16 matrix cores.
+// bf16 (or fp16) operands, fp32 accumulation on the 32x32x16 matrix cores.
 //
 // A workgroup of 4 wavefronts computes 128 output features x (64 or 128) tokens.  The features are the M side of
 // the MFMA and the tokens the N side, so a lane ends up holding 4 consecutive features of one token per accumulator
@@ -41,24 +41,32 @@ __device__ __forceinline__ void unpack4(uint2 raw, float (&o)[4]) {
   for (int e = 0; e < 4; ++e) o[e] = (float)v[e];
 }
 
+__device__ __forceinline__ f32x16 mma(bf16x8 a, bf16x8 b, f32x16 c) { return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0); }
+__device__ __forceinline__ f32x16 mma(f16x8 a, f16x8 b, f32x16 c) { return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0); }
+template <class T> struct Vec8;
+template <> struct Vec8<__bf16> { typedef bf16x8 type; };
+template <> struct Vec8<_Float16> { typedef f16x8 type; };
+
+// T: __bf16 or _Float16 (both operands).
 // w_row(r): pointer to the first of the K contiguous elements of the weight row that tile row r (0..127) stands
 // for (already advanced to the start of the k range when only a slice of the contraction is computed).
 // X: token rows of ldx elements, pointing at the first element of the k range; the tile covers token rows
 // m0 .. m0 + BT - 1 (clamped to M - 1 when reading); K elements are contracted.
 // On return acc[a][t] holds features (a ? fb_hi : fb_lo) * 32 + (r/4)*8 + 4*(lane/32) + r%4 of token
 // m0 + (wt*NTB + t)*32 + lane%32 in element r.
-template <int NTB, class WRow>
-__device__ __forceinline__ void mainloop(char *lds, WRow w_row, const __bf16 *__restrict__ X, int ldx, int m0, int M, int K,
+template <int NTB, class T, class WRow>
+__device__ __forceinline__ void mainloop(char *lds, WRow w_row, const T *__restrict__ X, int ldx, int m0, int M, int K,
                                          int fb_lo, int fb_hi, f32x16 (&acc)[2][NTB]) {
   using S = Shape<NTB>;
+  using V8 = typename Vec8<T>::type;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wt = wave >> 1;
   const int l32 = lane & 31, g = lane >> 5;
 
   // direct global -> LDS loads: wavefront instruction i fills bytes [1024 i, 1024 i + 1024) of a tile, lane l
   // the 16 bytes at 1024 i + 16 l, i.e. row (8 i + l / 8), physical chunk l % 8 <- logical chunk (l % 8) ^ swz(row)
-  const __bf16 *w_src[S::W_INSTR];
-  const __bf16 *x_src[S::X_INSTR];
+  const T *w_src[S::W_INSTR];
+  const T *x_src[S::X_INSTR];
 #pragma unroll
   for (int k = 0; k < S::W_INSTR; ++k) {
     const int row = (wave + k * NW) * 8 + (lane >> 3);
@@ -106,13 +114,13 @@ __device__ __forceinline__ void mainloop(char *lds, WRow w_row, const __bf16 *__
     const char *xb = lds + st * S::STAGE + S::W_BYTES + ((wt * NTB) * 32 + l32) * ROW;
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 a_lo = *(const bf16x8 *)(wl + rd[ks]);
-      bf16x8 a_hi = *(const bf16x8 *)(wh + rd[ks]);
+      V8 a_lo = *(const V8 *)(wl + rd[ks]);
+      V8 a_hi = *(const V8 *)(wh + rd[ks]);
 #pragma unroll
       for (int t = 0; t < NTB; ++t) {
-        bf16x8 b = *(const bf16x8 *)(xb + t * 32 * ROW + rd[ks]);
-        acc[0][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_lo, b, acc[0][t], 0, 0, 0);
-        acc[1][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi, b, acc[1][t], 0, 0, 0);
+        V8 b = *(const V8 *)(xb + t * 32 * ROW + rd[ks]);
+        acc[0][t] = mma(a_lo, b, acc[0][t]);
+        acc[1][t] = mma(a_hi, b, acc[1][t]);
       }
     }
     // the next stage's loads must have landed before anyone reads them; the barrier also retires this stage

@@ -7,7 +7,7 @@
 #include <climits>
 #include <cmath>
 
-#include "percache_internal.hpp"
+#include "gemm_tile.hpp"
 
 namespace {
 using pc::f16x8;
@@ -348,6 +348,81 @@ __global__ __launch_bounds__(64) void lookup_finalize_kernel(const Best *__restr
   }
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Many probes at once (more than a streaming pass or two): the scan is a matrix product E P^T and is bound by the
+// matrix cores, not by the stream of the bank.  A workgroup takes 128 probes and walks `tiles_per_wg` consecutive
+// 128-row tiles of the bank with the shared projection main loop (fp16 operands); the bank rows are the M side, so a
+// lane holds, for ONE probe, 32 rows per tile, scales them by the rows' inverse norms and feeds a running sorted
+// list.  Lists are merged across the two lanes and the two wavefronts that share a probe; the per-workgroup lists
+// go to the same finalize kernel as the streaming pass.
+// ---------------------------------------------------------------------------------------------------
+template <int K>
+__global__ __launch_bounds__(256, 2) void lookup_batched_kernel(const _Float16 *__restrict__ bank, const float *__restrict__ inv_norm,
+                                                                int N, int d, const _Float16 *__restrict__ probes, int n_probes,
+                                                                int tiles_per_wg, int p_pad, Best *__restrict__ partial) {
+  constexpr int NTB = 2;
+  __shared__ __align__(16) char lds[pc::gemm::Shape<NTB>::LDS_BYTES];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wf = wave & 1, wt = wave >> 1;
+  const int l32 = lane & 31, g = lane >> 5;
+  const int n_tiles = (N + 127) / 128;
+  const int tile_begin = blockIdx.x * tiles_per_wg, tile_end = min(n_tiles, tile_begin + tiles_per_wg);
+  const int m0 = blockIdx.y * 128;  // first probe of the tile
+  TopK<K> best[NTB];                // this lane's rows for probes m0 + (wt*2 + t)*32 + l32
+#pragma unroll
+  for (int t = 0; t < NTB; ++t) best[t].clear();
+  for (int tile = tile_begin; tile < tile_end; ++tile) {
+    const int r0 = tile * 128;
+    pc::f32x16 acc[2][NTB];
+    pc::gemm::mainloop<NTB>(lds, [&](int row) __attribute__((always_inline)) { return bank + (size_t)min(r0 + row, N - 1) * d; },
+                            probes, d, m0, n_probes, d, 2 * wf, 2 * wf + 1, acc);
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const int row0 = r0 + (2 * wf + a) * 32 + q4 * 8 + g * 4;
+        const f32x4 inv4 = *(const f32x4 *)(inv_norm + min(row0, (N - 1) & ~3));  // rows come in aligned fours
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int row = row0 + e;
+#pragma unroll
+          for (int t = 0; t < NTB; ++t)
+            if (row < N) best[t].insert(acc[a][t][q4 * 4 + e] * inv4[e], row);
+        }
+      }
+  }
+  // the two lanes of a probe, then the two wavefronts (wf) that hold other rows of the same probes
+  __syncthreads();
+  Best *red = (Best *)lds;  // [wt][wf][NTB*32][K]
+#pragma unroll
+  for (int t = 0; t < NTB; ++t) {
+#pragma unroll
+    for (int j = 0; j < K; ++j) {
+      float s = best[t].s[0];
+      int i = best[t].i[0];
+      const float s2 = __shfl_xor(s, 32, 64);
+      const int i2 = __shfl_xor(i, 32, 64);
+      if (better(s2, i2, s, i)) { s = s2; i = i2; }
+      best[t].pop_if(i != INT_MAX && best[t].i[0] == i);
+      if (g == 0) red[((wt * 2 + wf) * (NTB * 32) + t * 32 + l32) * K + j] = Best{s, i};
+    }
+  }
+  __syncthreads();
+  if (tid < 128) {  // one thread per probe of the tile: probe index wt2*64 + t*32 + l = tid
+    const int wt2 = tid >> 6, within = tid & 63;
+    const Best *la = red + ((wt2 * 2 + 0) * (NTB * 32) + within) * K, *lb = red + ((wt2 * 2 + 1) * (NTB * 32) + within) * K;
+    int ha = 0, hb = 0;
+    Best *out = partial + ((size_t)blockIdx.x * p_pad + m0 + tid) * K;
+    for (int j = 0; j < K; ++j) {
+      const Best a = ha < K ? la[ha] : Best{-INFINITY, INT_MAX}, b = hb < K ? lb[hb] : Best{-INFINITY, INT_MAX};
+      const bool take_a = b.idx == INT_MAX || (a.idx != INT_MAX && better(a.s, a.idx, b.s, b.idx));
+      out[j] = take_a ? a : b;
+      ha += take_a;
+      hb += !take_a;
+    }
+  }
+}
+
 // inverse L2 norms of n embedding rows (0 for a zero row); one wavefront per row
 __global__ __launch_bounds__(256) void inv_norm_kernel(const _Float16 *__restrict__ src, float *__restrict__ inv_norm, int n, int d) {
   const int lane = threadIdx.x & 63;
@@ -405,6 +480,23 @@ int max_stream_grid(const percache_ctx *ctx) {
 }
 
 constexpr int kMaxTopK = 8;
+constexpr int kBatchedFrom = 32;  // more probes than one streaming pass takes: the matrix-product kernel
+
+// Launch shape of the batched kernel: 128-probe tiles x groups of consecutive 128-row bank tiles, about four
+// workgroups per CU in total.
+struct BatchShape {
+  int p_tiles, tiles_per_wg, groups;
+};
+BatchShape batch_shape(int n_cu, int N, int n_probes) {
+  BatchShape b;
+  b.p_tiles = (n_probes + 127) / 128;
+  const int n_tiles = (N + 127) / 128;
+  const long want = 4L * n_cu;
+  b.tiles_per_wg = (int)(((long)n_tiles * b.p_tiles + want - 1) / want);
+  if (b.tiles_per_wg < 1) b.tiles_per_wg = 1;
+  b.groups = (n_tiles + b.tiles_per_wg - 1) / b.tiles_per_wg;
+  return b;
+}
 
 template <int NPB, int CHB, int NSTG, int K>
 pc_status launch_stream(percache_ctx *ctx, const StreamShape &sh, hipStream_t st, int N, int d, const _Float16 *pp, int np,
@@ -457,6 +549,28 @@ pc_status run_lookup(percache_ctx *ctx, const void *probes_dev, int32_t n_probes
   if ((uintptr_t)workspace_dev % 16) return pc::fail(ctx, PC_EINVAL, "workspace must be 16-byte aligned");
   Best *partial = (Best *)workspace_dev;
   const _Float16 *probes = (const _Float16 *)probes_dev;
+  if (n_probes > kBatchedFrom) {
+    // many probes: matrix-core bound product instead of repeated streaming passes
+    const BatchShape bs = batch_shape(ctx->n_cu, N, n_probes);
+    dim3 grid(bs.groups, bs.p_tiles);
+    pc::prof_begin(ctx, PC_KERNEL_LOOKUP, st);
+    if (k == 1)
+      hipLaunchKernelGGL(lookup_batched_kernel<1>, grid, dim3(256), 0, st, ctx->bank, ctx->bank_inv, N, d, probes, n_probes,
+                         bs.tiles_per_wg, bs.p_tiles * 128, partial);
+    else
+      hipLaunchKernelGGL(lookup_batched_kernel<kMaxTopK>, grid, dim3(256), 0, st, ctx->bank, ctx->bank_inv, N, d, probes, n_probes,
+                         bs.tiles_per_wg, bs.p_tiles * 128, partial);
+    pc::prof_end(ctx, PC_KERNEL_LOOKUP, st);
+    PC_HIP(ctx, hipGetLastError());
+    if (k == 1)
+      hipLaunchKernelGGL(lookup_finalize_kernel<1>, dim3(n_probes), dim3(64), 0, st, partial, bs.groups, bs.p_tiles * 128, probes, d, tau, 1,
+                         idx_out_dev, sim_out_dev, hit_out_dev);
+    else
+      hipLaunchKernelGGL(lookup_finalize_kernel<kMaxTopK>, dim3(n_probes), dim3(64), 0, st, partial, bs.groups, bs.p_tiles * 128, probes, d,
+                         tau, k, idx_out_dev, sim_out_dev, hit_out_dev);
+    PC_HIP(ctx, hipGetLastError());
+    return PC_OK;
+  }
   // two probe blocks per pass unless their LDS copy leaves no room for the rings (very wide embeddings)
   const int pass_probes = stream_shape(ctx, 2, N).lds <= kMaxLds ? kPassProbes : 16;
   for (int p0 = 0; p0 < n_probes; p0 += pass_probes) {
@@ -504,7 +618,14 @@ pc_status percache_bank_put(percache_ctx *ctx, int32_t index, const void *emb_de
 
 size_t percache_lookup_workspace_bytes(const percache_ctx *ctx, int32_t n_probes) {
   if (!ctx || n_probes < 0) return 0;
-  return pc::align_up((size_t)max_stream_grid(ctx) * kPassProbes * kMaxTopK * sizeof(Best));
+  size_t lists = (size_t)max_stream_grid(ctx) * kPassProbes;
+  if (n_probes > kBatchedFrom) {
+    // groups * p_tiles <= n_tiles * p_tiles / tiles_per_wg + p_tiles <= 4 n_cu + p_tiles, whatever the bank size
+    const size_t p_tiles = ((size_t)n_probes + 127) / 128;
+    const size_t batched = (4 * (size_t)ctx->n_cu + p_tiles) * 128;
+    if (batched > lists) lists = batched;
+  }
+  return pc::align_up(lists * kMaxTopK * sizeof(Best));
 }
 
 pc_status percache_lookup(percache_ctx *ctx, const void *probes_dev, int32_t n_probes, float tau, int32_t *idx_out_dev,

@@ -176,7 +176,7 @@ def _compare_topk(bank, probes, k, idx, sim):
     return n_loose
 
 
-@pytest.mark.parametrize("dim,n_probes,k", [(1024, 40, 8), (1024, 3, 3), (128, 17, 5), (384, 33, 2), (64, 5, 8)])
+@pytest.mark.parametrize("dim,n_probes,k", [(1024, 40, 8), (1024, 3, 3), (128, 17, 5), (384, 33, 2), (64, 5, 8), (1024, 150, 8), (192, 300, 4)])
 def test_topk_vs_oracle(dim, n_probes, k):
     w = wl.lookup_clustered("k", 300 + dim, 523, 41, dim, n_probes, 0.05, 0.02, 0.92, n_exact=1, n_near=1)
     pc = _ctx(w.bank.shape[0], dim)
