@@ -359,15 +359,21 @@ __global__ __launch_bounds__(64) void lookup_finalize_kernel(const Best *__restr
 template <int K>
 __global__ __launch_bounds__(256, 2) void lookup_batched_kernel(const _Float16 *__restrict__ bank, const float *__restrict__ inv_norm,
                                                                 int N, int d, const _Float16 *__restrict__ probes, int n_probes,
-                                                                int tiles_per_wg, int p_pad, Best *__restrict__ partial) {
+                                                                int tiles_per_wg, int p_pad, int n_groups, int p_tiles,
+                                                                Best *__restrict__ partial) {
   constexpr int NTB = 2;
+  // workgroup ids go round-robin over the 8 XCDs: the probe tiles of one bank group are made consecutive on ONE XCD,
+  // so the group's rows are fetched from HBM once and re-read from that XCD's L2
+  const int xcd = blockIdx.x & 7, jj = blockIdx.x >> 3;
+  const int group = (jj / p_tiles) * 8 + xcd, p_tile = jj % p_tiles;
+  if (group >= n_groups) return;
   __shared__ __align__(16) char lds[pc::gemm::Shape<NTB>::LDS_BYTES];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wf = wave & 1, wt = wave >> 1;
   const int l32 = lane & 31, g = lane >> 5;
   const int n_tiles = (N + 127) / 128;
-  const int tile_begin = blockIdx.x * tiles_per_wg, tile_end = min(n_tiles, tile_begin + tiles_per_wg);
-  const int m0 = blockIdx.y * 128;  // first probe of the tile
+  const int tile_begin = group * tiles_per_wg, tile_end = min(n_tiles, tile_begin + tiles_per_wg);
+  const int m0 = p_tile * 128;  // first probe of the tile
   TopK<K> best[NTB];                // this lane's rows for probes m0 + (wt*2 + t)*32 + l32
 #pragma unroll
   for (int t = 0; t < NTB; ++t) best[t].clear();
@@ -412,7 +418,7 @@ __global__ __launch_bounds__(256, 2) void lookup_batched_kernel(const _Float16 *
     const int wt2 = tid >> 6, within = tid & 63;
     const Best *la = red + ((wt2 * 2 + 0) * (NTB * 32) + within) * K, *lb = red + ((wt2 * 2 + 1) * (NTB * 32) + within) * K;
     int ha = 0, hb = 0;
-    Best *out = partial + ((size_t)blockIdx.x * p_pad + m0 + tid) * K;
+    Best *out = partial + ((size_t)group * p_pad + m0 + tid) * K;
     for (int j = 0; j < K; ++j) {
       const Best a = ha < K ? la[ha] : Best{-INFINITY, INT_MAX}, b = hb < K ? lb[hb] : Best{-INFINITY, INT_MAX};
       const bool take_a = b.idx == INT_MAX || (a.idx != INT_MAX && better(a.s, a.idx, b.s, b.idx));
@@ -552,14 +558,14 @@ pc_status run_lookup(percache_ctx *ctx, const void *probes_dev, int32_t n_probes
   if (n_probes > kBatchedFrom) {
     // many probes: matrix-core bound product instead of repeated streaming passes
     const BatchShape bs = batch_shape(ctx->n_cu, N, n_probes);
-    dim3 grid(bs.groups, bs.p_tiles);
+    dim3 grid((unsigned)((bs.groups + 7) / 8 * 8 * bs.p_tiles));
     pc::prof_begin(ctx, PC_KERNEL_LOOKUP, st);
     if (k == 1)
       hipLaunchKernelGGL(lookup_batched_kernel<1>, grid, dim3(256), 0, st, ctx->bank, ctx->bank_inv, N, d, probes, n_probes,
-                         bs.tiles_per_wg, bs.p_tiles * 128, partial);
+                         bs.tiles_per_wg, bs.p_tiles * 128, bs.groups, bs.p_tiles, partial);
     else
       hipLaunchKernelGGL(lookup_batched_kernel<kMaxTopK>, grid, dim3(256), 0, st, ctx->bank, ctx->bank_inv, N, d, probes, n_probes,
-                         bs.tiles_per_wg, bs.p_tiles * 128, partial);
+                         bs.tiles_per_wg, bs.p_tiles * 128, bs.groups, bs.p_tiles, partial);
     pc::prof_end(ctx, PC_KERNEL_LOOKUP, st);
     PC_HIP(ctx, hipGetLastError());
     if (k == 1)
