@@ -481,7 +481,8 @@ pc_status launch_attention(percache_ctx *ctx, int layer, const __bf16 *q, const 
   const int G = c.n_q_heads / c.n_kv_heads, R = G * t_fresh;
   // 8 wavefronts x 32 rows (one workgroup per CU, 3 LDS stages) once a kv head has more than 128 stacked rows,
   // else 4 wavefronts (two workgroups per CU, 2 stages)
-  const bool wide = R > 128;
+  // 256-row workgroups only when there are enough of them to go round; few, short key ranges prefer more, smaller ones
+  const bool wide = R > 128 && (long)batch * c.n_kv_heads * ((R + 255) / 256) * 4 >= ctx->n_cu;
   const int qrows = wide ? 256 : 128;
   const int q_tiles = (R + qrows - 1) / qrows;
   const int cap = max_splits_for(c, ctx->n_cu, batch, t_fresh);
