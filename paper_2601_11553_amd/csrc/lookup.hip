@@ -310,109 +310,6 @@ __global__ __launch_bounds__(256) void lookup_stream_kernel(const _Float16 *__re
 }
 
 // ---------------------------------------------------------------------------------------------------
-// The same pass for at most 16 probes of a width known at compile time (CHUNKS * 256 elements): the probes' MFMA
-// operands live in REGISTERS (one wavefront per SIMD has 512 of them), so that all of LDS but the inverse norms is
-// ring: four stages per wavefront, three 8 KB chunks in flight instead of two, and one LDS read per MFMA instead
-// of two.  This is the single-query case of Sec. 4.2.1.
-// ---------------------------------------------------------------------------------------------------
-template <int CHUNKS, int NSTG, int K>
-__global__ __launch_bounds__(256, 1) void lookup_stream_regprobe_kernel(const _Float16 *__restrict__ bank,
-                                                                        const float *__restrict__ inv_norm, int N,
-                                                                        const _Float16 *__restrict__ probes, int n_probes,
-                                                                        int per_wg, int ring_off, Best *__restrict__ partial) {
-  extern __shared__ __align__(16) char smem[];
-  constexpr int CHB = 512, CS = CHB / 64, STG = 16 * CHB, IPS = STG / 1024, LPR = CHB / 16, AHEAD = NSTG - 1;
-  constexpr int D = CHUNKS * (CHB / 2);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int r16 = lane & 15, g = lane >> 4;
-  const int n_blocks = (N + 15) / 16;
-  const int rb_begin = blockIdx.x * per_wg;
-  const int rb_end = min(n_blocks, rb_begin + per_wg);
-
-  // probe operands: lane (r16, g) holds elements [32 s + 8 g, +8) of probe r16 for every k-step s (zero past n_probes)
-  f16x8 breg[CHUNKS * CS];
-#pragma unroll
-  for (int s = 0; s < CHUNKS * CS; ++s) {
-    u32x4 raw = {0, 0, 0, 0};
-    if (r16 < n_probes) raw = *(const u32x4 *)(probes + (size_t)r16 * D + 32 * s + 8 * g);
-    breg[s] = __builtin_bit_cast(f16x8, raw);
-  }
-  float *inv_lds = (float *)smem;
-  for (int r = tid; r < per_wg * 16; r += 256) {
-    int row = rb_begin * 16 + r;
-    inv_lds[r] = row < N ? inv_norm[row] : 0.f;
-  }
-  __syncthreads();
-  char *ring = smem + ring_off + wave * (NSTG * STG);
-
-  TopK<K> best[1];
-  best[0].clear();
-  int ld_row[IPS], ld_col[IPS];
-#pragma unroll
-  for (int i = 0; i < IPS; ++i) {
-    const int row = i * (1024 / CHB) + lane / LPR, pc = lane % LPR;
-    ld_row[i] = row;
-    ld_col[i] = (pc ^ row_swz<CHB>(row)) * 8;
-  }
-  auto issue = [&](int rb, int chunk, int st) __attribute__((always_inline)) {
-    const _Float16 *base = bank + chunk * (CHB / 2);
-#pragma unroll
-    for (int i = 0; i < IPS; ++i) {
-      const int row = min(rb * 16 + ld_row[i], N - 1);
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(base + (size_t)row * D + ld_col[i]),
-                                       (__attribute__((address_space(3))) void *)(ring + st * STG + i * 1024), 16, 0, kBankLoadAux);
-    }
-  };
-  int rd_off[CS];
-#pragma unroll
-  for (int s = 0; s < CS; ++s) rd_off[s] = r16 * CHB + (((4 * s + g) ^ row_swz<CHB>(r16)) * 16);
-  auto advance = [&](int &rb_, int &c_) __attribute__((always_inline)) {
-    if (++c_ == CHUNKS) { c_ = 0; rb_ += 4; }
-  };
-
-  // flat pipeline over (row block, chunk) items as in the kernel above; the chunk loop is unrolled so that the probe
-  // registers are indexed statically
-  int prb = rb_begin + wave, pch = 0;
-  const int rb_last = rb_end - 1;
-  if (prb < rb_end) {
-    int st = 0, ist = 0;
-#pragma unroll
-    for (int k = 0; k < AHEAD; ++k) {
-      issue(min(prb, rb_last), pch, ist);
-      advance(prb, pch);
-      ist = ist + 1 == NSTG ? 0 : ist + 1;
-    }
-    for (int rb = rb_begin + wave; rb < rb_end; rb += 4) {
-      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int c = 0; c < CHUNKS; ++c) {
-        issue(min(prb, rb_last), pch, ist);
-        advance(prb, pch);
-        ist = ist + 1 == NSTG ? 0 : ist + 1;
-        PC_LOOKUP_WAIT_VMCNT(AHEAD * IPS);
-        asm volatile("" ::: "memory");
-        const char *abase = ring + st * STG;
-#pragma unroll
-        for (int s = 0; s < CS; ++s) {
-          f16x8 av = *(const f16x8 *)(abase + rd_off[s]);
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, breg[c * CS + s], acc, 0, 0, 0);
-        }
-        st = st + 1 == NSTG ? 0 : st + 1;
-      }
-      const f32x4 inv4 = *(const f32x4 *)(inv_lds + (rb - rb_begin) * 16 + g * 4);
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int row = rb * 16 + g * 4 + r;
-        if (row < N) best[0].insert(acc[r] * inv4[r], row);
-      }
-    }
-    PC_LOOKUP_WAIT_VMCNT(0);
-  }
-  __syncthreads();
-  merge_workgroup_lists<1, K>(best, smem, partial);
-}
-
-// ---------------------------------------------------------------------------------------------------
 // Per probe: merge the workgroup partial lists, divide by the probe's norm, compare the best with tau.
 // One workgroup (one wavefront) per probe; k <= K entries are written per probe.
 // ---------------------------------------------------------------------------------------------------
@@ -630,30 +527,9 @@ pc_status launch_stream(percache_ctx *ctx, const StreamShape &sh, hipStream_t st
   return PC_OK;
 }
 
-// Register-probe pass (top-1, at most 16 probes, width 512 / 768 / 1024): returns false if the shape is not covered.
-template <int CHUNKS>
-pc_status launch_regprobe(percache_ctx *ctx, int grid, int per_wg, hipStream_t st, int N, const _Float16 *pp, int np, Best *partial) {
-  constexpr int kStages = 4;
-  const int ring_off = (per_wg * 16 * (int)sizeof(float) + 1023) / 1024 * 1024;
-  const size_t lds = ring_off + (size_t)4 * kStages * 16 * 512;
-  static bool big_lds_set = false;
-  if (!big_lds_set) {
-    PC_HIP(ctx, hipFuncSetAttribute((const void *)lookup_stream_regprobe_kernel<CHUNKS, kStages, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxLds));
-    big_lds_set = true;
-  }
-  hipLaunchKernelGGL((lookup_stream_regprobe_kernel<CHUNKS, kStages, 1>), dim3(grid), dim3(256), lds, st, ctx->bank, ctx->bank_inv, N, pp, np,
-                     per_wg, ring_off, partial);
-  return PC_OK;
-}
-
 template <int K>
 pc_status launch_pass(percache_ctx *ctx, const StreamShape &sh, int npb, hipStream_t st, int N, int d, const _Float16 *pp, int np,
                       Best *partial, const RowScan &rs = RowScan{}) {
-  if (K == 1 && npb == 1 && (d == 1024 || d == 768 || d == 512)) {
-    if (d == 1024) return launch_regprobe<4>(ctx, sh.grid, sh.per_wg, st, N, pp, np, partial);
-    if (d == 768) return launch_regprobe<3>(ctx, sh.grid, sh.per_wg, st, N, pp, np, partial);
-    return launch_regprobe<2>(ctx, sh.grid, sh.per_wg, st, N, pp, np, partial);
-  }
   if (npb == 1 && sh.nstg == 3)
     return sh.chb == 128   ? launch_stream<1, 128, 3, K>(ctx, sh, st, N, d, pp, np, partial, rs)
            : sh.chb == 256 ? launch_stream<1, 256, 3, K>(ctx, sh, st, N, d, pp, np, partial, rs)
