@@ -139,7 +139,7 @@ __global__ __launch_bounds__(256, 2) void splitk_partial_kernel(const __bf16 *__
   const int f0 = blockIdx.x * BF, m0 = blockIdx.z * BT;
   const int k0 = blockIdx.y * k_slice;
   f32x16 acc[2][NTB];
-  pc::gemm::mainloop<NTB>(
+  pc::gemm::mainloop<NTB, true>(  // one token tile: every weight row is read by exactly one workgroup
       lds,
       [&](int row) __attribute__((always_inline)) {
         const int n = f0 + row;

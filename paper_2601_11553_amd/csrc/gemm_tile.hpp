@@ -54,7 +54,8 @@ template <> struct Vec8<_Float16> { typedef f16x8 type; };
 // m0 .. m0 + BT - 1 (clamped to M - 1 when reading); K elements are contracted.
 // On return acc[a][t] holds features (a ? fb_hi : fb_lo) * 32 + (r/4)*8 + 4*(lane/32) + r%4 of token
 // m0 + (wt*NTB + t)*32 + lane%32 in element r.
-template <int NTB, class T, class WRow>
+// NTW: the weight rows are streamed with the non-temporal policy (use when no other workgroup re-reads them soon).
+template <int NTB, bool NTW = false, class T, class WRow>
 __device__ __forceinline__ void mainloop(char *lds, WRow w_row, const T *__restrict__ X, int ldx, int m0, int M, int K,
                                          int fb_lo, int fb_hi, f32x16 (&acc)[2][NTB]) {
   using S = Shape<NTB>;
@@ -82,7 +83,7 @@ __device__ __forceinline__ void mainloop(char *lds, WRow w_row, const T *__restr
 #pragma unroll
     for (int k = 0; k < S::W_INSTR; ++k)
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(w_src[k] + kt * BK),
-                                       (__attribute__((address_space(3))) void *)(base + (wave + k * NW) * 1024), 16, 0, 0);
+                                       (__attribute__((address_space(3))) void *)(base + (wave + k * NW) * 1024), 16, 0, NTW ? 2 : 0);
 #pragma unroll
     for (int k = 0; k < S::X_INSTR; ++k)
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(x_src[k] + kt * BK),

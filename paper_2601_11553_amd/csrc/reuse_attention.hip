@@ -30,6 +30,7 @@ using pc::kTblHeader;
 using pc::u32x4;
 
 constexpr int TK = kKvTile;  // keys per tile
+constexpr int kKvAux = 2;   // cache policy of the K/V tile loads (aux operand): 2 = non-temporal
 constexpr float kLazy = 8.f; // log2 slack before the reference exponent is refreshed
 constexpr float kSumLimit = 32.f * 256.f;  // 32 probabilities of a lane and tile, each at most 2^kLazy
 
@@ -205,12 +206,12 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
     for (int k = 0; k < K_INSTR; ++k) {
       const int row = min(k_row[k], td.valid - 1);  // rows past a ragged end repeat the last valid row (masked later)
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(td.k + (size_t)row * D + k_col[k]),
-                                       (__attribute__((address_space(3))) void *)(kb + (wave + k * NW) * 1024), 16, 0, 0);
+                                       (__attribute__((address_space(3))) void *)(kb + (wave + k * NW) * 1024), 16, 0, kKvAux);
     }
 #pragma unroll
     for (int k = 0; k < V_INSTR; ++k)
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(td.v + v_goff[k]),
-                                       (__attribute__((address_space(3))) void *)(kb + L::K_BYTES + (wave + k * NW) * 1024), 16, 0, 0);
+                                       (__attribute__((address_space(3))) void *)(kb + L::K_BYTES + (wave + k * NW) * 1024), 16, 0, kKvAux);
   };
 
   // Pipeline: the tile computed in iteration t sits in stage t % NSTAGE; the loads of tile t+AHEAD are issued at
