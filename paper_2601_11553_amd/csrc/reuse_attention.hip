@@ -254,18 +254,27 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
     const char *kb = lds + buf * L::STAGE;
     const char *vb = kb + L::K_BYTES;
 
-    // ---- S^T = K Q^T : two 32-key blocks
+    // ---- S^T = K Q^T : two 32-key blocks.  The K operands are requested from LDS in batches of eight ahead of
+    // their MFMAs (the two accumulation chains alternating): one LDS latency per batch instead of one per MFMA.
     f32x16 s_acc[2];
 #pragma unroll
-    for (int kbk = 0; kbk < 2; ++kbk) {
+    for (int kbk = 0; kbk < 2; ++kbk)
 #pragma unroll
       for (int r = 0; r < 16; ++r) s_acc[kbk][r] = 0.f;
-      const char *krow = kb + (kbk * 32 + l32) * L::K_ROW;
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        bf16x8 a = *(const bf16x8 *)(krow + k_rd[ks]);
-        s_acc[kbk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s_acc[kbk], 0, 0, 0);
-      }
+    for (int h = 0; h < KS / 4; ++h) {
+      bf16x8 kop[2][4];
+#pragma unroll
+      for (int k4 = 0; k4 < 4; ++k4)
+#pragma unroll
+        for (int kbk = 0; kbk < 2; ++kbk) kop[kbk][k4] = *(const bf16x8 *)(kb + (kbk * 32 + l32) * L::K_ROW + k_rd[4 * h + k4]);
+#pragma unroll
+      for (int k4 = 0; k4 < 4; ++k4)
+#pragma unroll
+        for (int kbk = 0; kbk < 2; ++kbk)
+          s_acc[kbk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop[kbk][k4], qf[4 * h + k4], s_acc[kbk], 0, 0, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
     }
 
     // ---- mask: only tiles with a ragged end or in the causal part take this path (wave-uniform test)
@@ -329,17 +338,21 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
     }
     l_run += psum;
 
-    // ---- O^T += V^T P^T
+    // ---- O^T += V^T P^T, operands requested in batches of eight in the same way
 #pragma unroll
-    for (int db = 0; db < DB; ++db) {
-      const char *vrow = vb + (db * 32 + l32) * L::V_ROW;
+    for (int h = 0; h < 2; ++h) {
+      bf16x8 vop[DB][2];
 #pragma unroll
-      for (int kbk = 0; kbk < 2; ++kbk)
+      for (int c2 = 0; c2 < 2; ++c2)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          bf16x8 a = *(const bf16x8 *)(vrow + v_rd[kbk * 2 + j]);
-          o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[kbk][j], o_acc[db], 0, 0, 0);
-        }
+        for (int db = 0; db < DB; ++db) vop[db][c2] = *(const bf16x8 *)(vb + (db * 32 + l32) * L::V_ROW + v_rd[2 * h + c2]);
+#pragma unroll
+      for (int c2 = 0; c2 < 2; ++c2)
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+          o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop[db][c2], pf[h][c2], o_acc[db], 0, 0, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 2 * DB, 1);
+      __builtin_amdgcn_sched_group_barrier(0x008, 2 * DB, 1);
     }
 
     // (when nothing was fetched in this iteration fewer tiles are in flight: wait for all of them)
