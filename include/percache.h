@@ -242,6 +242,10 @@ typedef struct {
   const void *w_gate; /* [ffn, hidden] */
   const void *w_up;   /* [ffn, hidden] */
   const void *w_down; /* [hidden, ffn] */
+  /* model-family variants of the projection (the paper runs Llama and Qwen models, Sec. 5.1); NULL = absent */
+  const void *qkv_bias; /* [(Hq + 2 Hkv) * D]: added to the projection before anything else (Qwen2 style) */
+  const void *q_norm;   /* [D]: gain of an RMSNorm (same eps) over the head dimension of every q head, before RoPE */
+  const void *k_norm;   /* [D]: the same for every k head (Qwen3 style) */
 } percache_block_weights;
 
 /* Runs layers 0 .. n_layers-1 (layer l reads store layer l; the chunk list is the same for every layer and the

@@ -146,8 +146,12 @@ def rope(u, pos: int, theta: float) -> np.ndarray:
     return u
 
 
-def qkv_rope(X, W, Hq: int, Hkv: int, D: int, pos0: int, theta: float):
-    """Projection + RoPE of one query's retained rows.  Returns Q[Hq,T,D], K, V[Hkv,T,D]."""
+def qkv_rope(X, W, Hq: int, Hkv: int, D: int, pos0: int, theta: float, bias=None, q_gain=None, k_gain=None,
+             eps: float = 1e-6):
+    """Projection + RoPE of one query's retained rows.  Returns Q[Hq,T,D], K, V[Hkv,T,D].
+
+    Model-family variants (the paper runs Llama and Qwen models, Sec. 5.1): ``bias`` [(Hq+2Hkv)*D] is added to the
+    projection; ``q_gain`` / ``k_gain`` [D] switch on an RMSNorm over the head dimension of every q / k head before RoPE."""
     X = _f(X)
     W = _f(W)
     T, H = X.shape
@@ -155,9 +159,12 @@ def qkv_rope(X, W, Hq: int, Hkv: int, D: int, pos0: int, theta: float):
     Q = np.empty((Hq, T, D), np.float32)
     K = np.empty((Hkv, T, D), np.float32)
     V = np.empty((Hkv, T, D), np.float32)
-    _load().oracle_qkv_rope(_pf(X), _pf(W), ctypes.c_int(T), ctypes.c_int(H), ctypes.c_int(Hq),
-                            ctypes.c_int(Hkv), ctypes.c_int(D), ctypes.c_long(pos0),
-                            ctypes.c_double(theta), _pf(Q), _pf(K), _pf(V))
+    b = _f(bias) if bias is not None else None
+    qg = _f(q_gain) if q_gain is not None else None
+    kg = _f(k_gain) if k_gain is not None else None
+    _load().oracle_qkv_rope_ex(_pf(X), _pf(W), _pf(b), _pf(qg), _pf(kg), ctypes.c_double(eps), ctypes.c_int(T),
+                               ctypes.c_int(H), ctypes.c_int(Hq), ctypes.c_int(Hkv), ctypes.c_int(D),
+                               ctypes.c_long(pos0), ctypes.c_double(theta), _pf(Q), _pf(K), _pf(V))
     return Q, K, V
 
 
@@ -208,15 +215,20 @@ def attention_reuse(Q, Kf, Vf, store_k, store_v, slot_ids: Sequence[int], used_l
 
 def prefill_reuse(X, W, Hq: int, Hkv: int, D: int, theta: float, store_k=None, store_v=None,
                   slot_ids: Sequence[int] = (), used_len: Sequence[int] = (),
-                  samples: Optional[Tuple[Sequence[int], Sequence[int]]] = None):
+                  samples: Optional[Tuple[Sequence[int], Sequence[int]]] = None, extras: Optional[dict] = None):
     """One query, one layer: project+RoPE the fresh rows at offset L_pre, then attend.
 
     ``slot_ids=()`` is the full recomputation (plain causal prefill of a contiguous
-    prompt).  Returns (O, Kf, Vf, Q).
+    prompt).  ``extras``: keyword arguments of qkv_rope for the bias / QK-norm variants.  Returns (O, Kf, Vf, Q).
     """
     X = _f(X)
     W = _f(W)
     T, H = X.shape
+    if extras:
+        l_pre = int(np.sum(_i(used_len))) if len(slot_ids) else 0
+        Q, Kf, Vf = qkv_rope(X, W, Hq, Hkv, D, l_pre, theta, **extras)
+        O = attention_reuse(Q, Kf, Vf, store_k, store_v, slot_ids, used_len, samples=samples)
+        return O, Kf, Vf, Q
     sk, sv, C = _store_args(store_k, store_v, Hkv, D)
     ids = _i(slot_ids)
     ul = _i(used_len)
@@ -304,8 +316,8 @@ def block_tail(h_in, attn, Wo, gain2, Wgate, Wup, Wdown, eps: float) -> np.ndarr
 
 
 def block(h, gain1, Wqkv, Hq, Hkv, D, theta, Wo, gain2, Wgate, Wup, Wdown, eps,
-          store_k=None, store_v=None, slot_ids=(), used_len=()):
+          store_k=None, store_v=None, slot_ids=(), used_len=(), extras: Optional[dict] = None):
     """One full pre-norm block on one query's fresh rows.  Returns (h_out, Kf, Vf)."""
     n1 = rmsnorm(h, gain1, eps)
-    O, Kf, Vf, _ = prefill_reuse(n1, Wqkv, Hq, Hkv, D, theta, store_k, store_v, slot_ids, used_len)
+    O, Kf, Vf, _ = prefill_reuse(n1, Wqkv, Hq, Hkv, D, theta, store_k, store_v, slot_ids, used_len, extras=extras)
     return block_tail(h, O, Wo, gain2, Wgate, Wup, Wdown, eps), Kf, Vf

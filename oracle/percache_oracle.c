@@ -129,9 +129,33 @@ void oracle_rope(float *u, int D, long pos, double theta) {
 /* RoPE on every q and k head vector at position pos0 + i.              */
 /* Outputs head-major: Q[Hq,T,D], K[Hkv,T,D], V[Hkv,T,D].               */
 /* ------------------------------------------------------------------ */
+/* Model-family variants of the projection (the paper runs Llama and Qwen  */
+/* models, Sec. 5.1): bias [(Hq+2Hkv)*D] added to the projection (Qwen2    */
+/* style), and RMSNorm over the head dimension of every q and k head with */
+/* gains q_gain / k_gain [D] before RoPE (Qwen3 style).  NULL = absent.   */
+static void head_rmsnorm(float *u, int D, const float *gain, double eps) {
+  double ss = 0.0;
+  for (int c = 0; c < D; ++c) ss += (double)u[c] * (double)u[c];
+  double r = 1.0 / sqrt(ss / (double)D + eps);
+  for (int c = 0; c < D; ++c) u[c] = (float)((double)u[c] * r * (double)gain[c]);
+}
+
+void oracle_qkv_rope_ex(const float *X, const float *W, const float *bias,
+                        const float *q_gain, const float *k_gain, double eps,
+                        int T, int H, int Hq, int Hkv, int D, long pos0,
+                        double theta, float *Q, float *K, float *V);
+
 void oracle_qkv_rope(const float *X, const float *W, int T, int H, int Hq,
                      int Hkv, int D, long pos0, double theta, float *Q,
                      float *K, float *V) {
+  oracle_qkv_rope_ex(X, W, NULL, NULL, NULL, 0.0, T, H, Hq, Hkv, D, pos0, theta,
+                     Q, K, V);
+}
+
+void oracle_qkv_rope_ex(const float *X, const float *W, const float *bias,
+                        const float *q_gain, const float *k_gain, double eps,
+                        int T, int H, int Hq, int Hkv, int D, long pos0,
+                        double theta, float *Q, float *K, float *V) {
   int n_out = (Hq + 2 * Hkv) * D;
 #pragma omp parallel for collapse(2) schedule(static)
   for (int i = 0; i < T; ++i) {
@@ -140,6 +164,7 @@ void oracle_qkv_rope(const float *X, const float *W, int T, int H, int Hq,
       const float *w = W + (size_t)o * H;
       double acc = 0.0;
       for (int k = 0; k < H; ++k) acc += (double)x[k] * (double)w[k];
+      if (bias) acc += (double)bias[o];
       int head = o / D, c = o % D;
       if (head < Hq)
         Q[((size_t)head * T + i) * D + c] = (float)acc;
@@ -151,10 +176,14 @@ void oracle_qkv_rope(const float *X, const float *W, int T, int H, int Hq,
   }
 #pragma omp parallel for schedule(static)
   for (int i = 0; i < T; ++i) {
-    for (int h = 0; h < Hq; ++h)
+    for (int h = 0; h < Hq; ++h) {
+      if (q_gain) head_rmsnorm(Q + ((size_t)h * T + i) * D, D, q_gain, eps);
       oracle_rope(Q + ((size_t)h * T + i) * D, D, pos0 + i, theta);
-    for (int g = 0; g < Hkv; ++g)
+    }
+    for (int g = 0; g < Hkv; ++g) {
+      if (k_gain) head_rmsnorm(K + ((size_t)g * T + i) * D, D, k_gain, eps);
       oracle_rope(K + ((size_t)g * T + i) * D, D, pos0 + i, theta);
+    }
   }
 }
 

@@ -52,7 +52,8 @@ class Config(ctypes.Structure):
 
 class BlockWeights(ctypes.Structure):
     """percache_block_weights: device pointers of one block's weights."""
-    _fields_ = [(n, ctypes.c_void_p) for n in ("gain1", "wqkv", "wo", "gain2", "w_gate", "w_up", "w_down")]
+    _fields_ = [(n, ctypes.c_void_p) for n in ("gain1", "wqkv", "wo", "gain2", "w_gate", "w_up", "w_down",
+                                               "qkv_bias", "q_norm", "k_norm")]
 
 
 _lib = None
@@ -352,7 +353,7 @@ class Percache:
         arr = (BlockWeights * len(layers))()
         for i, lw in enumerate(layers):
             for name, _t in BlockWeights._fields_:
-                setattr(arr[i], name, _ptr(lw[name]))
+                setattr(arr[i], name, _ptr(lw.get(name)))   # the three variant fields may be missing (absent)
         return arr
 
     def percache_stack_reuse(self, layers, ffn: int, eps: float, h_in, slot_ids=None, used_len=None, n_chunks=None,

@@ -391,6 +391,9 @@ static pc_status run_stack(percache_ctx *ctx, const percache_block_weights *laye
     const void *ptrs[7] = {w.gain1, w.wqkv, w.wo, w.gain2, w.w_gate, w.w_up, w.w_down};
     for (const void *p : ptrs)
       if (!p || !aligned16(p)) return pc::fail(ctx, PC_EINVAL, "layer %d: NULL or misaligned weight pointer", l);
+    const void *opt[3] = {w.qkv_bias, w.q_norm, w.k_norm};
+    for (const void *p : opt)
+      if (p && !aligned16(p)) return pc::fail(ctx, PC_EINVAL, "layer %d: misaligned optional weight pointer", l);
   }
   // chunk tables of every layer (the slot table is per layer): all must agree, so that one upload serves the stack
   std::vector<int32_t> rows, rows_l;
@@ -441,8 +444,13 @@ static pc_status run_stack(percache_ctx *ctx, const percache_block_weights *laye
     // few token rows: split-k projections, whose reduce kernels also apply the residual and the next RMSNorm
     const bool skinny = pc::splitk_applies(M) && ffn % BF == 0;
     if (!skinny || l == 0) PC_TRY(launch_rmsnorm(ctx, h_cur, (const __bf16 *)w.gain1, ws.normed, (int)M, H, eps, s));
+    pc::QkvExtras extras;
+    extras.bias = (const __bf16 *)w.qkv_bias;
+    extras.q_norm = (const __bf16 *)w.q_norm;
+    extras.k_norm = (const __bf16 *)w.k_norm;
+    extras.eps = eps;
     PC_TRY(pc::launch_qkv_rope(ctx, ws.normed, (const __bf16 *)w.wqkv, batch, t_fresh, ws.pf.table, stride, ws.pf.q, ws.pf.k, ws.pf.v, s,
-                               skinny ? ws.pf.gemm_part : nullptr));
+                               skinny ? ws.pf.gemm_part : nullptr, extras));
     PC_TRY(pc::launch_v_repack(ctx, ws.pf.v, ws.pf.v_blk, batch, t_fresh, s));
     PC_TRY(pc::launch_attention(ctx, l, ws.pf.q, ws.pf.k, ws.pf.v_blk, batch, t_fresh, ws.pf.table, stride, min_tiles, 0, ws.attn,
                                 ws.pf.part_o, ws.pf.part_ml, s));

@@ -114,10 +114,17 @@ void prof_begin(percache_ctx *ctx, int kind, hipStream_t stream);
 void prof_end(percache_ctx *ctx, int kind, hipStream_t stream);
 
 // kernel launchers (defined in the .hip files)
+// Model-family variants of the projection: bias [(Hq+2Hkv)*D] added before everything else; RMSNorm over the head
+// dimension of every q / k head with gains [D] before RoPE.  Null pointers switch a part off.
+struct QkvExtras {
+  const __bf16 *bias = nullptr, *q_norm = nullptr, *k_norm = nullptr;
+  float eps = 1e-6f;
+  bool any() const { return bias || q_norm || k_norm; }
+};
 // gemm_part: workspace for the split-k path (nullptr: always the single-pass kernel)
 pc_status launch_qkv_rope(percache_ctx *ctx, const __bf16 *x, const __bf16 *w, int batch, int t_fresh,
                           const int32_t *table_dev, int tbl_stride, __bf16 *q, __bf16 *k, __bf16 *v,
-                          hipStream_t stream, float *gemm_part = nullptr);
+                          hipStream_t stream, float *gemm_part = nullptr, const QkvExtras &extras = QkvExtras());
 
 // Split-k projections for few token rows (see block.hip).  P[s][m][n] = sum over slice s of A[m][k] W[n][k];
 // weight rows >= n_split come from w1.  Returns the number of slices written (chosen by choose_split_k).

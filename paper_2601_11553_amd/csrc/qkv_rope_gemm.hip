@@ -16,12 +16,13 @@ using pc::gemm::BF;
 using pc::gemm::pack4;
 
 // NTB: 32-token blocks per wavefront (1 -> 64-token tile, 2 -> 128-token tile).
-template <int D, int NTB>
+// EXTRA: the bias / head-norm variants (see QkvExtras) are compiled in.
+template <int D, int NTB, bool EXTRA>
 __global__ __launch_bounds__(256, 2) void qkv_rope_kernel(const __bf16 *__restrict__ X, const __bf16 *__restrict__ W, int M,
                                                           int H, int t_fresh, int Hq, int Hkv,
                                                           const int32_t *__restrict__ table, int tbl_stride,
                                                           const float2 *__restrict__ rope, __bf16 *__restrict__ Q,
-                                                          __bf16 *__restrict__ K, __bf16 *__restrict__ V) {
+                                                          __bf16 *__restrict__ K, __bf16 *__restrict__ V, pc::QkvExtras ex) {
   constexpr int BT = 64 * NTB;
   __shared__ __align__(16) char lds[pc::gemm::Shape<NTB>::LDS_BYTES];
 
@@ -47,6 +48,53 @@ __global__ __launch_bounds__(256, 2) void qkv_rope_kernel(const __bf16 *__restri
   if (head < Hq) { dst = Q; hh = head; n_heads = Hq; }
   else if (head < Hq + Hkv) { dst = K; hh = head - Hq; n_heads = Hkv; }
   else { dst = V; hh = head - Hq - Hkv; n_heads = Hkv; rotate = false; }
+  if constexpr (EXTRA) {
+    // bias on the accumulators; then, for q and k heads, RMSNorm over the head dimension: a token's head is spread over
+    // the two lanes (l, l+32) and, at D = 128, over the wavefront pair (wf = 0, 1), which meet through LDS
+    if (ex.bias) {
+      const __bf16 *bl = ex.bias + (size_t)head * D + m_base + g * 4;
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float b_lo = (float)bl[q4 * 8 + e], b_hi = (float)bl[q4 * 8 + e + D / 2];
+#pragma unroll
+          for (int t = 0; t < NTB; ++t) { acc[0][t][q4 * 4 + e] += b_lo; acc[1][t][q4 * 4 + e] += b_hi; }
+        }
+    }
+    const __bf16 *gain = head < Hq ? ex.q_norm : (head < Hq + Hkv ? ex.k_norm : nullptr);
+    float ss[NTB];
+#pragma unroll
+    for (int t = 0; t < NTB; ++t) {
+      ss[t] = 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) ss[t] += acc[0][t][r] * acc[0][t][r] + acc[1][t][r] * acc[1][t][r];
+      ss[t] += __shfl_xor(ss[t], 32, 64);
+    }
+    if (D == 128) {
+      float *red = (float *)lds;  // [wt][NTB][32 tokens][wf]; the main loop is done with LDS (it ends in a barrier)
+#pragma unroll
+      for (int t = 0; t < NTB; ++t)
+        if (g == 0) red[((wt * NTB + t) * 32 + l32) * 2 + wf] = ss[t];
+      __syncthreads();
+#pragma unroll
+      for (int t = 0; t < NTB; ++t) ss[t] = red[((wt * NTB + t) * 32 + l32) * 2] + red[((wt * NTB + t) * 32 + l32) * 2 + 1];
+    }
+    if (gain) {
+      const __bf16 *gl = gain + m_base + g * 4;
+#pragma unroll
+      for (int t = 0; t < NTB; ++t) {
+        const float r = 1.0f / sqrtf(ss[t] / (float)D + ex.eps);
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            acc[0][t][q4 * 4 + e] *= r * (float)gl[q4 * 8 + e];
+            acc[1][t][q4 * 4 + e] *= r * (float)gl[q4 * 8 + e + D / 2];
+          }
+      }
+    }
+  }
 #pragma unroll
   for (int t = 0; t < NTB; ++t) {
     const int m_raw = m0 + (wt * NTB + t) * 32 + l32;
@@ -96,7 +144,7 @@ template <int D>
 __global__ __launch_bounds__(256) void reduce_rope_kernel(const float *__restrict__ P, int n_k, int M, int F, int t_fresh, int Hq,
                                                           int Hkv, const int32_t *__restrict__ table, int tbl_stride,
                                                           const float2 *__restrict__ rope, __bf16 *__restrict__ Q,
-                                                          __bf16 *__restrict__ K, __bf16 *__restrict__ V) {
+                                                          __bf16 *__restrict__ K, __bf16 *__restrict__ V, pc::QkvExtras ex) {
   constexpr int QUADS = D / 8;
   const long gid = (long)blockIdx.x * blockDim.x + threadIdx.x;
   const int n_heads_all = Hq + 2 * Hkv;
@@ -121,6 +169,29 @@ __global__ __launch_bounds__(256) void reduce_rope_kernel(const float *__restric
   else if (head < Hq + Hkv) { dst = K; hh = head - Hq; n_heads = Hkv; }
   else { dst = V; hh = head - Hq - Hkv; n_heads = Hkv; rotate = false; }
   float l4[4] = {lo.x, lo.y, lo.z, lo.w}, h4[4] = {hi.x, hi.y, hi.z, hi.w};
+  if (ex.bias) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      l4[e] += (float)ex.bias[(size_t)head * D + mm + e];
+      h4[e] += (float)ex.bias[(size_t)head * D + mm + e + D / 2];
+    }
+  }
+  const __bf16 *gain = head < Hq ? ex.q_norm : (head < Hq + Hkv ? ex.k_norm : nullptr);
+  if (ex.q_norm || ex.k_norm) {  // uniform: the QUADS consecutive threads of a (token, head) reduce together
+    float ss = 0.f;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) ss += l4[e] * l4[e] + h4[e] * h4[e];
+#pragma unroll
+    for (int o = 1; o < QUADS; o <<= 1) ss += __shfl_xor(ss, o, 64);
+    if (gain) {
+      const float rr = 1.0f / sqrtf(ss / (float)D + ex.eps);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        l4[e] *= rr * (float)gain[mm + e];
+        h4[e] *= rr * (float)gain[mm + e + D / 2];
+      }
+    }
+  }
   if (rotate) {
     const int pos = table[(size_t)b * tbl_stride + 1] + i;
     const float4 *csp = (const float4 *)(rope + (size_t)pos * (D / 2) + mm);
@@ -144,7 +215,7 @@ namespace pc {
 
 pc_status launch_qkv_rope(percache_ctx *ctx, const __bf16 *x, const __bf16 *w, int batch, int t_fresh,
                           const int32_t *table_dev, int tbl_stride, __bf16 *q, __bf16 *k, __bf16 *v,
-                          hipStream_t stream, float *gemm_part) {
+                          hipStream_t stream, float *gemm_part, const QkvExtras &extras) {
   const percache_config &c = ctx->cfg;
   const int M = batch * t_fresh;
   const int F = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
@@ -162,19 +233,25 @@ pc_status launch_qkv_rope(percache_ctx *ctx, const __bf16 *x, const __bf16 *w, i
     const dim3 rgrid((unsigned)((threads + 255) / 256));
     if (c.head_dim == 128)
       hipLaunchKernelGGL(reduce_rope_kernel<128>, rgrid, dim3(256), 0, stream, gemm_part, nk, M, F, t_fresh, c.n_q_heads,
-                         c.n_kv_heads, table_dev, tbl_stride, rope, q, k, v);
+                         c.n_kv_heads, table_dev, tbl_stride, rope, q, k, v, extras);
     else
       hipLaunchKernelGGL(reduce_rope_kernel<64>, rgrid, dim3(256), 0, stream, gemm_part, nk, M, F, t_fresh, c.n_q_heads,
-                         c.n_kv_heads, table_dev, tbl_stride, rope, q, k, v);
+                         c.n_kv_heads, table_dev, tbl_stride, rope, q, k, v, extras);
     prof_end(ctx, PC_KERNEL_QKV_ROPE, stream);
     PC_HIP(ctx, hipGetLastError());
     return PC_OK;
   }
   const bool big = M > 64 * 3;  // 128-token tiles once there are enough rows to fill them
   dim3 grid(F / BF, big ? (M + 127) / 128 : (M + 63) / 64);
-#define PC_LAUNCH(DD, NN)                                                                                          \
-  hipLaunchKernelGGL((qkv_rope_kernel<DD, NN>), grid, dim3(256), 0, stream, x, w, M, c.hidden, t_fresh, c.n_q_heads, \
-                     c.n_kv_heads, table_dev, tbl_stride, rope, q, k, v)
+#define PC_LAUNCH(DD, NN)                                                                                             \
+  do {                                                                                                                \
+    if (extras.any())                                                                                                 \
+      hipLaunchKernelGGL((qkv_rope_kernel<DD, NN, true>), grid, dim3(256), 0, stream, x, w, M, c.hidden, t_fresh,      \
+                         c.n_q_heads, c.n_kv_heads, table_dev, tbl_stride, rope, q, k, v, extras);                    \
+    else                                                                                                              \
+      hipLaunchKernelGGL((qkv_rope_kernel<DD, NN, false>), grid, dim3(256), 0, stream, x, w, M, c.hidden, t_fresh,     \
+                         c.n_q_heads, c.n_kv_heads, table_dev, tbl_stride, rope, q, k, v, extras);                    \
+  } while (0)
   prof_begin(ctx, PC_KERNEL_QKV_ROPE, stream);
   if (c.head_dim == 128) {
     if (big) PC_LAUNCH(128, 2); else PC_LAUNCH(128, 1);

@@ -34,8 +34,9 @@ def dev_layers(Ws):
                  w_up=bf16(W.Wup), w_down=bf16(W.Wdown)) for W in Ws]
 
 
-def oracle_block(h, W, Hq, Hkv, D, theta, sk=None, sv=None, ids=(), used=()):
-    return oracle.block(h, W.gain1, W.Wqkv, Hq, Hkv, D, theta, W.Wo, W.gain2, W.Wgate, W.Wup, W.Wdown, EPS, sk, sv, ids, used)
+def oracle_block(h, W, Hq, Hkv, D, theta, sk=None, sv=None, ids=(), used=(), extras=None):
+    return oracle.block(h, W.gain1, W.Wqkv, Hq, Hkv, D, theta, W.Wo, W.gain2, W.Wgate, W.Wup, W.Wdown, EPS, sk, sv, ids, used,
+                        extras=extras)
 
 
 @pytest.mark.parametrize("D,t_fresh,used_last", [(64, 48, 64), (128, 70, 40), (128, 200, 64)])
@@ -148,3 +149,38 @@ def test_config2_full_size_reuse_equals_full_recompute():
     # layer 0 of the full pass against the oracle on the first 96 rows (causal: they depend on nothing later)
     ref, _, _ = oracle_block(h0[:96], Ws[0], w.n_q_heads, w.n_kv_heads, w.head_dim, w.rope_theta)
     check_hidden(host(one[0, :96]), ref, "cfg2: layer 0 of the full pass, rows 0..95")
+
+
+@pytest.mark.parametrize("D,t_fresh,which", [(128, 40, "all"), (64, 40, "all"), (128, 260, "all"), (64, 260, "all"),
+                                             (128, 260, "bias"), (128, 40, "norm"), (64, 260, "qnorm")])
+def test_projection_variants_bias_and_head_norm(D, t_fresh, which):
+    """Qwen-family variants of the projection: bias, RMSNorm over the head dimension of q and k before RoPE; few rows
+    (split-k path) and many rows (single-pass kernel), both head sizes, each part alone and together."""
+    H, Hq, Hkv, F, C = 256, 4, 2, 384, 64
+    w = wl.make_prefill("var", 23, "bf16", H, Hq, Hkv, D, 1, t_fresh, 2, C, 4)
+    W = wl.stack_weights(23, 0, H, Hq, Hkv, D, F)
+    g = np.random.default_rng(50 + D)
+    n_out = (Hq + 2 * Hkv) * D
+    bias = wl.round_bf16(0.5 * g.standard_normal(n_out).astype(np.float32)) if which in ("all", "bias") else None
+    qg = wl.round_bf16(1 + 0.2 * g.standard_normal(D).astype(np.float32)) if which in ("all", "norm", "qnorm") else None
+    kg = wl.round_bf16(1 + 0.2 * g.standard_normal(D).astype(np.float32)) if which in ("all", "norm") else None
+    layer = dev_layers([W])[0]
+    if bias is not None:
+        layer["qkv_bias"] = bf16(bias)
+    if qg is not None:
+        layer["q_norm"] = bf16(qg)
+    if kg is not None:
+        layer["k_norm"] = bf16(kg)
+    pc = Percache(n_layers=1, hidden=H, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=D, n_slots=4, slot_capacity=C,
+                  max_pos=w.max_pos, device=DEV)
+    for s_ in sorted(set(int(x) for x in w.slot_ids.reshape(-1))):
+        k, v = w.slot_kv(s_)
+        pc.percache_kv_put(0, s_, bf16(k), bf16(v))
+    h_out = pc.percache_stack_reuse([layer], F, EPS, bf16(w.X), w.slot_ids, w.used_len)
+    plain = pc.percache_stack_reuse(dev_layers([W]), F, EPS, bf16(w.X), w.slot_ids, w.used_len)
+    torch.cuda.synchronize()
+    sk, sv, ids = w.compact_store(0)
+    ref, _, _ = oracle_block(w.X[0], W, Hq, Hkv, D, w.rope_theta, sk, sv, ids, w.used_len[0],
+                             extras=dict(bias=bias, q_gain=qg, k_gain=kg, eps=EPS))
+    check_hidden(host(h_out[0]), ref, f"variants {which} D={D} T={t_fresh}")
+    assert np.abs(host(h_out[0]) - host(plain[0])).max() > 1e-2     # the variant is not the plain block

@@ -294,3 +294,35 @@ def test_full_prefill_on_bf16_inputs_matches_textbook():
     O, K, V, _ = oracle.prefill_reuse(X, W, Hq, Hkv, D, 10000.0)
     Or, Kr, Vr = textbook_causal_layer(X, W, Hq, Hkv, D, 10000.0)
     assert np.abs(O - Or).max() < 2e-6 and np.abs(K - Kr).max() < 2e-6 and np.abs(V - Vr).max() < 2e-6
+
+
+def test_projection_variants_bias_and_head_norm_match_numpy():
+    """Bias on the projection and RMSNorm over the head dimension of q / k before RoPE (the Qwen-family variants):
+    against a float64 numpy statement with complex-number RoPE; the plain call is the variant with everything off."""
+    g = np.random.default_rng(3)
+    T, H, Hq, Hkv, D = 5, 32, 4, 2, 16
+    X = g.standard_normal((T, H)).astype(np.float32)
+    W = (g.standard_normal(((Hq + 2 * Hkv) * D, H)) * 0.2).astype(np.float32)
+    b = g.standard_normal((Hq + 2 * Hkv) * D).astype(np.float32)
+    qg = (1 + 0.1 * g.standard_normal(D)).astype(np.float32)
+    kg = (1 + 0.1 * g.standard_normal(D)).astype(np.float32)
+    Q, K, V = oracle.qkv_rope(X, W, Hq, Hkv, D, 7, 10000.0, bias=b, q_gain=qg, k_gain=kg, eps=1e-6)
+    Y = X.astype(np.float64) @ W.astype(np.float64).T + b
+
+    def rope(u, pos):
+        ang = pos * 10000.0 ** (-2 * np.arange(D // 2) / D)
+        z = (u[:D // 2] + 1j * u[D // 2:]) * np.exp(1j * ang)
+        return np.concatenate([z.real, z.imag])
+
+    for i in range(T):
+        for h in range(Hq + Hkv):
+            u = Y[i, h * D:(h + 1) * D]
+            u = u / np.sqrt((u * u).mean() + 1e-6) * (qg if h < Hq else kg)
+            got = Q[h, i] if h < Hq else K[h - Hq, i]
+            assert np.abs(rope(u, 7 + i) - got).max() < 1e-5
+        for h in range(Hkv):
+            assert np.abs(Y[i, (Hq + Hkv + h) * D:(Hq + Hkv + h + 1) * D] - V[h, i]).max() < 1e-5
+    Q0, K0, V0 = oracle.qkv_rope(X, W, Hq, Hkv, D, 7, 10000.0)
+    Q1, K1, V1 = oracle.qkv_rope(X, W, Hq, Hkv, D, 7, 10000.0, bias=np.zeros_like(b))
+    assert np.array_equal(Q0, Q1) and np.array_equal(K0, K1) and np.array_equal(V0, V1)
+    assert np.abs(Q0 - Q).max() > 0.1        # the variants do change the result
