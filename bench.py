@@ -76,10 +76,26 @@ def bench_cfg1(torch, wl, binding, Percache, dev, bf):
     ms_attn, n_attn = pc.percache_profile_read(binding.KERNEL_ATTENTION)
     ms_qkv, n_qkv = pc.percache_profile_read(binding.KERNEL_QKV_ROPE)
     pc.percache_profile_enable(False)
+    # GPU time of one call between two events on the stream, caches warm and flushed: for the latter a 512 MiB buffer
+    # (twice the last-level cache) is rewritten before each call
+    flush = torch.empty(1 << 29, dtype=torch.uint8, device=dev)
+    ev = {"warm": [], "cold": []}
+    for kind in ("warm", "cold"):
+        for _ in range(20):
+            if kind == "cold":
+                flush.fill_(1)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            e1.synchronize()
+            ev[kind].append(e0.elapsed_time(e1))
+    del flush
     pc.close()
     kv_bytes = float(w.l_pre[0]) * w.n_kv_heads * w.head_dim * 2 * 2
     w_bytes = float(w.Wqkv.size) * 2
-    return {"ms_per_call": round(ms, 4), "fresh_tokens_per_s": round(w.t_fresh / (ms * 1e-3), 1),
+    return {"ms_per_call": round(ms, 4), "gpu_ms_per_call_caches_warm": round(float(np.median(ev["warm"])), 4),
+            "gpu_ms_per_call_caches_flushed": round(float(np.median(ev["cold"])), 4), "fresh_tokens_per_s": round(w.t_fresh / (ms * 1e-3), 1),
             "attention_ms": round(ms_attn / n_attn, 4), "kv_stream_GBps": round(kv_bytes / (ms_attn / n_attn * 1e-3) / 1e9, 1),
             "qkv_rope_ms": round(ms_qkv / n_qkv, 4), "weight_stream_GBps": round(w_bytes / (ms_qkv / n_qkv * 1e-3) / 1e9, 1)}
 
@@ -213,7 +229,7 @@ def main():
         return (time.perf_counter() - a) / iters
 
     look = {}
-    for p in (1, 8, 32, 1024):
+    for p in (1, 8, 32, 128, 1024):
         t = time_lookup(probes_all[:p].contiguous())
         if p <= 32:   # one streaming pass of the bank: HBM bound
             look[f"P{p}"] = {"ms": round(t * 1e3, 4), "lookups_per_s": round(p / t, 1), "bound": "hbm",

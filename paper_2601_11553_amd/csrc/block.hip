@@ -126,20 +126,20 @@ __global__ __launch_bounds__(256, 2) void linear_swiglu_kernel(const __bf16 *__r
 // and a small second kernel adds the slices in a fixed order (deterministic) and applies the epilogue.
 // The weight rows may come from two matrices (rows >= n_split from W1): gate and up projections in one launch.
 // ---------------------------------------------------------------------------------------------------
-template <int NTB>
+template <int NTB, int NS>
 __global__ __launch_bounds__(256, 2) void splitk_partial_kernel(const __bf16 *__restrict__ A, int lda,
                                                                 const __bf16 *__restrict__ W0, const __bf16 *__restrict__ W1,
                                                                 int n_split, int ldw, float *__restrict__ P, int M, int N,
                                                                 int k_slice) {
   constexpr int BT = 64 * NTB;
-  __shared__ __align__(16) char lds[pc::gemm::Shape<NTB>::LDS_BYTES];
+  __shared__ __align__(16) char lds[NS * pc::gemm::Shape<NTB>::STAGE];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wf = wave & 1, wt = wave >> 1;
   const int l32 = lane & 31, g = lane >> 5;
   const int f0 = blockIdx.x * BF, m0 = blockIdx.z * BT;
   const int k0 = blockIdx.y * k_slice;
   f32x16 acc[2][NTB];
-  pc::gemm::mainloop<NTB, true>(  // one token tile: every weight row is read by exactly one workgroup
+  pc::gemm::mainloop_deep<NTB, true, NS>(  // one token tile: every weight row is read by exactly one workgroup
       lds,
       [&](int row) __attribute__((always_inline)) {
         const int n = f0 + row;
@@ -295,11 +295,11 @@ StackWs carve_stack_ws(const percache_ctx *ctx, void *base, int batch, int t_fre
 namespace pc {
 
 // Largest number of slices that divides the k steps, leaves every workgroup at least two of them and keeps the
-// launch within two workgroups per CU.
+// launch within one workgroup per CU (more slices only add fp32 partials to write and read back).
 int choose_split_k(int n_cu, int n_tiles, int k_steps) {
   int best = 1;
   for (int d = 1; d <= kMaxSplitK; ++d)
-    if (k_steps % d == 0 && k_steps / d >= 2 && (long)n_tiles * d <= 2L * n_cu) best = d;
+    if (k_steps % d == 0 && k_steps / d >= 2 && (long)n_tiles * d <= n_cu) best = d;
   return best;
 }
 
@@ -307,13 +307,18 @@ pc_status launch_splitk_partial(percache_ctx *ctx, const __bf16 *a, int lda, con
                                 int ldw, float *part, int M, int N, int K, int n_k, hipStream_t stream) {
   if (N % BF || n_split % BF || K % (pc::gemm::BK * n_k)) return fail(ctx, PC_ESHAPE, "split-k projection: N %d, K %d, slices %d", N, K, n_k);
   const int k_slice = K / n_k;
+  // LDS stages: all k-steps of a workgroup in flight at once when there are up to four of them
+  const bool deep = k_slice / pc::gemm::BK > 2;
+#define PC_SPLITK(NTB, NS) \
+  hipLaunchKernelGGL((splitk_partial_kernel<NTB, NS>), grid, dim3(256), 0, stream, a, lda, w0, w1, n_split, ldw, part, M, N, k_slice)
   if (M > 64) {
     dim3 grid(N / BF, n_k, (M + 127) / 128);
-    hipLaunchKernelGGL(splitk_partial_kernel<2>, grid, dim3(256), 0, stream, a, lda, w0, w1, n_split, ldw, part, M, N, k_slice);
+    if (deep) PC_SPLITK(2, 4); else PC_SPLITK(2, 2);
   } else {
     dim3 grid(N / BF, n_k, 1);
-    hipLaunchKernelGGL(splitk_partial_kernel<1>, grid, dim3(256), 0, stream, a, lda, w0, w1, n_split, ldw, part, M, N, k_slice);
+    if (deep) PC_SPLITK(1, 4); else PC_SPLITK(1, 2);
   }
+#undef PC_SPLITK
   PC_HIP(ctx, hipGetLastError());
   return PC_OK;
 }

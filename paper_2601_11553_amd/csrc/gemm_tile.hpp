@@ -26,10 +26,17 @@ struct Shape {
   static constexpr int W_BYTES = BF * ROW, X_BYTES = BT * ROW, STAGE = W_BYTES + X_BYTES;
   static constexpr int W_INSTR = W_BYTES / 1024 / NW, X_INSTR = X_BYTES / 1024 / NW;
   static constexpr int LDS_BYTES = 2 * STAGE;
+  static constexpr int INSTR = W_INSTR + X_INSTR;  // direct-to-LDS load instructions per wavefront and stage
 };
 
 __device__ __forceinline__ int swz128(int row) { return (row >> 1) & 7; }
 __device__ __forceinline__ void wait_vmcnt0() { __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8)); }
+// s_waitcnt vmcnt(N) alone, N < 64 (expcnt / lgkmcnt fields left at "no wait")
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit field");
+  __builtin_amdgcn_s_waitcnt((N & 0xf) | (7 << 4) | (15 << 8) | (((N >> 4) & 3) << 14));
+}
 
 __device__ __forceinline__ uint2 pack4(float a, float b, float c, float d) {
   bf16x4 v = {(__bf16)a, (__bf16)b, (__bf16)c, (__bf16)d};
@@ -129,6 +136,91 @@ __device__ __forceinline__ void mainloop(char *lds, WRow w_row, const T *__restr
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
+  }
+}
+
+// The same contraction for workgroups that own only a few k-steps (a slice of a split contraction): NS LDS stages,
+// all of them requested before the first MFMA, so that a workgroup with up to NS k-steps pays one memory latency
+// instead of one per step.  A stage is refilled (k-step kt + NS) once every wavefront has finished reading it.
+// Arguments and result as for mainloop(); the LDS buffer holds NS * Shape<NTB>::STAGE bytes.
+template <int NTB, bool NTW, int NS, class T, class WRow>
+__device__ __forceinline__ void mainloop_deep(char *lds, WRow w_row, const T *__restrict__ X, int ldx, int m0, int M,
+                                              int K, int fb_lo, int fb_hi, f32x16 (&acc)[2][NTB]) {
+  using S = Shape<NTB>;
+  using V8 = typename Vec8<T>::type;
+  static_assert(NS >= 2 && NS <= 4 && (NS - 1) * S::INSTR < 64, "stage count");
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wt = wave >> 1;
+  const int l32 = lane & 31, g = lane >> 5;
+  const T *w_src[S::W_INSTR];
+  const T *x_src[S::X_INSTR];
+#pragma unroll
+  for (int k = 0; k < S::W_INSTR; ++k) {
+    const int row = (wave + k * NW) * 8 + (lane >> 3);
+    w_src[k] = w_row(row) + (((lane & 7) ^ swz128(row)) * 8);
+  }
+#pragma unroll
+  for (int k = 0; k < S::X_INSTR; ++k) {
+    const int row = (wave + k * NW) * 8 + (lane >> 3);
+    x_src[k] = X + (size_t)min(m0 + row, M - 1) * ldx + (((lane & 7) ^ swz128(row)) * 8);
+  }
+  auto fetch = [&](int kt, int st) __attribute__((always_inline)) {
+    char *base = lds + st * S::STAGE;
+#pragma unroll
+    for (int k = 0; k < S::W_INSTR; ++k)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(w_src[k] + kt * BK),
+                                       (__attribute__((address_space(3))) void *)(base + (wave + k * NW) * 1024), 16, 0, NTW ? 2 : 0);
+#pragma unroll
+    for (int k = 0; k < S::X_INSTR; ++k)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(x_src[k] + kt * BK),
+                                       (__attribute__((address_space(3))) void *)(base + S::W_BYTES + (wave + k * NW) * 1024), 16, 0, 0);
+  };
+  int rd[BK / 16];
+#pragma unroll
+  for (int ks = 0; ks < BK / 16; ++ks) rd[ks] = ((2 * ks + g) ^ swz128(l32)) * 16;
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int t = 0; t < NTB; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[a][t][r] = 0.f;
+
+  const int nk = K / BK;
+#pragma unroll
+  for (int s = 0; s < NS; ++s)
+    if (s < nk) fetch(s, s);
+  int st = 0;
+  for (int kt = 0; kt < nk; ++kt) {
+    // k-step kt has landed once at most the loads of the (up to NS - 1) later steps in flight are outstanding
+    const int later = min(NS - 1, nk - 1 - kt);
+    if (later >= 3) wait_vmcnt<(NS > 3 ? 3 : 0) * S::INSTR>();
+    else if (later == 2) wait_vmcnt<(NS > 2 ? 2 : 0) * S::INSTR>();
+    else if (later == 1) wait_vmcnt<S::INSTR>();
+    else wait_vmcnt0();
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    const char *wl = lds + st * S::STAGE + (fb_lo * 32 + l32) * ROW;
+    const char *wh = lds + st * S::STAGE + (fb_hi * 32 + l32) * ROW;
+    const char *xb = lds + st * S::STAGE + S::W_BYTES + ((wt * NTB) * 32 + l32) * ROW;
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      V8 a_lo = *(const V8 *)(wl + rd[ks]);
+      V8 a_hi = *(const V8 *)(wh + rd[ks]);
+#pragma unroll
+      for (int t = 0; t < NTB; ++t) {
+        V8 b = *(const V8 *)(xb + t * 32 * ROW + rd[ks]);
+        acc[0][t] = mma(a_lo, b, acc[0][t]);
+        acc[1][t] = mma(a_hi, b, acc[1][t]);
+      }
+    }
+    if (kt + NS < nk) {
+      asm volatile("" ::: "memory");
+      __builtin_amdgcn_s_barrier();  // every wavefront has read this stage
+      asm volatile("" ::: "memory");
+      fetch(kt + NS, st);
+    }
+    st = st + 1 == NS ? 0 : st + 1;
   }
 }
 

@@ -86,9 +86,19 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
   const int l32 = lane & 31, g2 = lane >> 5;
   const int G = Hq / Hkv, R = G * T;
 
+  // Chunk list of this query.  Lane c keeps (slot, used length) of chunk c for the first 64 chunks, so that the
+  // walk over the list costs one memory latency in all; chunks past the 64th are read from the table when met.
   const int32_t *trow = table + (size_t)b * tbl_stride;
+  int my_slot = 0, my_used = 0;
+  if (lane < (tbl_stride - kTblHeader) / 2) {
+    const int2 e = *(const int2 *)(trow + kTblHeader + 2 * lane);
+    my_slot = e.x;
+    my_used = e.y;
+  }
   const int n_chunks = trow[0];
   const int n_cached_tiles = trow[2];
+  if (lane >= n_chunks) my_used = 0;
+  const unsigned long long live = __ballot(my_used > 0);  // chunks (of the first 64) with keys to read
 
   // rows of this workgroup and the fresh tiles they can see
   const int row_first = qt * QROWS;
@@ -111,10 +121,6 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
     const __bf16 *qrow = Q + (((size_t)b * Hq + head) * T + my_i) * D + g2 * 8;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) qf[ks] = *(const bf16x8 *)(qrow + ks * 16);
-    // Consume the fragments here, once: otherwise the loads are still "pending" at the loop header in the
-    // compiler's wait-count model and every iteration waits on its own K/V prefetch before the first MFMA.
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qf[ks]));
   }
 
   f32x16 o_acc[DB];
@@ -128,20 +134,42 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
   // re-read from the table only when the cursor enters another chunk.
   struct Cursor { int chunk, off, slot, used; };  // chunk index, tile index inside the chunk (or the fresh part)
   auto enter_chunk = [&](Cursor &c) __attribute__((always_inline)) {
-    while (c.chunk < n_chunks && trow[kTblHeader + 2 * c.chunk + 1] == 0) ++c.chunk;  // unused chunks
-    if (c.chunk < n_chunks) {
+    if (c.chunk < 64) {  // skip unused chunks
+      const unsigned long long rest = live >> c.chunk;
+      c.chunk = rest ? c.chunk + __builtin_ctzll(rest) : min(n_chunks, 64);
+    }
+    while (c.chunk >= 64 && c.chunk < n_chunks && trow[kTblHeader + 2 * c.chunk + 1] == 0) ++c.chunk;
+    if (c.chunk < min(n_chunks, 64)) {
+      const int ch = __builtin_amdgcn_readfirstlane(c.chunk);
+      c.slot = __builtin_amdgcn_readlane(my_slot, ch);
+      c.used = __builtin_amdgcn_readlane(my_used, ch);
+    } else if (c.chunk < n_chunks) {
       c.slot = trow[kTblHeader + 2 * c.chunk];
       c.used = trow[kTblHeader + 2 * c.chunk + 1];
     }
   };
   Cursor cur = {0, 0, 0, 0};
   {
-    int rem = tile_begin;
-    while (cur.chunk < n_chunks) {
-      int ntc = (trow[kTblHeader + 2 * cur.chunk + 1] + TK - 1) / TK;
-      if (rem < ntc) break;
-      rem -= ntc;
-      ++cur.chunk;
+    // tiles of the chunks before each lane's chunk (exclusive scan over the lanes), then the chunk tile_begin is in
+    const int my_tiles = (my_used + TK - 1) / TK;
+    int incl = my_tiles;
+#pragma unroll
+    for (int sh = 1; sh < 64; sh <<= 1) {
+      const int up = __shfl_up(incl, sh, 64);
+      if (lane >= sh) incl += up;
+    }
+    cur.chunk = __popcll(__ballot(incl <= tile_begin && lane < n_chunks));
+    int rem;
+    if (cur.chunk < min(n_chunks, 64)) {
+      rem = tile_begin - __builtin_amdgcn_readlane(incl - my_tiles, __builtin_amdgcn_readfirstlane(cur.chunk));
+    } else {
+      rem = tile_begin - __builtin_amdgcn_readlane(incl, 63);
+      while (cur.chunk < n_chunks) {
+        int ntc = (trow[kTblHeader + 2 * cur.chunk + 1] + TK - 1) / TK;
+        if (rem < ntc) break;
+        rem -= ntc;
+        ++cur.chunk;
+      }
     }
     cur.off = rem;
     enter_chunk(cur);
@@ -231,6 +259,11 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
       ++fetched;
     }
   }
+  // Consume the Q fragments here, once (their latency has run beside the first tiles'): otherwise the loads are
+  // still "pending" at the loop header in the compiler's wait-count model and every iteration waits on its own
+  // K/V prefetch before the first MFMA.
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qf[ks]));
   PC_WAIT_VMCNT(0);
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
@@ -398,43 +431,58 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
 }
 
 // Merge of the split-KV partials: m = max m_s, w_s = l_s 2^(m_s - m), o = sum w_s o_s / sum w_s.
-// One thread per (row, 8 head-dim elements).
+// A row is shared by 4 * D/8 neighbouring lanes: lane (sg, dv) adds up 8 head-dim elements over the partitions
+// s = sg, sg + 4, ..., and the four partial sums meet through lane shuffles.
 template <int D>
 __global__ __launch_bounds__(256) void splitkv_combine_kernel(const __bf16 *__restrict__ part_o,
                                                               const float *__restrict__ part_ml, int n_splits, int T,
                                                               int Hq, int Hkv, long total_rows,
                                                               __bf16 *__restrict__ out) {
-  constexpr int VPR = D / 8;
-  long gid = (long)blockIdx.x * blockDim.x + threadIdx.x;
-  long prow = gid / VPR;
-  int dv = (int)(gid - prow * VPR);
-  if (prow >= total_rows) return;
-  const int G = Hq / Hkv, R = G * T;
-  long bg = prow / R;
-  int row = (int)(prow - bg * R);
-  int b = (int)(bg / Hkv), gkv = (int)(bg - (long)b * Hkv);
-  int hg = row / T, i = row - hg * T;
-  int head = gkv * G + hg;
-  const float *ml = part_ml + prow * n_splits * 2;
+  constexpr int VPR = D / 8, SG = 4, LPR = VPR * SG;  // lanes per row
+  const long gid = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  const long prow_raw = gid / LPR;
+  const int r = (int)(gid - prow_raw * LPR);
+  const int sg = r / VPR, dv = r - sg * VPR;
+  const bool live = prow_raw < total_rows;
+  const long prow = live ? prow_raw : total_rows - 1;
+  const float2 *ml = (const float2 *)part_ml + prow * n_splits;
   float m = -INFINITY;
 #pragma unroll 4
-  for (int s = 0; s < n_splits; ++s) m = fmaxf(m, ml[2 * s + 1] > 0.f ? ml[2 * s] : -INFINITY);
+  for (int s = sg; s < n_splits; s += SG) {
+    const float2 e = ml[s];
+    m = fmaxf(m, e.y > 0.f ? e.x : -INFINITY);
+  }
+  m = fmaxf(m, __shfl_xor(m, VPR, 64));
+  m = fmaxf(m, __shfl_xor(m, 2 * VPR, 64));
   float wsum = 0.f;
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   const __bf16 *po = part_o + prow * n_splits * D + dv * 8;
 #pragma unroll 4
-  for (int s = 0; s < n_splits; ++s) {
-    const float ms = ml[2 * s], ls = ml[2 * s + 1];
-    const float w = ls > 0.f ? ls * exp2f(ms - m) : 0.f;  // an empty partition has weight 0 (its output row is 0)
+  for (int s = sg; s < n_splits; s += SG) {
+    const float2 e = ml[s];
+    const float w = e.y > 0.f ? e.y * exp2f(e.x - m) : 0.f;  // an empty partition has weight 0 (its output row is 0)
     pc::bf16x8 o = *(const pc::bf16x8 *)(po + (size_t)s * D);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) acc[e] += w * (float)o[e];
+    for (int e8 = 0; e8 < 8; ++e8) acc[e8] += w * (float)o[e8];
     wsum += w;
   }
-  float inv = wsum > 0.f ? 1.0f / wsum : 0.f;
+#pragma unroll
+  for (int sh = VPR; sh < LPR; sh <<= 1) {
+    wsum += __shfl_xor(wsum, sh, 64);
+#pragma unroll
+    for (int e8 = 0; e8 < 8; ++e8) acc[e8] += __shfl_xor(acc[e8], sh, 64);
+  }
+  if (!live || sg != 0) return;
+  const int G = Hq / Hkv, R = G * T;
+  const long bg = prow / R;
+  const int row = (int)(prow - bg * R);
+  const int b = (int)(bg / Hkv), gkv = (int)(bg - (long)b * Hkv);
+  const int hg = row / T, i = row - hg * T;
+  const int head = gkv * G + hg;
+  const float inv = wsum > 0.f ? 1.0f / wsum : 0.f;
   pc::bf16x8 v;
 #pragma unroll
-  for (int e = 0; e < 8; ++e) v[e] = (__bf16)(acc[e] * inv);
+  for (int e8 = 0; e8 < 8; ++e8) v[e8] = (__bf16)(acc[e8] * inv);
   *(pc::bf16x8 *)(out + ((size_t)b * T + i) * ((size_t)Hq * D) + (size_t)head * D + dv * 8) = v;
 }
 
@@ -522,7 +570,7 @@ pc_status launch_attention(percache_ctx *ctx, int layer, const __bf16 *q, const 
   PC_HIP(ctx, hipGetLastError());
   if (n_splits > 1) {
     long total_rows = (long)batch * c.n_kv_heads * R;
-    long threads = total_rows * (c.head_dim / 8);
+    long threads = total_rows * (c.head_dim / 8) * 4;  // 4 lanes per 16 output bytes
     int blocks = (int)((threads + 255) / 256);
     if (c.head_dim == 128)
       hipLaunchKernelGGL(splitkv_combine_kernel<128>, dim3(blocks), dim3(256), 0, stream, part_o, part_ml, n_splits,

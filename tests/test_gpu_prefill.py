@@ -166,6 +166,31 @@ def test_ragged_batch_with_partial_and_empty_chunks():
     pc.close()
 
 
+@pytest.mark.parametrize("n_splits", [0, 1, 5])
+def test_long_chunk_lists(n_splits):
+    """70 and 64 short chunks per query (the kernel keeps the first 64 list entries in registers and reads the
+    rest from memory), unused chunks before, at and after the 64th, ragged lengths; key-axis partitions that start
+    inside either part of the list."""
+    n_c, C = 70, 64
+    w = wl.make_prefill("long_list", 17, "bf16", 256, 4, 2, 64, 2, 40, n_c, C, 80)
+    g = np.random.default_rng(5)
+    w.used_len[:] = g.integers(1, C + 1, size=(2, n_c))
+    w.used_len[0, [0, 5, 62, 63, 64, 69]] = 0
+    w.used_len[1, [63, 65, 66]] = 0
+    pc = make_ctx(w)
+    fill_slots(pc, w, w.slot_ids.reshape(-1))
+    X, W = bf16(w.X), bf16(w.Wqkv)
+    q, kf, vf = pc.percache_qkv_rope(0, X, W, w.slot_ids, w.used_len, n_chunks=[70, 64])
+    out = pc.percache_attention_reuse(0, q, kf, vf, w.slot_ids, w.used_len, n_chunks=[70, 64], n_splits=n_splits)
+    torch.cuda.synchronize()
+    for b, nc in enumerate([70, 64]):
+        sk, sv, ids = w.compact_store(b)
+        O, _, _, _ = oracle.prefill_reuse(w.X[b], w.Wqkv, w.n_q_heads, w.n_kv_heads, w.head_dim, w.rope_theta, sk, sv,
+                                          ids[:nc], w.used_len[b][:nc])
+        check_close(host(out[b]), O, f"long list splits={n_splits} b={b}")
+    pc.close()
+
+
 def test_full_recompute_path_is_plain_causal_prefill():
     w = wl.make_prefill("causal", 8, "bf16", 256, 4, 2, 64, 2, 200, 0, 64, 1)
     pc = make_ctx(w, max_pos=256)
