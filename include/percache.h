@@ -56,6 +56,7 @@ typedef struct {
   float rope_theta;      /* RoPE base */
   int32_t bank_capacity; /* N_max: rows of the query-embedding bank (0 = no bank) */
   int32_t emb_dim;       /* d: embedding width */
+  int32_t kv_fp8;        /* 0: slots hold bf16.  1: slots hold 8-bit codes, half the bytes (see "8-bit slots" below) */
 } percache_config;
 
 /* Bytes of device memory the caller must provide for a context of this shape (0 on a bad
@@ -114,6 +115,17 @@ pc_status percache_bank_refresh_scan(percache_ctx *ctx, const void *new_emb_dev,
                                      const float *kth_sim_dev, float *best_sim_out_dev, int32_t *best_new_out_dev,
                                      uint8_t *stale_out_dev, void *workspace_dev, size_t workspace_bytes,
                                      void *stream);
+
+/* ---------------------------------------------------------------- 8-bit slots (kv_fp8 = 1)
+ * The paper keeps the chunks' complete tensors (Sec. 4.1.1) and leaves other cache organisations to future work
+ * (Sec. 7); this is a smaller slot for the same tensors.  An element is stored as an E4M3 code of the OCP 8-bit
+ * floating point specification (1 sign, 4 exponent bits with bias 7, 3 mantissa bits, largest magnitude 448, no
+ * infinities), with one power-of-two scale 2^e per (slot, kv head, block of 64 tokens), separately for K and V:
+ * e is the smallest integer with max|x| <= 448 * 2^e over the block's stored tokens (0 for an all-zero block), kept in
+ * [-110, 127]; code = E4M3(x * 2^-e), round to nearest, ties to even; the value read back is code * 2^e, exactly
+ * representable in bf16.  percache_kv_put / _put_batch / _slice and the save slots of percache_stack_reuse quantise;
+ * percache_kv_get returns the values read back; the attention calls read them on the fly (fresh K/V stay bf16).
+ * percache_kv_append and percache_stack_decode return PC_ESHAPE on such a context. */
 
 /* ---------------------------------------------------------------- K/V store (Sec. 4.1.1)
  * One slot holds one knowledge chunk's K and V for one layer, as collected from the attention

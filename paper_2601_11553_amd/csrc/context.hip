@@ -21,13 +21,14 @@ bool config_ok(const percache_config *c, std::string &why) {
   if (c->bank_capacity > 0 && (c->emb_dim < 64 || c->emb_dim % 64 || c->emb_dim > 2048))
     return bad("emb_dim must be a multiple of 64 in [64, 2048]");
   if (!(c->rope_theta > 1.0f)) return bad("rope_theta must exceed 1");
+  if (c->kv_fp8 != 0 && c->kv_fp8 != 1) return bad("kv_fp8 must be 0 or 1");
   if (((c->n_q_heads + 2 * c->n_kv_heads) * c->head_dim) % 128) return bad("(n_q_heads + 2 n_kv_heads) * head_dim must be a multiple of 128");
   (void)buf;
   return true;
 }
 
 struct Layout {
-  size_t rope, bank, bank_inv, k_store, v_store, total;
+  size_t rope, bank, bank_inv, k_store, v_store, k_scale, v_scale, total;
 };
 Layout layout_of(const percache_config &c) {
   Layout l;
@@ -38,11 +39,16 @@ Layout layout_of(const percache_config &c) {
   off += pc::align_up((size_t)c.bank_capacity * (size_t)(c.bank_capacity ? c.emb_dim : 0) * 2);
   l.bank_inv = off;
   off += pc::align_up((size_t)c.bank_capacity * sizeof(float));
-  size_t store = (size_t)c.n_layers * c.n_slots * c.n_kv_heads * c.slot_capacity * c.head_dim * 2;
+  size_t store = (size_t)c.n_layers * c.n_slots * c.n_kv_heads * c.slot_capacity * c.head_dim * (c.kv_fp8 ? 1 : 2);
   l.k_store = off;
   off += pc::align_up(store);
   l.v_store = off;
   off += pc::align_up(store);
+  size_t scales = c.kv_fp8 ? (size_t)c.n_layers * c.n_slots * c.n_kv_heads * (c.slot_capacity / pc::kKvTile) * sizeof(float) : 0;
+  l.k_scale = off;
+  off += pc::align_up(scales);
+  l.v_scale = off;
+  off += pc::align_up(scales);
   l.total = off;
   return l;
 }
@@ -185,8 +191,15 @@ pc_status percache_create(const percache_config *cfg, void *arena_dev, size_t ar
   ctx->rope = (float *)(ctx->arena + l.rope);
   ctx->bank = (_Float16 *)(ctx->arena + l.bank);
   ctx->bank_inv = (float *)(ctx->arena + l.bank_inv);
-  ctx->k_store = (__bf16 *)(ctx->arena + l.k_store);
-  ctx->v_store = (__bf16 *)(ctx->arena + l.v_store);
+  if (cfg->kv_fp8) {
+    ctx->k8_store = (uint8_t *)(ctx->arena + l.k_store);
+    ctx->v8_store = (uint8_t *)(ctx->arena + l.v_store);
+    ctx->k_scale = (float *)(ctx->arena + l.k_scale);
+    ctx->v_scale = (float *)(ctx->arena + l.v_scale);
+  } else {
+    ctx->k_store = (__bf16 *)(ctx->arena + l.k_store);
+    ctx->v_store = (__bf16 *)(ctx->arena + l.v_store);
+  }
   ctx->slot_stride = (size_t)cfg->n_kv_heads * cfg->slot_capacity * cfg->head_dim;
   ctx->layer_stride = ctx->slot_stride * cfg->n_slots;
   ctx->slot_len.assign((size_t)cfg->n_layers * cfg->n_slots, 0);

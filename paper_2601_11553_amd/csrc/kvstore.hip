@@ -118,6 +118,148 @@ __global__ __launch_bounds__(256) void kv_append_kernel(__bf16 *__restrict__ slo
   }
 }
 
+// ---------------------------------------------------------------------------------------------------
+// 8-bit slots.  Layout per (slot, kv head):  K [token][head_dim] bytes;  V [token / 64][head_dim][64] bytes with
+// key order pc::blocked_key8 inside a block, zero codes past the stored count;  one scale 2^e per 64-token block
+// for K and one for V.  One workgroup per (chunk, kv head, 64-token block).
+// ---------------------------------------------------------------------------------------------------
+// 2^e with e the smallest integer such that amax <= 448 * 2^e, e kept in [-110, 127] (0 for amax == 0).
+// 448 = 1.75 * 2^8: with amax = 1.f * 2^k the answer is k - 8 when 1.f <= 1.75, else k - 7.
+__device__ __forceinline__ int block_exponent(float amax) {
+  if (amax == 0.f) return 0;
+  const unsigned bits = __float_as_uint(amax);
+  const int field = (int)((bits >> 23) & 0xff);
+  if (field == 0) return -110;  // below 2^-126
+  const int k = field - 127;
+  const int e = (bits & 0x7fffffu) <= 0x600000u ? k - 8 : k - 7;
+  return e < -110 ? -110 : (e > 127 ? 127 : e);
+}
+__device__ __forceinline__ float pow2f(int e) { return __uint_as_float((unsigned)(e + 127) << 23); }  // e in [-126, 127]
+
+// four E4M3 codes of four floats already divided by the scale (round to nearest even in hardware; |y| <= 448)
+__device__ __forceinline__ unsigned encode4(float a, float b, float c, float d) {
+  int w = __builtin_amdgcn_cvt_pk_fp8_f32(__builtin_amdgcn_fmed3f(a, -448.f, 448.f), __builtin_amdgcn_fmed3f(b, -448.f, 448.f), 0, false);
+  w = __builtin_amdgcn_cvt_pk_fp8_f32(__builtin_amdgcn_fmed3f(c, -448.f, 448.f), __builtin_amdgcn_fmed3f(d, -448.f, 448.f), w, true);
+  return (unsigned)w;
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void kv_quant_kernel(uint8_t *__restrict__ slot_k, uint8_t *__restrict__ slot_v,
+                                                       float *__restrict__ scale_k, float *__restrict__ scale_v,
+                                                       const __bf16 *__restrict__ dense_k, const __bf16 *__restrict__ dense_v,
+                                                       int n_heads, int n_tok, int C, SlotList slots, long slot_stride_elems,
+                                                       long scale_slot_stride, long dense_head_stride) {
+  constexpr int DV = D / 8, NV = kKvTile * DV / 256;  // 8-element vectors per row; vectors per thread
+  __shared__ float red[2][4];
+  __shared__ __align__(16) uint8_t vt[kKvTile][D + 16];  // V codes [key][d] (padded rows), read back transposed
+  const int blk = blockIdx.x, g = blockIdx.y, tid = threadIdx.x;
+  const int slot = slots.slot[blockIdx.z];
+  const size_t dense_at = ((size_t)blockIdx.z * n_heads + g) * dense_head_stride;
+  pc::bf16x8 kv[NV], vv[NV];
+  float ak = 0.f, av = 0.f;
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    const int v = tid + 256 * j, r = v / DV, dc = v - r * DV;
+    const int t = blk * kKvTile + r;
+    if (t < n_tok) {
+      kv[j] = *(const pc::bf16x8 *)(dense_k + dense_at + (size_t)t * D + dc * 8);
+      vv[j] = *(const pc::bf16x8 *)(dense_v + dense_at + (size_t)t * D + dc * 8);
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { kv[j][e] = (__bf16)0.f; vv[j][e] = (__bf16)0.f; }
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      ak = fmaxf(ak, fabsf((float)kv[j][e]));
+      av = fmaxf(av, fabsf((float)vv[j][e]));
+    }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    ak = fmaxf(ak, __shfl_xor(ak, o, 64));
+    av = fmaxf(av, __shfl_xor(av, o, 64));
+  }
+  if ((tid & 63) == 0) { red[0][tid >> 6] = ak; red[1][tid >> 6] = av; }
+  __syncthreads();
+  ak = fmaxf(fmaxf(red[0][0], red[0][1]), fmaxf(red[0][2], red[0][3]));
+  av = fmaxf(fmaxf(red[1][0], red[1][1]), fmaxf(red[1][2], red[1][3]));
+  const int ek = block_exponent(ak), ev = block_exponent(av);
+  const float ik = pow2f(-ek), iv = pow2f(-ev);
+  const size_t slot_at = (size_t)slot * slot_stride_elems + (size_t)g * C * D;
+  if (tid == 0) {
+    const size_t sc = (size_t)slot * scale_slot_stride + (size_t)g * (C / kKvTile) + blk;
+    scale_k[sc] = pow2f(ek);
+    scale_v[sc] = pow2f(ev);
+  }
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    const int v = tid + 256 * j, r = v / DV, dc = v - r * DV;
+    const int t = blk * kKvTile + r;
+    uint2 ck, cv;
+    ck.x = encode4((float)kv[j][0] * ik, (float)kv[j][1] * ik, (float)kv[j][2] * ik, (float)kv[j][3] * ik);
+    ck.y = encode4((float)kv[j][4] * ik, (float)kv[j][5] * ik, (float)kv[j][6] * ik, (float)kv[j][7] * ik);
+    cv.x = encode4((float)vv[j][0] * iv, (float)vv[j][1] * iv, (float)vv[j][2] * iv, (float)vv[j][3] * iv);
+    cv.y = encode4((float)vv[j][4] * iv, (float)vv[j][5] * iv, (float)vv[j][6] * iv, (float)vv[j][7] * iv);
+    if (t < n_tok) *(uint2 *)(slot_k + slot_at + (size_t)t * D + dc * 8) = ck;
+    *(uint2 *)(&vt[r][dc * 8]) = cv;  // rows past the stored count hold zero codes
+  }
+  __syncthreads();
+  // transposed write: one 16-byte run of a head-dim row per thread and step
+  uint8_t *vblk = slot_v + slot_at + (size_t)blk * kKvTile * D;
+  for (int o = tid; o < D * (kKvTile / 16); o += 256) {
+    const int d = o / (kKvTile / 16), c16 = o - d * (kKvTile / 16);
+    unsigned w[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int p = 0; p < 16; ++p) w[p >> 2] |= (unsigned)vt[pc::blocked_key8(c16 * 16 + p)][d] << (8 * (p & 3));
+    *(uint4 *)(vblk + (size_t)d * kKvTile + c16 * 16) = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+}
+
+// The values an 8-bit slot holds, as dense bf16 [kv head][token][head_dim]: code * 2^e (exact).
+template <int D>
+__global__ __launch_bounds__(256) void kv_dequant_kernel(const uint8_t *__restrict__ slot_k, const uint8_t *__restrict__ slot_v,
+                                                         const float *__restrict__ scale_k, const float *__restrict__ scale_v,
+                                                         __bf16 *__restrict__ dense_k, __bf16 *__restrict__ dense_v, int n_heads,
+                                                         int n_tok, int C, SlotList slots, long slot_stride_elems,
+                                                         long scale_slot_stride, long dense_head_stride) {
+  constexpr int DV = D / 8, NV = kKvTile * DV / 256;
+  const int blk = blockIdx.x, g = blockIdx.y, tid = threadIdx.x;
+  const int slot = slots.slot[blockIdx.z];
+  const size_t dense_at = ((size_t)blockIdx.z * n_heads + g) * dense_head_stride;
+  const size_t slot_at = (size_t)slot * slot_stride_elems + (size_t)g * C * D;
+  const size_t sc = (size_t)slot * scale_slot_stride + (size_t)g * (C / kKvTile) + blk;
+  const float sk = scale_k[sc], sv = scale_v[sc];
+  const uint8_t *vblk = slot_v + slot_at + (size_t)blk * kKvTile * D;
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    const int v = tid + 256 * j, r = v / DV, dc = v - r * DV;
+    const int t = blk * kKvTile + r;
+    if (t >= n_tok) continue;
+    const uint2 ck = *(const uint2 *)(slot_k + slot_at + (size_t)t * D + dc * 8);
+    const int pos = pc::blocked_pos8(r);
+    unsigned cvx = 0, cvy = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      cvx |= (unsigned)vblk[(size_t)(dc * 8 + e) * kKvTile + pos] << (8 * e);
+      cvy |= (unsigned)vblk[(size_t)(dc * 8 + 4 + e) * kKvTile + pos] << (8 * e);
+    }
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    pc::bf16x8 ok, ov;
+    const unsigned wk[2] = {ck.x, ck.y}, wv[2] = {cvx, cvy};
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const f32x2 k0 = __builtin_amdgcn_cvt_pk_f32_fp8((int)wk[h], false), k1 = __builtin_amdgcn_cvt_pk_f32_fp8((int)wk[h], true);
+      const f32x2 v0 = __builtin_amdgcn_cvt_pk_f32_fp8((int)wv[h], false), v1 = __builtin_amdgcn_cvt_pk_f32_fp8((int)wv[h], true);
+      ok[4 * h + 0] = (__bf16)(k0[0] * sk); ok[4 * h + 1] = (__bf16)(k0[1] * sk);
+      ok[4 * h + 2] = (__bf16)(k1[0] * sk); ok[4 * h + 3] = (__bf16)(k1[1] * sk);
+      ov[4 * h + 0] = (__bf16)(v0[0] * sv); ov[4 * h + 1] = (__bf16)(v0[1] * sv);
+      ov[4 * h + 2] = (__bf16)(v1[0] * sv); ov[4 * h + 3] = (__bf16)(v1[1] * sv);
+    }
+    *(pc::bf16x8 *)(dense_k + dense_at + (size_t)t * D + dc * 8) = ok;
+    *(pc::bf16x8 *)(dense_v + dense_at + (size_t)t * D + dc * 8) = ov;
+  }
+}
+
 pc_status check_slot(percache_ctx *ctx, int32_t layer, int32_t slot) {
   if (!ctx) return PC_EINVAL;
   if (layer < 0 || layer >= ctx->cfg.n_layers) return pc::fail(ctx, PC_ESLOT, "layer %d out of range [0,%d)", layer, ctx->cfg.n_layers);
@@ -132,6 +274,24 @@ pc_status launch_copy(percache_ctx *ctx, int layer, const int32_t *slot_list, in
   size_t off = (size_t)layer * ctx->layer_stride;
   SlotList sl;
   for (int i = 0; i < 64; ++i) sl.slot[i] = i < n ? slot_list[i] : 0;
+  if (c.kv_fp8) {
+    const long sc_slot = (long)c.n_kv_heads * (c.slot_capacity / kKvTile);
+    const size_t sc_off = (size_t)layer * c.n_slots * sc_slot;
+    const long dhs = dense_head_stride ? dense_head_stride : (long)n_tokens * c.head_dim;
+    dim3 grid((n_tokens + kKvTile - 1) / kKvTile, c.n_kv_heads, n);
+#define PC_KV8(KERNEL, DD)                                                                                                    \
+  hipLaunchKernelGGL((KERNEL<DD>), grid, dim3(256), 0, stream, ctx->k8_store + off, ctx->v8_store + off, ctx->k_scale + sc_off, \
+                     ctx->v_scale + sc_off, (__bf16 *)k_dev, (__bf16 *)v_dev, c.n_kv_heads, n_tokens, c.slot_capacity, sl,      \
+                     (long)ctx->slot_stride, sc_slot, dhs)
+    if (kToStore) {
+      if (c.head_dim == 128) PC_KV8(kv_quant_kernel, 128); else PC_KV8(kv_quant_kernel, 64);
+    } else {
+      if (c.head_dim == 128) PC_KV8(kv_dequant_kernel, 128); else PC_KV8(kv_dequant_kernel, 64);
+    }
+#undef PC_KV8
+    PC_HIP(ctx, hipGetLastError());
+    return PC_OK;
+  }
   long total = (long)c.n_kv_heads * ((n_tokens + kKvTile - 1) / kKvTile) * kKvTile * c.head_dim / 8;
   int blocks = (int)((total + 255) / 256);
   if (blocks > 2048) blocks = 2048;
@@ -172,6 +332,7 @@ pc_status percache_kv_append(percache_ctx *ctx, int32_t layer, int32_t slot, con
   if (st != PC_OK) return st;
   if (!k_dev || !v_dev) return pc::fail(ctx, PC_EINVAL, "k_dev / v_dev is NULL");
   const percache_config &c = ctx->cfg;
+  if (c.kv_fp8) return pc::fail(ctx, PC_ESHAPE, "appending to 8-bit slots is not supported");
   const int have = ctx->slot_len[(size_t)layer * c.n_slots + slot];
   if (n_tokens < 1 || have + n_tokens > c.slot_capacity)
     return pc::fail(ctx, PC_ELEN, "slot %d holds %d tokens: %d more do not fit the capacity %d", slot, have, n_tokens, c.slot_capacity);

@@ -33,6 +33,16 @@ constexpr int kKvTile = 64;
 // its own inverse.
 __host__ __device__ inline int blocked_key(int p) { return 8 * ((p >> 2) & 1) + 4 * (p >> 3) + (p & 3); }
 
+// 8-bit slots: V blocks are [head_dim][kKvTile] bytes; physical byte p of a row holds key blocked_key8(p).  A lane of
+// the PV product reads 16 bytes = its 8 keys of two consecutive 16-key steps: p = 32 J + 16 g2 + 8 j + e  <->
+// key 32 J + 16 j + 8 (e >> 2) + 4 g2 + (e & 3)  (J: 32-key score block, j: half of it, g2: lane half).
+__host__ __device__ inline int blocked_key8(int p) {
+  return (p & 32) + 16 * ((p >> 3) & 1) + 8 * ((p >> 2) & 1) + 4 * ((p >> 4) & 1) + (p & 3);
+}
+__host__ __device__ inline int blocked_pos8(int key) {  // the inverse: the byte that holds a key
+  return (key & 32) + 16 * ((key >> 2) & 1) + 8 * ((key >> 4) & 1) + 4 * ((key >> 3) & 1) + (key & 3);
+}
+
 // Device chunk table, one row per query (int32):
 //   [0] n_chunks  [1] L_pre  [2] cached tiles (sum over chunks of ceil(used/kKvTile))  [3] unused
 //   [4 + 2c] slot id of chunk c   [5 + 2c] used length of chunk c
@@ -51,8 +61,10 @@ struct percache_ctx {
   float *rope = nullptr;      // [max_pos][D/2] float2 (cos, sin)
   _Float16 *bank = nullptr;   // [bank_capacity][emb_dim]
   float *bank_inv = nullptr;  // [bank_capacity]
-  __bf16 *k_store = nullptr;  // [n_layers][n_slots][Hkv][C][D]
+  __bf16 *k_store = nullptr;  // [n_layers][n_slots][Hkv][C][D]   (bf16 slots; null with 8-bit slots)
   __bf16 *v_store = nullptr;  // same
+  uint8_t *k8_store = nullptr, *v8_store = nullptr;  // 8-bit slots: the same shapes in bytes
+  float *k_scale = nullptr, *v_scale = nullptr;      // 8-bit slots: 2^e per [n_layers][n_slots][Hkv][C/64]
   size_t layer_stride = 0;    // elements per layer of one store
   size_t slot_stride = 0;     // elements per slot
   int32_t bank_size = 0;

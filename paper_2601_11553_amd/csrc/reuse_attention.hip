@@ -60,13 +60,33 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 __device__ __forceinline__ float pair_max(float x) { return fmaxf(x, __shfl_xor(x, 32, 64)); }
 __device__ __forceinline__ float pair_sum(float x) { return x + __shfl_xor(x, 32, 64); }
 
+// eight E4M3 codes (two dwords) times a power-of-two scale -> the eight bf16 values of one MFMA operand (exact)
+__device__ __forceinline__ bf16x8 codes_to_bf16(unsigned w0, unsigned w1, float scale) {
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  union { bf16x2 p[4]; bf16x8 v; } u;
+  u.p[0] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w0, scale, false);
+  u.p[1] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w0, scale, true);
+  u.p[2] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w1, scale, false);
+  u.p[3] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w1, scale, true);
+  return u.v;
+}
+
 // NW wavefronts per workgroup (32 query rows each), NSTAGE LDS stages of one K tile + one V block.
-template <int D, int NW, int NSTAGE>
+// KV8: the store holds 8-bit slots (E4M3 codes, one power-of-two scale per kv head and 64-token block; layouts in
+// kvstore.hip).  Such a tile takes half a stage; a lane's 16-byte LDS read then carries the operands of two
+// consecutive k-steps, which are turned into bf16 (exactly) on the way to the MFMA.  For that the head dim is
+// walked in the order  32 j + 16 g2 + 8 jj  (k-step 2 j + jj, lane half g2) by K, Q and the fresh bf16 K alike.
+// The fresh tiles stay bf16.  KV8 kernels run with two stages.
+template <int D, int NW, int NSTAGE, bool KV8 = false>
 __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
     const __bf16 *__restrict__ Q, const __bf16 *__restrict__ Kf, const __bf16 *__restrict__ Vf_blk,
-    const __bf16 *__restrict__ k_store, const __bf16 *__restrict__ v_store, const int32_t *__restrict__ table,
+    const void *__restrict__ k_store_any, const void *__restrict__ v_store_any, const float *__restrict__ k_scale,
+    const float *__restrict__ v_scale, const int32_t *__restrict__ table,
     int tbl_stride, int T, int Hq, int Hkv, int C, int n_splits, int q_tiles, int n_groups, float scale_log2e,
     __bf16 *__restrict__ out, __bf16 *__restrict__ part_o, float *__restrict__ part_ml) {
+  static_assert(!KV8 || NSTAGE == 2, "8-bit slots: two stages (the waits assume one tile in flight)");
+  const __bf16 *k_store = (const __bf16 *)k_store_any, *v_store = (const __bf16 *)v_store_any;
+  const uint8_t *k8_store = (const uint8_t *)k_store_any, *v8_store = (const uint8_t *)v_store_any;
   using L = Lds<D>;
   constexpr int KS = D / 16;  // k-steps of the QK^T contraction
   constexpr int DB = D / 32;  // 32-wide blocks of the head dim (rows of O^T)
@@ -115,12 +135,12 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
   const int hg = row_c / T, my_i = row_c - hg * T;
   const int head = gkv * G + hg;
 
-  // Q fragments (B operand): lane holds q[row][16 ks + 8 g2 .. +7]
+  // Q fragments (B operand): lane holds q[row][16 ks + 8 g2 .. +7]  (8-bit slots: [32 (ks/2) + 16 g2 + 8 (ks%2) .. +7])
   bf16x8 qf[KS];
   {
-    const __bf16 *qrow = Q + (((size_t)b * Hq + head) * T + my_i) * D + g2 * 8;
+    const __bf16 *qrow = Q + (((size_t)b * Hq + head) * T + my_i) * D;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) qf[ks] = *(const bf16x8 *)(qrow + ks * 16);
+    for (int ks = 0; ks < KS; ++ks) qf[ks] = *(const bf16x8 *)(qrow + (KV8 ? 32 * (ks >> 1) + 16 * g2 + 8 * (ks & 1) : ks * 16 + g2 * 8));
   }
 
   f32x16 o_acc[DB];
@@ -199,19 +219,55 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
   // swizzled byte offsets of this lane's MFMA operand reads inside its row
   int k_rd[KS], v_rd[4];
 #pragma unroll
-  for (int ks = 0; ks < KS; ++ks) k_rd[ks] = ((2 * ks + g2) ^ swz<L::K_ROW>(l32)) * 16;
+  for (int ks = 0; ks < KS; ++ks)
+    k_rd[ks] = ((KV8 ? 4 * (ks >> 1) + 2 * g2 + (ks & 1) : 2 * ks + g2) ^ swz<L::K_ROW>(l32)) * 16;
 #pragma unroll
   for (int c4 = 0; c4 < 4; ++c4) v_rd[c4] = ((2 * c4 + g2) ^ swz<L::V_ROW>(l32)) * 16;
-  struct TileDesc { const __bf16 *k, *v; int valid; int t0; bool fresh; };
+  // 8-bit tiles: K rows of D bytes, V^T rows of TK bytes; 16-byte chunk index XOR-swizzled by the row as above
+  // (rows of 128 bytes: (row >> 1) & 7; rows of 64 bytes: (row >> 2) & 3)
+  constexpr int K8_ROW = D, V8_ROW = TK;
+  constexpr int K8_TOTAL = TK * K8_ROW / 1024, V8_TOTAL = D * V8_ROW / 1024;  // load instructions per tile (all wavefronts)
+  constexpr int K8_INSTR = KV8 ? (K8_TOTAL + NW - 1) / NW : 1, V8_INSTR = KV8 ? (V8_TOTAL + NW - 1) / NW : 1;
+  auto swz8 = [](int row_bytes, int row) { return row_bytes == 128 ? ((row >> 1) & 7) : ((row >> 2) & 3); };
+  int k8_row[K8_INSTR], k8_col[K8_INSTR], v8_goff[V8_INSTR], k8_rd[KS / 2], v8_rd[2];
+  if (KV8) {
+#pragma unroll
+    for (int k = 0; k < K8_INSTR; ++k) {
+      const int byte = (wave + k * NW) * 1024 + lane * 16;
+      const int row = byte / K8_ROW, pc = (byte % K8_ROW) / 16;
+      k8_row[k] = row;
+      k8_col[k] = (pc ^ swz8(K8_ROW, row)) * 16;
+    }
+#pragma unroll
+    for (int k = 0; k < V8_INSTR; ++k) {
+      const int byte = (wave + k * NW) * 1024 + lane * 16;
+      const int d = byte / V8_ROW, pc = (byte % V8_ROW) / 16;
+      v8_goff[k] = d * V8_ROW + (pc ^ swz8(V8_ROW, d)) * 16;
+    }
+#pragma unroll
+    for (int j = 0; j < KS / 2; ++j) k8_rd[j] = ((2 * j + g2) ^ swz8(K8_ROW, l32)) * 16;
+#pragma unroll
+    for (int J = 0; J < 2; ++J) v8_rd[J] = ((2 * J + g2) ^ swz8(V8_ROW, l32)) * 16;
+  }
+  struct TileDesc { const __bf16 *k, *v; int valid; int t0; bool fresh; float ks, vs; };
   auto describe = [&](const Cursor &c, TileDesc &td) __attribute__((always_inline)) {
     if (c.chunk < n_chunks) {
       size_t base = (((size_t)c.slot * Hkv + gkv) * C + (size_t)c.off * TK) * D;  // same offset in both layouts
-      td.k = k_store + base;
-      td.v = v_store + base;
+      if (KV8) {
+        td.k = (const __bf16 *)(k8_store + base);
+        td.v = (const __bf16 *)(v8_store + base);
+        const size_t sc = ((size_t)c.slot * Hkv + gkv) * (C / TK) + c.off;
+        td.ks = k_scale[sc];
+        td.vs = v_scale[sc];
+      } else {
+        td.k = k_store + base;
+        td.v = v_store + base;
+      }
       td.valid = min(TK, c.used - c.off * TK);
       td.t0 = 0;
       td.fresh = false;
     } else {
+      td.ks = td.vs = 1.f;
       const int ft = (T + TK - 1) / TK;
       td.k = Kf + (((size_t)b * Hkv + gkv) * T + (size_t)c.off * TK) * D;
       td.v = Vf_blk + (((size_t)b * Hkv + gkv) * ft + c.off) * (size_t)(TK * D);
@@ -230,6 +286,22 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
   };
   auto fetch_tile = [&](const TileDesc &td, int st) __attribute__((always_inline)) {
     char *kb = lds + st * L::STAGE;
+    if (KV8 && !td.fresh) {
+      const uint8_t *k8 = (const uint8_t *)td.k, *v8 = (const uint8_t *)td.v;
+#pragma unroll
+      for (int k = 0; k < K8_INSTR; ++k)
+        if ((wave + k * NW) < K8_TOTAL) {
+          const int row = min(k8_row[k], td.valid - 1);
+          __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(k8 + (size_t)row * K8_ROW + k8_col[k]),
+                                           (__attribute__((address_space(3))) void *)(kb + (wave + k * NW) * 1024), 16, 0, kKvAux);
+        }
+#pragma unroll
+      for (int k = 0; k < V8_INSTR; ++k)
+        if ((wave + k * NW) < V8_TOTAL)
+          __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(v8 + v8_goff[k]),
+                                           (__attribute__((address_space(3))) void *)(kb + L::K_BYTES + (wave + k * NW) * 1024), 16, 0, kKvAux);
+      return;
+    }
 #pragma unroll
     for (int k = 0; k < K_INSTR; ++k) {
       const int row = min(k_row[k], td.valid - 1);  // rows past a ragged end repeat the last valid row (masked later)
@@ -294,6 +366,26 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
     for (int kbk = 0; kbk < 2; ++kbk)
 #pragma unroll
       for (int r = 0; r < 16; ++r) s_acc[kbk][r] = 0.f;
+    if (KV8 && !td.fresh) {
+      // 8-bit tile: one 16-byte read per key block and pair of k-steps, turned into two bf16 operands
+#pragma unroll
+      for (int h = 0; h < KS / 4; ++h) {
+        pc::u32x4 raw[2][2];
+#pragma unroll
+        for (int j2 = 0; j2 < 2; ++j2)
+#pragma unroll
+          for (int kbk = 0; kbk < 2; ++kbk) raw[kbk][j2] = *(const pc::u32x4 *)(kb + (kbk * 32 + l32) * K8_ROW + k8_rd[2 * h + j2]);
+#pragma unroll
+        for (int j2 = 0; j2 < 2; ++j2)
+#pragma unroll
+          for (int kbk = 0; kbk < 2; ++kbk) {
+            const bf16x8 a0 = codes_to_bf16(raw[kbk][j2][0], raw[kbk][j2][1], td.ks);
+            const bf16x8 a1 = codes_to_bf16(raw[kbk][j2][2], raw[kbk][j2][3], td.ks);
+            s_acc[kbk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qf[4 * h + 2 * j2], s_acc[kbk], 0, 0, 0);
+            s_acc[kbk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qf[4 * h + 2 * j2 + 1], s_acc[kbk], 0, 0, 0);
+          }
+      }
+    } else {
 #pragma unroll
     for (int h = 0; h < KS / 4; ++h) {
       bf16x8 kop[2][4];
@@ -308,6 +400,7 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
           s_acc[kbk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop[kbk][k4], qf[4 * h + k4], s_acc[kbk], 0, 0, 0);
       __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
       __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+    }
     }
 
     // ---- mask: only tiles with a ragged end or in the causal part take this path (wave-uniform test)
@@ -372,6 +465,21 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
     l_run += psum;
 
     // ---- O^T += V^T P^T, operands requested in batches of eight in the same way
+    if (KV8 && !td.fresh) {
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        pc::u32x4 raw[DB];
+#pragma unroll
+        for (int db = 0; db < DB; ++db) raw[db] = *(const pc::u32x4 *)(vb + (db * 32 + l32) * V8_ROW + v8_rd[h]);
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+          const bf16x8 a0 = codes_to_bf16(raw[db][0], raw[db][1], td.vs);
+          const bf16x8 a1 = codes_to_bf16(raw[db][2], raw[db][3], td.vs);
+          o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, pf[h][0], o_acc[db], 0, 0, 0);
+          o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, pf[h][1], o_acc[db], 0, 0, 0);
+        }
+      }
+    } else {
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       bf16x8 vop[DB][2];
@@ -386,6 +494,7 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
           o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop[db][c2], pf[h][c2], o_acc[db], 0, 0, 0);
       __builtin_amdgcn_sched_group_barrier(0x100, 2 * DB, 1);
       __builtin_amdgcn_sched_group_barrier(0x008, 2 * DB, 1);
+    }
     }
 
     // (when nothing was fetched in this iteration fewer tiles are in flight: wait for all of them)
@@ -544,23 +653,40 @@ pc_status launch_attention(percache_ctx *ctx, int layer, const __bf16 *q, const 
   // 8 wavefronts x 32 rows (one workgroup per CU, 3 LDS stages) once a kv head has more than 128 stacked rows,
   // else 4 wavefronts (two workgroups per CU, 2 stages)
   // 256-row workgroups only when there are enough of them to go round; few, short key ranges prefer more, smaller ones
-  const bool wide = R > 128 && (long)batch * c.n_kv_heads * ((R + 255) / 256) * 4 >= ctx->n_cu;
+  // (8-bit slots with D = 64: a tile is too small for eight wavefronts to load)
+  const bool wide = R > 128 && (long)batch * c.n_kv_heads * ((R + 255) / 256) * 4 >= ctx->n_cu && !(c.kv_fp8 && c.head_dim == 64);
   const int qrows = wide ? 256 : 128;
   const int q_tiles = (R + qrows - 1) / qrows;
   const int cap = max_splits_for(c, ctx->n_cu, batch, t_fresh);
   if (n_splits <= 0) n_splits = choose_splits(wide ? ctx->n_cu : 2 * ctx->n_cu, (long)batch * c.n_kv_heads * q_tiles, min_tiles, cap);
   if (n_splits > cap) n_splits = cap;
-  const __bf16 *ks = ctx->k_store + (size_t)layer * ctx->layer_stride;
-  const __bf16 *vs = ctx->v_store + (size_t)layer * ctx->layer_stride;
+  const void *ks, *vs;
+  const float *ksc = nullptr, *vsc = nullptr;
+  if (c.kv_fp8) {
+    ks = ctx->k8_store + (size_t)layer * ctx->layer_stride;
+    vs = ctx->v8_store + (size_t)layer * ctx->layer_stride;
+    const size_t sc_layer = (size_t)c.n_slots * c.n_kv_heads * (c.slot_capacity / TK);
+    ksc = ctx->k_scale + (size_t)layer * sc_layer;
+    vsc = ctx->v_scale + (size_t)layer * sc_layer;
+  } else {
+    ks = ctx->k_store + (size_t)layer * ctx->layer_stride;
+    vs = ctx->v_store + (size_t)layer * ctx->layer_stride;
+  }
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)c.head_dim);
   const int n_groups = batch * c.n_kv_heads * n_splits;
   dim3 grid((unsigned)(((n_groups + 7) / 8) * 8 * q_tiles));
   prof_begin(ctx, PC_KERNEL_ATTENTION, stream);
-#define PC_ATTN(DD, NWW, NS)                                                                                          \
-  hipLaunchKernelGGL((reuse_attention_kernel<DD, NWW, NS>), grid, dim3(64 * NWW), 0, stream, q, kf, vf_blk, ks, vs,     \
-                     table_dev, tbl_stride, t_fresh, c.n_q_heads, c.n_kv_heads, c.slot_capacity, n_splits, q_tiles,  \
-                     n_groups, scale_log2e, out, part_o, part_ml)
-  if (c.head_dim == 128) {
+#define PC_ATTN(DD, NWW, NS, ...)                                                                                     \
+  hipLaunchKernelGGL((reuse_attention_kernel<DD, NWW, NS, ##__VA_ARGS__>), grid, dim3(64 * NWW), 0, stream, q, kf,     \
+                     vf_blk, ks, vs, ksc, vsc, table_dev, tbl_stride, t_fresh, c.n_q_heads, c.n_kv_heads,            \
+                     c.slot_capacity, n_splits, q_tiles, n_groups, scale_log2e, out, part_o, part_ml)
+  if (c.kv_fp8) {
+    if (c.head_dim == 128) {
+      if (wide) PC_ATTN(128, 8, 2, true); else PC_ATTN(128, 4, 2, true);
+    } else {
+      PC_ATTN(64, 4, 2, true);
+    }
+  } else if (c.head_dim == 128) {
     if (wide) PC_ATTN(128, 8, 2); else PC_ATTN(128, 4, 2);
   } else {
     if (wide) PC_ATTN(64, 8, 4); else PC_ATTN(64, 4, 4);

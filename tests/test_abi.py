@@ -57,3 +57,15 @@ def test_create_rejects_bad_arguments_without_touching_a_device(lib):
     assert lib.percache_bank_size(None) == -1
     assert lib.percache_kv_len(None, 0, 0) == -1
     lib.percache_destroy(None)
+
+
+def test_arena_of_8_bit_slots_is_half_the_store_plus_scales(lib):
+    from paper_2601_11553_amd.binding import Config
+    c = Config(2, 1024, 16, 8, 128, 16, 512, 4096, 10000.0, 0, 0, 0)
+    c8 = Config(2, 1024, 16, 8, 128, 16, 512, 4096, 10000.0, 0, 0, 1)
+    a, a8 = lib.percache_arena_bytes(ctypes.byref(c)), lib.percache_arena_bytes(ctypes.byref(c8))
+    store = 2 * 16 * 8 * 512 * 128          # elements of one store (K or V)
+    scales = 2 * 16 * 8 * (512 // 64) * 4   # bytes
+    assert a - a8 == 2 * store - 2 * scales
+    bad = Config(2, 1024, 16, 8, 128, 16, 512, 4096, 10000.0, 0, 0, 2)
+    assert lib.percache_arena_bytes(ctypes.byref(bad)) == 0
