@@ -84,6 +84,7 @@ def bench_cfg1(torch, wl, binding, Percache, dev, bf):
         for _ in range(20):
             if kind == "cold":
                 flush.fill_(1)
+            torch.cuda._sleep(400_000)   # keeps the GPU busy while the host queues the call: the events then bracket GPU time
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
             fn()
@@ -98,6 +99,32 @@ def bench_cfg1(torch, wl, binding, Percache, dev, bf):
             "gpu_ms_per_call_caches_flushed": round(float(np.median(ev["cold"])), 4), "fresh_tokens_per_s": round(w.t_fresh / (ms * 1e-3), 1),
             "attention_ms": round(ms_attn / n_attn, 4), "kv_stream_GBps": round(kv_bytes / (ms_attn / n_attn * 1e-3) / 1e9, 1),
             "qkv_rope_ms": round(ms_qkv / n_qkv, 4), "weight_stream_GBps": round(w_bytes / (ms_qkv / n_qkv * 1e-3) / 1e9, 1)}
+
+
+def bench_fp8_slots(torch, wl, binding, Percache, dev, bf, w, X, W):
+    """The config 4 layer over 8-bit slots (half the store): attention of the 256-token prefill and of one decoding
+    token per query over the same 16 chunks."""
+    B, T = w.batch, w.t_fresh
+    pc = Percache(n_layers=1, hidden=w.hidden, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
+                  n_slots=w.n_slots, slot_capacity=w.chunk_tokens, max_pos=w.max_pos + 64, rope_theta=w.rope_theta,
+                  kv_fp8=True, device=dev)
+    for s_, (k, v) in w.slots_kv(sorted(set(int(s) for s in w.slot_ids.reshape(-1)))).items():
+        pc.percache_kv_put(0, s_, bf(k), bf(v))
+    attn = torch.empty((B, T, w.n_q_heads * w.head_dim), dtype=torch.bfloat16, device=dev)
+    attn1 = torch.empty((B, 1, w.n_q_heads * w.head_dim), dtype=torch.bfloat16, device=dev)
+    x1 = X[:, :1].contiguous()
+    res = {"store_bytes_per_token_and_layer": w.n_kv_heads * w.head_dim * 2 + w.n_kv_heads * 8 // 64,
+           "bf16_store_bytes_per_token_and_layer": w.n_kv_heads * w.head_dim * 4}
+    for name, fn, iters in (("prefill_attention_ms", lambda: pc.percache_prefill_reuse(0, X, W, w.slot_ids, w.used_len, attn_out=attn), 20),
+                            ("decode_attention_ms", lambda: pc.percache_prefill_reuse(0, x1, W, w.slot_ids, w.used_len, attn_out=attn1), 50)):
+        _wall_ms(torch, fn, 5, 3)
+        pc.percache_profile_enable(True)
+        _wall_ms(torch, fn, iters, 0)
+        ms, n = pc.percache_profile_read(binding.KERNEL_ATTENTION)
+        pc.percache_profile_enable(False)
+        res[name] = round(ms / max(n, 1), 4)
+    pc.close()
+    return res
 
 
 def bench_cfg2(torch, wl, Percache, dev, bf):
@@ -281,6 +308,8 @@ def main():
     if not args.no_extra:
         pc.close()
         del pc
+        torch.cuda.empty_cache()
+        out["breakdown"]["cfg4_layer_8bit_slots"] = bench_fp8_slots(torch, wl, binding, Percache, dev, bf, w, X, W)
         torch.cuda.empty_cache()
         out["breakdown"]["cfg1_layer"] = bench_cfg1(torch, wl, binding, Percache, dev, bf)
         out["breakdown"]["cfg2_stack"] = bench_cfg2(torch, wl, Percache, dev, bf)

@@ -131,6 +131,7 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
   // this lane's query row (as column of S^T / O^T)
   const int my_row = row_first + wave * 32 + l32;
   const bool row_ok = my_row < R;
+  const bool wave_live = row_first + wave * 32 < R;  // wave-uniform: does this wavefront own any row?
   const int row_c = row_ok ? my_row : R - 1;
   const int hg = row_c / T, my_i = row_c - hg * T;
   const int head = gkv * G + hg;
@@ -359,6 +360,7 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
     const char *kb = lds + buf * L::STAGE;
     const char *vb = kb + L::K_BYTES;
 
+    if (wave_live) {  // (a wavefront without rows only helps to load the tiles)
     // ---- S^T = K Q^T : two 32-key blocks.  The K operands are requested from LDS in batches of eight ahead of
     // their MFMAs (the two accumulation chains alternating): one LDS latency per batch instead of one per MFMA.
     f32x16 s_acc[2];
@@ -496,6 +498,8 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
       __builtin_amdgcn_sched_group_barrier(0x008, 2 * DB, 1);
     }
     }
+
+    }  // wave_live
 
     // (when nothing was fetched in this iteration fewer tiles are in flight: wait for all of them)
     if (AHEAD == 1 || !has_next) PC_WAIT_VMCNT(0); else PC_WAIT_VMCNT((AHEAD - 1) * (K_INSTR + V_INSTR));
