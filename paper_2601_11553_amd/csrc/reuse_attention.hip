@@ -77,7 +77,10 @@ __device__ __forceinline__ bf16x8 codes_to_bf16(unsigned w0, unsigned w1, float 
 // consecutive k-steps, which are turned into bf16 (exactly) on the way to the MFMA.  For that the head dim is
 // walked in the order  32 j + 16 g2 + 8 jj  (k-step 2 j + jj, lane half g2) by K, Q and the fresh bf16 K alike.
 // The fresh tiles stay bf16.  KV8 kernels run with two stages.
-template <int D, int NW, int NSTAGE, bool KV8 = false>
+// KSP = 2: two wavefronts share a 32-row block and take one 32-key block of every tile each (separate running
+// maximum / sum / output, merged through LDS at the end); for the cases with few rows per kv head, where the per-tile
+// chain of one wavefront, not the key stream, would set the pace.
+template <int D, int NW, int NSTAGE, bool KV8 = false, int KSP = 1>
 __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
     const __bf16 *__restrict__ Q, const __bf16 *__restrict__ Kf, const __bf16 *__restrict__ Vf_blk,
     const void *__restrict__ k_store_any, const void *__restrict__ v_store_any, const float *__restrict__ k_scale,
@@ -91,7 +94,9 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
   constexpr int KS = D / 16;  // k-steps of the QK^T contraction
   constexpr int DB = D / 32;  // 32-wide blocks of the head dim (rows of O^T)
   constexpr int NT = 64 * NW;      // threads
-  constexpr int QROWS = 32 * NW;   // query rows per workgroup
+  constexpr int QROWS = 32 * NW / KSP;   // query rows per workgroup
+  constexpr int NKB = 2 / KSP;           // 32-key blocks of a tile per wavefront
+  static_assert(KSP == 1 || (KSP == 2 && NW % 2 == 0), "key split over one or two wavefronts");
   constexpr int AHEAD = NSTAGE - 1;  // tiles in flight ahead of the one being computed
   __shared__ __align__(16) char lds[NSTAGE * L::STAGE];
 
@@ -129,9 +134,10 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
   const int tile_end = (int)((long)(split + 1) * n_tiles / n_splits);
 
   // this lane's query row (as column of S^T / O^T)
-  const int my_row = row_first + wave * 32 + l32;
+  const int kb0 = KSP == 2 ? (wave & 1) : 0;  // this wavefront's first key block inside a tile
+  const int my_row = row_first + (wave / KSP) * 32 + l32;
   const bool row_ok = my_row < R;
-  const bool wave_live = row_first + wave * 32 < R;  // wave-uniform: does this wavefront own any row?
+  const bool wave_live = row_first + (wave / KSP) * 32 < R;  // wave-uniform: does this wavefront own any row?
   const int row_c = row_ok ? my_row : R - 1;
   const int hg = row_c / T, my_i = row_c - hg * T;
   const int head = gkv * G + hg;
@@ -223,7 +229,7 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
   for (int ks = 0; ks < KS; ++ks)
     k_rd[ks] = ((KV8 ? 4 * (ks >> 1) + 2 * g2 + (ks & 1) : 2 * ks + g2) ^ swz<L::K_ROW>(l32)) * 16;
 #pragma unroll
-  for (int c4 = 0; c4 < 4; ++c4) v_rd[c4] = ((2 * c4 + g2) ^ swz<L::V_ROW>(l32)) * 16;
+  for (int c4 = 0; c4 < 2 * NKB; ++c4) v_rd[c4] = ((2 * (2 * kb0 + c4) + g2) ^ swz<L::V_ROW>(l32)) * 16;
   // 8-bit tiles: K rows of D bytes, V^T rows of TK bytes; 16-byte chunk index XOR-swizzled by the row as above
   // (rows of 128 bytes: (row >> 1) & 7; rows of 64 bytes: (row >> 2) & 3)
   constexpr int K8_ROW = D, V8_ROW = TK;
@@ -248,7 +254,7 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
 #pragma unroll
     for (int j = 0; j < KS / 2; ++j) k8_rd[j] = ((2 * j + g2) ^ swz8(K8_ROW, l32)) * 16;
 #pragma unroll
-    for (int J = 0; J < 2; ++J) v8_rd[J] = ((2 * J + g2) ^ swz8(V8_ROW, l32)) * 16;
+    for (int J = 0; J < NKB; ++J) v8_rd[J] = ((2 * (kb0 + J) + g2) ^ swz8(V8_ROW, l32)) * 16;
   }
   struct TileDesc { const __bf16 *k, *v; int valid; int t0; bool fresh; float ks, vs; };
   auto describe = [&](const Cursor &c, TileDesc &td) __attribute__((always_inline)) {
@@ -363,24 +369,25 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
     if (wave_live) {  // (a wavefront without rows only helps to load the tiles)
     // ---- S^T = K Q^T : two 32-key blocks.  The K operands are requested from LDS in batches of eight ahead of
     // their MFMAs (the two accumulation chains alternating): one LDS latency per batch instead of one per MFMA.
-    f32x16 s_acc[2];
+    f32x16 s_acc[NKB];
 #pragma unroll
-    for (int kbk = 0; kbk < 2; ++kbk)
+    for (int kbk = 0; kbk < NKB; ++kbk)
 #pragma unroll
       for (int r = 0; r < 16; ++r) s_acc[kbk][r] = 0.f;
+    const char *kbw = kb + kb0 * 32 * (KV8 && !td.fresh ? K8_ROW : L::K_ROW);  // this wavefront's key rows
     if (KV8 && !td.fresh) {
       // 8-bit tile: one 16-byte read per key block and pair of k-steps, turned into two bf16 operands
 #pragma unroll
       for (int h = 0; h < KS / 4; ++h) {
-        pc::u32x4 raw[2][2];
+        pc::u32x4 raw[NKB][2];
 #pragma unroll
         for (int j2 = 0; j2 < 2; ++j2)
 #pragma unroll
-          for (int kbk = 0; kbk < 2; ++kbk) raw[kbk][j2] = *(const pc::u32x4 *)(kb + (kbk * 32 + l32) * K8_ROW + k8_rd[2 * h + j2]);
+          for (int kbk = 0; kbk < NKB; ++kbk) raw[kbk][j2] = *(const pc::u32x4 *)(kbw + (kbk * 32 + l32) * K8_ROW + k8_rd[2 * h + j2]);
 #pragma unroll
         for (int j2 = 0; j2 < 2; ++j2)
 #pragma unroll
-          for (int kbk = 0; kbk < 2; ++kbk) {
+          for (int kbk = 0; kbk < NKB; ++kbk) {
             const bf16x8 a0 = codes_to_bf16(raw[kbk][j2][0], raw[kbk][j2][1], td.ks);
             const bf16x8 a1 = codes_to_bf16(raw[kbk][j2][2], raw[kbk][j2][3], td.ks);
             s_acc[kbk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qf[4 * h + 2 * j2], s_acc[kbk], 0, 0, 0);
@@ -390,28 +397,28 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
     } else {
 #pragma unroll
     for (int h = 0; h < KS / 4; ++h) {
-      bf16x8 kop[2][4];
+      bf16x8 kop[NKB][4];
 #pragma unroll
       for (int k4 = 0; k4 < 4; ++k4)
 #pragma unroll
-        for (int kbk = 0; kbk < 2; ++kbk) kop[kbk][k4] = *(const bf16x8 *)(kb + (kbk * 32 + l32) * L::K_ROW + k_rd[4 * h + k4]);
+        for (int kbk = 0; kbk < NKB; ++kbk) kop[kbk][k4] = *(const bf16x8 *)(kbw + (kbk * 32 + l32) * L::K_ROW + k_rd[4 * h + k4]);
 #pragma unroll
       for (int k4 = 0; k4 < 4; ++k4)
 #pragma unroll
-        for (int kbk = 0; kbk < 2; ++kbk)
+        for (int kbk = 0; kbk < NKB; ++kbk)
           s_acc[kbk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop[kbk][k4], qf[4 * h + k4], s_acc[kbk], 0, 0, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
-      __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 4 * NKB, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 4 * NKB, 0);
     }
     }
 
     // ---- mask: only tiles with a ragged end or in the causal part take this path (wave-uniform test)
     if (td.valid < TK || td.fresh) {
 #pragma unroll
-      for (int kbk = 0; kbk < 2; ++kbk)
+      for (int kbk = 0; kbk < NKB; ++kbk)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          int t = kbk * 32 + (r >> 2) * 8 + g2 * 4 + (r & 3);
+          int t = (kb0 + kbk) * 32 + (r >> 2) * 8 + g2 * 4 + (r & 3);
           bool vis = t < td.valid && (!td.fresh || td.t0 + t <= my_i);
           s_acc[kbk][r] = vis ? s_acc[kbk][r] : -INFINITY;
         }
@@ -421,13 +428,13 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
     // probabilities are taken against the current reference and only their sum is looked at -- a probability above
     // 2^kLazy shows up there, so no row maximum is needed.  The row sum is taken over the bf16-rounded
     // probabilities (the very values the PV product uses), two per instruction.
-    bf16x8 pf[2][2];
+    bf16x8 pf[NKB][2];
     auto exponentials = [&](float neg_m) __attribute__((always_inline)) {
       typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
       const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
       float sum = 0.f;
 #pragma unroll
-      for (int kbk = 0; kbk < 2; ++kbk)
+      for (int kbk = 0; kbk < NKB; ++kbk)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -450,7 +457,7 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
     if (refresh) {  // rare: row maxima, exchange between the two lanes of a row, rescale, probabilities again
       float mx = s_acc[0][0];
 #pragma unroll
-      for (int kbk = 0; kbk < 2; ++kbk)
+      for (int kbk = 0; kbk < NKB; ++kbk)
 #pragma unroll
         for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s_acc[kbk][r]);
       const float mc = pair_max(mx) * scale_log2e;
@@ -469,7 +476,7 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
     // ---- O^T += V^T P^T, operands requested in batches of eight in the same way
     if (KV8 && !td.fresh) {
 #pragma unroll
-      for (int h = 0; h < 2; ++h) {
+      for (int h = 0; h < NKB; ++h) {
         pc::u32x4 raw[DB];
 #pragma unroll
         for (int db = 0; db < DB; ++db) raw[db] = *(const pc::u32x4 *)(vb + (db * 32 + l32) * V8_ROW + v8_rd[h]);
@@ -483,7 +490,7 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
       }
     } else {
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
+    for (int h = 0; h < NKB; ++h) {
       bf16x8 vop[DB][2];
 #pragma unroll
       for (int c2 = 0; c2 < 2; ++c2)
@@ -507,6 +514,30 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
     stage = stage + 1 == NSTAGE ? 0 : stage + 1;
+  }
+
+  if (KSP == 2) {
+    // the wavefront of the odd key blocks hands its state over lane to lane (the loop's last barrier has retired the tiles)
+    float *mine = (float *)lds + (size_t)(wave >> 1) * (DB * 16 + 2) * 64 + lane;
+    if (kb0 == 1) {
+      mine[0] = m_ref;
+      mine[64] = l_run;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mine[(2 + db * 16 + r) * 64] = o_acc[db][r];
+    }
+    __syncthreads();
+    if (kb0 == 1) return;
+    const float m1 = mine[0], l1 = mine[64];
+    const float m = fmaxf(m_ref, m1);
+    const float a0 = m_ref == -INFINITY ? 0.f : fast_exp2(m_ref - m), a1 = m1 == -INFINITY ? 0.f : fast_exp2(m1 - m);
+    l_run = l_run * a0 + l1 * a1;
+    m_ref = m;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o_acc[db][r] = o_acc[db][r] * a0 + mine[(2 + db * 16 + r) * 64] * a1;
   }
 
   // ---- finish: combine the two lanes of a row, normalise, write
@@ -659,7 +690,11 @@ pc_status launch_attention(percache_ctx *ctx, int layer, const __bf16 *q, const 
   // 256-row workgroups only when there are enough of them to go round; few, short key ranges prefer more, smaller ones
   // (8-bit slots with D = 64: a tile is too small for eight wavefronts to load)
   const bool wide = R > 128 && (long)batch * c.n_kv_heads * ((R + 255) / 256) * 4 >= ctx->n_cu && !(c.kv_fp8 && c.head_dim == 64);
-  const int qrows = wide ? 256 : 128;
+  // at most 32 rows per kv head (decoding steps) over 8-bit slots: two wavefronts share the rows and halve every
+  // tile between them.  (Over bf16 slots such a step is bound by the key stream already, and the 4-wavefront kernel
+  // with its three loader wavefronts measures 3 % faster.)
+  const bool few = R <= 32 && c.kv_fp8;
+  const int qrows = few ? 32 : wide ? 256 : 128;
   const int q_tiles = (R + qrows - 1) / qrows;
   const int cap = max_splits_for(c, ctx->n_cu, batch, t_fresh);
   if (n_splits <= 0) n_splits = choose_splits(wide ? ctx->n_cu : 2 * ctx->n_cu, (long)batch * c.n_kv_heads * q_tiles, min_tiles, cap);
@@ -686,9 +721,9 @@ pc_status launch_attention(percache_ctx *ctx, int layer, const __bf16 *q, const 
                      c.slot_capacity, n_splits, q_tiles, n_groups, scale_log2e, out, part_o, part_ml)
   if (c.kv_fp8) {
     if (c.head_dim == 128) {
-      if (wide) PC_ATTN(128, 8, 2, true); else PC_ATTN(128, 4, 2, true);
+      if (few) PC_ATTN(128, 2, 2, true, 2); else if (wide) PC_ATTN(128, 8, 2, true); else PC_ATTN(128, 4, 2, true);
     } else {
-      PC_ATTN(64, 4, 2, true);
+      if (few) PC_ATTN(64, 2, 2, true, 2); else PC_ATTN(64, 4, 2, true);
     }
   } else if (c.head_dim == 128) {
     if (wide) PC_ATTN(128, 8, 2); else PC_ATTN(128, 4, 2);
