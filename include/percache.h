@@ -125,7 +125,8 @@ pc_status percache_bank_refresh_scan(percache_ctx *ctx, const void *new_emb_dev,
  * [-110, 127]; code = E4M3(x * 2^-e), round to nearest, ties to even; the value read back is code * 2^e, exactly
  * representable in bf16.  percache_kv_put / _put_batch / _slice and the save slots of percache_stack_reuse quantise;
  * percache_kv_get returns the values read back; the attention calls read them on the fly (fresh K/V stay bf16).
- * percache_kv_append and percache_stack_decode return PC_ESHAPE on such a context. */
+ * percache_kv_append (and the decoding steps that use it): everything from the block that holds the first new token
+ * on is quantised afresh from the values the slot reads back plus the new tokens; full blocks before it stay. */
 
 /* ---------------------------------------------------------------- K/V store (Sec. 4.1.1)
  * One slot holds one knowledge chunk's K and V for one layer, as collected from the attention

@@ -13,6 +13,9 @@ checked bit for bit:
     kept inside [-110, 127] (so that every value read back is a normal bf16 number); the stored code of x is
     E4M3(x * 2^-e) and the value read back is code * 2^e.
 
+  * appending tokens to a slot that holds n: everything from the block that contains token n on is quantised afresh
+    from the values the slot currently reads back plus the new tokens (full blocks before it stay as they are).
+
 Everything is computed in float64 on values that are exactly representable, so no step rounds except the one the
 format defines.  parity unpinned by the paper (it prints no such format); pinned by tests/test_oracle_kv_fp8.py against
 the format's definition by brute force and against a library conversion routine.
@@ -98,3 +101,14 @@ def dequantize(codes, exps) -> np.ndarray:
 def round_trip(x) -> np.ndarray:
     """What a slot returns for x: quantize, then dequantize."""
     return dequantize(*quantize(x))
+
+
+def append(stored, new) -> np.ndarray:
+    """stored [heads, n, D]: what the slot reads back now; new [heads, m, D]: tokens of the storage dtype to append.
+    Returns what the slot reads back afterwards ([heads, n + m, D])."""
+    stored = np.asarray(stored, np.float32)
+    new = np.asarray(new, np.float32)
+    n = stored.shape[1]
+    first = (n // BLOCK) * BLOCK
+    tail = np.concatenate([stored[:, first:], new], axis=1)
+    return np.concatenate([stored[:, :first], round_trip(tail)], axis=1)

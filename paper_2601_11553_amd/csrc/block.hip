@@ -517,7 +517,6 @@ pc_status percache_stack_decode(percache_ctx *ctx, const percache_block_weights 
                                 size_t workspace_bytes, void *stream) {
   if (!ctx) return PC_EINVAL;
   if (!append_slots_host) return pc::fail(ctx, PC_EINVAL, "append_slots_host is NULL");
-  if (ctx->cfg.kv_fp8) return pc::fail(ctx, PC_ESHAPE, "decoding steps append to their slot: not supported with 8-bit slots");
   return run_stack(ctx, layers_host, n_layers, ffn, eps, h_in_dev, batch, n_new, slot_ids_host, used_len_host, n_chunks_host,
                    max_chunks, nullptr, nullptr, 0, append_slots_host, h_out_dev, workspace_dev, workspace_bytes, stream);
 }

@@ -143,27 +143,52 @@ __device__ __forceinline__ unsigned encode4(float a, float b, float c, float d) 
   return (unsigned)w;
 }
 
+// off > 0: the slot already holds `off` tokens and the dense tensors are the tokens that follow them (append).  The
+// block that was partly filled is then quantised afresh from the values its old tokens read back as plus the new
+// tokens (its exponent is recomputed over all of them; old codes are re-rounded only if the exponent moves); the
+// launch covers the blocks from off / 64 on, and n_tok counts old and new tokens together.
 template <int D>
 __global__ __launch_bounds__(256) void kv_quant_kernel(uint8_t *__restrict__ slot_k, uint8_t *__restrict__ slot_v,
                                                        float *__restrict__ scale_k, float *__restrict__ scale_v,
                                                        const __bf16 *__restrict__ dense_k, const __bf16 *__restrict__ dense_v,
                                                        int n_heads, int n_tok, int C, SlotList slots, long slot_stride_elems,
-                                                       long scale_slot_stride, long dense_head_stride) {
+                                                       long scale_slot_stride, long dense_head_stride, int off) {
   constexpr int DV = D / 8, NV = kKvTile * DV / 256;  // 8-element vectors per row; vectors per thread
   __shared__ float red[2][4];
   __shared__ __align__(16) uint8_t vt[kKvTile][D + 16];  // V codes [key][d] (padded rows), read back transposed
-  const int blk = blockIdx.x, g = blockIdx.y, tid = threadIdx.x;
+  const int blk = blockIdx.x + off / kKvTile, g = blockIdx.y, tid = threadIdx.x;
   const int slot = slots.slot[blockIdx.z];
   const size_t dense_at = ((size_t)blockIdx.z * n_heads + g) * dense_head_stride;
+  const size_t slot_at = (size_t)slot * slot_stride_elems + (size_t)g * C * D;
+  const size_t sc = (size_t)slot * scale_slot_stride + (size_t)g * (C / kKvTile) + blk;
+  const bool has_old = blk * kKvTile < off;  // (only the first block of an append)
+  const float old_sk = has_old ? scale_k[sc] : 1.f, old_sv = has_old ? scale_v[sc] : 1.f;
   pc::bf16x8 kv[NV], vv[NV];
   float ak = 0.f, av = 0.f;
 #pragma unroll
   for (int j = 0; j < NV; ++j) {
     const int v = tid + 256 * j, r = v / DV, dc = v - r * DV;
     const int t = blk * kKvTile + r;
-    if (t < n_tok) {
-      kv[j] = *(const pc::bf16x8 *)(dense_k + dense_at + (size_t)t * D + dc * 8);
-      vv[j] = *(const pc::bf16x8 *)(dense_v + dense_at + (size_t)t * D + dc * 8);
+    if (t < off) {
+      // what the stored codes read back as (exact in bf16)
+      typedef float f32x2 __attribute__((ext_vector_type(2)));
+      const uint2 ck = *(const uint2 *)(slot_k + slot_at + (size_t)t * D + dc * 8);
+      const uint8_t *vcol = slot_v + slot_at + (size_t)blk * kKvTile * D + pc::blocked_pos8(r);
+      unsigned wk[2] = {ck.x, ck.y}, wv[2] = {0, 0};
+#pragma unroll
+      for (int e = 0; e < 8; ++e) wv[e >> 2] |= (unsigned)vcol[(size_t)(dc * 8 + e) * kKvTile] << (8 * (e & 3));
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const f32x2 k0 = __builtin_amdgcn_cvt_pk_f32_fp8((int)wk[h], false), k1 = __builtin_amdgcn_cvt_pk_f32_fp8((int)wk[h], true);
+        const f32x2 v0 = __builtin_amdgcn_cvt_pk_f32_fp8((int)wv[h], false), v1 = __builtin_amdgcn_cvt_pk_f32_fp8((int)wv[h], true);
+        kv[j][4 * h + 0] = (__bf16)(k0[0] * old_sk); kv[j][4 * h + 1] = (__bf16)(k0[1] * old_sk);
+        kv[j][4 * h + 2] = (__bf16)(k1[0] * old_sk); kv[j][4 * h + 3] = (__bf16)(k1[1] * old_sk);
+        vv[j][4 * h + 0] = (__bf16)(v0[0] * old_sv); vv[j][4 * h + 1] = (__bf16)(v0[1] * old_sv);
+        vv[j][4 * h + 2] = (__bf16)(v1[0] * old_sv); vv[j][4 * h + 3] = (__bf16)(v1[1] * old_sv);
+      }
+    } else if (t < n_tok) {
+      kv[j] = *(const pc::bf16x8 *)(dense_k + dense_at + (size_t)(t - off) * D + dc * 8);
+      vv[j] = *(const pc::bf16x8 *)(dense_v + dense_at + (size_t)(t - off) * D + dc * 8);
     } else {
 #pragma unroll
       for (int e = 0; e < 8; ++e) { kv[j][e] = (__bf16)0.f; vv[j][e] = (__bf16)0.f; }
@@ -185,9 +210,7 @@ __global__ __launch_bounds__(256) void kv_quant_kernel(uint8_t *__restrict__ slo
   av = fmaxf(fmaxf(red[1][0], red[1][1]), fmaxf(red[1][2], red[1][3]));
   const int ek = block_exponent(ak), ev = block_exponent(av);
   const float ik = pow2f(-ek), iv = pow2f(-ev);
-  const size_t slot_at = (size_t)slot * slot_stride_elems + (size_t)g * C * D;
   if (tid == 0) {
-    const size_t sc = (size_t)slot * scale_slot_stride + (size_t)g * (C / kKvTile) + blk;
     scale_k[sc] = pow2f(ek);
     scale_v[sc] = pow2f(ev);
   }
@@ -221,7 +244,7 @@ __global__ __launch_bounds__(256) void kv_dequant_kernel(const uint8_t *__restri
                                                          const float *__restrict__ scale_k, const float *__restrict__ scale_v,
                                                          __bf16 *__restrict__ dense_k, __bf16 *__restrict__ dense_v, int n_heads,
                                                          int n_tok, int C, SlotList slots, long slot_stride_elems,
-                                                         long scale_slot_stride, long dense_head_stride) {
+                                                         long scale_slot_stride, long dense_head_stride, int /*unused*/) {
   constexpr int DV = D / 8, NV = kKvTile * DV / 256;
   const int blk = blockIdx.x, g = blockIdx.y, tid = threadIdx.x;
   const int slot = slots.slot[blockIdx.z];
@@ -282,7 +305,7 @@ pc_status launch_copy(percache_ctx *ctx, int layer, const int32_t *slot_list, in
 #define PC_KV8(KERNEL, DD)                                                                                                    \
   hipLaunchKernelGGL((KERNEL<DD>), grid, dim3(256), 0, stream, ctx->k8_store + off, ctx->v8_store + off, ctx->k_scale + sc_off, \
                      ctx->v_scale + sc_off, (__bf16 *)k_dev, (__bf16 *)v_dev, c.n_kv_heads, n_tokens, c.slot_capacity, sl,      \
-                     (long)ctx->slot_stride, sc_slot, dhs)
+                     (long)ctx->slot_stride, sc_slot, dhs, 0)
     if (kToStore) {
       if (c.head_dim == 128) PC_KV8(kv_quant_kernel, 128); else PC_KV8(kv_quant_kernel, 64);
     } else {
@@ -313,6 +336,24 @@ pc_status launch_kv_store(percache_ctx *ctx, int layer, int slot, const __bf16 *
 pc_status launch_kv_append(percache_ctx *ctx, int layer, int slot, const __bf16 *k, const __bf16 *v, int off, int n_tokens,
                            long new_head_stride, hipStream_t stream) {
   const percache_config &c = ctx->cfg;
+  if (c.kv_fp8) {
+    const long sc_slot = (long)c.n_kv_heads * (c.slot_capacity / kKvTile);
+    const size_t lo = (size_t)layer * ctx->layer_stride, sc_off = (size_t)layer * c.n_slots * sc_slot;
+    SlotList sl;
+    for (int i = 0; i < 64; ++i) sl.slot[i] = i == 0 ? slot : 0;
+    const int total = off + n_tokens;
+    dim3 grid((total + kKvTile - 1) / kKvTile - off / kKvTile, c.n_kv_heads, 1);
+    if (c.head_dim == 128)
+      hipLaunchKernelGGL((kv_quant_kernel<128>), grid, dim3(256), 0, stream, ctx->k8_store + lo, ctx->v8_store + lo,
+                         ctx->k_scale + sc_off, ctx->v_scale + sc_off, k, v, c.n_kv_heads, total, c.slot_capacity, sl,
+                         (long)ctx->slot_stride, sc_slot, new_head_stride, off);
+    else
+      hipLaunchKernelGGL((kv_quant_kernel<64>), grid, dim3(256), 0, stream, ctx->k8_store + lo, ctx->v8_store + lo,
+                         ctx->k_scale + sc_off, ctx->v_scale + sc_off, k, v, c.n_kv_heads, total, c.slot_capacity, sl,
+                         (long)ctx->slot_stride, sc_slot, new_head_stride, off);
+    PC_HIP(ctx, hipGetLastError());
+    return PC_OK;
+  }
   const size_t at = (size_t)layer * ctx->layer_stride + (size_t)slot * ctx->slot_stride;
   const long work = (long)c.n_kv_heads * c.head_dim * ((n_tokens + kKvTile - 1) / kKvTile + 1) * kKvTile;
   int blocks = (int)((work + 255) / 256);
@@ -332,7 +373,6 @@ pc_status percache_kv_append(percache_ctx *ctx, int32_t layer, int32_t slot, con
   if (st != PC_OK) return st;
   if (!k_dev || !v_dev) return pc::fail(ctx, PC_EINVAL, "k_dev / v_dev is NULL");
   const percache_config &c = ctx->cfg;
-  if (c.kv_fp8) return pc::fail(ctx, PC_ESHAPE, "appending to 8-bit slots is not supported");
   const int have = ctx->slot_len[(size_t)layer * c.n_slots + slot];
   if (n_tokens < 1 || have + n_tokens > c.slot_capacity)
     return pc::fail(ctx, PC_ELEN, "slot %d holds %d tokens: %d more do not fit the capacity %d", slot, have, n_tokens, c.slot_capacity);

@@ -84,9 +84,6 @@ def test_put_batch_slice_and_errors():
         kk, vv = pc.percache_kv_get(0, s)
         torch.cuda.synchronize()
         assert np.array_equal(host(kk), kv_fp8.round_trip(seq_k[:, lo:hi])) and np.array_equal(host(vv), kv_fp8.round_trip(seq_v[:, lo:hi]))
-    with pytest.raises(PercacheError) as e:
-        pc.percache_kv_append(0, 1, bf16(kb[0, :, :5]), bf16(vb[0, :, :5]))
-    assert e.value.status == -2
     pc.close()
 
 
@@ -171,7 +168,77 @@ def test_stack_population_then_reuse_on_8_bit_slots():
     check_hidden(host(reuse[0]), h_fresh, "reuse pass over 8-bit slots vs oracle")
     # and the quantisation itself stays small against the exact stack
     check_hidden(host(reuse[0]), h_full[n_c * C:], "reuse pass over 8-bit slots vs exact full recompute", rel_max=2.0 ** -4, rel_fro=3e-2)
+    pc.close()
+
+
+@pytest.mark.parametrize("D", [64, 128])
+def test_append_to_8_bit_slots_follows_the_oracles_rule(D):
+    """Appends that start and end inside blocks and on block borders; later tokens larger (the open block's scale
+    rises and its old codes are re-rounded) and smaller."""
+    g = np.random.default_rng(11 + D)
+    Hkv, C = 2, 256
+    pc = _ctx(D, C, n_slots=2)
+    mag = np.exp2(g.integers(-2, 5, (1, 250, 1))).astype(np.float32)
+    k = wl.round_bf16(g.standard_normal((Hkv, 250, D)).astype(np.float32) * mag)
+    v = wl.round_bf16(g.standard_normal((Hkv, 250, D)).astype(np.float32) * mag[:, ::-1])
+    cuts = [0, 37, 38, 64, 65, 129, 192, 250]
+    want_k = want_v = None
+    for lo, hi in zip(cuts[:-1], cuts[1:]):
+        if lo == 0:
+            pc.percache_kv_put(0, 1, bf16(k[:, :hi]), bf16(v[:, :hi]))
+            want_k, want_v = kv_fp8.round_trip(k[:, :hi]), kv_fp8.round_trip(v[:, :hi])
+        else:
+            pc.percache_kv_append(0, 1, bf16(k[:, lo:hi]), bf16(v[:, lo:hi]))
+            want_k, want_v = kv_fp8.append(want_k, k[:, lo:hi]), kv_fp8.append(want_v, v[:, lo:hi])
+        assert pc.percache_kv_len(0, 1) == hi
+        kk, vv = pc.percache_kv_get(0, 1)
+        torch.cuda.synchronize()
+        assert np.array_equal(host(kk), want_k), f"K after the append to {hi}"
+        assert np.array_equal(host(vv), want_v), f"V after the append to {hi}"
     with pytest.raises(PercacheError) as e:
-        pc.percache_stack_decode(layers, F, EPS, bf16(h0[None, :1]), [slots], [6])
-    assert e.value.status == -2
+        pc.percache_kv_append(0, 1, bf16(k[:, :7]), bf16(v[:, :7]))      # 250 + 7 > 256
+    assert e.value.status == -4 and pc.percache_kv_len(0, 1) == 250
+    pc.close()
+
+
+def test_decode_steps_on_8_bit_slots():
+    """Decoding steps whose sequence slot and reused chunks are 8-bit slots, against the oracle doing the same thing
+    with its own numbers: per layer, the step's K/V (rounded to the storage dtype) appended by the oracle's append rule,
+    attention over what its slots read back."""
+    from test_gpu_stack import EPS, check_hidden, dev_layers, oracle_block
+    H, Hq, Hkv, D, F, L, C = 256, 4, 2, 64, 384, 2, 64
+    n_c, t_prompt, n_steps = 2, 20, 5
+    Ws = [wl.stack_weights(33, l, H, Hq, Hkv, D, F) for l in range(L)]
+    layers = dev_layers(Ws)
+    pc = Percache(n_layers=L, hidden=H, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=D, n_slots=3, slot_capacity=C,
+                  max_pos=n_c * C + C, kv_fp8=True, device=DEV)
+    g = np.random.default_rng(44)
+    total = n_c * C + t_prompt + n_steps
+    seq = wl.round_bf16(g.standard_normal((total, H)).astype(np.float32))
+    chunk_slots, seq_slot = [0, 1], 2
+    bounds = [c * C for c in range(n_c + 1)] + [n_c * C + t_prompt]
+    pc.percache_stack_reuse(layers, F, EPS, bf16(seq[None, :n_c * C + t_prompt]), save_bounds=bounds, save_slots=[chunk_slots + [seq_slot]])
+    # oracle population: exact full pass; slots = quantised (bf16-rounded) K/V of every layer
+    store = []      # per layer: list of read-back (k, v) for [chunk 0, chunk 1, sequence slot]
+    h = seq[:n_c * C + t_prompt]
+    for W in Ws:
+        h, K, V = oracle_block(h, W, Hq, Hkv, D, 10000.0)
+        cuts = list(zip(bounds[:-1], bounds[1:]))
+        store.append([(kv_fp8.round_trip(wl.round_bf16(K[:, lo:hi])), kv_fp8.round_trip(wl.round_bf16(V[:, lo:hi]))) for lo, hi in cuts])
+    for step in range(n_steps):
+        pos = n_c * C + t_prompt + step
+        out = pc.percache_stack_decode(layers, F, EPS, bf16(seq[None, pos:pos + 1]), [chunk_slots + [seq_slot]], [seq_slot])
+        torch.cuda.synchronize()
+        hx = seq[pos:pos + 1]
+        for l, W in enumerate(Ws):
+            used = [C, C, store[l][2][0].shape[1]]
+            sk = np.zeros((3, Hkv, C, D), np.float32)
+            sv = np.zeros((3, Hkv, C, D), np.float32)
+            for i, (k_, v_) in enumerate(store[l]):
+                sk[i, :, :k_.shape[1]] = k_
+                sv[i, :, :v_.shape[1]] = v_
+            hx, Kn, Vn = oracle_block(hx, W, Hq, Hkv, D, 10000.0, sk, sv, np.arange(3, dtype=np.int32), used)
+            store[l][2] = (kv_fp8.append(store[l][2][0], wl.round_bf16(Kn)), kv_fp8.append(store[l][2][1], wl.round_bf16(Vn)))
+        assert pc.percache_kv_len(L - 1, seq_slot) == t_prompt + step + 1
+        check_hidden(host(out[0]), hx, f"decode step {step} over 8-bit slots vs oracle", rel_max=2.0 ** -5)
     pc.close()

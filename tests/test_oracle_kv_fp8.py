@@ -103,3 +103,23 @@ def test_quantize_blocks_and_error_bound():
     # the largest element of a block uses the upper half of the code range
     top = np.abs(kv_fp8.e4m3_decode(codes)).reshape(H, -1)
     assert top[0].max() > 224
+
+
+def test_append_requantises_only_from_the_open_block_on():
+    g = np.random.default_rng(4)
+    x = g.standard_normal((2, 200, 64)).astype(np.float32)
+    x[:, 100:] *= 8.0                                      # later tokens raise the scale of the open block
+    a = kv_fp8.round_trip(x[:, :70])
+    b = kv_fp8.append(a, x[:, 70:150])
+    assert b.shape == (2, 150, 64)
+    assert np.array_equal(b[:, :64], a[:, :64])            # the full block before the open one is untouched
+    # tokens appended on a block border are quantised as a slot of their own
+    c = kv_fp8.append(kv_fp8.round_trip(x[:, :128]), x[:, 128:200])
+    assert np.array_equal(c[:, 128:], kv_fp8.round_trip(x[:, 128:200])) and np.array_equal(c[:, :128], kv_fp8.round_trip(x[:, :128]))
+    # the open block: same result as quantising [what was read back ; new tokens] in one go, and never further from the
+    # source than one coarser rounding of the read-back values
+    again = kv_fp8.round_trip(np.concatenate([a[:, 64:70], x[:, 70:128]], axis=1))
+    assert np.array_equal(b[:, 64:128], again)
+    # appending nothing-changing data is idempotent: values that are already codes at the block's scale stay put
+    d = kv_fp8.append(a[:, :64], a[:, 64:70])
+    assert np.array_equal(d, a)
