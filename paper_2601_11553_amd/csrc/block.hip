@@ -162,6 +162,35 @@ __global__ __launch_bounds__(256, 2) void splitk_partial_kernel(const __bf16 *__
   }
 }
 
+// One or two 128-token tiles and many features (the gate / up projections): one pass, no slices.  A workgroup owns 16
+// gate rows and the 16 up rows of the same features (tile rows j and j + 16), which a lane finds in its accumulators
+// r and r + 8, and all token rows of its tile (gemm_tile.hpp: mainloop_skinny).
+__global__ __launch_bounds__(256, 2) void swiglu_skinny_kernel(const __bf16 *__restrict__ A, const __bf16 *__restrict__ Wg,
+                                                               const __bf16 *__restrict__ Wu, __bf16 *__restrict__ Y, int M,
+                                                               int F, int K) {
+  constexpr int NS = 5;
+  __shared__ __align__(16) char lds[NS * pc::gemm::Skinny::STAGE];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int l32 = lane & 31, g = lane >> 5;
+  const int f0 = blockIdx.x * 16, m0 = blockIdx.y * 128;
+  f32x16 acc;
+  pc::gemm::mainloop_skinny<NS>(
+      lds, [&](int row) __attribute__((always_inline)) { return (row < 16 ? Wg : Wu) + (size_t)(f0 + (row & 15)) * K; }, A, K, m0, M, K,
+      acc);
+  const int m = m0 + wave * 32 + l32;
+  if (m >= M) return;
+#pragma unroll
+  for (int q2 = 0; q2 < 2; ++q2) {
+    float o[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float gate = acc[q2 * 4 + e], up = acc[8 + q2 * 4 + e];
+      o[e] = gate / (1.0f + __expf(-gate)) * up;
+    }
+    *(uint2 *)(Y + (size_t)m * F + f0 + q2 * 8 + g * 4) = pack4(o[0], o[1], o[2], o[3]);
+  }
+}
+
 // y = sum of slices + residual (rounded to bf16), and optionally n = RMSNorm(y) * gain on the rounded values.
 // One workgroup per row, four columns per thread and pass.
 __global__ __launch_bounds__(256) void reduce_residual_norm_kernel(const float *__restrict__ P, int n_k, int M, int N,
@@ -483,9 +512,16 @@ static pc_status run_stack(percache_ctx *ctx, const percache_block_weights *laye
       int nk = pc::choose_split_k(ctx->n_cu, H / BF * m_tiles, A / pc::gemm::BK);
       PC_TRY(pc::launch_splitk_partial(ctx, ws.attn, A, (const __bf16 *)w.wo, (const __bf16 *)w.wo, H, A, ws.part, (int)M, H, A, nk, s));
       PC_TRY(launch_reduce_residual_norm(ctx, ws.part, nk, (int)M, H, h_cur, ws.mid, (const __bf16 *)w.gain2, ws.normed, eps, s));
-      nk = pc::choose_split_k(ctx->n_cu, 2 * ffn / BF * m_tiles, H / pc::gemm::BK);
-      PC_TRY(pc::launch_splitk_partial(ctx, ws.normed, H, (const __bf16 *)w.w_gate, (const __bf16 *)w.w_up, ffn, H, ws.part, (int)M, 2 * ffn, H, nk, s));
-      PC_TRY(launch_reduce_swiglu(ctx, ws.part, nk, (int)M, ffn, ws.act, s));
+      if (M > 64 && ffn % 16 == 0) {
+        // many features, short contraction: one pass with 32 weight rows per workgroup beats slices + a second kernel
+        hipLaunchKernelGGL(swiglu_skinny_kernel, dim3(ffn / 16, m_tiles), dim3(256), 0, s, ws.normed, (const __bf16 *)w.w_gate,
+                           (const __bf16 *)w.w_up, ws.act, (int)M, ffn, H);
+        PC_HIP(ctx, hipGetLastError());
+      } else {
+        nk = pc::choose_split_k(ctx->n_cu, 2 * ffn / BF * m_tiles, H / pc::gemm::BK);
+        PC_TRY(pc::launch_splitk_partial(ctx, ws.normed, H, (const __bf16 *)w.w_gate, (const __bf16 *)w.w_up, ffn, H, ws.part, (int)M, 2 * ffn, H, nk, s));
+        PC_TRY(launch_reduce_swiglu(ctx, ws.part, nk, (int)M, ffn, ws.act, s));
+      }
       nk = pc::choose_split_k(ctx->n_cu, H / BF * m_tiles, ffn / pc::gemm::BK);
       PC_TRY(pc::launch_splitk_partial(ctx, ws.act, ffn, (const __bf16 *)w.w_down, (const __bf16 *)w.w_down, H, ffn, ws.part, (int)M, H, ffn, nk, s));
       PC_TRY(launch_reduce_residual_norm(ctx, ws.part, nk, (int)M, H, ws.mid, h_out, next_gain, ws.normed, eps, s));

@@ -224,5 +224,91 @@ __device__ __forceinline__ void mainloop_deep(char *lds, WRow w_row, const T *__
   }
 }
 
+// Few token rows, many output features: the weight stream bounds the projection, and it takes many workgroups to pull
+// it.  Here a workgroup owns only 32 weight rows -- N/32 workgroups -- and up to 128 token rows over the WHOLE
+// contraction (no slices to add up afterwards); wavefront w owns token block w.  NS stages of 64 k-elements
+// (4 KB of weights + 16 KB of tokens each), NS - 1 of them in flight, one barrier per k-step.
+//   w_row(r): the K contiguous elements of the weight row that tile row r (0..31) stands for.
+//   On return acc[r] = tile row (r/4)*8 + 4*(lane/32) + r%4 of token m0 + 32*wave + lane%32.
+struct Skinny {
+  static constexpr int W_BYTES = 32 * ROW, X_BYTES = 128 * ROW, STAGE = W_BYTES + X_BYTES;
+  static constexpr int INSTR = 1 + X_BYTES / 1024 / NW;  // direct-to-LDS load instructions per wavefront and stage
+};
+template <int NS, class T, class WRow>
+__device__ __forceinline__ void mainloop_skinny(char *lds, WRow w_row, const T *__restrict__ X, int ldx, int m0, int M, int K,
+                                                f32x16 &acc) {
+  using S = Skinny;
+  using V8 = typename Vec8<T>::type;
+  static_assert(NS >= 2 && NS <= 7 && (NS - 1) * S::INSTR < 64, "stage count");
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, g = lane >> 5;
+  constexpr int XI = S::X_BYTES / 1024 / NW;
+  const T *w_src;
+  const T *x_src[XI];
+  {
+    const int row = wave * 8 + (lane >> 3);  // the 32 weight rows: one load instruction per wavefront
+    w_src = w_row(row) + (((lane & 7) ^ swz128(row)) * 8);
+  }
+#pragma unroll
+  for (int k = 0; k < XI; ++k) {
+    const int row = (wave + k * NW) * 8 + (lane >> 3);
+    x_src[k] = X + (size_t)min(m0 + row, M - 1) * ldx + (((lane & 7) ^ swz128(row)) * 8);
+  }
+  // Every workgroup reads the same token rows: each starts its walk over the contraction somewhere else, so that they
+  // do not all ask the same cache lines at the same time.
+  const int nk = K / BK;
+  const int k_rot = (int)((blockIdx.x * 5u) % (unsigned)nk);
+  auto fetch = [&](int kt0, int st) __attribute__((always_inline)) {
+    char *base = lds + st * S::STAGE;
+    int kt = kt0 + k_rot;
+    if (kt >= nk) kt -= nk;
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(w_src + kt * BK),
+                                     (__attribute__((address_space(3))) void *)(base + wave * 1024), 16, 0, 2);
+#pragma unroll
+    for (int k = 0; k < XI; ++k)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(x_src[k] + kt * BK),
+                                       (__attribute__((address_space(3))) void *)(base + S::W_BYTES + (wave + k * NW) * 1024), 16, 0, 0);
+  };
+  int rd[BK / 16];
+#pragma unroll
+  for (int ks = 0; ks < BK / 16; ++ks) rd[ks] = ((2 * ks + g) ^ swz128(l32)) * 16;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+  // two accumulation chains (even / odd k-steps of 16): a lone chain would wait out every MFMA's latency
+  f32x16 acc_odd;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc_odd[r] = 0.f;
+
+#pragma unroll
+  for (int s = 0; s < NS - 1; ++s)
+    if (s < nk) fetch(s, s);
+  int st = 0, fill = NS - 1;  // stage of k-step kt; stage that k-step kt + NS - 1 goes to (the one kt - 1 has left)
+  for (int kt = 0; kt < nk; ++kt) {
+    const int later = min(NS - 2, nk - 1 - kt);  // k-steps in flight behind this one
+    if (later >= 5) wait_vmcnt<(NS > 6 ? 5 : 0) * S::INSTR>();
+    else if (later == 4) wait_vmcnt<(NS > 5 ? 4 : 0) * S::INSTR>();
+    else if (later == 3) wait_vmcnt<(NS > 4 ? 3 : 0) * S::INSTR>();
+    else if (later == 2) wait_vmcnt<(NS > 3 ? 2 : 0) * S::INSTR>();
+    else if (later == 1) wait_vmcnt<(NS > 2 ? 1 : 0) * S::INSTR>();
+    else wait_vmcnt0();
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();  // k-step kt has landed for everyone, and everyone has left the stage of kt - 1
+    asm volatile("" ::: "memory");
+    if (kt + NS - 1 < nk) fetch(kt + NS - 1, fill);
+    const char *wb = lds + st * S::STAGE + l32 * ROW;
+    const char *xb = lds + st * S::STAGE + S::W_BYTES + (wave * 32 + l32) * ROW;
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      const V8 a = *(const V8 *)(wb + rd[ks]);
+      const V8 b = *(const V8 *)(xb + rd[ks]);
+      if (ks & 1) acc_odd = mma(a, b, acc_odd); else acc = mma(a, b, acc);
+    }
+    st = st + 1 == NS ? 0 : st + 1;
+    fill = fill + 1 == NS ? 0 : fill + 1;
+  }
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[r] += acc_odd[r];
+}
+
 }  // namespace gemm
 }  // namespace pc

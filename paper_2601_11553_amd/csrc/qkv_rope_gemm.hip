@@ -138,6 +138,67 @@ __global__ __launch_bounds__(256, 2) void qkv_rope_kernel(const __bf16 *__restri
   }
 }
 
+// Few token rows (one or two 128-token tiles) without the bias / head-norm variants: one pass, no slices.  A workgroup
+// owns 32 weight rows = 16 rotation pairs of one head (rows j and j + 16 of the tile are features m and m + D/2), which a
+// lane finds in its accumulators r and r + 8, and all token rows of its tile (gemm_tile.hpp: mainloop_skinny).
+template <int D>
+__global__ __launch_bounds__(256, 2) void qkv_rope_skinny_kernel(const __bf16 *__restrict__ X, const __bf16 *__restrict__ W,
+                                                                 int M, int H, int t_fresh, int Hq, int Hkv,
+                                                                 const int32_t *__restrict__ table, int tbl_stride,
+                                                                 const float2 *__restrict__ rope, __bf16 *__restrict__ Q,
+                                                                 __bf16 *__restrict__ K, __bf16 *__restrict__ V) {
+  constexpr int NS = 5, TPH = D / 32;  // stages; tiles per head
+  __shared__ __align__(16) char lds[NS * pc::gemm::Skinny::STAGE];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int l32 = lane & 31, g = lane >> 5;
+  const int head = blockIdx.x / TPH, sub = blockIdx.x % TPH;
+  const int m0 = blockIdx.y * 128;
+  f32x16 acc;
+  pc::gemm::mainloop_skinny<NS>(
+      lds,
+      [&](int row) __attribute__((always_inline)) {
+        return W + (size_t)(head * D + (row < 16 ? 0 : D / 2 - 16) + sub * 16 + row) * H;
+      },
+      X, H, m0, M, H, acc);
+  __bf16 *dst;
+  int hh, n_heads;
+  bool rotate = true;
+  if (head < Hq) { dst = Q; hh = head; n_heads = Hq; }
+  else if (head < Hq + Hkv) { dst = K; hh = head - Hq; n_heads = Hkv; }
+  else { dst = V; hh = head - Hq - Hkv; n_heads = Hkv; rotate = false; }
+  const int m_raw = m0 + wave * 32 + l32;
+  if (m_raw >= M) return;
+  const int b = m_raw / t_fresh, i = m_raw - b * t_fresh;
+  const int pos = table[(size_t)b * tbl_stride + 1] + i;
+  __bf16 *row = dst + (((size_t)b * n_heads + hh) * t_fresh + i) * D;
+#pragma unroll
+  for (int q2 = 0; q2 < 2; ++q2) {
+    const int mm = sub * 16 + q2 * 8 + g * 4;  // first of this lane's 4 consecutive pair indices
+    float lo[4], hi[4];
+    float4 cs[2];
+    if (rotate) {
+      const float4 *csp = (const float4 *)(rope + (size_t)pos * (D / 2) + mm);
+      cs[0] = csp[0];
+      cs[1] = csp[1];
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float a = acc[q2 * 4 + e], c = acc[8 + q2 * 4 + e];
+      if (rotate) {
+        const float4 w4 = cs[e >> 1];
+        const float wc = (e & 1) ? w4.z : w4.x, ws = (e & 1) ? w4.w : w4.y;
+        lo[e] = a * wc - c * ws;
+        hi[e] = c * wc + a * ws;
+      } else {
+        lo[e] = a;
+        hi[e] = c;
+      }
+    }
+    *(uint2 *)(row + mm) = pack4(lo[0], lo[1], lo[2], lo[3]);
+    *(uint2 *)(row + mm + D / 2) = pack4(hi[0], hi[1], hi[2], hi[3]);
+  }
+}
+
 // Epilogue of the split-k path (few token rows): adds the fp32 slices P[s][m][f] in a fixed order, rotates q and k
 // exactly as above, rounds once.  One thread per (token, head, 4 consecutive rotation pairs).
 template <int D>
@@ -223,8 +284,23 @@ pc_status launch_qkv_rope(percache_ctx *ctx, const __bf16 *x, const __bf16 *w, i
   if ((long)F * c.hidden >= (1L << 31) || (long)M * c.hidden >= (1L << 31))
     return fail(ctx, PC_ESHAPE, "operand larger than 2^31 elements");
   const float2 *rope = (const float2 *)ctx->rope;
+  if (gemm_part && splitk_applies(M) && M > 64 && !extras.any()) {
+    // one or two 128-token tiles: weight-stream bound; one pass with 32 weight rows per workgroup (with at most 64
+    // rows the slices below are faster: they do not pay for a 128-token tile)
+    dim3 sgrid(F / 32, (M + 127) / 128);
+    prof_begin(ctx, PC_KERNEL_QKV_ROPE, stream);
+    if (c.head_dim == 128)
+      hipLaunchKernelGGL(qkv_rope_skinny_kernel<128>, sgrid, dim3(256), 0, stream, x, w, M, c.hidden, t_fresh, c.n_q_heads,
+                         c.n_kv_heads, table_dev, tbl_stride, rope, q, k, v);
+    else
+      hipLaunchKernelGGL(qkv_rope_skinny_kernel<64>, sgrid, dim3(256), 0, stream, x, w, M, c.hidden, t_fresh, c.n_q_heads,
+                         c.n_kv_heads, table_dev, tbl_stride, rope, q, k, v);
+    prof_end(ctx, PC_KERNEL_QKV_ROPE, stream);
+    PC_HIP(ctx, hipGetLastError());
+    return PC_OK;
+  }
   if (gemm_part && splitk_applies(M)) {
-    // few token rows: weight-stream bound, contraction cut into slices (see block.hip)
+    // few token rows with the bias / head-norm variants: contraction cut into slices (see block.hip)
     const int nk = choose_split_k(ctx->n_cu, F / BF * (M > 128 ? 2 : 1), c.hidden / pc::gemm::BK);
     prof_begin(ctx, PC_KERNEL_QKV_ROPE, stream);
     pc_status st = launch_splitk_partial(ctx, x, c.hidden, w, w, F, c.hidden, gemm_part, M, F, c.hidden, nk, stream);
