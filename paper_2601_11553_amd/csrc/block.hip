@@ -478,14 +478,15 @@ static pc_status run_stack(percache_ctx *ctx, const percache_block_weights *laye
     // few token rows: split-k projections, whose reduce kernels also apply the residual and the next RMSNorm
     const bool skinny = pc::splitk_applies(M) && ffn % BF == 0;
     if (!skinny || l == 0) PC_TRY(launch_rmsnorm(ctx, h_cur, (const __bf16 *)w.gain1, ws.normed, (int)M, H, eps, s));
+    bool v_blocked = false;
     pc::QkvExtras extras;
     extras.bias = (const __bf16 *)w.qkv_bias;
     extras.q_norm = (const __bf16 *)w.q_norm;
     extras.k_norm = (const __bf16 *)w.k_norm;
     extras.eps = eps;
     PC_TRY(pc::launch_qkv_rope(ctx, ws.normed, (const __bf16 *)w.wqkv, batch, t_fresh, ws.pf.table, stride, ws.pf.q, ws.pf.k, ws.pf.v, s,
-                               skinny ? ws.pf.gemm_part : nullptr, extras));
-    PC_TRY(pc::launch_v_repack(ctx, ws.pf.v, ws.pf.v_blk, batch, t_fresh, s));
+                               skinny ? ws.pf.gemm_part : nullptr, extras, ws.pf.v_blk, &v_blocked));
+    if (!v_blocked) PC_TRY(pc::launch_v_repack(ctx, ws.pf.v, ws.pf.v_blk, batch, t_fresh, s));
     PC_TRY(pc::launch_attention(ctx, l, ws.pf.q, ws.pf.k, ws.pf.v_blk, batch, t_fresh, ws.pf.table, stride, min_tiles, 0, ws.attn,
                                 ws.pf.part_o, ws.pf.part_ml, s));
     for (int b = 0; b < batch && n_save > 0; ++b)

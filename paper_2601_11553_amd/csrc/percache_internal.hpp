@@ -134,9 +134,11 @@ struct QkvExtras {
   bool any() const { return bias || q_norm || k_norm; }
 };
 // gemm_part: workspace for the split-k path (nullptr: always the single-pass kernel)
+// v_blk / v_blk_done: if given, the launch may also write V as the 64-key blocks of launch_v_repack and says so
 pc_status launch_qkv_rope(percache_ctx *ctx, const __bf16 *x, const __bf16 *w, int batch, int t_fresh,
                           const int32_t *table_dev, int tbl_stride, __bf16 *q, __bf16 *k, __bf16 *v,
-                          hipStream_t stream, float *gemm_part = nullptr, const QkvExtras &extras = QkvExtras());
+                          hipStream_t stream, float *gemm_part = nullptr, const QkvExtras &extras = QkvExtras(),
+                          __bf16 *v_blk = nullptr, bool *v_blk_done = nullptr);
 
 // Split-k projections for few token rows (see block.hip).  P[s][m][n] = sum over slice s of A[m][k] W[n][k];
 // weight rows >= n_split come from w1.  Returns the number of slices written (chosen by choose_split_k).

@@ -113,10 +113,11 @@ pc_status percache_prefill_reuse(percache_ctx *ctx, int32_t layer, const void *x
   if (st != PC_OK) return st;
   __bf16 *kf = k_fresh_out_dev ? (__bf16 *)k_fresh_out_dev : p.ws.k;
   __bf16 *vf = v_fresh_out_dev ? (__bf16 *)v_fresh_out_dev : p.ws.v;
+  bool v_blocked = false;
   st = pc::launch_qkv_rope(ctx, (const __bf16 *)x_fresh_dev, (const __bf16 *)wqkv_dev, batch, t_fresh, p.ws.table,
-                           p.tbl_stride, p.ws.q, kf, vf, s, p.ws.gemm_part);
+                           p.tbl_stride, p.ws.q, kf, vf, s, p.ws.gemm_part, pc::QkvExtras(), p.ws.v_blk, &v_blocked);
   if (st != PC_OK) return st;
-  st = pc::launch_v_repack(ctx, vf, p.ws.v_blk, batch, t_fresh, s);
+  if (!v_blocked) st = pc::launch_v_repack(ctx, vf, p.ws.v_blk, batch, t_fresh, s);
   if (st != PC_OK) return st;
   return pc::launch_attention(ctx, layer, p.ws.q, kf, p.ws.v_blk, batch, t_fresh, p.ws.table, p.tbl_stride, p.min_tiles, 0,
                               (__bf16 *)attn_out_dev, p.ws.part_o, p.ws.part_ml, s);

@@ -146,7 +146,8 @@ __global__ __launch_bounds__(256, 2) void qkv_rope_skinny_kernel(const __bf16 *_
                                                                  int M, int H, int t_fresh, int Hq, int Hkv,
                                                                  const int32_t *__restrict__ table, int tbl_stride,
                                                                  const float2 *__restrict__ rope, __bf16 *__restrict__ Q,
-                                                                 __bf16 *__restrict__ K, __bf16 *__restrict__ V) {
+                                                                 __bf16 *__restrict__ K, __bf16 *__restrict__ V,
+                                                                 __bf16 *__restrict__ V_blk) {
   constexpr int NS = 5, TPH = D / 32;  // stages; tiles per head
   __shared__ __align__(16) char lds[NS * pc::gemm::Skinny::STAGE];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -196,6 +197,17 @@ __global__ __launch_bounds__(256, 2) void qkv_rope_skinny_kernel(const __bf16 *_
     }
     *(uint2 *)(row + mm) = pack4(lo[0], lo[1], lo[2], lo[3]);
     *(uint2 *)(row + mm + D / 2) = pack4(hi[0], hi[1], hi[2], hi[3]);
+    if (V_blk && !rotate) {
+      // the 64-key blocks [D][64] the attention kernel reads for the fresh part (t_fresh is a multiple of 64 here:
+      // no padding to write), saving the repack launch
+      const int tin = i & 63;
+      __bf16 *vb = V_blk + ((((size_t)b * n_heads + hh) * (t_fresh >> 6) + (i >> 6)) * D) * 64 + (tin & ~15) + pc::blocked_key(tin & 15);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        vb[(size_t)(mm + e) * 64] = (__bf16)lo[e];
+        vb[(size_t)(mm + e + D / 2) * 64] = (__bf16)hi[e];
+      }
+    }
   }
 }
 
@@ -276,7 +288,8 @@ namespace pc {
 
 pc_status launch_qkv_rope(percache_ctx *ctx, const __bf16 *x, const __bf16 *w, int batch, int t_fresh,
                           const int32_t *table_dev, int tbl_stride, __bf16 *q, __bf16 *k, __bf16 *v,
-                          hipStream_t stream, float *gemm_part, const QkvExtras &extras) {
+                          hipStream_t stream, float *gemm_part, const QkvExtras &extras, __bf16 *v_blk, bool *v_blk_done) {
+  if (v_blk_done) *v_blk_done = false;
   const percache_config &c = ctx->cfg;
   const int M = batch * t_fresh;
   const int F = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
@@ -288,13 +301,15 @@ pc_status launch_qkv_rope(percache_ctx *ctx, const __bf16 *x, const __bf16 *w, i
     // one or two 128-token tiles: weight-stream bound; one pass with 32 weight rows per workgroup (with at most 64
     // rows the slices below are faster: they do not pay for a 128-token tile)
     dim3 sgrid(F / 32, (M + 127) / 128);
+    __bf16 *vb = (v_blk && v_blk_done && t_fresh % 64 == 0) ? v_blk : nullptr;  // also lay V out for the attention kernel
+    if (vb) *v_blk_done = true;
     prof_begin(ctx, PC_KERNEL_QKV_ROPE, stream);
     if (c.head_dim == 128)
       hipLaunchKernelGGL(qkv_rope_skinny_kernel<128>, sgrid, dim3(256), 0, stream, x, w, M, c.hidden, t_fresh, c.n_q_heads,
-                         c.n_kv_heads, table_dev, tbl_stride, rope, q, k, v);
+                         c.n_kv_heads, table_dev, tbl_stride, rope, q, k, v, vb);
     else
       hipLaunchKernelGGL(qkv_rope_skinny_kernel<64>, sgrid, dim3(256), 0, stream, x, w, M, c.hidden, t_fresh, c.n_q_heads,
-                         c.n_kv_heads, table_dev, tbl_stride, rope, q, k, v);
+                         c.n_kv_heads, table_dev, tbl_stride, rope, q, k, v, vb);
     prof_end(ctx, PC_KERNEL_QKV_ROPE, stream);
     PC_HIP(ctx, hipGetLastError());
     return PC_OK;

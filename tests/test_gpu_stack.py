@@ -39,7 +39,7 @@ def oracle_block(h, W, Hq, Hkv, D, theta, sk=None, sv=None, ids=(), used=(), ext
                         extras=extras)
 
 
-@pytest.mark.parametrize("D,t_fresh,used_last", [(64, 48, 64), (128, 70, 40), (128, 200, 64)])
+@pytest.mark.parametrize("D,t_fresh,used_last", [(64, 48, 64), (128, 70, 40), (128, 200, 64), (64, 64, 64), (128, 64, 33)])
 def test_one_block_vs_oracle(D, t_fresh, used_last):
     """One block over two loaded chunks (random K/V) + a ragged fresh part, against the oracle's block."""
     H, Hq, Hkv, F, C = 256, 4, 2, 448, 64
