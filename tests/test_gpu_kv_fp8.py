@@ -7,6 +7,7 @@ import torch
 
 import oracle
 from oracle import kv_fp8
+from oracle import kv_fp8 as kv_fp8_mod
 from paper_2601_11553_amd import workloads as wl
 from paper_2601_11553_amd.binding import Percache, PercacheError
 
@@ -241,4 +242,24 @@ def test_decode_steps_on_8_bit_slots():
             store[l][2] = (kv_fp8.append(store[l][2][0], wl.round_bf16(Kn)), kv_fp8.append(store[l][2][1], wl.round_bf16(Vn)))
         assert pc.percache_kv_len(L - 1, seq_slot) == t_prompt + step + 1
         check_hidden(host(out[0]), hx, f"decode step {step} over 8-bit slots vs oracle", rel_max=2.0 ** -5)
+    pc.close()
+
+
+@pytest.mark.parametrize("kv_fp8", [False, True])
+def test_config4_decode_step_shape_full_size(kv_fp8):
+    """One new token per query over the 16 x 1024 cached tokens of config 4 (batch 8), over bf16 and over 8-bit slots: the
+    launch configurations of the benchmark's decode-step lines.  One row per query and head: the oracle computes all."""
+    w = wl.config4(t_fresh=1)
+    pc = Percache(n_layers=1, hidden=w.hidden, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
+                  n_slots=w.n_slots, slot_capacity=w.chunk_tokens, max_pos=w.max_pos, kv_fp8=kv_fp8, device=DEV)
+    store = {}
+    for s in sorted(set(int(x) for x in w.slot_ids.reshape(-1))):
+        k, v = w.slot_kv(s)
+        pc.percache_kv_put(0, s, bf16(k), bf16(v))
+        store[s] = (kv_fp8_mod.round_trip(k), kv_fp8_mod.round_trip(v)) if kv_fp8 else (k, v)
+    out = pc.percache_prefill_reuse(0, bf16(w.X), bf16(w.Wqkv), w.slot_ids, w.used_len)
+    torch.cuda.synchronize()
+    for b in range(w.batch):
+        O, _, _, _ = _oracle_on(store, w, b)
+        check_close(host(out[b]), O, f"cfg4 decode shape kv_fp8={kv_fp8} b={b}")
     pc.close()
