@@ -4,7 +4,9 @@
 // crops them once more):
 //   h' = h + (attention(RMSNorm(h) ...)) Wo^T,   h'' = h' + (silu(n Wgate^T) * (n Wup^T)) Wdown^T,  n = RMSNorm(h').
 // Kernels: a row-wise RMSNorm, and the shared projection main loop with two epilogues (residual add; SwiGLU on a
-// gate/up feature pair held by the same lane).  percache_stack_reuse chains the layers; percache_kv_slice is the
+// gate/up feature pair held by the same lane); for few token rows, where the weight stream bounds a projection,
+// slices of the contraction + small reduce kernels (few features, long contraction) or a one-pass kernel with 32
+// weight rows per workgroup (many features).  percache_stack_reuse chains the layers; percache_kv_slice is the
 // cache slicer of Sec. 4.1.1 (cuts the K/V of a prefilled sequence at chunk boundaries into slots).
 #include <cstring>
 

@@ -254,14 +254,9 @@ __device__ __forceinline__ void mainloop_skinny(char *lds, WRow w_row, const T *
     const int row = (wave + k * NW) * 8 + (lane >> 3);
     x_src[k] = X + (size_t)min(m0 + row, M - 1) * ldx + (((lane & 7) ^ swz128(row)) * 8);
   }
-  // Every workgroup reads the same token rows: each starts its walk over the contraction somewhere else, so that they
-  // do not all ask the same cache lines at the same time.
   const int nk = K / BK;
-  const int k_rot = (int)((blockIdx.x * 5u) % (unsigned)nk);
-  auto fetch = [&](int kt0, int st) __attribute__((always_inline)) {
+  auto fetch = [&](int kt, int st) __attribute__((always_inline)) {
     char *base = lds + st * S::STAGE;
-    int kt = kt0 + k_rot;
-    if (kt >= nk) kt -= nk;
     __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(w_src + kt * BK),
                                      (__attribute__((address_space(3))) void *)(base + wave * 1024), 16, 0, 2);
 #pragma unroll

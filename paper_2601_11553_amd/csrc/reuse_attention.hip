@@ -685,8 +685,8 @@ pc_status launch_attention(percache_ctx *ctx, int layer, const __bf16 *q, const 
                            int n_splits, __bf16 *out, __bf16 *part_o, float *part_ml, hipStream_t stream) {
   const percache_config &c = ctx->cfg;
   const int G = c.n_q_heads / c.n_kv_heads, R = G * t_fresh;
-  // 8 wavefronts x 32 rows (one workgroup per CU, 3 LDS stages) once a kv head has more than 128 stacked rows,
-  // else 4 wavefronts (two workgroups per CU, 2 stages)
+  // 8 wavefronts x 32 rows (one workgroup per CU) once a kv head has more than 128 stacked rows, else 4 wavefronts
+  // (two workgroups per CU); two LDS stages at D = 128, four at D = 64.
   // 256-row workgroups only when there are enough of them to go round; few, short key ranges prefer more, smaller ones
   // (8-bit slots with D = 64: a tile is too small for eight wavefronts to load)
   const bool wide = R > 128 && (long)batch * c.n_kv_heads * ((R + 255) / 256) * 4 >= ctx->n_cu && !(c.kv_fp8 && c.head_dim == 64);
