@@ -15,7 +15,8 @@ using pc::f32x16;
 using pc::gemm::BF;
 using pc::gemm::pack4;
 
-// NTB: 32-token blocks per wavefront (1 -> 64-token tile, 2 -> 128-token tile).
+// NTB: 32-token blocks per wavefront (1 -> 64-token tile, 2 -> 128-token tile, 3 -> 192-token tile: 80 KB of LDS,
+// still two workgroups per CU).
 // EXTRA: the bias / head-norm variants (see QkvExtras) are compiled in.
 template <int D, int NTB, bool EXTRA>
 __global__ __launch_bounds__(256, 2) void qkv_rope_kernel(const __bf16 *__restrict__ X, const __bf16 *__restrict__ W, int M,
@@ -24,7 +25,7 @@ __global__ __launch_bounds__(256, 2) void qkv_rope_kernel(const __bf16 *__restri
                                                           const float2 *__restrict__ rope, __bf16 *__restrict__ Q,
                                                           __bf16 *__restrict__ K, __bf16 *__restrict__ V, pc::QkvExtras ex) {
   constexpr int BT = 64 * NTB;
-  __shared__ __align__(16) char lds[pc::gemm::Shape<NTB>::LDS_BYTES];
+  extern __shared__ __align__(16) char lds[];  // Shape<NTB>::LDS_BYTES
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wf = wave & 1, wt = wave >> 1;
@@ -332,24 +333,38 @@ pc_status launch_qkv_rope(percache_ctx *ctx, const __bf16 *x, const __bf16 *w, i
     PC_HIP(ctx, hipGetLastError());
     return PC_OK;
   }
-  const bool big = M > 64 * 3;  // 128-token tiles once there are enough rows to fill them
-  dim3 grid(F / BF, big ? (M + 127) / 128 : (M + 63) / 64);
+  // Token tile: two workgroups share a CU, so a launch runs in rounds of 2 * n_cu tiles and a tile's time grows with
+  // its token blocks; take the width with the fewest block-rounds (the wider one on a tie: fewer operand reads per
+  // MFMA).  64-token tiles while there are too few rows to fill wider ones.
+  int ntb = 1;
+  if (M > 64 * 3) {
+    long best = -1;
+    for (int cand = 3; cand >= 2; --cand) {
+      const long tiles = (long)(F / BF) * ((M + 64 * cand - 1) / (64 * cand));
+      const long cost = (tiles + 2L * ctx->n_cu - 1) / (2L * ctx->n_cu) * cand;
+      if (best < 0 || cost < best) { best = cost; ntb = cand; }
+    }
+  }
+  dim3 grid(F / BF, (M + 64 * ntb - 1) / (64 * ntb));
+#define PC_LAUNCH_E(DD, NN, EE)                                                                                        \
+  do {                                                                                                                \
+    constexpr int lds_bytes = pc::gemm::Shape<NN>::LDS_BYTES;                                                         \
+    PC_HIP(ctx, hipFuncSetAttribute((const void *)qkv_rope_kernel<DD, NN, EE>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes)); \
+    hipLaunchKernelGGL((qkv_rope_kernel<DD, NN, EE>), grid, dim3(256), lds_bytes, stream, x, w, M, c.hidden, t_fresh,  \
+                       c.n_q_heads, c.n_kv_heads, table_dev, tbl_stride, rope, q, k, v, extras);                      \
+  } while (0)
 #define PC_LAUNCH(DD, NN)                                                                                             \
   do {                                                                                                                \
-    if (extras.any())                                                                                                 \
-      hipLaunchKernelGGL((qkv_rope_kernel<DD, NN, true>), grid, dim3(256), 0, stream, x, w, M, c.hidden, t_fresh,      \
-                         c.n_q_heads, c.n_kv_heads, table_dev, tbl_stride, rope, q, k, v, extras);                    \
-    else                                                                                                              \
-      hipLaunchKernelGGL((qkv_rope_kernel<DD, NN, false>), grid, dim3(256), 0, stream, x, w, M, c.hidden, t_fresh,     \
-                         c.n_q_heads, c.n_kv_heads, table_dev, tbl_stride, rope, q, k, v, extras);                    \
+    if (extras.any()) PC_LAUNCH_E(DD, NN, true); else PC_LAUNCH_E(DD, NN, false);                                      \
   } while (0)
   prof_begin(ctx, PC_KERNEL_QKV_ROPE, stream);
   if (c.head_dim == 128) {
-    if (big) PC_LAUNCH(128, 2); else PC_LAUNCH(128, 1);
+    if (ntb == 3) PC_LAUNCH(128, 3); else if (ntb == 2) PC_LAUNCH(128, 2); else PC_LAUNCH(128, 1);
   } else {
-    if (big) PC_LAUNCH(64, 2); else PC_LAUNCH(64, 1);
+    if (ntb == 3) PC_LAUNCH(64, 3); else if (ntb == 2) PC_LAUNCH(64, 2); else PC_LAUNCH(64, 1);
   }
 #undef PC_LAUNCH
+#undef PC_LAUNCH_E
   prof_end(ctx, PC_KERNEL_QKV_ROPE, stream);
   PC_HIP(ctx, hipGetLastError());
   return PC_OK;

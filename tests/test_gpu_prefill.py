@@ -90,6 +90,9 @@ def test_kv_store_round_trip_and_errors():
     dict(hidden=1024, n_q_heads=16, n_kv_heads=8, head_dim=128, batch=1, t_fresh=64, n_chunks=4, chunk_tokens=512, n_slots=16),
     dict(hidden=512, n_q_heads=6, n_kv_heads=2, head_dim=128, batch=3, t_fresh=50, n_chunks=2, chunk_tokens=64, n_slots=8),
     dict(hidden=320, n_q_heads=4, n_kv_heads=4, head_dim=64, batch=2, t_fresh=131, n_chunks=1, chunk_tokens=192, n_slots=3),
+    # enough tiles that the launcher takes its 192-token tiles (more than two workgroups per CU otherwise), ragged last tile
+    dict(hidden=256, n_q_heads=24, n_kv_heads=8, head_dim=128, batch=13, t_fresh=131, n_chunks=1, chunk_tokens=64, n_slots=16),
+    dict(hidden=192, n_q_heads=48, n_kv_heads=16, head_dim=64, batch=7, t_fresh=250, n_chunks=1, chunk_tokens=64, n_slots=8),
 ])
 def test_qkv_rope_matches_oracle(shape):
     w = wl.make_prefill("proj", 5, "bf16", last_used_len=shape["chunk_tokens"] - 3, **shape)

@@ -151,12 +151,16 @@ def test_config2_full_size_reuse_equals_full_recompute():
     check_hidden(host(one[0, :96]), ref, "cfg2: layer 0 of the full pass, rows 0..95")
 
 
-@pytest.mark.parametrize("D,t_fresh,which", [(128, 40, "all"), (64, 40, "all"), (128, 260, "all"), (64, 260, "all"),
-                                             (128, 260, "bias"), (128, 40, "norm"), (64, 260, "qnorm")])
-def test_projection_variants_bias_and_head_norm(D, t_fresh, which):
+@pytest.mark.parametrize("D,t_fresh,which,heads", [
+    (128, 40, "all", (4, 2)), (64, 40, "all", (4, 2)), (128, 260, "all", (4, 2)), (64, 260, "all", (4, 2)),
+    (128, 260, "bias", (4, 2)), (128, 40, "norm", (4, 2)), (64, 260, "qnorm", (4, 2)),
+    (128, 1700, "all", (24, 8)),   # enough tiles for the launcher's 192-token tiles
+])
+def test_projection_variants_bias_and_head_norm(D, t_fresh, which, heads):
     """Qwen-family variants of the projection: bias, RMSNorm over the head dimension of q and k before RoPE; few rows
-    (split-k path) and many rows (single-pass kernel), both head sizes, each part alone and together."""
-    H, Hq, Hkv, F, C = 256, 4, 2, 384, 64
+    (split-k path) and many rows (single-pass kernel, 128- and 192-token tiles), both head sizes, each part alone and
+    together."""
+    H, (Hq, Hkv), F, C = 256, heads, 384, 64
     w = wl.make_prefill("var", 23, "bf16", H, Hq, Hkv, D, 1, t_fresh, 2, C, 4)
     W = wl.stack_weights(23, 0, H, Hq, Hkv, D, F)
     g = np.random.default_rng(50 + D)
