@@ -258,7 +258,7 @@ def main():
     look = {}
     for p in (1, 8, 32, 128, 1024):
         t = time_lookup(probes_all[:p].contiguous())
-        if p <= 32:   # one streaming pass of the bank: HBM bound
+        if p <= 128:  # one streaming pass of the bank (2 N d p flop on N d 2 bytes: below the ridge): HBM bound
             look[f"P{p}"] = {"ms": round(t * 1e3, 4), "lookups_per_s": round(p / t, 1), "bound": "hbm",
                              "bank_GBps": round(bank_bytes / t / 1e9, 1), "frac_of_hbm_peak": round(bank_bytes / t / 1e9 / PEAK_HBM_GBS, 4)}
         else:         # matrix-product kernel: fp16 MFMA bound (2 N d flop per probe)

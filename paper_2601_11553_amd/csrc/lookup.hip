@@ -439,6 +439,155 @@ __global__ __launch_bounds__(256, 2) void lookup_batched_kernel(const _Float16 *
   }
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Up to 128 probes in one pass of the bank (embedding widths of 512, 768 and 1024 elements).
+// One workgroup per CU; wavefront w keeps ITS 32 probes in registers as the N-side operands of the 32x32x16 product
+// (d/4 registers per lane: one wavefront per SIMD), and all four wavefronts multiply the same 32-row blocks of the
+// bank, which stream through a ring of LDS stages shared by the workgroup (32 rows x 512 bytes per stage; every
+// load instruction brings two contiguous 512-byte runs; NSTG - 1 stages in flight).  One barrier per stage: it
+// publishes the stage that has landed and retires the one just multiplied.  A lane ends up with 16 rows of one
+// probe per block, scales them by the rows' inverse norms and keeps a running sorted list, as in the kernel above.
+// ---------------------------------------------------------------------------------------------------
+constexpr int kWideProbes = 128;
+constexpr int kWideStages = 8;
+constexpr int kWideChunk = 512;             // bytes of a row per stage
+constexpr int kWideMaxBlocksPerWg = 192;    // 6144 rows: bounds the LDS copy of the inverse norms (24 KB)
+
+template <int D_EMB, int K>
+__global__ __launch_bounds__(256, 1) void lookup_wide_kernel(const _Float16 *__restrict__ bank, const float *__restrict__ inv_norm,
+                                                             int N, const _Float16 *__restrict__ probes, int n_probes, int per_wg,
+                                                             Best *__restrict__ partial) {
+  extern __shared__ __align__(16) char smem[];
+  constexpr int CHB = kWideChunk, NSTG = kWideStages;
+  constexpr int CHUNKS = D_EMB * 2 / CHB;  // stages per row block
+  constexpr int CS = CHB / 32;             // MFMA k-steps (16 elements) per stage
+  constexpr int STG = 32 * CHB;            // bytes per stage
+  constexpr int IPS = STG / 1024 / 4;      // load instructions per stage and wavefront
+  static_assert(D_EMB * 2 % CHB == 0, "row must be a whole number of chunks");
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, g2 = lane >> 5;
+  const int n_blocks = (N + 31) / 32;
+  const int rb_begin = blockIdx.x * per_wg, rb_end = min(n_blocks, rb_begin + per_wg);
+
+  // inverse norms of this workgroup's rows (zero beyond N), then the ring
+  float *inv_lds = (float *)smem;
+  char *ring = smem + kWideMaxBlocksPerWg * 32 * sizeof(float);
+  for (int r = tid; r < per_wg * 32; r += 256) {
+    const int row = rb_begin * 32 + r;
+    inv_lds[r] = row < N ? inv_norm[row] : 0.f;
+  }
+  // this lane's probe: elements [16 ks + 8 g2, +8) for every k-step (zero for a padding probe)
+  f16x8 pq[D_EMB / 16];
+  {
+    const int p = wave * 32 + l32;
+    const u32x4 *src = (const u32x4 *)(probes + (size_t)min(p, n_probes - 1) * D_EMB);
+#pragma unroll
+    for (int ks = 0; ks < D_EMB / 16; ++ks) {
+      u32x4 raw = src[2 * ks + g2];
+      if (p >= n_probes) raw = u32x4{0, 0, 0, 0};
+      pq[ks] = __builtin_bit_cast(f16x8, raw);
+    }
+  }
+  // (the probes' loads must not be counted by the ring's partial waits below)
+#pragma unroll
+  for (int ks = 0; ks < D_EMB / 16; ++ks) asm volatile("" : "+v"(pq[ks]));
+  PC_LOOKUP_WAIT_VMCNT(0);
+  __syncthreads();
+
+  // load instruction i of a stage (i = wave + 4 k): stage bytes [1024 i, +1024) = rows 2i, 2i+1
+  int ld_row[IPS], ld_col[IPS];
+#pragma unroll
+  for (int k = 0; k < IPS; ++k) {
+    const int row = (wave + 4 * k) * 2 + (lane >> 5), pc = lane & 31;
+    ld_row[k] = row;
+    ld_col[k] = (pc ^ (row & 15)) * 8;  // element offset of the logical 16-byte chunk this lane fetches
+  }
+  auto issue = [&](int rb, int chunk, int st) __attribute__((always_inline)) {
+    const _Float16 *base = bank + chunk * (CHB / 2);
+#pragma unroll
+    for (int k = 0; k < IPS; ++k) {
+      const int row = min(rb * 32 + ld_row[k], N - 1);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(base + (size_t)row * D_EMB + ld_col[k]),
+                                       (__attribute__((address_space(3))) void *)(ring + st * STG + (wave + 4 * k) * 1024), 16, 0, kBankLoadAux);
+    }
+  };
+  int rd_off[CS];  // swizzled byte offsets of this lane's operand reads inside a stage
+#pragma unroll
+  for (int s = 0; s < CS; ++s) rd_off[s] = l32 * CHB + (((2 * s + g2) ^ (l32 & 15)) * 16);
+
+  TopK<K> best;
+  best.clear();
+  const int rb_last = rb_end - 1;
+  if (rb_begin < rb_end) {
+    // flat sequence of (row block, chunk) items; loads go out unconditionally (past the end they repeat the last
+    // block into a stage nobody reads), so the count of loads in flight is the same at every wait
+    int prb = rb_begin, pch = 0, ist = 0, st = 0;
+    auto advance = [&](int &rb_, int &c_) __attribute__((always_inline)) {
+      if (++c_ == CHUNKS) { c_ = 0; ++rb_; }
+    };
+#pragma unroll
+    for (int k = 0; k < NSTG - 1; ++k) {
+      issue(min(prb, rb_last), pch, ist);
+      advance(prb, pch);
+      ist = ist + 1 == NSTG ? 0 : ist + 1;
+    }
+    for (int rb = rb_begin; rb < rb_end; ++rb) {
+      pc::f32x16 acc[2];  // two accumulation chains: an MFMA does not wait for the one before it
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[a][r] = 0.f;
+#pragma unroll
+      for (int c = 0; c < CHUNKS; ++c) {
+        // the oldest stage in flight has landed (mine), then (barrier) everyone's; the barrier also says that the
+        // stage multiplied last is free for the next load
+        PC_LOOKUP_WAIT_VMCNT((NSTG - 2) * IPS);
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        issue(min(prb, rb_last), pch, ist);
+        advance(prb, pch);
+        ist = ist + 1 == NSTG ? 0 : ist + 1;
+        // all of the stage's operands are asked for before its first MFMA (left to itself the compiler reads one
+        // operand, waits, multiplies: one LDS latency per MFMA instead of one per stage)
+        const char *abase = ring + st * STG;
+        f16x8 av[CS];
+#pragma unroll
+        for (int s = 0; s < CS; ++s) av[s] = *(const f16x8 *)(abase + rd_off[s]);
+#pragma unroll
+        for (int s = 0; s < CS; ++s) acc[s & 1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av[s], pq[c * CS + s], acc[s & 1], 0, 0, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, CS, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, CS, 0);
+        st = st + 1 == NSTG ? 0 : st + 1;
+      }
+      // element r of the product: row (r/4)*8 + 4*g2 + r%4 of the block, probe wave*32 + l32
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const int rin = q4 * 8 + g2 * 4;
+        const f32x4 inv4 = *(const f32x4 *)(inv_lds + (rb - rb_begin) * 32 + rin);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int row = rb * 32 + rin + e;
+          if (row < N) best.insert((acc[0][q4 * 4 + e] + acc[1][q4 * 4 + e]) * inv4[e], row);
+        }
+      }
+    }
+    PC_LOOKUP_WAIT_VMCNT(0);
+  }
+  // the two lanes of a probe hold different rows: merge (K rounds of "best head wins and is popped")
+  Best *out = partial + ((size_t)blockIdx.x * kWideProbes + wave * 32 + l32) * K;
+#pragma unroll
+  for (int j = 0; j < K; ++j) {
+    float s = best.s[0];
+    int i = best.i[0];
+    const float s2 = __shfl_xor(s, 32, 64);
+    const int i2 = __shfl_xor(i, 32, 64);
+    if (better(s2, i2, s, i)) { s = s2; i = i2; }
+    best.pop_if(i != INT_MAX && best.i[0] == i);
+    if (g2 == 0) out[j] = Best{s, i};
+  }
+}
+
 // inverse L2 norms of n embedding rows (0 for a zero row); one wavefront per row
 __global__ __launch_bounds__(256) void inv_norm_kernel(const _Float16 *__restrict__ src, float *__restrict__ inv_norm, int n, int d) {
   const int lane = threadIdx.x & 63;
@@ -496,7 +645,8 @@ int max_stream_grid(const percache_ctx *ctx) {
 }
 
 constexpr int kMaxTopK = 8;
-constexpr int kBatchedFrom = 32;  // more probes than one streaming pass takes: the matrix-product kernel
+constexpr int kBatchedFrom = 32;  // more probes than one streaming pass takes: the 128-probe pass or the matrix-product kernel
+constexpr int kWideUpTo = 128;    // one such pass; beyond it the matrix-product kernel is the faster one
 
 // Launch shape of the batched kernel: 128-probe tiles x groups of consecutive 128-row bank tiles, about four
 // workgroups per CU in total.
@@ -565,6 +715,41 @@ pc_status run_lookup(percache_ctx *ctx, const void *probes_dev, int32_t n_probes
   if ((uintptr_t)workspace_dev % 16) return pc::fail(ctx, PC_EINVAL, "workspace must be 16-byte aligned");
   Best *partial = (Best *)workspace_dev;
   const _Float16 *probes = (const _Float16 *)probes_dev;
+  if (n_probes > kBatchedFrom && n_probes <= kWideUpTo && (d == 512 || d == 768 || d == 1024)) {
+    // up to 128 probes: one pass of the bank
+    const int n_blocks = (N + 31) / 32;
+    int grid = ctx->n_cu < n_blocks ? ctx->n_cu : n_blocks;
+    int per_wg = (n_blocks + grid - 1) / grid;
+    if (per_wg > kWideMaxBlocksPerWg) { per_wg = kWideMaxBlocksPerWg; grid = (n_blocks + per_wg - 1) / per_wg; }
+    const size_t lds = (size_t)kWideMaxBlocksPerWg * 32 * sizeof(float) + (size_t)kWideStages * 32 * kWideChunk;
+#define PC_WIDE(DD, KK)                                                                                               \
+  do {                                                                                                                \
+    PC_HIP(ctx, hipFuncSetAttribute((const void *)lookup_wide_kernel<DD, KK>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)); \
+    hipLaunchKernelGGL((lookup_wide_kernel<DD, KK>), dim3(grid), dim3(256), lds, st, ctx->bank, ctx->bank_inv, N, pp, np, per_wg, partial); \
+  } while (0)
+    for (int p0 = 0; p0 < n_probes; p0 += kWideProbes) {
+      const int np = n_probes - p0 < kWideProbes ? n_probes - p0 : kWideProbes;
+      const _Float16 *pp = probes + (size_t)p0 * d;
+      pc::prof_begin(ctx, PC_KERNEL_LOOKUP, st);
+      if (k == 1) {
+        if (d == 512) PC_WIDE(512, 1); else if (d == 768) PC_WIDE(768, 1); else PC_WIDE(1024, 1);
+      } else {
+        if (d == 512) PC_WIDE(512, kMaxTopK); else if (d == 768) PC_WIDE(768, kMaxTopK); else PC_WIDE(1024, kMaxTopK);
+      }
+      pc::prof_end(ctx, PC_KERNEL_LOOKUP, st);
+      PC_HIP(ctx, hipGetLastError());
+      uint8_t *hit = hit_out_dev ? hit_out_dev + p0 : nullptr;
+      if (k == 1)
+        hipLaunchKernelGGL(lookup_finalize_kernel<1>, dim3(np), dim3(64), 0, st, partial, grid, kWideProbes, pp, d, tau, 1,
+                           idx_out_dev + p0, sim_out_dev + p0, hit);
+      else
+        hipLaunchKernelGGL(lookup_finalize_kernel<kMaxTopK>, dim3(np), dim3(64), 0, st, partial, grid, kWideProbes, pp, d, tau, k,
+                           idx_out_dev + (size_t)p0 * k, sim_out_dev + (size_t)p0 * k, hit);
+      PC_HIP(ctx, hipGetLastError());
+    }
+#undef PC_WIDE
+    return PC_OK;
+  }
   if (n_probes > kBatchedFrom) {
     // many probes: matrix-core bound product instead of repeated streaming passes
     const BatchShape bs = batch_shape(ctx->n_cu, N, n_probes);
@@ -640,6 +825,10 @@ size_t percache_lookup_workspace_bytes(const percache_ctx *ctx, int32_t n_probes
     const size_t p_tiles = ((size_t)n_probes + 127) / 128;
     const size_t batched = (4 * (size_t)ctx->n_cu + p_tiles) * 128;
     if (batched > lists) lists = batched;
+    // the 128-probe pass: one list per workgroup and probe
+    const size_t wide_grid = (size_t)ctx->cfg.bank_capacity / (32 * kWideMaxBlocksPerWg) + 1;
+    const size_t wide = (wide_grid > (size_t)ctx->n_cu ? wide_grid : (size_t)ctx->n_cu) * kWideProbes;
+    if (wide > lists) lists = wide;
   }
   return pc::align_up(lists * kMaxTopK * sizeof(Best));
 }

@@ -63,7 +63,8 @@ def test_clustered_ragged_sizes(n_clusters, per_cluster, n_probes):
     assert hit[-6:].all()
 
 
-@pytest.mark.parametrize("dim,n_probes", [(64, 5), (64, 20), (192, 7), (256, 31), (384, 9), (384, 25), (768, 3), (768, 33), (2048, 20)])
+@pytest.mark.parametrize("dim,n_probes", [(64, 5), (64, 20), (192, 7), (256, 31), (384, 9), (384, 25), (768, 3), (768, 33), (2048, 20),
+                                          (512, 100), (512, 129), (768, 260), (1024, 128)])   # 512/100 and 1024/128: the 128-probe pass
 def test_every_embedding_width(dim, n_probes):
     """Each row-chunk width of the streaming kernel (one chunk per row up to 256 elements, several beyond),
     with one and two probe blocks, on a bank long enough that every wavefront streams many row blocks."""
@@ -95,6 +96,37 @@ def test_ties_zero_vectors_and_empty_bank():
     assert idx[0].item() == 12 and idx[2].item() == 12 and idx[1].item() == 0
     assert np.array_equal(hit.cpu().numpy(), o_hit)
     assert np.abs(sim.cpu().numpy() - o_sim).max() < 2e-5
+
+
+@pytest.mark.parametrize("n_probes,k", [(40, 1), (128, 1), (40, 8)])
+def test_ties_and_zero_vectors_in_the_128_probe_pass(n_probes, k):
+    """Exact ties (lowest row wins), a zero row, a zero probe and a ragged last 32-row block, at a width and probe
+    counts the 128-probe pass takes."""
+    d = 512
+    g = np.random.default_rng(15)
+    bank = wl.round_f16(g.standard_normal((75, d)).astype(np.float32))
+    bank[7] = 0.0
+    bank[40] = bank[12] * 2.0
+    bank[70] = bank[12] * 0.5
+    probes = wl.round_f16(g.standard_normal((n_probes, d)).astype(np.float32))
+    probes[0] = bank[12]
+    probes[1] = 0.0
+    probes[n_probes - 1] = bank[70]
+    pc = _ctx(128, d)
+    pc.percache_bank_put(0, f16(bank))
+    if k == 1:
+        idx, sim, hit = pc.percache_lookup(f16(probes), 0.5)
+        torch.cuda.synchronize()
+        o_idx, o_sim, o_hit, _ = oracle.lookup(bank, probes, 0.5)
+        assert idx.cpu().tolist() == o_idx.tolist()
+        assert idx[0].item() == 12 and idx[n_probes - 1].item() == 12 and idx[1].item() == 0
+        assert np.array_equal(hit.cpu().numpy(), o_hit)
+        assert np.abs(sim.cpu().numpy() - o_sim).max() < 2e-5
+    else:
+        idx, sim = pc.percache_lookup_topk(f16(probes), k)
+        torch.cuda.synchronize()
+        assert idx[0, :3].cpu().tolist() == [12, 40, 70] and idx[1, :k].cpu().tolist() == list(range(k))
+        _compare_topk(bank, probes, k, idx, sim)
 
 
 def test_overwrite_rows_and_error_paths():
@@ -140,6 +172,11 @@ def test_config3_full_size_sampled_probes():
         i1, s1, h1 = pc.percache_lookup(probes_dev[p:p + 1], w.tau)
         torch.cuda.synchronize()
         assert i1.item() == idx[p].item() and h1.item() == hit[p].item() and abs(s1.item() - sim[p].item()) < 2e-6
+    # 128 probes go through the 128-probe pass, the full call through the matrix-product kernel: same answers
+    for lo in (0, 1000):
+        i3, s3, h3 = pc.percache_lookup(probes_dev[lo:lo + 128], w.tau)
+        torch.cuda.synchronize()
+        assert torch.equal(i3, idx[lo:lo + 128]) and torch.equal(h3, hit[lo:lo + 128]) and (s3 - sim[lo:lo + 128]).abs().max().item() < 2e-6
     g = np.random.default_rng(0)
     sample = np.sort(np.concatenate([g.choice(1024, 128, replace=False), 1024 + g.choice(128, 64, replace=False)]))
     n_near_ties = _compare(w.bank, w.probes[sample], w.tau, idx[sample], sim[sample], hit[sample])
