@@ -349,7 +349,8 @@ pc_status launch_qkv_rope(percache_ctx *ctx, const __bf16 *x, const __bf16 *w, i
 #define PC_LAUNCH_E(DD, NN, EE)                                                                                        \
   do {                                                                                                                \
     constexpr int lds_bytes = pc::gemm::Shape<NN>::LDS_BYTES;                                                         \
-    PC_HIP(ctx, hipFuncSetAttribute((const void *)qkv_rope_kernel<DD, NN, EE>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes)); \
+    if (lds_bytes > 64 * 1024) /* above the default limit: opt in */                                                  \
+      PC_HIP(ctx, hipFuncSetAttribute((const void *)qkv_rope_kernel<DD, NN, EE>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes)); \
     hipLaunchKernelGGL((qkv_rope_kernel<DD, NN, EE>), grid, dim3(256), lds_bytes, stream, x, w, M, c.hidden, t_fresh,  \
                        c.n_q_heads, c.n_kv_heads, table_dev, tbl_stride, rope, q, k, v, extras);                      \
   } while (0)
