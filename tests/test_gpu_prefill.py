@@ -285,6 +285,20 @@ def test_config4_reduced():
     _run_and_check(wl.config4(batch=2, n_chunks=3, n_slots=8, t_fresh=256), "cfg4-reduced")
 
 
+def test_repeated_calls_are_bit_identical():
+    """No atomics, no order that depends on timing: the same call gives the same bits (split-KV merge included)."""
+    w = wl.config4(batch=2, n_chunks=5, n_slots=12, t_fresh=200)
+    pc = make_ctx(w)
+    fill_slots(pc, w, w.slot_ids.reshape(-1))
+    x, wq = bf16(w.X), bf16(w.Wqkv)
+    first = pc.percache_prefill_reuse(0, x, wq, w.slot_ids, w.used_len).clone()
+    for _ in range(3):
+        again = pc.percache_prefill_reuse(0, x, wq, w.slot_ids, w.used_len)
+        torch.cuda.synchronize()
+        assert torch.equal(first, again)
+    pc.close()
+
+
 def test_config4_full_size_sampled_rows():
     """Full config 4 (batch 8, 16 x 1024 cached tokens, 256 fresh) in the launch configuration the benchmark
     times; the oracle computes 96 sampled (query, row, head) outputs plus fresh K/V of one query."""
