@@ -77,6 +77,23 @@ def test_every_embedding_width(dim, n_probes):
     _compare(w.bank, w.probes, w.tau, idx, sim, hit)
 
 
+@pytest.mark.parametrize("seed", list(range(16)))
+def test_seeded_random_bank_shapes(seed):
+    """Embedding width, bank size (ragged against every block size) and probe count drawn from a seed: every kernel
+    of the lookup (one or two probe blocks per pass, the 128-probe pass, the matrix-product kernel) meets odd sizes."""
+    g = np.random.default_rng(3000 + seed)
+    dim = int(g.choice([64, 128, 192, 256, 384, 512, 768, 1024]))
+    n_clusters = int(g.integers(1, 60))
+    per_cluster = int(g.integers(1, 70))
+    n_probes = int(g.choice([1, 5, 16, 17, 32, 33, 100, 128, 129, 200]))
+    w = wl.lookup_clustered("r", 3100 + seed, n_clusters, per_cluster, dim, n_probes, 0.05, 0.02, 0.92, n_exact=1, n_near=1)
+    pc = _ctx(w.bank.shape[0], dim)
+    pc.percache_bank_put(0, f16(w.bank))
+    idx, sim, hit = pc.percache_lookup(f16(w.probes), w.tau)
+    torch.cuda.synchronize()
+    _compare(w.bank, w.probes, w.tau, idx, sim, hit)
+
+
 def test_ties_zero_vectors_and_empty_bank():
     d = 128
     g = np.random.default_rng(5)

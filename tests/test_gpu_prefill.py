@@ -169,6 +169,41 @@ def test_ragged_batch_with_partial_and_empty_chunks():
     pc.close()
 
 
+@pytest.mark.parametrize("seed", list(range(24)))
+def test_seeded_random_shapes(seed):
+    """Shapes drawn from a seed: head size, GQA ratio, batch, fresh length (1 .. a few tiles), chunk count (0 .. 5),
+    chunk capacity, ragged used lengths (zero included), over bf16 and over 8-bit slots (the latter against the
+    oracle run on what the slots read back)."""
+    g = np.random.default_rng(1000 + seed)
+    D = int(g.choice([64, 128]))
+    Hkv = int(g.choice([1, 2, 3, 4]))
+    G = int(g.choice([1, 2, 3, 4]))
+    while ((G + 2) * Hkv * D) % 128:
+        Hkv += 1
+    batch = int(g.integers(1, 4))
+    t_fresh = int(g.choice([1, 2, 17, 31, 64, 65, 100, 129, 150]))
+    n_chunks = int(g.integers(0, 6))
+    C = int(g.choice([64, 128, 192]))
+    hidden = int(g.choice([128, 192, 256, 320]))
+    w = wl.make_prefill(f"rnd{seed}", 2000 + seed, "bf16", hidden, G * Hkv, Hkv, D, batch, t_fresh, n_chunks, C, max(8, n_chunks + 2))
+    if n_chunks:
+        w.used_len[:] = g.integers(0, C + 1, size=(batch, n_chunks))
+    fp8 = bool(seed % 2)
+    pc = make_ctx(w, kv_fp8=fp8)
+    fill_slots(pc, w, w.slot_ids.reshape(-1))
+    out = pc.percache_prefill_reuse(0, bf16(w.X), bf16(w.Wqkv), w.slot_ids if n_chunks else None, w.used_len if n_chunks else None)
+    torch.cuda.synchronize()
+    for b in range(batch):
+        sk, sv, ids = w.compact_store(b)
+        if fp8 and n_chunks:
+            from oracle import kv_fp8
+            sk = np.stack([kv_fp8.round_trip(wl.round_bf16(x)) for x in sk])
+            sv = np.stack([kv_fp8.round_trip(wl.round_bf16(x)) for x in sv])
+        O, _, _, _ = oracle.prefill_reuse(w.X[b], w.Wqkv, w.n_q_heads, w.n_kv_heads, w.head_dim, w.rope_theta, sk, sv, ids, w.used_len[b])
+        check_close(host(out[b]), O, f"seed {seed} (D={D} G={G} Hkv={Hkv} B={batch} T={t_fresh} chunks={n_chunks}x{C} fp8={fp8}) b={b}")
+    pc.close()
+
+
 @pytest.mark.parametrize("n_splits", [0, 1, 5])
 def test_long_chunk_lists(n_splits):
     """70 and 64 short chunks per query (the kernel keeps the first 64 list entries in registers and reads the
