@@ -58,6 +58,50 @@ def test_one_block_vs_oracle(D, t_fresh, used_last):
         check_hidden(host(h_out[b]), ref, f"block D={D} T={t_fresh} query {b}")
 
 
+@pytest.mark.parametrize("seed", list(range(16)))
+def test_seeded_random_block_shapes(seed):
+    """One block with every size drawn from a seed: the token-row count decides which projection kernels run (slices
+    of the contraction, the one-pass kernels for few rows, the 64/128-token tiles), the rest varies head size, GQA
+    ratio, widths, chunk lists and the projection variants."""
+    g = np.random.default_rng(4000 + seed)
+    D = int(g.choice([64, 128]))
+    Hkv = int(g.choice([1, 2, 4]))
+    G = int(g.choice([1, 2, 4]))
+    while ((G + 2) * Hkv * D) % 128:
+        Hkv += 1
+    Hq = G * Hkv
+    H = int(g.choice([128, 256, 384]))
+    F = int(g.choice([64, 192, 448, 640]))
+    batch = int(g.integers(1, 4))
+    t_fresh = int(g.choice([1, 3, 20, 33, 64, 70, 100, 130]))
+    n_chunks = int(g.integers(0, 4))
+    C = int(g.choice([64, 128]))
+    w = wl.make_prefill(f"blk{seed}", 4100 + seed, "bf16", H, Hq, Hkv, D, batch, t_fresh, n_chunks, C, 6)
+    if n_chunks:
+        w.used_len[:] = g.integers(1, C + 1, size=(batch, n_chunks))
+    W = wl.stack_weights(4100 + seed, 0, H, Hq, Hkv, D, F)
+    layer = dev_layers([W])[0]
+    extras = None
+    if seed % 3 == 0:
+        n_out = (Hq + 2 * Hkv) * D
+        bias = wl.round_bf16(0.5 * g.standard_normal(n_out).astype(np.float32))
+        qg = wl.round_bf16(1 + 0.2 * g.standard_normal(D).astype(np.float32))
+        kg = wl.round_bf16(1 + 0.2 * g.standard_normal(D).astype(np.float32))
+        layer.update(qkv_bias=bf16(bias), q_norm=bf16(qg), k_norm=bf16(kg))
+        extras = dict(bias=bias, q_gain=qg, k_gain=kg, eps=EPS)
+    pc = Percache(n_layers=1, hidden=H, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=D, n_slots=6, slot_capacity=C,
+                  max_pos=w.max_pos, device=DEV)
+    for s_ in sorted(set(int(x) for x in w.slot_ids.reshape(-1))):
+        k, v = w.slot_kv(s_)
+        pc.percache_kv_put(0, s_, bf16(k), bf16(v))
+    h_out = pc.percache_stack_reuse([layer], F, EPS, bf16(w.X), w.slot_ids if n_chunks else None, w.used_len if n_chunks else None)
+    torch.cuda.synchronize()
+    for b in range(batch):
+        sk, sv, ids = w.compact_store(b)
+        ref, _, _ = oracle_block(w.X[b], W, Hq, Hkv, D, w.rope_theta, sk, sv, ids, w.used_len[b], extras=extras)
+        check_hidden(host(h_out[b]), ref, f"seed {seed}: D={D} Hq={Hq} Hkv={Hkv} H={H} F={F} B={batch} T={t_fresh} chunks={n_chunks}x{C} variants={extras is not None} b={b}")
+
+
 def test_kv_slice_round_trip_and_errors():
     Hkv, D, C, T = 2, 64, 64, 150
     pc = Percache(n_layers=2, hidden=256, n_q_heads=4, n_kv_heads=Hkv, head_dim=D, n_slots=8, slot_capacity=C,
