@@ -43,9 +43,9 @@ def test_kv_append_equals_put_of_the_concatenation():
     assert torch.equal(a0, a1)
 
 
-@pytest.mark.parametrize("batch", [1, 3])
-def test_decode_steps_match_full_prefill(batch):
-    H, Hq, Hkv, D, F, L, C = 256, 4, 2, 64, 384, 2, 64
+@pytest.mark.parametrize("batch,D,Hq", [(1, 64, 4), (3, 64, 4), (2, 128, 8), (1, 128, 2)])
+def test_decode_steps_match_full_prefill(batch, D, Hq):
+    H, Hkv, F, L, C = 256, 2, 384, 2, 64
     n_c, t_prompt, n_steps = 2, 20, 6
     Ws = [wl.stack_weights(31, l, H, Hq, Hkv, D, F) for l in range(L)]
     layers = dev_layers(Ws)
