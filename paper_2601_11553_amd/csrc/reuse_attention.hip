@@ -694,7 +694,11 @@ pc_status launch_attention(percache_ctx *ctx, int layer, const __bf16 *q, const 
   // tile between them.  (Over bf16 slots such a step is bound by the key stream already, and the 4-wavefront kernel
   // with its three loader wavefronts measures 3 % faster.)
   const bool few = R <= 32 && c.kv_fp8;
-  const int qrows = few ? 32 : wide ? 256 : 128;
+  // few workgroups for the whole chip (one or two short queries): 64-row workgroups whose wavefront pairs halve every
+  // tile between them -- twice the workgroups, half the dependent chain per tile
+  const bool halved = !wide && !few && !c.kv_fp8 && c.head_dim == 128 && R > 32 &&
+                      (long)batch * c.n_kv_heads * ((R + 63) / 64) * 4 <= ctx->n_cu;
+  const int qrows = few ? 32 : wide ? 256 : halved ? 64 : 128;
   const int q_tiles = (R + qrows - 1) / qrows;
   const int cap = max_splits_for(c, ctx->n_cu, batch, t_fresh);
   if (n_splits <= 0) n_splits = choose_splits(wide ? ctx->n_cu : 2 * ctx->n_cu, (long)batch * c.n_kv_heads * q_tiles, min_tiles, cap);
@@ -726,7 +730,7 @@ pc_status launch_attention(percache_ctx *ctx, int layer, const __bf16 *q, const 
       if (few) PC_ATTN(64, 2, 2, true, 2); else PC_ATTN(64, 4, 2, true);
     }
   } else if (c.head_dim == 128) {
-    if (wide) PC_ATTN(128, 8, 2); else PC_ATTN(128, 4, 2);
+    if (wide) PC_ATTN(128, 8, 2); else if (halved) PC_ATTN(128, 4, 2, false, 2); else PC_ATTN(128, 4, 2);
   } else {
     if (wide) PC_ATTN(64, 8, 4); else PC_ATTN(64, 4, 4);
   }
