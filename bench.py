@@ -266,6 +266,26 @@ def main():
             look[f"P{p}"] = {"ms": round(t * 1e3, 4), "lookups_per_s": round(p / t, 1), "bound": "mfma", "TFLOPs": round(tf, 1),
                              "frac_of_fp16_peak": round(tf / PEAK_BF16_TFLOPS, 4)}
 
+    # ------------------------------------------------------------------ top-k ranking and the cache refresh scan (same bank)
+    def wall(fn, iters=20):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        a = time.perf_counter()
+        for _ in range(iters):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - a) / iters
+
+    p8 = probes_all[:8].contiguous()
+    t_topk = wall(lambda: pc.percache_lookup_topk(p8, 8))
+    new64 = probes_all[64:128].contiguous()               # 64 "new chunk" embeddings against every stored row
+    kth = torch.full((N,), 0.5, dtype=torch.float32, device=dev)
+    t_scan = wall(lambda: pc.percache_bank_refresh_scan(new64, kth), iters=10)
+    look["topk_P8_k8"] = {"ms": round(t_topk * 1e3, 4), "bank_GBps": round(bank_bytes / t_topk / 1e9, 1)}
+    look["refresh_scan_64_new"] = {"ms": round(t_scan * 1e3, 4), "passes_of_the_bank": 2,
+                                   "bank_GBps": round(2 * bank_bytes / t_scan / 1e9, 1)}
+
     # ------------------------------------------------------------------ one decoding step of the same layer
     # (one new token per query over the 16 reused chunks + the 256-token prompt slot written by the step above)
     x1 = X[:, :1].contiguous()

@@ -190,9 +190,13 @@ __global__ __launch_bounds__(256) void lookup_stream_kernel(const _Float16 *__re
   TopK<KL> best[NPB];  // this lane's best rows for probe pb*16 + r16
 #pragma unroll
   for (int pb = 0; pb < NPB; ++pb) best[pb].clear();
-  float pinv[NPB];     // per-row mode: inverse norm of this lane's probes (-inf marks padding probes)
+  // per-row mode: the product is taken the other way round (probes on the M side), so a lane holds ONE row (r16) and
+  // the probes pb*16 + 4g + 0..3; their inverse norms (-inf marks padding probes)
+  float pinv[NPB][4];
 #pragma unroll
-  for (int pb = 0; pb < NPB; ++pb) pinv[pb] = (K == 0 && pb * 16 + r16 < n_probes) ? rs.probe_inv[pb * 16 + r16] : -INFINITY;
+  for (int pb = 0; pb < NPB; ++pb)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) pinv[pb][e] = (K == 0 && pb * 16 + g * 4 + e < n_probes) ? rs.probe_inv[pb * 16 + g * 4 + e] : -INFINITY;
 
   // load instruction i of a stage: lane lands at stage byte 1024 i + 16 lane = (row, physical chunk)
   int ld_row[IPS], ld_col[IPS];
@@ -230,44 +234,53 @@ __global__ __launch_bounds__(256) void lookup_stream_kernel(const _Float16 *__re
 #pragma unroll
       for (int pb = 0; pb < NPB; ++pb) {
         f16x8 bv = *(const f16x8 *)(pbase + (size_t)pb * 16 * row_bytes + s * 64);
-        acc[pb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, acc[pb], 0, 0, 0);
+        // (both operands have the same lane layout -- index lane%16, elements 8*(lane/16).. -- so swapping them
+        // transposes the result: lane holds row r16 and probes 4g + 0..3)
+        acc[pb] = K == 0 ? __builtin_amdgcn_mfma_f32_16x16x32_f16(bv, av, acc[pb], 0, 0, 0)
+                         : __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, acc[pb], 0, 0, 0);
       }
     }
   };
   // scale by the rows' inverse norms and keep the running best list (the lowest row wins ties)
   auto epilogue = [&](int rb) __attribute__((always_inline)) {
-    const f32x4 inv4 = *(const f32x4 *)(inv_lds + (rb - rb_begin) * 16 + g * 4);
+    if (K > 0) {
+      const f32x4 inv4 = *(const f32x4 *)(inv_lds + (rb - rb_begin) * 16 + g * 4);
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int row = rb * 16 + g * 4 + r;
-      const bool ok = row < N;
-      if (K > 0) {
+      for (int r = 0; r < 4; ++r) {
+        const int row = rb * 16 + g * 4 + r;
+        const bool ok = row < N;
 #pragma unroll
         for (int pb = 0; pb < NPB; ++pb) {
           const float s = acc[pb][r] * inv4[r];
           if (ok) best[pb].insert(s, row);
         }
-      } else {
-        // best probe of this row: this lane's probes first, then the 16 lanes that hold the row (lowest probe wins ties)
-        float s = -INFINITY;
-        int pi = INT_MAX;
+      }
+    } else {
+      // best probe of row r16: this lane's probes first (ascending, so the lowest wins ties), then the four lanes
+      // that hold the row
+      const int row = rb * 16 + r16;
+      const float inv = inv_lds[(rb - rb_begin) * 16 + r16];
+      float s = -INFINITY;
+      int pi = INT_MAX;
 #pragma unroll
-        for (int pb = 0; pb < NPB; ++pb) {
-          const float c = pinv[pb] == -INFINITY ? -INFINITY : acc[pb][r] * inv4[r] * pinv[pb];
-          if (better(c, rs.p0 + pb * 16 + r16, s, pi)) { s = c; pi = rs.p0 + pb * 16 + r16; }
+      for (int pb = 0; pb < NPB; ++pb)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float c = pinv[pb][e] == -INFINITY ? -INFINITY : acc[pb][e] * inv * pinv[pb][e];
+          const int p = rs.p0 + pb * 16 + g * 4 + e;
+          if (better(c, p, s, pi)) { s = c; pi = p; }
         }
 #pragma unroll
-        for (int o = 1; o < 16; o <<= 1) {
-          const float s2 = __shfl_xor(s, o, 64);
-          const int p2 = __shfl_xor(pi, o, 64);
-          if (better(s2, p2, s, pi)) { s = s2; pi = p2; }
-        }
-        if (ok && r16 == 0) {
-          if (!rs.first && !better(s, pi, rs.best_sim[row], rs.best_new[row])) { s = rs.best_sim[row]; pi = rs.best_new[row]; }
-          rs.best_sim[row] = s;
-          rs.best_new[row] = pi;
-          rs.stale[row] = s > rs.kth[row] ? 1 : 0;
-        }
+      for (int o = 16; o < 64; o <<= 1) {
+        const float s2 = __shfl_xor(s, o, 64);
+        const int p2 = __shfl_xor(pi, o, 64);
+        if (better(s2, p2, s, pi)) { s = s2; pi = p2; }
+      }
+      if (row < N && g == 0) {
+        if (!rs.first && !better(s, pi, rs.best_sim[row], rs.best_new[row])) { s = rs.best_sim[row]; pi = rs.best_new[row]; }
+        rs.best_sim[row] = s;
+        rs.best_new[row] = pi;
+        rs.stale[row] = s > rs.kth[row] ? 1 : 0;
       }
     }
   };
