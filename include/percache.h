@@ -57,6 +57,9 @@ typedef struct {
   int32_t bank_capacity; /* N_max: rows of the query-embedding bank (0 = no bank) */
   int32_t emb_dim;       /* d: embedding width */
   int32_t kv_fp8;        /* 0: slots hold bf16.  1: slots hold 8-bit codes, half the bytes (see "8-bit slots" below) */
+  int32_t n_slots_8bit;  /* with kv_fp8 = 0: the LAST n_slots_8bit of the n_slots slots hold 8-bit codes, the others bf16
+                            (a store of two organisations: which chunk goes where is the caller's choice by slot id);
+                            must be 0 with kv_fp8 = 1 */
 } percache_config;
 
 /* Bytes of device memory the caller must provide for a context of this shape (0 on a bad
@@ -116,7 +119,7 @@ pc_status percache_bank_refresh_scan(percache_ctx *ctx, const void *new_emb_dev,
                                      uint8_t *stale_out_dev, void *workspace_dev, size_t workspace_bytes,
                                      void *stream);
 
-/* ---------------------------------------------------------------- 8-bit slots (kv_fp8 = 1)
+/* ---------------------------------------------------------------- 8-bit slots (kv_fp8 = 1, or the last n_slots_8bit slots)
  * The paper keeps the chunks' complete tensors (Sec. 4.1.1) and leaves other cache organisations to future work
  * (Sec. 7); this is a smaller slot for the same tensors.  An element is stored as an E4M3 code of the OCP 8-bit
  * floating point specification (1 sign, 4 exponent bits with bias 7, 3 mantissa bits, largest magnitude 448, no
@@ -126,7 +129,11 @@ pc_status percache_bank_refresh_scan(percache_ctx *ctx, const void *new_emb_dev,
  * representable in bf16.  percache_kv_put / _put_batch / _slice and the save slots of percache_stack_reuse quantise;
  * percache_kv_get returns the values read back; the attention calls read them on the fly (fresh K/V stay bf16).
  * percache_kv_append (and the decoding steps that use it): everything from the block that holds the first new token
- * on is quantised afresh from the values the slot reads back plus the new tokens; full blocks before it stay. */
+ * on is quantised afresh from the values the slot reads back plus the new tokens; full blocks before it stay.
+ * A store of both organisations (n_slots_8bit > 0 with kv_fp8 = 0; Sec. 7 names "different tensor components for
+ * different knowledge chunks" as the direction): slot ids below n_slots - n_slots_8bit are bf16 slots, the others 8-bit
+ * slots.  Every call treats each slot by its own format; one chunk list, one batched put or one list of save slots may
+ * name slots of both kinds. */
 
 /* ---------------------------------------------------------------- K/V store (Sec. 4.1.1)
  * One slot holds one knowledge chunk's K and V for one layer, as collected from the attention

@@ -47,6 +47,7 @@ class Config(ctypes.Structure):
         ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32), ("n_slots", ctypes.c_int32),
         ("slot_capacity", ctypes.c_int32), ("max_pos", ctypes.c_int32), ("rope_theta", ctypes.c_float),
         ("bank_capacity", ctypes.c_int32), ("emb_dim", ctypes.c_int32), ("kv_fp8", ctypes.c_int32),
+        ("n_slots_8bit", ctypes.c_int32),
     ]
 
 
@@ -138,11 +139,11 @@ class Percache:
 
     def __init__(self, *, n_layers=1, hidden=1024, n_q_heads=16, n_kv_heads=8, head_dim=128, n_slots=16,
                  slot_capacity=512, max_pos=4096, rope_theta=10000.0, bank_capacity=0, emb_dim=0, kv_fp8=False,
-                 device="cuda:0"):
+                 n_slots_8bit=0, device="cuda:0"):
         import torch
         self.lib = load_library()
         self.cfg = Config(n_layers, hidden, n_q_heads, n_kv_heads, head_dim, n_slots, slot_capacity, max_pos,
-                          rope_theta, bank_capacity, emb_dim, int(bool(kv_fp8)))
+                          rope_theta, bank_capacity, emb_dim, int(bool(kv_fp8)), int(n_slots_8bit))
         self.device = torch.device(device)
         need = self.lib.percache_arena_bytes(ctypes.byref(self.cfg))
         if need == 0:

@@ -440,6 +440,7 @@ static pc_status run_stack(percache_ctx *ctx, const percache_block_weights *laye
     if (st != PC_OK) return st;
     if (rows_l != rows) return pc::fail(ctx, PC_ELEN, "the chunks' stored lengths differ between layer 0 and layer %d", l);
   }
+  const int formats = pc::table_formats(rows, pc::tbl_stride(max_chunks), batch);
   const long M = (long)batch * t_fresh;
   if (M * (long)(ffn > c.hidden ? ffn : c.hidden) >= (1L << 31)) return pc::fail(ctx, PC_ESHAPE, "activation larger than 2^31 elements");
   for (int b = 0; b < batch && n_save > 0; ++b) {
@@ -490,7 +491,7 @@ static pc_status run_stack(percache_ctx *ctx, const percache_block_weights *laye
                                skinny ? ws.pf.gemm_part : nullptr, extras, ws.pf.v_blk, &v_blocked));
     if (!v_blocked) PC_TRY(pc::launch_v_repack(ctx, ws.pf.v, ws.pf.v_blk, batch, t_fresh, s));
     PC_TRY(pc::launch_attention(ctx, l, ws.pf.q, ws.pf.k, ws.pf.v_blk, batch, t_fresh, ws.pf.table, stride, min_tiles, 0, ws.attn,
-                                ws.pf.part_o, ws.pf.part_ml, s));
+                                ws.pf.part_o, ws.pf.part_ml, s, formats));
     for (int b = 0; b < batch && n_save > 0; ++b)
       for (int j = 0; j < n_save; ++j) {
         const int slot = save_slots_host[(size_t)b * n_save + j];

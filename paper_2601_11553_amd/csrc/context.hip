@@ -22,13 +22,15 @@ bool config_ok(const percache_config *c, std::string &why) {
     return bad("emb_dim must be a multiple of 64 in [64, 2048]");
   if (!(c->rope_theta > 1.0f)) return bad("rope_theta must exceed 1");
   if (c->kv_fp8 != 0 && c->kv_fp8 != 1) return bad("kv_fp8 must be 0 or 1");
+  if (c->n_slots_8bit < 0 || c->n_slots_8bit > c->n_slots) return bad("n_slots_8bit must lie in [0, n_slots]");
+  if (c->kv_fp8 && c->n_slots_8bit) return bad("n_slots_8bit must be 0 when every slot is 8-bit (kv_fp8 = 1)");
   if (((c->n_q_heads + 2 * c->n_kv_heads) * c->head_dim) % 128) return bad("(n_q_heads + 2 n_kv_heads) * head_dim must be a multiple of 128");
   (void)buf;
   return true;
 }
 
 struct Layout {
-  size_t rope, bank, bank_inv, k_store, v_store, k_scale, v_scale, total;
+  size_t rope, bank, bank_inv, k_store, v_store, k8_store, v8_store, k_scale, v_scale, total;
 };
 Layout layout_of(const percache_config &c) {
   Layout l;
@@ -39,12 +41,17 @@ Layout layout_of(const percache_config &c) {
   off += pc::align_up((size_t)c.bank_capacity * (size_t)(c.bank_capacity ? c.emb_dim : 0) * 2);
   l.bank_inv = off;
   off += pc::align_up((size_t)c.bank_capacity * sizeof(float));
-  size_t store = (size_t)c.n_layers * c.n_slots * c.n_kv_heads * c.slot_capacity * c.head_dim * (c.kv_fp8 ? 1 : 2);
+  const size_t n8 = c.kv_fp8 ? c.n_slots : c.n_slots_8bit, n16 = c.n_slots - n8;
+  const size_t per_slot = (size_t)c.n_layers * c.n_kv_heads * c.slot_capacity * c.head_dim;
   l.k_store = off;
-  off += pc::align_up(store);
+  off += pc::align_up(n16 * per_slot * 2);
   l.v_store = off;
-  off += pc::align_up(store);
-  size_t scales = c.kv_fp8 ? (size_t)c.n_layers * c.n_slots * c.n_kv_heads * (c.slot_capacity / pc::kKvTile) * sizeof(float) : 0;
+  off += pc::align_up(n16 * per_slot * 2);
+  l.k8_store = off;
+  off += pc::align_up(n8 * per_slot);
+  l.v8_store = off;
+  off += pc::align_up(n8 * per_slot);
+  size_t scales = (size_t)c.n_layers * n8 * c.n_kv_heads * (c.slot_capacity / pc::kKvTile) * sizeof(float);
   l.k_scale = off;
   off += pc::align_up(scales);
   l.v_scale = off;
@@ -90,6 +97,7 @@ pc_status build_chunk_table(percache_ctx *ctx, int32_t layer, int32_t batch, int
       if (used < 0 || used > stored) return fail(ctx, PC_ELEN, "query %d chunk %d: used length %d outside [0,%d]", b, ci, used, stored);
       row[kTblHeader + 2 * ci] = slot;
       row[kTblHeader + 2 * ci + 1] = used;
+      if (used > 0) row[3] |= ctx->is8(slot) ? 1 : 2;
       l_pre += used;
       tiles += (used + kKvTile - 1) / kKvTile;
     }
@@ -191,17 +199,17 @@ pc_status percache_create(const percache_config *cfg, void *arena_dev, size_t ar
   ctx->rope = (float *)(ctx->arena + l.rope);
   ctx->bank = (_Float16 *)(ctx->arena + l.bank);
   ctx->bank_inv = (float *)(ctx->arena + l.bank_inv);
-  if (cfg->kv_fp8) {
-    ctx->k8_store = (uint8_t *)(ctx->arena + l.k_store);
-    ctx->v8_store = (uint8_t *)(ctx->arena + l.v_store);
-    ctx->k_scale = (float *)(ctx->arena + l.k_scale);
-    ctx->v_scale = (float *)(ctx->arena + l.v_scale);
-  } else {
-    ctx->k_store = (__bf16 *)(ctx->arena + l.k_store);
-    ctx->v_store = (__bf16 *)(ctx->arena + l.v_store);
-  }
+  ctx->n_slots8 = cfg->kv_fp8 ? cfg->n_slots : cfg->n_slots_8bit;
+  ctx->n_slots16 = cfg->n_slots - ctx->n_slots8;
+  ctx->k_store = (__bf16 *)(ctx->arena + l.k_store);
+  ctx->v_store = (__bf16 *)(ctx->arena + l.v_store);
+  ctx->k8_store = (uint8_t *)(ctx->arena + l.k8_store);
+  ctx->v8_store = (uint8_t *)(ctx->arena + l.v8_store);
+  ctx->k_scale = (float *)(ctx->arena + l.k_scale);
+  ctx->v_scale = (float *)(ctx->arena + l.v_scale);
   ctx->slot_stride = (size_t)cfg->n_kv_heads * cfg->slot_capacity * cfg->head_dim;
-  ctx->layer_stride = ctx->slot_stride * cfg->n_slots;
+  ctx->layer_stride = ctx->slot_stride * ctx->n_slots16;
+  ctx->layer_stride8 = ctx->slot_stride * ctx->n_slots8;
   ctx->slot_len.assign((size_t)cfg->n_layers * cfg->n_slots, 0);
 
   auto bail = [&](hipError_t e, const char *what) {

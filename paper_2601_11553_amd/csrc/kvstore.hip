@@ -25,6 +25,7 @@ __global__ __launch_bounds__(256) void kv_copy_kernel(pc::u32x4 *__restrict__ sl
                                                       long slot_stride_elems, long dense_head_stride) {
   // blockIdx.z selects the chunk: its slot and its dense tensor.  dense_head_stride: elements between the heads of
   // a dense tensor (n_tok * D when the chunk is a tensor of its own, more when it is a token range of a longer one)
+  if (slots.slot[blockIdx.z] < 0) return;  // (an entry of the other slot format: the other launch copies it)
   {
     const long so = (long)slots.slot[blockIdx.z] * slot_stride_elems;
     const long dn = (long)blockIdx.z * n_heads * dense_head_stride;
@@ -158,6 +159,7 @@ __global__ __launch_bounds__(256) void kv_quant_kernel(uint8_t *__restrict__ slo
   __shared__ __align__(16) uint8_t vt[kKvTile][D + 16];  // V codes [key][d] (padded rows), read back transposed
   const int blk = blockIdx.x + off / kKvTile, g = blockIdx.y, tid = threadIdx.x;
   const int slot = slots.slot[blockIdx.z];
+  if (slot < 0) return;  // (a bf16 slot: the other launch copies it; the whole workgroup leaves)
   const size_t dense_at = ((size_t)blockIdx.z * n_heads + g) * dense_head_stride;
   const size_t slot_at = (size_t)slot * slot_stride_elems + (size_t)g * C * D;
   const size_t sc = (size_t)slot * scale_slot_stride + (size_t)g * (C / kKvTile) + blk;
@@ -248,6 +250,7 @@ __global__ __launch_bounds__(256) void kv_dequant_kernel(const uint8_t *__restri
   constexpr int DV = D / 8, NV = kKvTile * DV / 256;
   const int blk = blockIdx.x, g = blockIdx.y, tid = threadIdx.x;
   const int slot = slots.slot[blockIdx.z];
+  if (slot < 0) return;
   const size_t dense_at = ((size_t)blockIdx.z * n_heads + g) * dense_head_stride;
   const size_t slot_at = (size_t)slot * slot_stride_elems + (size_t)g * C * D;
   const size_t sc = (size_t)slot * scale_slot_stride + (size_t)g * (C / kKvTile) + blk;
@@ -290,21 +293,29 @@ pc_status check_slot(percache_ctx *ctx, int32_t layer, int32_t slot) {
   return PC_OK;
 }
 
+// Copies between dense tensors and the slots of a list (at most 64 entries; entry i <-> dense block i).  A list may
+// name slots of both formats: each format gets its own launch, in which the entries of the other format are marked -1.
 template <bool kToStore>
 pc_status launch_copy(percache_ctx *ctx, int layer, const int32_t *slot_list, int n, void *k_dev, void *v_dev, int n_tokens,
                       hipStream_t stream, long dense_head_stride = 0) {
   const percache_config &c = ctx->cfg;
-  size_t off = (size_t)layer * ctx->layer_stride;
-  SlotList sl;
-  for (int i = 0; i < 64; ++i) sl.slot[i] = i < n ? slot_list[i] : 0;
-  if (c.kv_fp8) {
+  SlotList sl16, sl8;
+  int n16 = 0, n8 = 0;
+  for (int i = 0; i < 64; ++i) {
+    sl16.slot[i] = sl8.slot[i] = -1;
+    if (i >= n) continue;
+    if (ctx->is8(slot_list[i])) { sl8.slot[i] = slot_list[i] - ctx->n_slots16; ++n8; }
+    else { sl16.slot[i] = slot_list[i]; ++n16; }
+  }
+  const long dhs = dense_head_stride ? dense_head_stride : (long)n_tokens * c.head_dim;
+  if (n8) {
+    const size_t off = (size_t)layer * ctx->layer_stride8;
     const long sc_slot = (long)c.n_kv_heads * (c.slot_capacity / kKvTile);
-    const size_t sc_off = (size_t)layer * c.n_slots * sc_slot;
-    const long dhs = dense_head_stride ? dense_head_stride : (long)n_tokens * c.head_dim;
+    const size_t sc_off = (size_t)layer * ctx->n_slots8 * sc_slot;
     dim3 grid((n_tokens + kKvTile - 1) / kKvTile, c.n_kv_heads, n);
 #define PC_KV8(KERNEL, DD)                                                                                                    \
   hipLaunchKernelGGL((KERNEL<DD>), grid, dim3(256), 0, stream, ctx->k8_store + off, ctx->v8_store + off, ctx->k_scale + sc_off, \
-                     ctx->v_scale + sc_off, (__bf16 *)k_dev, (__bf16 *)v_dev, c.n_kv_heads, n_tokens, c.slot_capacity, sl,      \
+                     ctx->v_scale + sc_off, (__bf16 *)k_dev, (__bf16 *)v_dev, c.n_kv_heads, n_tokens, c.slot_capacity, sl8,     \
                      (long)ctx->slot_stride, sc_slot, dhs, 0)
     if (kToStore) {
       if (c.head_dim == 128) PC_KV8(kv_quant_kernel, 128); else PC_KV8(kv_quant_kernel, 64);
@@ -313,16 +324,17 @@ pc_status launch_copy(percache_ctx *ctx, int layer, const int32_t *slot_list, in
     }
 #undef PC_KV8
     PC_HIP(ctx, hipGetLastError());
-    return PC_OK;
   }
-  long total = (long)c.n_kv_heads * ((n_tokens + kKvTile - 1) / kKvTile) * kKvTile * c.head_dim / 8;
-  int blocks = (int)((total + 255) / 256);
-  if (blocks > 2048) blocks = 2048;
-  hipLaunchKernelGGL(kv_copy_kernel<kToStore>, dim3(blocks, 2, n), dim3(256), 0, stream, (pc::u32x4 *)(ctx->k_store + off),
-                     ctx->v_store + off, (pc::u32x4 *)k_dev, (__bf16 *)v_dev, c.n_kv_heads, n_tokens, c.head_dim,
-                     c.slot_capacity, sl, (long)ctx->slot_stride,
-                     dense_head_stride ? dense_head_stride : (long)n_tokens * c.head_dim);
-  PC_HIP(ctx, hipGetLastError());
+  if (n16) {
+    const size_t off = (size_t)layer * ctx->layer_stride;
+    long total = (long)c.n_kv_heads * ((n_tokens + kKvTile - 1) / kKvTile) * kKvTile * c.head_dim / 8;
+    int blocks = (int)((total + 255) / 256);
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(kv_copy_kernel<kToStore>, dim3(blocks, 2, n), dim3(256), 0, stream, (pc::u32x4 *)(ctx->k_store + off),
+                       ctx->v_store + off, (pc::u32x4 *)k_dev, (__bf16 *)v_dev, c.n_kv_heads, n_tokens, c.head_dim,
+                       c.slot_capacity, sl16, (long)ctx->slot_stride, dhs);
+    PC_HIP(ctx, hipGetLastError());
+  }
   return PC_OK;
 }
 
@@ -336,11 +348,11 @@ pc_status launch_kv_store(percache_ctx *ctx, int layer, int slot, const __bf16 *
 pc_status launch_kv_append(percache_ctx *ctx, int layer, int slot, const __bf16 *k, const __bf16 *v, int off, int n_tokens,
                            long new_head_stride, hipStream_t stream) {
   const percache_config &c = ctx->cfg;
-  if (c.kv_fp8) {
+  if (ctx->is8(slot)) {
     const long sc_slot = (long)c.n_kv_heads * (c.slot_capacity / kKvTile);
-    const size_t lo = (size_t)layer * ctx->layer_stride, sc_off = (size_t)layer * c.n_slots * sc_slot;
+    const size_t lo = (size_t)layer * ctx->layer_stride8, sc_off = (size_t)layer * ctx->n_slots8 * sc_slot;
     SlotList sl;
-    for (int i = 0; i < 64; ++i) sl.slot[i] = i == 0 ? slot : 0;
+    for (int i = 0; i < 64; ++i) sl.slot[i] = i == 0 ? slot - ctx->n_slots16 : -1;
     const int total = off + n_tokens;
     dim3 grid((total + kKvTile - 1) / kKvTile - off / kKvTile, c.n_kv_heads, 1);
     if (c.head_dim == 128)

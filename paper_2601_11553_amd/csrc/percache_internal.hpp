@@ -44,7 +44,8 @@ __host__ __device__ inline int blocked_pos8(int key) {  // the inverse: the byte
 }
 
 // Device chunk table, one row per query (int32):
-//   [0] n_chunks  [1] L_pre  [2] cached tiles (sum over chunks of ceil(used/kKvTile))  [3] unused
+//   [0] n_chunks  [1] L_pre  [2] cached tiles (sum over chunks of ceil(used/kKvTile))
+//   [3] formats of the chunks with keys: bit 0 = some sit in 8-bit slots, bit 1 = some in bf16 slots
 //   [4 + 2c] slot id of chunk c   [5 + 2c] used length of chunk c
 constexpr int kTblHeader = 4;
 inline int tbl_stride(int max_chunks) { return kTblHeader + 2 * (max_chunks > 0 ? max_chunks : 0); }
@@ -61,12 +62,15 @@ struct percache_ctx {
   float *rope = nullptr;      // [max_pos][D/2] float2 (cos, sin)
   _Float16 *bank = nullptr;   // [bank_capacity][emb_dim]
   float *bank_inv = nullptr;  // [bank_capacity]
-  __bf16 *k_store = nullptr;  // [n_layers][n_slots][Hkv][C][D]   (bf16 slots; null with 8-bit slots)
+  __bf16 *k_store = nullptr;  // [n_layers][n_slots16][Hkv][C][D]   (bf16 slots)
   __bf16 *v_store = nullptr;  // same
-  uint8_t *k8_store = nullptr, *v8_store = nullptr;  // 8-bit slots: the same shapes in bytes
-  float *k_scale = nullptr, *v_scale = nullptr;      // 8-bit slots: 2^e per [n_layers][n_slots][Hkv][C/64]
-  size_t layer_stride = 0;    // elements per layer of one store
+  uint8_t *k8_store = nullptr, *v8_store = nullptr;  // 8-bit slots: [n_layers][n_slots8][Hkv][C][D] bytes
+  float *k_scale = nullptr, *v_scale = nullptr;      // 8-bit slots: 2^e per [n_layers][n_slots8][Hkv][C/64]
+  size_t layer_stride = 0;    // elements per layer of the bf16 store (n_slots16 slots)
+  size_t layer_stride8 = 0;   // bytes per layer of the 8-bit store (n_slots8 slots)
   size_t slot_stride = 0;     // elements per slot
+  int n_slots16 = 0, n_slots8 = 0;  // slots [0, n_slots16) hold bf16, slots [n_slots16, n_slots) 8-bit codes
+  bool is8(int slot) const { return slot >= n_slots16; }
   int32_t bank_size = 0;
   std::vector<int32_t> slot_len;  // [n_layers * n_slots], 0 = empty
   // pinned staging ring for chunk tables (host -> workspace copies ordered on the stream)
@@ -148,9 +152,15 @@ int choose_split_k(int n_cu, int n_tiles, int k_steps);
 pc_status launch_splitk_partial(percache_ctx *ctx, const __bf16 *a, int lda, const __bf16 *w0, const __bf16 *w1, int n_split,
                                 int ldw, float *part, int M, int N, int K, int n_k, hipStream_t stream);
 pc_status launch_v_repack(percache_ctx *ctx, const __bf16 *vf, __bf16 *vf_blk, int batch, int t_fresh, hipStream_t stream);
+// formats: which slot formats the call's chunks sit in (see table_formats): bit 0 = 8-bit, bit 1 = bf16
 pc_status launch_attention(percache_ctx *ctx, int layer, const __bf16 *q, const __bf16 *kf, const __bf16 *vf_blk,
                            int batch, int t_fresh, const int32_t *table_dev, int tbl_stride, int max_tiles,
-                           int n_splits, __bf16 *out, __bf16 *part_o, float *part_ml, hipStream_t stream);
+                           int n_splits, __bf16 *out, __bf16 *part_o, float *part_ml, hipStream_t stream, int formats);
+inline int table_formats(const std::vector<int32_t> &rows, int stride, int batch) {
+  int f = 0;
+  for (int b = 0; b < batch; ++b) f |= rows[(size_t)b * stride + 3];
+  return f;
+}
 
 // Copies n_tokens tokens of a dense [Hkv][.][D] tensor whose heads are dense_head_stride elements apart into a
 // slot (no validation, no slot-table update).

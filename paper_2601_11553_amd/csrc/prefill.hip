@@ -90,7 +90,7 @@ pc_status percache_attention_reuse(percache_ctx *ctx, int32_t layer, const void 
   if (st != PC_OK) return st;
   return pc::launch_attention(ctx, layer, (const __bf16 *)q_dev, (const __bf16 *)k_fresh_dev, p.ws.v_blk,
                               batch, t_fresh, p.ws.table, p.tbl_stride, p.min_tiles, n_splits, (__bf16 *)attn_out_dev,
-                              p.ws.part_o, p.ws.part_ml, s);
+                              p.ws.part_o, p.ws.part_ml, s, pc::table_formats(rows, p.tbl_stride, batch));
 }
 
 pc_status percache_prefill_reuse(percache_ctx *ctx, int32_t layer, const void *x_fresh_dev, const void *wqkv_dev,
@@ -120,7 +120,7 @@ pc_status percache_prefill_reuse(percache_ctx *ctx, int32_t layer, const void *x
   if (!v_blocked) st = pc::launch_v_repack(ctx, vf, p.ws.v_blk, batch, t_fresh, s);
   if (st != PC_OK) return st;
   return pc::launch_attention(ctx, layer, p.ws.q, kf, p.ws.v_blk, batch, t_fresh, p.ws.table, p.tbl_stride, p.min_tiles, 0,
-                              (__bf16 *)attn_out_dev, p.ws.part_o, p.ws.part_ml, s);
+                              (__bf16 *)attn_out_dev, p.ws.part_o, p.ws.part_ml, s, pc::table_formats(rows, p.tbl_stride, batch));
 }
 
 }  // extern "C"

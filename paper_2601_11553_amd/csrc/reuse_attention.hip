@@ -80,11 +80,12 @@ __device__ __forceinline__ bf16x8 codes_to_bf16(unsigned w0, unsigned w1, float 
 // KSP = 2: two wavefronts share a 32-row block and take one 32-key block of every tile each (separate running
 // maximum / sum / output, merged through LDS at the end); for the cases with few rows per kv head, where the per-tile
 // chain of one wavefront, not the key stream, would set the pace.
-template <int D, int NW, int NSTAGE, bool KV8 = false, int KSP = 1>
+template <int D, int NW, int NSTAGE, bool KV8 = false, int KSP = 1, bool MIXED = false>
 __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
     const __bf16 *__restrict__ Q, const __bf16 *__restrict__ Kf, const __bf16 *__restrict__ Vf_blk,
     const void *__restrict__ k_store_any, const void *__restrict__ v_store_any, const float *__restrict__ k_scale,
-    const float *__restrict__ v_scale, const int32_t *__restrict__ table,
+    const float *__restrict__ v_scale, const __bf16 *__restrict__ k_store16, const __bf16 *__restrict__ v_store16, int n_slots16,
+    const int32_t *__restrict__ table,
     int tbl_stride, int T, int Hq, int Hkv, int C, int n_splits, int q_tiles, int n_groups, float scale_log2e,
     __bf16 *__restrict__ out, __bf16 *__restrict__ part_o, float *__restrict__ part_ml) {
   static_assert(!KV8 || NSTAGE == 2, "8-bit slots: two stages (the waits assume one tile in flight)");
@@ -256,25 +257,37 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
 #pragma unroll
     for (int J = 0; J < NKB; ++J) v8_rd[J] = ((2 * (kb0 + J) + g2) ^ swz8(V8_ROW, l32)) * 16;
   }
-  struct TileDesc { const __bf16 *k, *v; int valid; int t0; bool fresh; float ks, vs; };
+  // is8: the tile holds 8-bit codes (a chunk in an 8-bit slot); fresh tiles and chunks in bf16 slots are bf16 tiles.
+  // A context may hold slots of both formats: ids below n_slots16 are bf16 slots of k_store16 / v_store16.
+  struct TileDesc { const __bf16 *k, *v; int valid; int t0; bool fresh; bool is8; float ks, vs; };
   auto describe = [&](const Cursor &c, TileDesc &td) __attribute__((always_inline)) {
     if (c.chunk < n_chunks) {
-      size_t base = (((size_t)c.slot * Hkv + gkv) * C + (size_t)c.off * TK) * D;  // same offset in both layouts
+      // (no branch around the scale loads: a branch would make the wavefront wait for them here instead of at their
+      // first use, a tile later)
+      // MIXED: the call names chunks of both formats (else every chunk of a KV8 launch sits in an 8-bit slot, and the
+      // compiler keeps the bf16 path out of the cached part of the loop)
+      const bool is8 = KV8 && (!MIXED || c.slot >= n_slots16);
+      const int s = is8 ? c.slot - n_slots16 : c.slot;
+      const size_t base = (((size_t)s * Hkv + gkv) * C + (size_t)c.off * TK) * D;  // same offset in both layouts
       if (KV8) {
-        td.k = (const __bf16 *)(k8_store + base);
-        td.v = (const __bf16 *)(v8_store + base);
-        const size_t sc = ((size_t)c.slot * Hkv + gkv) * (C / TK) + c.off;
-        td.ks = k_scale[sc];
-        td.vs = v_scale[sc];
+        td.k = is8 ? (const __bf16 *)(k8_store + base) : k_store16 + base;
+        td.v = is8 ? (const __bf16 *)(v8_store + base) : v_store16 + base;
+        const size_t sc = is8 ? ((size_t)s * Hkv + gkv) * (C / TK) + c.off : 0;
+        const float lk = k_scale[sc], lv = v_scale[sc];
+        td.ks = is8 ? lk : 1.f;
+        td.vs = is8 ? lv : 1.f;
       } else {
         td.k = k_store + base;
         td.v = v_store + base;
+        td.ks = td.vs = 1.f;
       }
+      td.is8 = is8;
       td.valid = min(TK, c.used - c.off * TK);
       td.t0 = 0;
       td.fresh = false;
     } else {
       td.ks = td.vs = 1.f;
+      td.is8 = false;
       const int ft = (T + TK - 1) / TK;
       td.k = Kf + (((size_t)b * Hkv + gkv) * T + (size_t)c.off * TK) * D;
       td.v = Vf_blk + (((size_t)b * Hkv + gkv) * ft + c.off) * (size_t)(TK * D);
@@ -293,7 +306,7 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
   };
   auto fetch_tile = [&](const TileDesc &td, int st) __attribute__((always_inline)) {
     char *kb = lds + st * L::STAGE;
-    if (KV8 && !td.fresh) {
+    if (KV8 && td.is8) {
       const uint8_t *k8 = (const uint8_t *)td.k, *v8 = (const uint8_t *)td.v;
 #pragma unroll
       for (int k = 0; k < K8_INSTR; ++k)
@@ -374,8 +387,8 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
     for (int kbk = 0; kbk < NKB; ++kbk)
 #pragma unroll
       for (int r = 0; r < 16; ++r) s_acc[kbk][r] = 0.f;
-    const char *kbw = kb + kb0 * 32 * (KV8 && !td.fresh ? K8_ROW : L::K_ROW);  // this wavefront's key rows
-    if (KV8 && !td.fresh) {
+    const char *kbw = kb + kb0 * 32 * (KV8 && td.is8 ? K8_ROW : L::K_ROW);  // this wavefront's key rows
+    if (KV8 && td.is8) {
       // 8-bit tile: one 16-byte read per key block and pair of k-steps, turned into two bf16 operands
 #pragma unroll
       for (int h = 0; h < KS / 4; ++h) {
@@ -474,7 +487,7 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
     l_run += psum;
 
     // ---- O^T += V^T P^T, operands requested in batches of eight in the same way
-    if (KV8 && !td.fresh) {
+    if (KV8 && td.is8) {
 #pragma unroll
       for (int h = 0; h < NKB; ++h) {
         pc::u32x4 raw[DB];
@@ -682,21 +695,25 @@ pc_status launch_v_repack(percache_ctx *ctx, const __bf16 *vf, __bf16 *vf_blk, i
 
 pc_status launch_attention(percache_ctx *ctx, int layer, const __bf16 *q, const __bf16 *kf, const __bf16 *vf_blk,
                            int batch, int t_fresh, const int32_t *table_dev, int tbl_stride, int min_tiles,
-                           int n_splits, __bf16 *out, __bf16 *part_o, float *part_ml, hipStream_t stream) {
+                           int n_splits, __bf16 *out, __bf16 *part_o, float *part_ml, hipStream_t stream, int formats) {
   const percache_config &c = ctx->cfg;
   const int G = c.n_q_heads / c.n_kv_heads, R = G * t_fresh;
+  // the kernels that can read 8-bit tiles are taken only when the call names a chunk in an 8-bit slot, and their
+  // variant that tells the formats apart tile by tile only when it names chunks of both formats
+  const bool use8 = (formats & 1) && ctx->n_slots8 > 0;
+  const bool mixed = use8 && (formats & 2);
   // 8 wavefronts x 32 rows (one workgroup per CU) once a kv head has more than 128 stacked rows, else 4 wavefronts
   // (two workgroups per CU); two LDS stages at D = 128, four at D = 64.
   // 256-row workgroups only when there are enough of them to go round; few, short key ranges prefer more, smaller ones
   // (8-bit slots with D = 64: a tile is too small for eight wavefronts to load)
-  const bool wide = R > 128 && (long)batch * c.n_kv_heads * ((R + 255) / 256) * 4 >= ctx->n_cu && !(c.kv_fp8 && c.head_dim == 64);
+  const bool wide = R > 128 && (long)batch * c.n_kv_heads * ((R + 255) / 256) * 4 >= ctx->n_cu && !(use8 && c.head_dim == 64);
   // at most 32 rows per kv head (decoding steps) over 8-bit slots: two wavefronts share the rows and halve every
   // tile between them.  (Over bf16 slots such a step is bound by the key stream already, and the 4-wavefront kernel
   // with its three loader wavefronts measures 3 % faster.)
-  const bool few = R <= 32 && c.kv_fp8;
+  const bool few = R <= 32 && use8;
   // few workgroups for the whole chip (one or two short queries): 64-row workgroups whose wavefront pairs halve every
   // tile between them -- twice the workgroups, half the dependent chain per tile
-  const bool halved = !wide && !few && !c.kv_fp8 && c.head_dim == 128 && R > 32 &&
+  const bool halved = !wide && !few && !use8 && c.head_dim == 128 && R > 32 &&
                       (long)batch * c.n_kv_heads * ((R + 63) / 64) * 4 <= ctx->n_cu;
   const int qrows = few ? 32 : wide ? 256 : halved ? 64 : 128;
   const int q_tiles = (R + qrows - 1) / qrows;
@@ -705,15 +722,16 @@ pc_status launch_attention(percache_ctx *ctx, int layer, const __bf16 *q, const 
   if (n_splits > cap) n_splits = cap;
   const void *ks, *vs;
   const float *ksc = nullptr, *vsc = nullptr;
-  if (c.kv_fp8) {
-    ks = ctx->k8_store + (size_t)layer * ctx->layer_stride;
-    vs = ctx->v8_store + (size_t)layer * ctx->layer_stride;
-    const size_t sc_layer = (size_t)c.n_slots * c.n_kv_heads * (c.slot_capacity / TK);
+  const __bf16 *k16 = ctx->k_store + (size_t)layer * ctx->layer_stride, *v16 = ctx->v_store + (size_t)layer * ctx->layer_stride;
+  if (use8) {
+    ks = ctx->k8_store + (size_t)layer * ctx->layer_stride8;
+    vs = ctx->v8_store + (size_t)layer * ctx->layer_stride8;
+    const size_t sc_layer = (size_t)ctx->n_slots8 * c.n_kv_heads * (c.slot_capacity / TK);
     ksc = ctx->k_scale + (size_t)layer * sc_layer;
     vsc = ctx->v_scale + (size_t)layer * sc_layer;
   } else {
-    ks = ctx->k_store + (size_t)layer * ctx->layer_stride;
-    vs = ctx->v_store + (size_t)layer * ctx->layer_stride;
+    ks = k16;
+    vs = v16;
   }
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)c.head_dim);
   const int n_groups = batch * c.n_kv_heads * n_splits;
@@ -721,9 +739,15 @@ pc_status launch_attention(percache_ctx *ctx, int layer, const __bf16 *q, const 
   prof_begin(ctx, PC_KERNEL_ATTENTION, stream);
 #define PC_ATTN(DD, NWW, NS, ...)                                                                                     \
   hipLaunchKernelGGL((reuse_attention_kernel<DD, NWW, NS, ##__VA_ARGS__>), grid, dim3(64 * NWW), 0, stream, q, kf,     \
-                     vf_blk, ks, vs, ksc, vsc, table_dev, tbl_stride, t_fresh, c.n_q_heads, c.n_kv_heads,            \
+                     vf_blk, ks, vs, ksc, vsc, k16, v16, ctx->n_slots16, table_dev, tbl_stride, t_fresh, c.n_q_heads, c.n_kv_heads, \
                      c.slot_capacity, n_splits, q_tiles, n_groups, scale_log2e, out, part_o, part_ml)
-  if (c.kv_fp8) {
+  if (use8 && mixed) {
+    if (c.head_dim == 128) {
+      if (few) PC_ATTN(128, 2, 2, true, 2, true); else if (wide) PC_ATTN(128, 8, 2, true, 1, true); else PC_ATTN(128, 4, 2, true, 1, true);
+    } else {
+      if (few) PC_ATTN(64, 2, 2, true, 2, true); else PC_ATTN(64, 4, 2, true, 1, true);
+    }
+  } else if (use8) {
     if (c.head_dim == 128) {
       if (few) PC_ATTN(128, 2, 2, true, 2); else if (wide) PC_ATTN(128, 8, 2, true); else PC_ATTN(128, 4, 2, true);
     } else {

@@ -69,3 +69,16 @@ def test_arena_of_8_bit_slots_is_half_the_store_plus_scales(lib):
     assert a - a8 == 2 * store - 2 * scales
     bad = Config(2, 1024, 16, 8, 128, 16, 512, 4096, 10000.0, 0, 0, 2)
     assert lib.percache_arena_bytes(ctypes.byref(bad)) == 0
+
+
+def test_arena_of_a_store_with_both_slot_formats(lib):
+    from paper_2601_11553_amd.binding import Config
+    base = Config(2, 1024, 16, 8, 128, 16, 512, 4096, 10000.0, 0, 0, 0, 0)
+    mixed = Config(2, 1024, 16, 8, 128, 16, 512, 4096, 10000.0, 0, 0, 0, 6)
+    a, m = lib.percache_arena_bytes(ctypes.byref(base)), lib.percache_arena_bytes(ctypes.byref(mixed))
+    per_slot = 2 * 8 * 512 * 128            # elements of one slot over both layers (K or V)
+    scales = 2 * 6 * 8 * (512 // 64) * 4    # bytes
+    assert a - m == 2 * 6 * per_slot - 2 * scales   # six slots shrink from 2 bytes to 1 byte per element, plus their scales
+    all8 = Config(2, 1024, 16, 8, 128, 16, 512, 4096, 10000.0, 0, 0, 0, 16)
+    flag = Config(2, 1024, 16, 8, 128, 16, 512, 4096, 10000.0, 0, 0, 1, 0)
+    assert lib.percache_arena_bytes(ctypes.byref(all8)) == lib.percache_arena_bytes(ctypes.byref(flag))
