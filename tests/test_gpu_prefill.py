@@ -172,8 +172,8 @@ def test_ragged_batch_with_partial_and_empty_chunks():
 @pytest.mark.parametrize("seed", list(range(24)))
 def test_seeded_random_shapes(seed):
     """Shapes drawn from a seed: head size, GQA ratio, batch, fresh length (1 .. a few tiles), chunk count (0 .. 5),
-    chunk capacity, ragged used lengths (zero included), over bf16 and over 8-bit slots (the latter against the
-    oracle run on what the slots read back)."""
+    chunk capacity, ragged used lengths (zero included), over bf16 slots, 8-bit slots and a store of both (against the
+    oracle run on what each slot reads back)."""
     g = np.random.default_rng(1000 + seed)
     D = int(g.choice([64, 128]))
     Hkv = int(g.choice([1, 2, 3, 4]))
@@ -188,19 +188,21 @@ def test_seeded_random_shapes(seed):
     w = wl.make_prefill(f"rnd{seed}", 2000 + seed, "bf16", hidden, G * Hkv, Hkv, D, batch, t_fresh, n_chunks, C, max(8, n_chunks + 2))
     if n_chunks:
         w.used_len[:] = g.integers(0, C + 1, size=(batch, n_chunks))
-    fp8 = bool(seed % 2)
-    pc = make_ctx(w, kv_fp8=fp8)
+    mode = seed % 3                                   # 0: bf16 slots, 1: 8-bit slots, 2: the upper half of the slots 8-bit
+    n16 = {0: w.n_slots, 1: 0, 2: w.n_slots // 2}[mode]
+    pc = make_ctx(w, kv_fp8=mode == 1, n_slots_8bit=w.n_slots - n16 if mode == 2 else 0)
     fill_slots(pc, w, w.slot_ids.reshape(-1))
     out = pc.percache_prefill_reuse(0, bf16(w.X), bf16(w.Wqkv), w.slot_ids if n_chunks else None, w.used_len if n_chunks else None)
     torch.cuda.synchronize()
+    from oracle import kv_fp8
     for b in range(batch):
         sk, sv, ids = w.compact_store(b)
-        if fp8 and n_chunks:
-            from oracle import kv_fp8
-            sk = np.stack([kv_fp8.round_trip(wl.round_bf16(x)) for x in sk])
-            sv = np.stack([kv_fp8.round_trip(wl.round_bf16(x)) for x in sv])
+        if n_chunks:   # what each chunk's slot reads back
+            is8 = [int(s_) >= n16 for s_ in w.slot_ids[b]]
+            sk = np.stack([kv_fp8.round_trip(wl.round_bf16(x)) if e else x for x, e in zip(sk, is8)])
+            sv = np.stack([kv_fp8.round_trip(wl.round_bf16(x)) if e else x for x, e in zip(sv, is8)])
         O, _, _, _ = oracle.prefill_reuse(w.X[b], w.Wqkv, w.n_q_heads, w.n_kv_heads, w.head_dim, w.rope_theta, sk, sv, ids, w.used_len[b])
-        check_close(host(out[b]), O, f"seed {seed} (D={D} G={G} Hkv={Hkv} B={batch} T={t_fresh} chunks={n_chunks}x{C} fp8={fp8}) b={b}")
+        check_close(host(out[b]), O, f"seed {seed} (D={D} G={G} Hkv={Hkv} B={batch} T={t_fresh} chunks={n_chunks}x{C} slots mode {mode}) b={b}")
     pc.close()
 
 
