@@ -286,6 +286,25 @@ def main():
     look["refresh_scan_64_new"] = {"ms": round(t_scan * 1e3, 4), "passes_of_the_bank": 2,
                                    "bank_GBps": round(2 * bank_bytes / t_scan / 1e9, 1)}
 
+    # ------------------------------------------------------------------ the K/V store itself: 16 whole chunks written / read
+    # (their contents are overwritten with other N(0,1) values: nothing after this point compares outputs)
+    C = w.chunk_tokens
+    some = [int(x) for x in w.slot_ids[0]]
+    kc = torch.randn((len(some), w.n_kv_heads, C, w.head_dim), device=dev).to(torch.bfloat16)
+    vc = torch.randn_like(kc)
+    chunk_bytes = kc.numel() * 2 * 2                                    # K and V
+    t_put = wall(lambda: pc.percache_kv_put_batch(0, some, kc, vc, C))
+    ko, vo = torch.empty_like(kc[0]), torch.empty_like(kc[0])
+
+    def get_all():
+        for s_ in some:
+            pc.lib.percache_kv_get(pc.ctx, 0, s_, binding._ptr(ko), binding._ptr(vo), None, binding._stream())
+    t_get = wall(get_all)
+    store_io = {"chunks": len(some), "tokens_per_chunk": C, "put_batch_ms": round(t_put * 1e3, 4),
+                "put_GBps_read_plus_written": round(2 * chunk_bytes / t_put / 1e9, 1),
+                "get_ms_per_chunk": round(t_get * 1e3 / len(some), 4),
+                "get_GBps_read_plus_written": round(2 * chunk_bytes / t_get / 1e9, 1)}
+
     # ------------------------------------------------------------------ one decoding step of the same layer
     # (one new token per query over the 16 reused chunks + the 256-token prompt slot written by the step above)
     x1 = X[:, :1].contiguous()
@@ -318,6 +337,7 @@ def main():
             "lookup_in_step": {"avg_pass_ms": round(look_ms, 4), "bank_GBps": round(bank_bytes / (look_ms * 1e-3) / 1e9, 1),
                                "frac_of_hbm_peak": round(bank_bytes / (look_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)},
             "lookup_alone": look,
+            "kv_store_io": store_io,
             "decode_step_layer": {"ms_per_call": round(dec_ms, 4), "attention_ms": round(dec_attn_ms / max(dec_n, 1), 4),
                                   "kv_stream_GBps": round(dec_bytes / (dec_attn_ms / max(dec_n, 1) * 1e-3) / 1e9, 1),
                                   "keys_per_query": int(w.l_pre[0] + T), "batch": B},
