@@ -88,6 +88,7 @@ __global__ __launch_bounds__(256) void bank_put_kernel(const _Float16 *__restric
 // ---------------------------------------------------------------------------------------------------
 // cache policy of the bank stream (aux operand of the global->LDS load): 2 = non-temporal, the rows are used once
 constexpr int kBankLoadAux = 2;
+constexpr int kProbePad = 16;  // bytes added to every probe row in LDS
 constexpr int kMaxBlocksPerWg = 128;  // 2048 rows: bounds the LDS copy of the inverse norms (8 KB)
 #define PC_LOOKUP_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xf) | (7 << 4) | (15 << 8) | ((((n) >> 4) & 3) << 14))
 
@@ -160,7 +161,9 @@ __global__ __launch_bounds__(256) void lookup_stream_kernel(const _Float16 *__re
   constexpr int IPS = STG / 1024;        // load instructions per stage
   constexpr int LPR = CHB / 16;          // lanes (16-byte chunks) per row
   constexpr int AHEAD = NSTG - 1;
-  const int row_bytes = d * 2 + 64;  // padded probe row in LDS
+  // probe rows in LDS are padded by 16 bytes: the 16 lanes that read one 16-byte operand chunk each from 16
+  // consecutive probes then start 16 bytes apart modulo 256 (a row is a multiple of 128 bytes) -- no bank conflicts
+  const int row_bytes = d * 2 + kProbePad;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r16 = lane & 15, g = lane >> 4;
 
@@ -645,7 +648,7 @@ StreamShape stream_shape(const percache_ctx *ctx, int npb, int N) {
     s.per_wg = kMaxBlocksPerWg;
     s.grid = (n_blocks + s.per_wg - 1) / s.per_wg;
   }
-  size_t head = (size_t)npb * 16 * (d * 2 + 64) + (size_t)s.per_wg * 16 * sizeof(float);
+  size_t head = (size_t)npb * 16 * (d * 2 + kProbePad) + (size_t)s.per_wg * 16 * sizeof(float);
   s.ring_off = (int)((head + 1023) / 1024 * 1024);
   // three stages per wavefront for a single probe block if they fit beside the probes, else two
   s.nstg = npb == 1 && s.ring_off + (size_t)4 * 3 * 16 * s.chb <= kMaxLds ? 3 : 2;
