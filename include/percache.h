@@ -130,8 +130,8 @@ pc_status percache_bank_refresh_scan(percache_ctx *ctx, const void *new_emb_dev,
  * percache_kv_get returns the values read back; the attention calls read them on the fly (fresh K/V stay bf16).
  * percache_kv_append (and the decoding steps that use it): everything from the block that holds the first new token
  * on is quantised afresh from the values the slot reads back plus the new tokens; full blocks before it stay.
- * A store of both organisations (n_slots_8bit > 0 with kv_fp8 = 0; Sec. 7 names "different tensor components for
- * different knowledge chunks" as the direction): slot ids below n_slots - n_slots_8bit are bf16 slots, the others 8-bit
+ * A store of both organisations (n_slots_8bit > 0 with kv_fp8 = 0; Sec. 7 looks ahead to chunks that are not all kept in the
+ * same form): slot ids below n_slots - n_slots_8bit are bf16 slots, the others 8-bit
  * slots.  Every call treats each slot by its own format; one chunk list, one batched put or one list of save slots may
  * name slots of both kinds. */
 

@@ -15,7 +15,7 @@
  * Paper passages followed (PerCache, arXiv 2601.11553):
  *   - Similar Query Reuse (Sec. 4.2.1): cosine similarity against all stored
  *     query embeddings; the best one is a hit if it exceeds tau_query.
- *   - QKV Cache Reuse (Sec. 4.2.2) and App. B.1 "inference with QKV cache":
+ *   - QKV Cache Reuse (Sec. 4.2.2) and App. B.1 (how inference runs over cached tensors):
  *     drop the first L_pre rows of the attention input, project only the
  *     suffix, apply RoPE with the position counter advanced by L_pre, put the
  *     loaded tensors in front of the fresh ones along the sequence axis, then
@@ -356,8 +356,8 @@ void oracle_attend_stats(const float *q, const float *K, const float *V, int L,
 
 /* ------------------------------------------------------------------ */
 /* The rest of a pre-norm transformer block on the fresh rows, needed   */
-/* only to chain layers ("the subsequent operations proceed normally",  */
-/* App. B.1).  RMSNorm with gain and eps; y = x W^T linear; SwiGLU MLP. */
+/* only to chain layers (App. B.1: after the concatenation the block    */
+/* runs as it always does).  RMSNorm with gain and eps; y = x W^T linear; SwiGLU MLP. */
 /* ------------------------------------------------------------------ */
 void oracle_rmsnorm(const float *X, const float *gain, int T, int H, double eps,
                     float *Y) {

@@ -143,8 +143,8 @@ int32_t percache_tree_insert(percache_tree *t, const char *const *chunk_texts, c
   *n_evicted_out = 0;
   std::vector<Node *> chain;
   int common = longest_chain(&t->root, chunk_texts, 0, n, chain);
-  // the chain is shared only where the stored chunk has the same length, and only up to the second-to-last node
-  // of the common prefix; a chain that is already there in full is shared in full (nothing new to store)
+  // the chain is shared only where the stored chunk has the same length, and the last node the two chains have in
+  // common is not shared but stored again; a chain that is already there in full is shared in full (nothing new)
   for (int i = 0; i < common; ++i)
     if (chain[i]->tokens != chunk_tokens[i]) { common = i; break; }
   const int shared = common == n ? n : std::max(0, common - 1);
