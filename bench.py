@@ -166,7 +166,7 @@ def main():
                     help="also run one plain 1 GiB device copy (a kernel of known traffic to scale HBM byte counters by)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        print("bench.py measures one GPU only: this library has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
         sys.exit(2)
 
     import torch

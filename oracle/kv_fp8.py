@@ -2,7 +2,7 @@
 bench.py's cpu_baseline leg may import this package; it shares nothing with the HIP library.
 
 The paper stores the chunks' complete tensors and leaves other cache organisations to future work (Sec. 7, fine-grained
-cache organisation); this format is this build's smaller variant of a slot, defined here so that both sides can be
+cache organisation); this format is the library's smaller variant of a slot, defined here so that both sides can be
 checked bit for bit:
 
   * element code: E4M3 of the OCP 8-bit floating point specification -- 1 sign bit, 4 exponent bits (bias 7),
