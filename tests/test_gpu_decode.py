@@ -45,8 +45,27 @@ def test_kv_append_equals_put_of_the_concatenation():
 
 @pytest.mark.parametrize("batch,D,Hq", [(1, 64, 4), (3, 64, 4), (2, 128, 8), (1, 128, 2)])
 def test_decode_steps_match_full_prefill(batch, D, Hq):
-    H, Hkv, F, L, C = 256, 2, 384, 2, 64
-    n_c, t_prompt, n_steps = 2, 20, 6
+    _decode_case(batch, D, Hq, 2, 256, 384, 2, 64, 2, 20, 6, 40 + batch, full_slot=True)
+
+
+@pytest.mark.parametrize("seed", list(range(12)))
+def test_seeded_random_decode_shapes(seed):
+    """Shapes drawn from a seed: batch, head size, GQA ratio, widths, layers, chunk count (none included) and capacity,
+    prompt length, number of steps (the sequence slot ends exactly full in some draws)."""
+    g = np.random.default_rng(9000 + seed)
+    D = int(g.choice([64, 128]))
+    Hkv = int(g.choice([1, 2, 4]))
+    Hq = Hkv * int(g.choice([1, 2, 4]))
+    while ((Hq + 2 * Hkv) * D) % 128:
+        Hq += Hkv
+    C = int(g.choice([64, 128]))
+    n_steps = int(g.integers(1, 6))
+    t_prompt = int(g.choice([1, 2, 31, C - n_steps]))
+    _decode_case(int(g.integers(1, 4)), D, Hq, Hkv, int(g.choice([128, 256, 384])), int(g.choice([192, 448])),
+                 int(g.integers(1, 3)), C, int(g.integers(0, 4)), t_prompt, n_steps, 9100 + seed, full_slot=False)
+
+
+def _decode_case(batch, D, Hq, Hkv, H, F, L, C, n_c, t_prompt, n_steps, seed, full_slot):
     Ws = [wl.stack_weights(31, l, H, Hq, Hkv, D, F) for l in range(L)]
     layers = dev_layers(Ws)
     n_slots = batch * (n_c + 1)
@@ -54,7 +73,7 @@ def test_decode_steps_match_full_prefill(batch, D, Hq):
                   max_pos=n_c * C + C, device=DEV)
     plain = Percache(n_layers=L, hidden=H, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=D, n_slots=1, slot_capacity=C,
                      max_pos=n_c * C + C, device=DEV)
-    g = np.random.default_rng(40 + batch)
+    g = np.random.default_rng(seed)
     total = n_c * C + t_prompt + n_steps
     seqs = wl.round_bf16(g.standard_normal((batch, total, H)).astype(np.float32))   # chunks, prompt, then the fed tokens
     chunk_slots = [[b * (n_c + 1) + c for c in range(n_c)] for b in range(batch)]
@@ -72,11 +91,14 @@ def test_decode_steps_match_full_prefill(batch, D, Hq):
         torch.cuda.synchronize()
         for b in range(batch):
             assert pc.percache_kv_len(0, seq_slots[b]) == t_prompt + step + 1 == pc.percache_kv_len(L - 1, seq_slots[b])
-        check_hidden(host(out[:, 0]), host(ref[:, -1]), f"decode step {step} (batch {batch}) vs full prefill", rel_max=2.0 ** -5)
+        check_hidden(host(out[:, 0]), host(ref[:, -1]), f"decode step {step} (batch {batch} D {D} heads {Hq}/{Hkv} H {H} layers {L} "
+                     f"chunks {n_c}x{C} prompt {t_prompt}) vs full prefill", rel_max=2.0 ** -5)
     h = seqs[0]
     for W in Ws:
         h, _, _ = oracle_block(h, W, Hq, Hkv, D, 10000.0)
     check_hidden(host(out[0, 0]), h[-1], "last decode step vs oracle stack")
+    if not full_slot:
+        return
     # a sequence slot that is full refuses the step and nothing changes
     filler = bf16(g.standard_normal((Hkv, C - t_prompt - n_steps, D)))
     for l in range(L):
