@@ -327,27 +327,43 @@ __global__ __launch_bounds__(256) void lookup_stream_kernel(const _Float16 *__re
 
 // ---------------------------------------------------------------------------------------------------
 // Per probe: merge the workgroup partial lists, divide by the probe's norm, compare the best with tau.
-// One workgroup (one wavefront) per probe; k <= K entries are written per probe.
+// One workgroup of four wavefronts per probe, one thread per partial list (a thread takes its first list as it
+// stands -- the lists are sorted, best first -- and inserts any further ones); then k rounds of "the best head of
+// all threads wins and its owner pops it".  k <= K entries are written per probe.
 // ---------------------------------------------------------------------------------------------------
+constexpr int kFinalizeThreads = 256;
 template <int K>
-__global__ __launch_bounds__(64) void lookup_finalize_kernel(const Best *__restrict__ partial, int n_partials,
-                                                             int partial_stride, const _Float16 *__restrict__ probes,
-                                                             int d, float tau, int k, int32_t *__restrict__ idx_out,
-                                                             float *__restrict__ sim_out, uint8_t *__restrict__ hit_out) {
-  const int p = blockIdx.x, lane = threadIdx.x;
+__global__ __launch_bounds__(kFinalizeThreads) void lookup_finalize_kernel(const Best *__restrict__ partial, int n_partials,
+                                                                           int partial_stride, const _Float16 *__restrict__ probes,
+                                                                           int d, float tau, int k, int32_t *__restrict__ idx_out,
+                                                                           float *__restrict__ sim_out, uint8_t *__restrict__ hit_out) {
+  constexpr int NWV = kFinalizeThreads / 64;
+  __shared__ float norm_part[NWV];
+  __shared__ float red_s[2][NWV];
+  __shared__ int red_i[2][NWV];
+  const int p = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   float ss = 0.f;
   const u32x4 *src = (const u32x4 *)(probes + (size_t)p * d);
-  for (int v = lane; v < d / 8; v += 64) {
+  for (int v = tid; v < d / 8; v += kFinalizeThreads) {
     f16x8 h = __builtin_bit_cast(f16x8, src[v]);
 #pragma unroll
     for (int e = 0; e < 8; ++e) ss += (float)h[e] * (float)h[e];
   }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
-  const float inv = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
+  if (lane == 0) norm_part[wave] = ss;
   TopK<K> mine;
   mine.clear();
-  for (int w = lane; w < n_partials; w += 64) {
+  if (tid < n_partials) {
+    const Best *lst = partial + ((size_t)tid * partial_stride + p) * K;
+#pragma unroll
+    for (int j = 0; j < K; ++j) {
+      const Best b = lst[j];
+      mine.s[j] = b.idx != INT_MAX ? b.s : -INFINITY;
+      mine.i[j] = b.idx;
+    }
+  }
+  for (int w = tid + kFinalizeThreads; w < n_partials; w += kFinalizeThreads) {
     const Best *lst = partial + ((size_t)w * partial_stride + p) * K;
 #pragma unroll
     for (int j = 0; j < K; ++j) {
@@ -355,6 +371,11 @@ __global__ __launch_bounds__(64) void lookup_finalize_kernel(const Best *__restr
       if (b.idx != INT_MAX) mine.insert(b.s, b.idx);
     }
   }
+  __syncthreads();
+  float tot = 0.f;
+#pragma unroll
+  for (int w = 0; w < NWV; ++w) tot += norm_part[w];
+  const float inv = tot > 0.f ? 1.0f / sqrtf(tot) : 0.f;
   for (int j = 0; j < k; ++j) {
     float s = mine.s[0];
     int i = mine.i[0];
@@ -364,8 +385,18 @@ __global__ __launch_bounds__(64) void lookup_finalize_kernel(const Best *__restr
       int i2 = __shfl_xor(i, o, 64);
       if (better(s2, i2, s, i)) { s = s2; i = i2; }
     }
+    if (lane == 0) { red_s[j & 1][wave] = s; red_i[j & 1][wave] = i; }
+    __syncthreads();  // (the buffer of round j is written again in round j + 2, behind the barrier of round j + 1)
+    s = red_s[j & 1][0];
+    i = red_i[j & 1][0];
+#pragma unroll
+    for (int w = 1; w < NWV; ++w) {
+      const float s2 = red_s[j & 1][w];
+      const int i2 = red_i[j & 1][w];
+      if (better(s2, i2, s, i)) { s = s2; i = i2; }
+    }
     mine.pop_if(i != INT_MAX && mine.i[0] == i);
-    if (lane == 0) {
+    if (tid == 0) {
       const float sim = i == INT_MAX ? -INFINITY : s * inv;
       idx_out[(size_t)p * k + j] = i == INT_MAX ? -1 : i;
       sim_out[(size_t)p * k + j] = sim;
@@ -756,10 +787,10 @@ pc_status run_lookup(percache_ctx *ctx, const void *probes_dev, int32_t n_probes
       PC_HIP(ctx, hipGetLastError());
       uint8_t *hit = hit_out_dev ? hit_out_dev + p0 : nullptr;
       if (k == 1)
-        hipLaunchKernelGGL(lookup_finalize_kernel<1>, dim3(np), dim3(64), 0, st, partial, grid, kWideProbes, pp, d, tau, 1,
+        hipLaunchKernelGGL(lookup_finalize_kernel<1>, dim3(np), dim3(kFinalizeThreads), 0, st, partial, grid, kWideProbes, pp, d, tau, 1,
                            idx_out_dev + p0, sim_out_dev + p0, hit);
       else
-        hipLaunchKernelGGL(lookup_finalize_kernel<kMaxTopK>, dim3(np), dim3(64), 0, st, partial, grid, kWideProbes, pp, d, tau, k,
+        hipLaunchKernelGGL(lookup_finalize_kernel<kMaxTopK>, dim3(np), dim3(kFinalizeThreads), 0, st, partial, grid, kWideProbes, pp, d, tau, k,
                            idx_out_dev + (size_t)p0 * k, sim_out_dev + (size_t)p0 * k, hit);
       PC_HIP(ctx, hipGetLastError());
     }
@@ -780,10 +811,10 @@ pc_status run_lookup(percache_ctx *ctx, const void *probes_dev, int32_t n_probes
     pc::prof_end(ctx, PC_KERNEL_LOOKUP, st);
     PC_HIP(ctx, hipGetLastError());
     if (k == 1)
-      hipLaunchKernelGGL(lookup_finalize_kernel<1>, dim3(n_probes), dim3(64), 0, st, partial, bs.groups, bs.p_tiles * 128, probes, d, tau, 1,
+      hipLaunchKernelGGL(lookup_finalize_kernel<1>, dim3(n_probes), dim3(kFinalizeThreads), 0, st, partial, bs.groups, bs.p_tiles * 128, probes, d, tau, 1,
                          idx_out_dev, sim_out_dev, hit_out_dev);
     else
-      hipLaunchKernelGGL(lookup_finalize_kernel<kMaxTopK>, dim3(n_probes), dim3(64), 0, st, partial, bs.groups, bs.p_tiles * 128, probes, d,
+      hipLaunchKernelGGL(lookup_finalize_kernel<kMaxTopK>, dim3(n_probes), dim3(kFinalizeThreads), 0, st, partial, bs.groups, bs.p_tiles * 128, probes, d,
                          tau, k, idx_out_dev, sim_out_dev, hit_out_dev);
     PC_HIP(ctx, hipGetLastError());
     return PC_OK;
@@ -803,10 +834,10 @@ pc_status run_lookup(percache_ctx *ctx, const void *probes_dev, int32_t n_probes
     PC_HIP(ctx, hipGetLastError());
     uint8_t *hit = hit_out_dev ? hit_out_dev + p0 : nullptr;
     if (k == 1)
-      hipLaunchKernelGGL(lookup_finalize_kernel<1>, dim3(np), dim3(64), 0, st, partial, sh.grid, npb * 16, pp, d, tau, 1,
+      hipLaunchKernelGGL(lookup_finalize_kernel<1>, dim3(np), dim3(kFinalizeThreads), 0, st, partial, sh.grid, npb * 16, pp, d, tau, 1,
                          idx_out_dev + p0, sim_out_dev + p0, hit);
     else
-      hipLaunchKernelGGL(lookup_finalize_kernel<kMaxTopK>, dim3(np), dim3(64), 0, st, partial, sh.grid, npb * 16, pp, d, tau, k,
+      hipLaunchKernelGGL(lookup_finalize_kernel<kMaxTopK>, dim3(np), dim3(kFinalizeThreads), 0, st, partial, sh.grid, npb * 16, pp, d, tau, k,
                          idx_out_dev + (size_t)p0 * k, sim_out_dev + (size_t)p0 * k, hit);
     PC_HIP(ctx, hipGetLastError());
   }
