@@ -590,12 +590,14 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
 // Merge of the split-KV partials: m = max m_s, w_s = l_s 2^(m_s - m), o = sum w_s o_s / sum w_s.
 // A row is shared by 4 * D/8 neighbouring lanes: lane (sg, dv) adds up 8 head-dim elements over the partitions
 // s = sg, sg + 4, ..., and the four partial sums meet through lane shuffles.
-template <int D>
+// FEW (at most four partitions): one lane per 16 output bytes takes all of them, four independent loads in flight,
+// and adds them up in the order the shuffles would, (0 + 1) + (2 + 3), so both forms give the same bits.
+template <int D, bool FEW>
 __global__ __launch_bounds__(256) void splitkv_combine_kernel(const __bf16 *__restrict__ part_o,
                                                               const float *__restrict__ part_ml, int n_splits, int T,
                                                               int Hq, int Hkv, long total_rows,
                                                               __bf16 *__restrict__ out) {
-  constexpr int VPR = D / 8, SG = 4, LPR = VPR * SG;  // lanes per row
+  constexpr int VPR = D / 8, SG = FEW ? 1 : 4, LPR = VPR * SG;  // lanes per row
   const long gid = (long)blockIdx.x * blockDim.x + threadIdx.x;
   const long prow_raw = gid / LPR;
   const int r = (int)(gid - prow_raw * LPR);
@@ -603,6 +605,31 @@ __global__ __launch_bounds__(256) void splitkv_combine_kernel(const __bf16 *__re
   const bool live = prow_raw < total_rows;
   const long prow = live ? prow_raw : total_rows - 1;
   const float2 *ml = (const float2 *)part_ml + prow * n_splits;
+  const __bf16 *po = part_o + prow * n_splits * D + dv * 8;
+  float wsum = 0.f;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if constexpr (FEW) {
+#pragma clang fp contract(off)  // products rounded before the sums, as in the other form
+    float2 e[4];
+    pc::bf16x8 o[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const int sc = s < n_splits ? s : 0;
+      e[s] = ml[sc];
+      o[s] = *(const pc::bf16x8 *)(po + (size_t)sc * D);
+      if (s >= n_splits) e[s].y = 0.f;
+    }
+    float m = -INFINITY;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) m = fmaxf(m, e[s].y > 0.f ? e[s].x : -INFINITY);
+    float w[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) w[s] = e[s].y > 0.f ? e[s].y * exp2f(e[s].x - m) : 0.f;
+    wsum = (w[0] + w[1]) + (w[2] + w[3]);
+#pragma unroll
+    for (int e8 = 0; e8 < 8; ++e8)
+      acc[e8] = (w[0] * (float)o[0][e8] + w[1] * (float)o[1][e8]) + (w[2] * (float)o[2][e8] + w[3] * (float)o[3][e8]);
+  } else {
   float m = -INFINITY;
 #pragma unroll 4
   for (int s = sg; s < n_splits; s += SG) {
@@ -611,9 +638,6 @@ __global__ __launch_bounds__(256) void splitkv_combine_kernel(const __bf16 *__re
   }
   m = fmaxf(m, __shfl_xor(m, VPR, 64));
   m = fmaxf(m, __shfl_xor(m, 2 * VPR, 64));
-  float wsum = 0.f;
-  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  const __bf16 *po = part_o + prow * n_splits * D + dv * 8;
 #pragma unroll 4
   for (int s = sg; s < n_splits; s += SG) {
     const float2 e = ml[s];
@@ -628,6 +652,7 @@ __global__ __launch_bounds__(256) void splitkv_combine_kernel(const __bf16 *__re
     wsum += __shfl_xor(wsum, sh, 64);
 #pragma unroll
     for (int e8 = 0; e8 < 8; ++e8) acc[e8] += __shfl_xor(acc[e8], sh, 64);
+  }
   }
   if (!live || sg != 0) return;
   const int G = Hq / Hkv, R = G * T;
@@ -763,14 +788,15 @@ pc_status launch_attention(percache_ctx *ctx, int layer, const __bf16 *q, const 
   PC_HIP(ctx, hipGetLastError());
   if (n_splits > 1) {
     long total_rows = (long)batch * c.n_kv_heads * R;
-    long threads = total_rows * (c.head_dim / 8) * 4;  // 4 lanes per 16 output bytes
+    const bool few_parts = n_splits <= 4;              // one lane per 16 output bytes, else four
+    long threads = total_rows * (c.head_dim / 8) * (few_parts ? 1 : 4);
     int blocks = (int)((threads + 255) / 256);
-    if (c.head_dim == 128)
-      hipLaunchKernelGGL(splitkv_combine_kernel<128>, dim3(blocks), dim3(256), 0, stream, part_o, part_ml, n_splits,
-                         t_fresh, c.n_q_heads, c.n_kv_heads, total_rows, out);
-    else
-      hipLaunchKernelGGL(splitkv_combine_kernel<64>, dim3(blocks), dim3(256), 0, stream, part_o, part_ml, n_splits,
-                         t_fresh, c.n_q_heads, c.n_kv_heads, total_rows, out);
+#define PC_COMBINE(DD, FF)                                                                                          \
+  hipLaunchKernelGGL((splitkv_combine_kernel<DD, FF>), dim3(blocks), dim3(256), 0, stream, part_o, part_ml, n_splits, \
+                     t_fresh, c.n_q_heads, c.n_kv_heads, total_rows, out)
+    if (c.head_dim == 128) { if (few_parts) PC_COMBINE(128, true); else PC_COMBINE(128, false); }
+    else { if (few_parts) PC_COMBINE(64, true); else PC_COMBINE(64, false); }
+#undef PC_COMBINE
     PC_HIP(ctx, hipGetLastError());
   }
   return PC_OK;
