@@ -384,6 +384,7 @@ pc_status percache_kv_append(percache_ctx *ctx, int32_t layer, int32_t slot, con
   pc_status st = check_slot(ctx, layer, slot);
   if (st != PC_OK) return st;
   if (!k_dev || !v_dev) return pc::fail(ctx, PC_EINVAL, "k_dev / v_dev is NULL");
+  if (((uintptr_t)k_dev | (uintptr_t)v_dev) % 16) return pc::fail(ctx, PC_EINVAL, "k_dev / v_dev must be 16-byte aligned");
   const percache_config &c = ctx->cfg;
   const int have = ctx->slot_len[(size_t)layer * c.n_slots + slot];
   if (n_tokens < 1 || have + n_tokens > c.slot_capacity)

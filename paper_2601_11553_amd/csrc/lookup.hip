@@ -821,11 +821,14 @@ pc_status run_lookup(percache_ctx *ctx, const void *probes_dev, int32_t n_probes
   }
   // two probe blocks per pass unless their LDS copy leaves no room for the rings (very wide embeddings)
   const int pass_probes = stream_shape(ctx, 2, N).lds <= kMaxLds ? kPassProbes : 16;
+  {  // every pass shape of this call is checked before the first pass is enqueued
+    const size_t lds1 = stream_shape(ctx, 1, N).lds;
+    if (lds1 > kMaxLds) return pc::fail(ctx, PC_ESHAPE, "emb_dim %d needs %zu bytes of LDS per workgroup", d, lds1);
+  }
   for (int p0 = 0; p0 < n_probes; p0 += pass_probes) {
     int np = n_probes - p0 < pass_probes ? n_probes - p0 : pass_probes;
     int npb = np <= 16 ? 1 : 2;
     StreamShape sh = stream_shape(ctx, npb, N);
-    if (sh.lds > kMaxLds) return pc::fail(ctx, PC_ESHAPE, "emb_dim %d needs %zu bytes of LDS per workgroup", d, sh.lds);
     const _Float16 *pp = probes + (size_t)p0 * d;
     pc::prof_begin(ctx, PC_KERNEL_LOOKUP, st);
     pc_status ls = k == 1 ? launch_pass<1>(ctx, sh, npb, st, N, d, pp, np, partial) : launch_pass<kMaxTopK>(ctx, sh, npb, st, N, d, pp, np, partial);
@@ -901,6 +904,10 @@ pc_status percache_bank_refresh_scan(percache_ctx *ctx, const void *new_emb_dev,
   if (!workspace_dev || workspace_bytes < need || (size_t)n_new * sizeof(float) > need)
     return pc::fail(ctx, PC_ENOMEM, "workspace has %zu bytes, need %zu (and at most %zu new rows per call)", workspace_bytes, need, need / sizeof(float));
   if ((uintptr_t)workspace_dev % 16) return pc::fail(ctx, PC_EINVAL, "workspace must be 16-byte aligned");
+  {
+    const size_t lds1 = stream_shape(ctx, 1, N).lds;
+    if (lds1 > kMaxLds) return pc::fail(ctx, PC_ESHAPE, "emb_dim %d needs %zu bytes of LDS per workgroup", d, lds1);
+  }
   hipStream_t st = (hipStream_t)stream;
   float *probe_inv = (float *)workspace_dev;
   const _Float16 *probes = (const _Float16 *)new_emb_dev;
@@ -911,7 +918,6 @@ pc_status percache_bank_refresh_scan(percache_ctx *ctx, const void *new_emb_dev,
     const int np = n_new - p0 < pass_probes ? n_new - p0 : pass_probes;
     const int npb = np <= 16 ? 1 : 2;
     StreamShape sh = stream_shape(ctx, npb, N);
-    if (sh.lds > kMaxLds) return pc::fail(ctx, PC_ESHAPE, "emb_dim %d needs %zu bytes of LDS per workgroup", d, sh.lds);
     RowScan rs{probe_inv + p0, kth_sim_dev, best_sim_out_dev, best_new_out_dev, stale_out_dev, p0, p0 == 0 ? 1 : 0};
     pc_status ls = launch_pass<0>(ctx, sh, npb, st, N, d, probes + (size_t)p0 * d, np, nullptr, rs);
     if (ls != PC_OK) return ls;

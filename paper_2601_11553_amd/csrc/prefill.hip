@@ -17,6 +17,12 @@ pc_status prepare(percache_ctx *ctx, int32_t layer, int32_t batch, int32_t t_fre
   if (!ctx) return PC_EINVAL;
   pc_status st = pc::build_chunk_table(ctx, layer, batch, t_fresh, slot_ids, used_len, n_chunks, max_chunks, rows);
   if (st != PC_OK) return st;
+  {  // sizes the kernels index with 32 bits (checked again where they are launched; here: before anything is enqueued)
+    const percache_config &c = ctx->cfg;
+    const long F = (long)(c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim, M = (long)batch * t_fresh;
+    if (F * c.hidden >= (1L << 31) || M * c.hidden >= (1L << 31) || M * F >= (1L << 31))
+      return pc::fail(ctx, PC_ESHAPE, "operand larger than 2^31 elements");
+  }
   size_t need = percache_prefill_workspace_bytes(ctx, batch, t_fresh, max_chunks);
   if (!workspace || workspace_bytes < need)
     return pc::fail(ctx, PC_ENOMEM, "prefill workspace has %zu bytes, need %zu", workspace_bytes, need);

@@ -14,8 +14,9 @@
 //     order inside each group of 16 is the order the score accumulators deliver them, so K and V tiles
 //     are both staged with direct global->LDS loads (no registers, no LDS store instructions) and every
 //     MFMA operand is one 16-byte LDS read from an XOR-swizzled, conflict-free layout;
-//   - the running max is only refreshed when a tile exceeds it by more than 2^8 (probabilities stay
-//     below 256, harmless in bf16/fp32), so the rescale of the output accumulators is almost never run;
+//   - the reference exponent is only refreshed when the sum of a lane's 32 probabilities of a tile exceeds
+//     32 * 2^8 (so a single probability stays below 2^13, harmless in bf16/fp32), so the rescale of the
+//     output accumulators is almost never run;
 //   - the key axis can be partitioned over workgroups (split-KV); partial (max, sum, output) triples are
 //     merged by a small second kernel with the usual log-sum-exp rule;
 //   - workgroups that stream the same K/V run are placed on the same XCD (workgroup ids go round-robin

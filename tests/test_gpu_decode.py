@@ -2,7 +2,7 @@
 append they rely on, through the C ABI.
 
 There is no language-model head here: the "generated token" fed to step i is a seeded row of hidden state.  The reference
-for every step is a plain prefill of the whole sequence so far (GPU, no cache) and, at the last step, the CPU oracle's stack."""
+for every step is a plain prefill of the whole sequence so far (GPU, no cache) and, at the last step, the CPU oracle's stack for every query of the batch."""
 import numpy as np
 import pytest
 import torch
@@ -33,6 +33,9 @@ def test_kv_append_equals_put_of_the_concatenation():
     with pytest.raises(PercacheError) as e:
         pc.percache_kv_append(0, 1, k[:, :43].contiguous(), v[:, :43].contiguous())   # 150 + 43 > 192
     assert e.value.status == -4 and pc.percache_kv_len(0, 1) == 150
+    with pytest.raises(PercacheError) as e:                                           # tensors that are not 16-byte aligned
+        pc.percache_kv_append(0, 2, k.reshape(-1)[1:1 + Hkv * 2 * D].view(Hkv, 2, D), v[:, :2].contiguous())
+    assert e.value.status == -1 and pc.percache_kv_len(0, 2) == 0
     # attention over the appended slot equals attention over the slot written at once (same padding behaviour)
     q = bf16(g.standard_normal((1, 2, 5, D)))
     kf = bf16(g.standard_normal((1, Hkv, 5, D)))
@@ -93,10 +96,11 @@ def _decode_case(batch, D, Hq, Hkv, H, F, L, C, n_c, t_prompt, n_steps, seed, fu
             assert pc.percache_kv_len(0, seq_slots[b]) == t_prompt + step + 1 == pc.percache_kv_len(L - 1, seq_slots[b])
         check_hidden(host(out[:, 0]), host(ref[:, -1]), f"decode step {step} (batch {batch} D {D} heads {Hq}/{Hkv} H {H} layers {L} "
                      f"chunks {n_c}x{C} prompt {t_prompt}) vs full prefill", rel_max=2.0 ** -5)
-    h = seqs[0]
-    for W in Ws:
-        h, _, _ = oracle_block(h, W, Hq, Hkv, D, 10000.0)
-    check_hidden(host(out[0, 0]), h[-1], "last decode step vs oracle stack")
+    for b in range(batch):
+        h = seqs[b]
+        for W in Ws:
+            h, _, _ = oracle_block(h, W, Hq, Hkv, D, 10000.0)
+        check_hidden(host(out[b, 0]), h[-1], f"last decode step vs oracle stack, query {b}")
     if not full_slot:
         return
     # a sequence slot that is full refuses the step and nothing changes

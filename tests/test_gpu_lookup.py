@@ -30,8 +30,7 @@ def _compare(bank, probes, tau, idx, sim, hit):
     for p in np.nonzero(~clear)[0]:
         s = oracle.similarities(bank, probes[p])
         assert o_sim[p] - s[idx[p]] < 1e-4
-    margin = np.abs(o_sim - tau) > 1e-4
-    assert np.array_equal(hit[margin], o_hit[margin])
+    assert np.array_equal(hit, o_hit)
     return int((~clear).sum())
 
 
@@ -173,9 +172,9 @@ def test_overwrite_rows_and_error_paths():
     assert e.value.status == -2
 
 
-def test_config3_full_size_sampled_probes():
-    """200k x 1024 fp16 bank, the 1024 probes of the recipe plus the hit-branch block; the oracle checks
-    a seeded sample of 192 probes (the rest are checked for internal consistency)."""
+def test_config3_full_size_every_probe():
+    """200k x 1024 fp16 bank, the 1024 probes of the recipe plus the hit-branch block; every one of the 1152 probes
+    goes through the oracle's exhaustive scan."""
     w = wl.lookup_config3(n_exact=64, n_near=64)
     N, d = w.bank.shape
     P = w.probes.shape[0]
@@ -194,10 +193,9 @@ def test_config3_full_size_sampled_probes():
         i3, s3, h3 = pc.percache_lookup(probes_dev[lo:lo + 128], w.tau)
         torch.cuda.synchronize()
         assert torch.equal(i3, idx[lo:lo + 128]) and torch.equal(h3, hit[lo:lo + 128]) and (s3 - sim[lo:lo + 128]).abs().max().item() < 2e-6
-    g = np.random.default_rng(0)
-    sample = np.sort(np.concatenate([g.choice(1024, 128, replace=False), 1024 + g.choice(128, 64, replace=False)]))
-    n_near_ties = _compare(w.bank, w.probes[sample], w.tau, idx[sample], sim[sample], hit[sample])
-    print(f"cfg3: {len(sample)} sampled probes, {n_near_ties} with top-2 gap < 1e-4; hits in main block "
+    print("cfg3: oracle scan of all probes ...", flush=True)
+    n_near_ties = _compare(w.bank, w.probes, w.tau, idx, sim, hit)
+    print(f"cfg3: {P} probes through the oracle, {n_near_ties} with top-2 gap < 1e-4; hits in main block "
           f"{int(hit[:1024].sum())}/1024, in hit block {int(hit[1024:].sum())}/128", flush=True)
     idx_h, hit_h = idx.cpu().numpy(), hit.cpu().numpy()
     copies = w.source[:1024] >= 0
@@ -266,7 +264,7 @@ def test_topk_ties_small_bank_and_errors():
 
 @pytest.mark.parametrize("dim,n_new", [(1024, 5), (1024, 70), (128, 33)])
 def test_refresh_scan_vs_oracle(dim, n_new):
-    """Cache refresh (Sec. 4.1.3): stored queries in the bank, thresholds from a top-k over the chunk embeddings (GPU),
+    """Cache refresh (Sec. 4.1.3): stored queries in the bank, thresholds from the oracle's top-k over the chunk embeddings,
     new chunks scanned; against the oracle's row-by-row definition, and against a direct re-ranking."""
     k = 3
     wq = wl.lookup_clustered("q", 500 + dim, 97, 53, dim, 4, 0.05, 0.02, 0.92)       # bank rows = stored queries
@@ -274,10 +272,8 @@ def test_refresh_scan_vs_oracle(dim, n_new):
     g = np.random.default_rng(dim + n_new)
     pick = g.integers(0, wq.bank.shape[0], size=n_new)
     new = wl.round_f16(wq.bank[pick] + 0.03 * g.standard_normal((n_new, dim)).astype(np.float32))
-    chunks_ctx = _ctx(wc.bank.shape[0], dim)
-    chunks_ctx.percache_bank_put(0, f16(wc.bank))
-    _, sk = chunks_ctx.percache_lookup_topk(f16(wq.bank), k)                          # each stored query's best chunks
-    kth = sk[:, k - 1].contiguous()
+    _, o_sk, _ = oracle.lookup_topk(wc.bank, wq.bank, k)                              # each stored query's best chunks
+    kth = torch.from_numpy(np.ascontiguousarray(o_sk[:, k - 1], np.float32)).to(DEV)
     qctx = _ctx(wq.bank.shape[0], dim)
     qctx.percache_bank_put(0, f16(wq.bank))
     best_sim, best_new, stale = qctx.percache_bank_refresh_scan(f16(new), kth)
@@ -290,7 +286,7 @@ def test_refresh_scan_vs_oracle(dim, n_new):
         s = oracle.similarities(new, wq.bank[j])
         assert o_sim[j] - s[bn[j]] < 1e-4
         loose += 1
-    margin = np.abs(o_sim - kth.cpu().numpy()) > 1e-4
+    margin = np.abs(o_sim - kth.cpu().numpy()) > 2e-5           # the similarity tolerance: closer than that, either decision
     assert np.array_equal(st[margin], o_stale[margin])
     assert st[pick].all()                                                             # a near copy of a query enters its top-k
     print(f"refresh scan: {int(st.sum())}/{st.size} stored queries outdated, {loose} near-tie indices", flush=True)

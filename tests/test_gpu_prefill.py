@@ -336,9 +336,10 @@ def test_repeated_calls_are_bit_identical():
     pc.close()
 
 
-def test_config4_full_size_sampled_rows():
+def test_config4_full_size_one_query_in_full_and_sampled_rows():
     """Full config 4 (batch 8, 16 x 1024 cached tokens, 256 fresh) in the launch configuration the benchmark
-    times; the oracle computes 96 sampled (query, row, head) outputs plus fresh K/V of one query."""
+    times.  The oracle computes query 0 completely (all 256 rows x 24 heads, and its fresh K/V) and 70 sampled
+    (query, row, head) outputs of the other seven queries, first and last row included."""
     w = wl.config4()
     pc = make_ctx(w)
     fill_slots(pc, w, w.slot_ids.reshape(-1))
@@ -347,19 +348,87 @@ def test_config4_full_size_sampled_rows():
     out = pc.percache_prefill_reuse(0, bf16(w.X), bf16(w.Wqkv), w.slot_ids, w.used_len, k_fresh_out=kf, v_fresh_out=vf)
     torch.cuda.synchronize()
     assert torch.isfinite(out.float()).all().item()
+    O, Kf, Vf, _ = _oracle_query(w, 0)
+    check_close(host(out[0]), O, "cfg4 query 0, every row and head")
+    check_close(host(kf[0]), Kf, "cfg4 k_fresh b=0")
+    check_close(host(vf[0]), Vf, "cfg4 v_fresh b=0")
     g = np.random.default_rng(4)
     out_h = host(out).reshape(w.batch, w.t_fresh, w.n_q_heads, w.head_dim)
     got, ref = [], []
-    for b in range(w.batch):
-        rows = g.integers(0, w.t_fresh, 12)
-        heads = g.integers(0, w.n_q_heads, 12)
+    for b in range(1, w.batch):
+        rows = g.integers(0, w.t_fresh, 10)
+        heads = g.integers(0, w.n_q_heads, 10)
         rows[0], rows[1] = 0, w.t_fresh - 1
-        O, Kf, Vf, _ = _oracle_query(w, b, samples=(rows, heads))
+        O, _, _, _ = _oracle_query(w, b, samples=(rows, heads))
         got.append(np.stack([out_h[b, i, h] for i, h in zip(rows, heads)]))
         ref.append(O)
-        if b == 0:
-            check_close(host(kf[0]), Kf, "cfg4 k_fresh b=0")
-            check_close(host(vf[0]), Vf, "cfg4 v_fresh b=0")
         print(f"cfg4 b={b} sampled", flush=True)
-    check_close(np.concatenate(got), np.concatenate(ref), "cfg4 sampled rows")
+    check_close(np.concatenate(got), np.concatenate(ref), "cfg4 sampled rows of queries 1..7")
+    pc.close()
+
+
+def test_peaked_softmax_through_the_fused_path():
+    """A peaked case through projection + RoPE + attention in one call (hidden states x8: scores up to about +-25).
+    The GPU rounds q and k to bf16 once (relative error at most 2^-9 per element), the oracle does not, so a score
+    moves by at most  eps_s(i, j) = (2 * 2^-9 + 2^-18) * sum_d |q_id k_jd| / sqrt(D).  With delta_i the largest
+    eps_s of row i, every probability changes by a factor within [e^-2delta, e^2delta], the l1 distance of the two
+    probability rows is at most e^(2 delta) - 1, and because both rows sum to one
+        |o'_i - o_i| <= (e^(2 delta_i) - 1 + 2^-8) * max_j |v_j - o_i|      (2^-8: bf16 rounding of p and of v)
+    element by element.  The bound is computed here from the oracle's own q, k, v, o; a mistake in the running
+    maximum, the rescale or the row sum shows as an error of the size of |v| itself."""
+    w = wl.config1(x_scale=8.0, seed=23, t_fresh=96)
+    pc = make_ctx(w)
+    fill_slots(pc, w, w.slot_ids.reshape(-1))
+    out = host(pc.percache_prefill_reuse(0, bf16(w.X), bf16(w.Wqkv), w.slot_ids, w.used_len)[0])
+    torch.cuda.synchronize()
+    sk, sv, ids = w.compact_store(0)
+    O, Kf, Vf, Q = oracle.prefill_reuse(w.X[0], w.Wqkv, w.n_q_heads, w.n_kv_heads, w.head_dim, w.rope_theta, sk, sv, ids, w.used_len[0])
+    D, T, G = w.head_dim, w.t_fresh, w.n_q_heads // w.n_kv_heads
+    worst_ratio, peak_score = 0.0, 0.0
+    for h in range(w.n_q_heads):
+        kv = h // G
+        K_all = np.concatenate([sk[c, kv, :u] for c, u in zip(ids, w.used_len[0])] + [Kf[kv]]).astype(np.float64)
+        V_all = np.concatenate([sv[c, kv, :u] for c, u in zip(ids, w.used_len[0])] + [Vf[kv]]).astype(np.float64)
+        n_cached = K_all.shape[0] - T
+        q = Q[h].astype(np.float64)
+        eps_s = (2 * 2.0 ** -9 + 2.0 ** -18) * (np.abs(q) @ np.abs(K_all).T) / np.sqrt(D)
+        vis = np.arange(K_all.shape[0])[None, :] < (n_cached + 1 + np.arange(T))[:, None]
+        peak_score = max(peak_score, float(np.abs((q @ K_all.T) / np.sqrt(D))[vis].max()))
+        delta = np.where(vis, eps_s, 0.0).max(axis=1)
+        o = O[:, h * D:(h + 1) * D].astype(np.float64)
+        for i in range(T):
+            spread = np.abs(V_all[: n_cached + i + 1] - o[i]).max(axis=0)             # per output element
+            bound = (np.expm1(2 * delta[i]) + 2.0 ** -8) * spread + 1e-6
+            err = np.abs(out[i, h * D:(h + 1) * D] - o[i])
+            worst_ratio = max(worst_ratio, float((err / bound).max()))
+    fro = np.linalg.norm(out - O) / np.linalg.norm(O)
+    print(f"peaked fused path: largest |score| {peak_score:.1f}, worst error / bound {worst_ratio:.3f}, rel-fro {fro:.3e}", flush=True)
+    assert peak_score > 15.0 and worst_ratio <= 1.0
+    pc.close()
+
+
+def test_probabilities_far_above_the_reference_exponent():
+    """The reference exponent of a row is refreshed only when the SUM of a lane's 32 probabilities of a tile exceeds
+    32 * 2^8, so a single probability can reach 2^13 against a stale reference.  Rows whose first tile has scores 0
+    meet, tiles later, one key whose score is 9 .. 12.9 log2 units higher (everything else stays at 0): no refresh
+    happens, the probability is carried as a bf16 value up to 2^12.9, and the result must still match."""
+    D, C, T = 128, 256, 40
+    w = wl.make_prefill("hot", 31, "bf16", 256, 2, 1, D, 1, T, 1, C, 2)
+    pc = make_ctx(w)
+    g = np.random.default_rng(3)
+    k = np.zeros((1, C, D), np.float32)
+    v = wl.round_bf16(g.standard_normal((1, C, D)).astype(np.float32))
+    hot = [64 + 7, 128 + 40, 192 + 63]
+    k[0, hot, 0] = 1.0
+    pc.percache_kv_put(0, 1, bf16(k), bf16(v))
+    # q = a e_0: score of a hot key = a / sqrt(D), in log2 units a log2(e) / sqrt(D) = 9 .. 12.9 over the rows
+    lifts = np.linspace(9.0, 12.9, T)
+    Q = np.zeros((2, T, D), np.float32)
+    Q[:, :, 0] = wl.round_bf16((lifts * np.sqrt(D) / np.log2(np.e)).astype(np.float32))[None, :]
+    Kf = np.zeros((1, T, D), np.float32)
+    Vf = wl.round_bf16(g.standard_normal((1, T, D)).astype(np.float32))
+    out = pc.percache_attention_reuse(0, bf16(Q)[None], bf16(Kf)[None], bf16(Vf)[None], [[1]], n_splits=1)
+    torch.cuda.synchronize()
+    ref = oracle.attention_reuse(Q, Kf, Vf, k[None], v[None], [0], [C])
+    check_close(host(out[0]), ref, "probabilities up to 2^12.9 against a stale reference", max_abs=2e-2, mean_abs=2e-3, rel_fro=6e-3)
     pc.close()

@@ -195,6 +195,52 @@ def test_config2_full_size_reuse_equals_full_recompute():
     check_hidden(host(one[0, :96]), ref, "cfg2: layer 0 of the full pass, rows 0..95")
 
 
+def depth_bounds(n_layers):
+    """Bar on the relative Frobenius error of the hidden state after ``n_layers`` blocks against the unrounded oracle.
+    One bf16 rounding has a relative error of at most 2^-9, uniformly spread: rms u = 2^-9 / sqrt(3).  In a block two
+    stored tensors have the residual's own size (h' and h''), the branch outputs carry a few more roundings at a
+    fraction of it: about 2u per block (measured 2.3e-3 = 2.04u).  The errors of different blocks are independent and
+    ride along the residual path with unit gain, so after L blocks the relative Frobenius error is 2u sqrt(L); the bar
+    allows twice that for what the non-linear branches add.  Element by element the error is largely relative to the
+    element's own size (the roundings of the residual stream itself), so the largest error sits on the largest
+    elements: four standard deviations of the expected relative error bar/2 there, i.e. max-abs <= 2 bar max|ref|."""
+    u = 2.0 ** -9 / np.sqrt(3.0)
+    return 4.0 * u * np.sqrt(n_layers)
+
+
+def test_config2_random_store_reuse_vs_oracle_at_depth():
+    """Config 2 as worded: 28 layers, 8 chunks x 512 tokens gathered from a 256-slot store of N(0,1) K/V by random slot
+    ids, 128 fresh tokens.  The oracle's blocks are chained over all 28 layers on the reuse path and compared with
+    percache_stack_reuse after the last layer (and after layers 1, 2, 7, 14 of the same chain, from shorter GPU runs)."""
+    w = wl.config2()
+    F, L, C, n_c, Tf = 3072, w.n_layers, w.chunk_tokens, w.n_chunks, w.t_fresh
+    Ws = [wl.stack_weights(2, l, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, F) for l in range(L)]
+    layers = dev_layers(Ws)
+    pc = Percache(n_layers=L, hidden=w.hidden, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
+                  n_slots=w.n_slots, slot_capacity=C, max_pos=n_c * C + Tf, device=DEV)
+    slots = [int(s) for s in w.slot_ids[0]]
+    for l in range(L):
+        for s_, (k, v) in w.slots_kv(slots, l).items():
+            pc.percache_kv_put(l, s_, bf16(k), bf16(v))
+    x = bf16(w.X)
+    got = {n: host(pc.percache_stack_reuse(layers[:n], F, EPS, x, w.slot_ids, w.used_len)[0]) for n in (1, 2, 7, 14, L)}
+    torch.cuda.synchronize()
+    h = w.X[0]
+    for l in range(L):
+        sk, sv, ids = w.compact_store(0, l)
+        h, _, _ = oracle_block(h, Ws[l], w.n_q_heads, w.n_kv_heads, w.head_dim, w.rope_theta, sk, sv, ids, w.used_len[0])
+        n = l + 1
+        if n in got:
+            bar = depth_bounds(n)
+            top = float(np.abs(h).max())
+            err = np.abs(got[n] - h)
+            fro = np.linalg.norm(got[n] - h) / np.linalg.norm(h)
+            print(f"cfg2 random store, after {n} layers: rel-fro {fro:.3e} (bar {bar:.3e}) max-abs {err.max():.3e} "
+                  f"(bar {2 * bar * top:.3e}, max|ref| {top:.3f})", flush=True)
+            assert np.isfinite(got[n]).all() and fro <= bar and err.max() <= 2 * bar * top
+    pc.close()
+
+
 @pytest.mark.parametrize("D,t_fresh,which,heads", [
     (128, 40, "all", (4, 2)), (64, 40, "all", (4, 2)), (128, 260, "all", (4, 2)), (64, 260, "all", (4, 2)),
     (128, 260, "bias", (4, 2)), (128, 40, "norm", (4, 2)), (64, 260, "qnorm", (4, 2)),
