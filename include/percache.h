@@ -97,6 +97,18 @@ pc_status percache_lookup(percache_ctx *ctx, const void *probes_dev, int32_t n_p
                           int32_t *idx_out_dev, float *sim_out_dev, uint8_t *hit_out_dev,
                           void *workspace_dev, size_t workspace_bytes, void *stream);
 
+/* percache_lookup for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same result as percache_lookup.  The per-workgroup
+ * partial results go to a file-scope device array of the library (1 MiB, held by every GPU the library has created
+ * a context on until the process ends) instead of a caller workspace; the call allocates and frees nothing.
+ *   limits: n_probes <= 32 (one streaming pass of the bank) and a bank whose percache_lookup_workspace_bytes(ctx, 32)
+ *           fits the array (bank_capacity up to about one million rows); beyond them PC_ESHAPE, nothing enqueued.
+ *   sharing: every call on one GPU, from any context, uses that GPU's one array, and the array keeps the last call's
+ *           contents (nothing in it needs clearing: a pass writes every entry it later reads).  Calls that can
+ *           overlap on one GPU (different streams, different contexts) race on it; serialise them. */
+pc_status percache_lookup_noalloc(percache_ctx *ctx, const void *probes_dev, int32_t n_probes, float tau,
+                                  int32_t *idx_out_dev, float *sim_out_dev, uint8_t *hit_out_dev, void *stream);
+
 /* The k best rows per probe instead of the best one (1 <= k <= 8): the ranking that cache refresh (Sec. 4.1.3,
  * "top-k_refresh") and dense retrieval over chunk embeddings need.  Same similarity, same tie rule (equal
  * similarities: lower row first), sorted best first.

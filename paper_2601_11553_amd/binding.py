@@ -23,7 +23,7 @@ STATUS_NAMES = {0: "PC_OK", -1: "PC_EINVAL", -2: "PC_ESHAPE", -3: "PC_ESLOT", -4
 EXPORTS = [
     "percache_arena_bytes", "percache_create", "percache_destroy", "percache_last_error",
     "percache_bank_put", "percache_bank_size", "percache_lookup_workspace_bytes", "percache_lookup",
-    "percache_lookup_topk", "percache_bank_refresh_scan",
+    "percache_lookup_noalloc", "percache_lookup_topk", "percache_bank_refresh_scan",
     "percache_kv_put", "percache_kv_put_batch", "percache_kv_get", "percache_kv_evict", "percache_kv_len",
     "percache_kv_slice", "percache_kv_append", "percache_stack_workspace_bytes", "percache_stack_reuse",
     "percache_stack_decode",
@@ -80,6 +80,7 @@ def load_library() -> ctypes.CDLL:
         "percache_bank_size": (_i32, [_vp]),
         "percache_lookup_workspace_bytes": (_sz, [_vp, _i32]),
         "percache_lookup": (_i32, [_vp, _vp, _i32, ctypes.c_float, _vp, _vp, _vp, _vp, _sz, _vp]),
+        "percache_lookup_noalloc": (_i32, [_vp, _vp, _i32, ctypes.c_float, _vp, _vp, _vp, _vp]),
         "percache_lookup_topk": (_i32, [_vp, _vp, _i32, _i32, _vp, _vp, _vp, _sz, _vp]),
         "percache_bank_refresh_scan": (_i32, [_vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
         "percache_kv_put": (_i32, [_vp, _i32, _i32, _vp, _vp, _i32, _vp]),
@@ -215,6 +216,12 @@ class Percache:
         ws = (self._lookup_ws.data_ptr() + 255) // 256 * 256
         self._check(self.lib.percache_lookup(self.ctx, _ptr(probes), n, tau, _ptr(idx_out), _ptr(sim_out),
                                              _ptr(hit_out), ws, need, _stream()))
+        return idx_out, sim_out, hit_out
+
+    def percache_lookup_noalloc(self, probes, tau: float, idx_out, sim_out, hit_out):
+        """percache_lookup into caller-provided outputs, partial results in the library's static scratch (no workspace)."""
+        self._check(self.lib.percache_lookup_noalloc(self.ctx, _ptr(probes), probes.shape[0], tau, _ptr(idx_out),
+                                                     _ptr(sim_out), _ptr(hit_out), _stream()))
         return idx_out, sim_out, hit_out
 
     def percache_lookup_topk(self, probes, k: int):

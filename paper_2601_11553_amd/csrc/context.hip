@@ -7,6 +7,13 @@
 namespace {
 thread_local std::string g_create_err;
 
+// Scratch of the entry points that allocate nothing (partial results of the lookup pass).  Every GPU holds its own
+// copy of this array at its own address; in host code the array's name is only a stand-in for hipGetSymbolAddress,
+// never a pointer to hand to a kernel.  Address per device, resolved at percache_create with that device current.
+__device__ __align__(256) unsigned char scratch[pc::kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices] = {};
+
 bool config_ok(const percache_config *c, std::string &why) {
   char buf[256];
   auto bad = [&](const char *m) { why = m; return false; };
@@ -224,6 +231,14 @@ pc_status percache_create(const percache_config *cfg, void *arena_dev, size_t ar
   e = hipGetDeviceProperties(&prop, dev);
   if (e != hipSuccess) return bail(e, "hipGetDeviceProperties");
   ctx->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+  if (dev < 0 || dev >= kMaxDevices) return bail(hipErrorInvalidDevice, "device ordinal beyond the library's table");
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return bail(e, "hipGetSymbolAddress(scratch)");
+    g_scratch_ptr[dev] = p;
+  }
+  ctx->static_scratch = g_scratch_ptr[dev];
   for (int i = 0; i < pc::kStageRing; ++i) {
     e = hipEventCreateWithFlags(&ctx->stage_ev[i], hipEventDisableTiming);
     if (e != hipSuccess) return bail(e, "hipEventCreate");

@@ -889,6 +889,22 @@ pc_status percache_lookup(percache_ctx *ctx, const void *probes_dev, int32_t n_p
   return run_lookup(ctx, probes_dev, n_probes, tau, 1, idx_out_dev, sim_out_dev, hit_out_dev, workspace_dev, workspace_bytes, stream);
 }
 
+pc_status percache_lookup_noalloc(percache_ctx *ctx, const void *probes_dev, int32_t n_probes, float tau,
+                                  int32_t *idx_out_dev, float *sim_out_dev, uint8_t *hit_out_dev, void *stream) {
+  if (!ctx) return PC_EINVAL;
+  if (n_probes > kPassProbes)
+    return pc::fail(ctx, PC_ESHAPE, "percache_lookup_noalloc takes at most %d probes per call, got %d", kPassProbes, n_probes);
+  const size_t need = percache_lookup_workspace_bytes(ctx, n_probes < 0 ? 0 : n_probes);
+  if (need > pc::kStaticScratchBytes)
+    return pc::fail(ctx, PC_ESHAPE, "a bank of %d rows needs %zu bytes of scratch, the library's static scratch holds %zu",
+                    ctx->cfg.bank_capacity, need, pc::kStaticScratchBytes);
+  if (!ctx->static_scratch) return pc::fail(ctx, PC_EHIP, "static scratch was not resolved on this device");
+  // nothing in the scratch has to start at zero: every workgroup of a pass writes all of its lists before the
+  // finalize kernel (next on the stream) reads exactly those
+  return run_lookup(ctx, probes_dev, n_probes, tau, 1, idx_out_dev, sim_out_dev, hit_out_dev, ctx->static_scratch,
+                    pc::kStaticScratchBytes, stream);
+}
+
 pc_status percache_bank_refresh_scan(percache_ctx *ctx, const void *new_emb_dev, int32_t n_new, const float *kth_sim_dev,
                                      float *best_sim_out_dev, int32_t *best_new_out_dev, uint8_t *stale_out_dev,
                                      void *workspace_dev, size_t workspace_bytes, void *stream) {

@@ -52,6 +52,9 @@ inline int tbl_stride(int max_chunks) { return kTblHeader + 2 * (max_chunks > 0 
 
 constexpr int kStageRing = 16;
 
+// Size of the file-scope scratch array behind the entry points that allocate nothing.
+constexpr size_t kStaticScratchBytes = 1u << 20;
+
 }  // namespace pc
 
 struct percache_ctx {
@@ -80,6 +83,9 @@ struct percache_ctx {
   size_t stage_ints = 0;
   int stage_next = 0;
   int n_cu = 256;
+  // this device's copy of the library's file-scope scratch array (resolved once per device at create), for the
+  // entry points that must not take a workspace
+  void *static_scratch = nullptr;
   // optional kernel timing (event pairs per kernel kind)
   bool prof_on = false;
   std::vector<hipEvent_t> prof_beg[3], prof_end[3];
