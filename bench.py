@@ -60,8 +60,75 @@ def _wall_ms(torch, fn, iters, warmup):
     return (time.perf_counter() - a) * 1e3 / iters
 
 
+def _stats(torch, fn, iters=50, warmup=5):
+    """Side-measurement protocol: `iters` (>= 50) calls back to back; per call the GPU time between two events on the
+    stream (median and min), and the wall-clock mean over the whole run (what a caller's loop sees, host launches
+    included)."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+    a = time.perf_counter()
+    for e0, e1 in ev:
+        e0.record()
+        fn()
+        e1.record()
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - a) * 1e3 / iters
+    t = np.array([e0.elapsed_time(e1) for e0, e1 in ev])
+    return {"median_ms": round(float(np.median(t)), 4), "min_ms": round(float(t.min()), 4), "wall_mean_ms": round(wall, 4), "iters": iters}
+
+
+def achievable_peaks(torch, pc, dev):
+    """What this GPU sustains with kernels that do nothing else: a register-resident bf16 MFMA loop on constant and on
+    random operands, and a streaming read of 1 GiB in which every workgroup walks one contiguous range."""
+    res = {}
+    for name, rnd in (("mfma_bf16_constant_operands_TFLOPs", False), ("mfma_bf16_random_operands_TFLOPs", True)):
+        pc.percache_peak_mfma_bf16(200, rnd)
+        torch.cuda.synchronize()
+        best = []
+        for _ in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fl = pc.percache_peak_mfma_bf16(20000, rnd)       # about 10-15 ms: long enough for the clock to settle
+            e1.record()
+            e1.synchronize()
+            best.append(fl / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+        res[name] = round(float(np.median(best)), 1)
+    buf = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(3)
+    pc.percache_peak_stream_read(buf)
+    torch.cuda.synchronize()
+    rates = []
+    for _ in range(10):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        n = pc.percache_peak_stream_read(buf)
+        e1.record()
+        e1.synchronize()
+        rates.append(n / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+    del buf
+    res["stream_read_GBps"] = round(float(np.median(rates)), 1)
+    return res
+
+
+def _capture(torch, fn):
+    """Captures one call of fn (kernels only) into a HIP graph on a side stream; returns the graph."""
+    fn()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        graph.capture_begin()
+        fn()
+        graph.capture_end()
+    torch.cuda.synchronize()
+    return graph
+
+
 def bench_cfg1(torch, wl, binding, Percache, dev, bf):
-    """One 0.6B-shaped layer, batch 1, 4 x 512 cached + 64 fresh tokens: bound by the K/V stream and launch latency."""
+    """One 0.6B-shaped layer, batch 1, 4 x 512 cached + 64 fresh tokens: bound by the K/V stream and launch latency.
+    Three ways to issue the same call: host chunk lists (a small copy per call), a device-resident chunk table
+    (kernels only), and that call captured into a HIP graph and replayed."""
     w = wl.config1()
     pc = Percache(n_layers=1, hidden=w.hidden, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
                   n_slots=w.n_slots, slot_capacity=w.chunk_tokens, max_pos=w.max_pos, rope_theta=w.rope_theta, device=dev)
@@ -70,24 +137,30 @@ def bench_cfg1(torch, wl, binding, Percache, dev, bf):
     X, W = bf(w.X), bf(w.Wqkv)
     out = torch.empty((1, w.t_fresh, w.n_q_heads * w.head_dim), dtype=torch.bfloat16, device=dev)
     fn = lambda: pc.percache_prefill_reuse(0, X, W, w.slot_ids, w.used_len, attn_out=out)
+    table = pc.percache_chunk_table_put(w.slot_ids, w.used_len)
+    fn_table = lambda: pc.percache_prefill_reuse_table(0, X, W, table, out)
     _wall_ms(torch, fn, 20, 10)
     pc.percache_profile_enable(True)
     ms = _wall_ms(torch, fn, 100, 0)
     ms_attn, n_attn = pc.percache_profile_read(binding.KERNEL_ATTENTION)
     ms_qkv, n_qkv = pc.percache_profile_read(binding.KERNEL_QKV_ROPE)
     pc.percache_profile_enable(False)
+    eager = _stats(torch, fn, 100, 10)
+    eager_table = _stats(torch, fn_table, 100, 10)
+    graph = _capture(torch, fn_table)
+    replay = _stats(torch, graph.replay, 100, 10)
     # GPU time of one call between two events on the stream, caches warm and flushed: for the latter a 512 MiB buffer
     # (twice the last-level cache) is rewritten before each call
     flush = torch.empty(1 << 29, dtype=torch.uint8, device=dev)
     ev = {"warm": [], "cold": []}
     for kind in ("warm", "cold"):
-        for _ in range(20):
+        for _ in range(50):
             if kind == "cold":
                 flush.fill_(1)
             torch.cuda._sleep(400_000)   # keeps the GPU busy while the host queues the call: the events then bracket GPU time
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
-            fn()
+            fn_table()
             e1.record()
             e1.synchronize()
             ev[kind].append(e0.elapsed_time(e1))
@@ -95,8 +168,12 @@ def bench_cfg1(torch, wl, binding, Percache, dev, bf):
     pc.close()
     kv_bytes = float(w.l_pre[0]) * w.n_kv_heads * w.head_dim * 2 * 2
     w_bytes = float(w.Wqkv.size) * 2
-    return {"ms_per_call": round(ms, 4), "gpu_ms_per_call_caches_warm": round(float(np.median(ev["warm"])), 4),
-            "gpu_ms_per_call_caches_flushed": round(float(np.median(ev["cold"])), 4), "fresh_tokens_per_s": round(w.t_fresh / (ms * 1e-3), 1),
+    gpu_warm = float(np.median(ev["warm"]))
+    return {"ms_per_call": round(ms, 4), "fresh_tokens_per_s": round(w.t_fresh / (ms * 1e-3), 1),
+            "host_lists_eager": eager, "device_table_eager": eager_table, "device_table_graph_replay": replay,
+            "gpu_ms_per_call_caches_warm": round(gpu_warm, 4), "gpu_ms_per_call_caches_warm_min": round(float(np.min(ev["warm"])), 4),
+            "gpu_ms_per_call_caches_flushed": round(float(np.median(ev["cold"])), 4),
+            "graph_wall_over_gpu_time": round(replay["wall_mean_ms"] / gpu_warm, 3),
             "attention_ms": round(ms_attn / n_attn, 4), "kv_stream_GBps": round(kv_bytes / (ms_attn / n_attn * 1e-3) / 1e9, 1),
             "qkv_rope_ms": round(ms_qkv / n_qkv, 4), "weight_stream_GBps": round(w_bytes / (ms_qkv / n_qkv * 1e-3) / 1e9, 1)}
 
@@ -129,7 +206,8 @@ def bench_fp8_slots(torch, wl, binding, Percache, dev, bf, w, X, W):
 
 def bench_cfg2(torch, wl, Percache, dev, bf):
     """28-layer 0.6B-shaped stack: reuse of 8 x 512 cached tokens + 128 fresh rows against the full prefill of all
-    4224 tokens (same kernels, no chunks).  The cache is filled by the full pass itself (slicer)."""
+    4224 tokens (same kernels, no chunks).  The cache is filled by the full pass itself (slicer).  The reuse pass is
+    issued with host chunk lists, with a device-resident chunk table, and as a captured HIP graph."""
     w = wl.config2()
     F, L, C, n_c, Tf = 3072, w.n_layers, w.chunk_tokens, w.n_chunks, w.t_fresh
     total = n_c * C + Tf
@@ -147,10 +225,19 @@ def bench_cfg2(torch, wl, Percache, dev, bf):
     pc.percache_stack_reuse(layers, F, 1e-6, h0, save_bounds=bounds, save_slots=[slots + [-1]], h_out=h_full)
     hf = h0[:, n_c * C:].contiguous()
     h_reuse = torch.empty_like(hf)
-    reuse_ms = _wall_ms(torch, lambda: pc.percache_stack_reuse(layers, F, 1e-6, hf, [slots], h_out=h_reuse), 20, 5)
-    full_ms = _wall_ms(torch, lambda: pc.percache_stack_reuse(layers, F, 1e-6, h0, h_out=h_full), 5, 2)
+    eager = _stats(torch, lambda: pc.percache_stack_reuse(layers, F, 1e-6, hf, [slots], h_out=h_reuse), 50, 5)
+    table = pc.percache_chunk_table_put([slots])
+    arr = pc.percache_stack_reuse_table(layers, F, 1e-6, hf, table, h_reuse)
+    fn_table = lambda: pc.percache_stack_reuse_table(layers, F, 1e-6, hf, table, h_reuse, weights=arr)
+    eager_table = _stats(torch, fn_table, 50, 5)
+    graph = _capture(torch, fn_table)
+    replay = _stats(torch, graph.replay, 50, 5)
+    full = _stats(torch, lambda: pc.percache_stack_reuse(layers, F, 1e-6, h0, h_out=h_full), 50, 2)
     pc.close()
-    return {"reuse_ms": round(reuse_ms, 3), "full_recompute_ms": round(full_ms, 3), "speedup": round(full_ms / reuse_ms, 2),
+    reuse_ms = min(eager["wall_mean_ms"], eager_table["wall_mean_ms"], replay["wall_mean_ms"])
+    return {"reuse_ms": round(reuse_ms, 3), "reuse_host_lists_eager": eager, "reuse_device_table_eager": eager_table,
+            "reuse_device_table_graph_replay": replay, "full_recompute": full,
+            "full_recompute_ms": full["wall_mean_ms"], "speedup": round(full["wall_mean_ms"] / reuse_ms, 2),
             "fresh_tokens_per_s": round(Tf / (reuse_ms * 1e-3), 1), "layers": L, "cached_tokens": n_c * C, "fresh_tokens": Tf}
 
 
@@ -231,6 +318,24 @@ def main():
     ms_step = (t1 - t0) * 1e3 / K_steps
     tokens_per_s = B * T / (ms_step * 1e-3)
 
+    # the same step with the bank pass on a second stream of the same priority: the lookup touches only the bank and
+    # its own workspace, so it may run beside the prefill (per-kernel figures above come from the serial run)
+    side = torch.cuda.Stream()
+    ev_fork, ev_join = torch.cuda.Event(), torch.cuda.Event()
+
+    def step_overlapped():
+        ev_fork.record()
+        with torch.cuda.stream(side):
+            side.wait_event(ev_fork)
+            pc.percache_lookup(probes, lw.tau, idx, sim, hit)
+            ev_join.record()
+        pc.percache_prefill_reuse(0, X, W, w.slot_ids, w.used_len, attn_out=attn, k_fresh_out=kf, v_fresh_out=vf)
+        pc.percache_kv_put_batch(0, spare, kf, vf, T)
+        torch.cuda.current_stream().wait_event(ev_join)
+
+    ms_step_overlapped = _wall_ms(torch, step_overlapped, K_steps, max(args.warmup, 3))
+    peaks = achievable_peaks(torch, pc, dev)
+
     fl_attn = attention_flops(B, w.n_q_heads, w.head_dim, T, w.l_pre)
     attn_ms = ms_attn / max(n_attn, 1)
     attn_tflops = fl_attn / (attn_ms * 1e-3) / 1e12
@@ -241,50 +346,44 @@ def main():
     kv_bytes = float(sum(w.l_pre)) * w.n_kv_heads * w.head_dim * 2 * 2
 
     # ------------------------------------------------------------------ lookup on its own (lookups/s)
-    def time_lookup(p_dev, iters=20):
+    def time_lookup(p_dev):
         n = p_dev.shape[0]
         oi = torch.empty(n, dtype=torch.int32, device=dev)
         os_ = torch.empty(n, dtype=torch.float32, device=dev)
         oh = torch.empty(n, dtype=torch.uint8, device=dev)
-        for _ in range(3):
-            pc.percache_lookup(p_dev, lw.tau, oi, os_, oh)
-        torch.cuda.synchronize()
-        a = time.perf_counter()
-        for _ in range(iters):
-            pc.percache_lookup(p_dev, lw.tau, oi, os_, oh)
-        torch.cuda.synchronize()
-        return (time.perf_counter() - a) / iters
+        return _stats(torch, lambda: pc.percache_lookup(p_dev, lw.tau, oi, os_, oh), 50, 3), oh
 
     look = {}
     for p in (1, 8, 32, 128, 1024):
-        t = time_lookup(probes_all[:p].contiguous())
+        st, oh = time_lookup(probes_all[:p].contiguous())
+        t = st["median_ms"] * 1e-3
         if p <= 128:  # one streaming pass of the bank (2 N d p flop on N d 2 bytes: below the ridge): HBM bound
-            look[f"P{p}"] = {"ms": round(t * 1e3, 4), "lookups_per_s": round(p / t, 1), "bound": "hbm",
-                             "bank_GBps": round(bank_bytes / t / 1e9, 1), "frac_of_hbm_peak": round(bank_bytes / t / 1e9 / PEAK_HBM_GBS, 4)}
+            look[f"P{p}"] = dict(st, lookups_per_s=round(p / (st["wall_mean_ms"] * 1e-3), 1), bound="hbm", bank_GBps=round(bank_bytes / t / 1e9, 1),
+                                 frac_of_hbm_peak=round(bank_bytes / t / 1e9 / PEAK_HBM_GBS, 4),
+                                 frac_of_achievable_stream=round(bank_bytes / t / 1e9 / peaks["stream_read_GBps"], 4))
         else:         # matrix-product kernel: fp16 MFMA bound (2 N d flop per probe)
             tf = 2.0 * N * d * p / t / 1e12
-            look[f"P{p}"] = {"ms": round(t * 1e3, 4), "lookups_per_s": round(p / t, 1), "bound": "mfma", "TFLOPs": round(tf, 1),
-                             "frac_of_fp16_peak": round(tf / PEAK_BF16_TFLOPS, 4)}
+            look[f"P{p}"] = dict(st, lookups_per_s=round(p / (st["wall_mean_ms"] * 1e-3), 1), bound="mfma", TFLOPs=round(tf, 1),
+                                 frac_of_fp16_peak=round(tf / PEAK_BF16_TFLOPS, 4),
+                                 frac_of_achievable_mfma_random=round(tf / peaks["mfma_bf16_random_operands_TFLOPs"], 4))
+            hit_rate = float(oh.float().mean().item())
+    # hit rate and the distribution of the gap between the two best similarities of the recipe's 1024 probes
+    _, s2 = pc.percache_lookup_topk(probes_all[:1024].contiguous(), 2)
+    torch.cuda.synchronize()
+    gap = (s2[:, 0] - s2[:, 1]).cpu().numpy()
+    edges = [0.0, 1e-4, 1e-3, 1e-2, 1e-1, 2.0]
+    hist = np.histogram(gap, bins=edges)[0]
+    look["cfg3_probes"] = {"hit_rate_at_tau": round(hit_rate, 4), "tau": lw.tau,
+                           "top2_gap_histogram": {f"[{edges[i]:g},{edges[i + 1]:g})": int(hist[i]) for i in range(len(hist))}}
 
     # ------------------------------------------------------------------ top-k ranking and the cache refresh scan (same bank)
-    def wall(fn, iters=20):
-        for _ in range(3):
-            fn()
-        torch.cuda.synchronize()
-        a = time.perf_counter()
-        for _ in range(iters):
-            fn()
-        torch.cuda.synchronize()
-        return (time.perf_counter() - a) / iters
-
     p8 = probes_all[:8].contiguous()
-    t_topk = wall(lambda: pc.percache_lookup_topk(p8, 8))
+    st_topk = _stats(torch, lambda: pc.percache_lookup_topk(p8, 8), 50, 3)
     new64 = probes_all[64:128].contiguous()               # 64 "new chunk" embeddings against every stored row
     kth = torch.full((N,), 0.5, dtype=torch.float32, device=dev)
-    t_scan = wall(lambda: pc.percache_bank_refresh_scan(new64, kth), iters=10)
-    look["topk_P8_k8"] = {"ms": round(t_topk * 1e3, 4), "bank_GBps": round(bank_bytes / t_topk / 1e9, 1)}
-    look["refresh_scan_64_new"] = {"ms": round(t_scan * 1e3, 4), "passes_of_the_bank": 2,
-                                   "bank_GBps": round(2 * bank_bytes / t_scan / 1e9, 1)}
+    st_scan = _stats(torch, lambda: pc.percache_bank_refresh_scan(new64, kth), 50, 3)
+    look["topk_P8_k8"] = dict(st_topk, bank_GBps=round(bank_bytes / (st_topk["median_ms"] * 1e-3) / 1e9, 1))
+    look["refresh_scan_64_new"] = dict(st_scan, passes_of_the_bank=2, bank_GBps=round(2 * bank_bytes / (st_scan["median_ms"] * 1e-3) / 1e9, 1))
 
     # ------------------------------------------------------------------ the K/V store itself: 16 whole chunks written / read
     # (their contents are overwritten with other N(0,1) values: nothing after this point compares outputs)
@@ -293,17 +392,12 @@ def main():
     kc = torch.randn((len(some), w.n_kv_heads, C, w.head_dim), device=dev).to(torch.bfloat16)
     vc = torch.randn_like(kc)
     chunk_bytes = kc.numel() * 2 * 2                                    # K and V
-    t_put = wall(lambda: pc.percache_kv_put_batch(0, some, kc, vc, C))
-    ko, vo = torch.empty_like(kc[0]), torch.empty_like(kc[0])
-
-    def get_all():
-        for s_ in some:
-            pc.lib.percache_kv_get(pc.ctx, 0, s_, binding._ptr(ko), binding._ptr(vo), None, binding._stream())
-    t_get = wall(get_all)
-    store_io = {"chunks": len(some), "tokens_per_chunk": C, "put_batch_ms": round(t_put * 1e3, 4),
-                "put_GBps_read_plus_written": round(2 * chunk_bytes / t_put / 1e9, 1),
-                "get_ms_per_chunk": round(t_get * 1e3 / len(some), 4),
-                "get_GBps_read_plus_written": round(2 * chunk_bytes / t_get / 1e9, 1)}
+    st_put = _stats(torch, lambda: pc.percache_kv_put_batch(0, some, kc, vc, C), 50, 3)
+    ko, vo = torch.empty_like(kc), torch.empty_like(kc)
+    st_get = _stats(torch, lambda: pc.percache_kv_get_batch(0, some, C, ko, vo), 50, 3)
+    store_io = {"chunks": len(some), "tokens_per_chunk": C, "put_batch": st_put,
+                "put_GBps_read_plus_written": round(2 * chunk_bytes / (st_put["median_ms"] * 1e-3) / 1e9, 1),
+                "get_batch": st_get, "get_GBps_read_plus_written": round(2 * chunk_bytes / (st_get["median_ms"] * 1e-3) / 1e9, 1)}
 
     # ------------------------------------------------------------------ one decoding step of the same layer
     # (one new token per query over the 16 reused chunks + the 256-token prompt slot written by the step above)
@@ -311,7 +405,7 @@ def main():
     ids1 = np.concatenate([w.slot_ids, np.asarray(spare, np.int32)[:, None]], axis=1)
     attn1 = torch.empty((B, 1, w.n_q_heads * w.head_dim), dtype=torch.bfloat16, device=dev)
     dec = lambda: pc.percache_prefill_reuse(0, x1, W, ids1, None, attn_out=attn1)
-    _wall_ms(torch, dec, 10, 5)
+    st_dec = _stats(torch, dec, 50, 5)
     pc.percache_profile_enable(True)
     dec_ms = _wall_ms(torch, dec, 50, 0)
     dec_attn_ms, dec_n = pc.percache_profile_read(binding.KERNEL_ATTENTION)
@@ -330,15 +424,22 @@ def main():
         "roofline": {"bound": "mfma", "kernel": "reuse_attention_kernel<128>", "achieved": round(attn_tflops, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4),
                      "traffic": attention_traffic(), "avg_launch_ms": round(attn_ms, 4), "launches": n_attn,
-                     "algorithmic_flops_per_launch": fl_attn, "kv_stream_GBps": round(kv_bytes / (attn_ms * 1e-3) / 1e9, 1)},
+                     "algorithmic_flops_per_launch": fl_attn, "kv_stream_GBps": round(kv_bytes / (attn_ms * 1e-3) / 1e9, 1),
+                     "achievable_peak": peaks,
+                     "frac_of_achievable_mfma_random": round(attn_tflops / peaks["mfma_bf16_random_operands_TFLOPs"], 4),
+                     "frac_of_achievable_mfma_constant": round(attn_tflops / peaks["mfma_bf16_constant_operands_TFLOPs"], 4)},
+        "step_variants": {"serial_ms": round(ms_step, 4), "lookup_on_second_stream_ms": round(ms_step_overlapped, 4),
+                          "fresh_tokens_per_s_overlapped": round(B * T / (ms_step_overlapped * 1e-3), 1)},
         "breakdown": {
             "qkv_rope": {"avg_launch_ms": round(qkv_ms, 4), "TFLOPs": round(fl_qkv / (qkv_ms * 1e-3) / 1e12, 2),
-                         "frac_of_bf16_peak": round(fl_qkv / (qkv_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)},
+                         "frac_of_bf16_peak": round(fl_qkv / (qkv_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                         "frac_of_achievable_mfma_random": round(fl_qkv / (qkv_ms * 1e-3) / 1e12 / peaks["mfma_bf16_random_operands_TFLOPs"], 4)},
             "lookup_in_step": {"avg_pass_ms": round(look_ms, 4), "bank_GBps": round(bank_bytes / (look_ms * 1e-3) / 1e9, 1),
-                               "frac_of_hbm_peak": round(bank_bytes / (look_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)},
+                               "frac_of_hbm_peak": round(bank_bytes / (look_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                               "frac_of_achievable_stream": round(bank_bytes / (look_ms * 1e-3) / 1e9 / peaks["stream_read_GBps"], 4)},
             "lookup_alone": look,
             "kv_store_io": store_io,
-            "decode_step_layer": {"ms_per_call": round(dec_ms, 4), "attention_ms": round(dec_attn_ms / max(dec_n, 1), 4),
+            "decode_step_layer": {"ms_per_call": round(dec_ms, 4), "per_call": st_dec, "attention_ms": round(dec_attn_ms / max(dec_n, 1), 4),
                                   "kv_stream_GBps": round(dec_bytes / (dec_attn_ms / max(dec_n, 1) * 1e-3) / 1e9, 1),
                                   "keys_per_query": int(w.l_pre[0] + T), "batch": B},
         },
@@ -384,6 +485,7 @@ def main():
         per_query = (t_proj + t_attn) / n_q + t_look / n_look_cpu
         out["cpu_baseline"] = {
             "value": round(T / per_query, 2), "unit": "tokens/s", "cores": nthreads, "kind": "oracle",
+            "cores_in_affinity_mask": len(os.sched_getaffinity(0)), "openmp_threads": nthreads,
             "sample": f"the first {n_q} of the {B} queries of the same workload in full (projection+RoPE of {T} fresh tokens "
                       f"{t_proj:.2f} s, attention of {T} rows x {w.n_q_heads} heads over {int(w.l_pre[0])} cached + fresh keys "
                       f"{t_attn:.2f} s) and the lookup of {n_look_cpu} probes against the {N}-row bank ({t_look:.2f} s); "

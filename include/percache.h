@@ -13,11 +13,21 @@
  *     memory: the caller hands over one arena at create time and a workspace per call.
  *   - Storage dtypes are fixed: hidden states, weights, Q/K/V and attention output are bf16;
  *     query embeddings are fp16; similarities and softmax state are fp32.
- *   - Every call validates its arguments on the host BEFORE enqueuing anything, so a call that
- *     returns an error has had no effect.  Work is enqueued on the caller's stream (a
- *     hipStream_t passed as void*; NULL = the default stream) and is complete once the caller
- *     synchronises that stream.  No call synchronises the device except percache_create.
- *   - One context serves one stream at a time; concurrent calls on one context are not safe.
+ *   - Every call validates its arguments (pointers, shapes, sizes, slot occupancy, lengths) on the host
+ *     BEFORE enqueuing anything, so a call that returns any status but PC_EHIP has had no effect.
+ *     PC_EHIP reports a failure of the HIP runtime itself (a launch or copy that was refused); work
+ *     enqueued before it, and slot lengths already recorded for it, stay as they are.
+ *   - Work is enqueued on the caller's stream (a hipStream_t passed as void*; NULL = the default
+ *     stream) and is complete once the caller synchronises that stream.  Only percache_create
+ *     synchronises the device.  Calls that take a chunk list as HOST arrays copy a small table to the
+ *     device through a ring of 16 pinned staging buffers: the 17th such call in flight waits on the host
+ *     for the oldest copy (hipEventSynchronize), a longer list than any before re-allocates the ring
+ *     (hipHostMalloc), and such a call cannot be captured into a HIP graph with live contents.  The calls
+ *     that take a device-resident chunk table (percache_chunk_table_put once, then *_table calls) do
+ *     none of this: they enqueue kernels only, wait for nothing, allocate nothing, and can be captured.
+ *   - One context serves one stream at a time; concurrent calls on one context are not safe, with one
+ *     exception: percache_lookup / _topk / _refresh_scan touch only the bank and their own workspace and
+ *     may run on a second stream beside a prefill or stack call (not beside percache_bank_put).
  *   - All functions return PC_OK (0) or a negative pc_status; percache_last_error gives text.
  */
 #ifndef PERCACHE_H
@@ -164,6 +174,11 @@ pc_status percache_kv_evict(percache_ctx *ctx, int32_t layer, int32_t slot);
  * saved at once); chunk i goes to slot slots_host[i].  Slots must be distinct. */
 pc_status percache_kv_put_batch(percache_ctx *ctx, int32_t layer, const int32_t *slots_host, int32_t n,
                                 const void *k_dev, const void *v_dev, int32_t n_tokens, void *stream);
+/* percache_kv_get for n chunks in one launch: the first n_tokens tokens of slot slots_host[i] go to chunk i of the
+ * output tensors [n, n_kv_heads, n_tokens, head_dim]; every slot named must hold at least n_tokens tokens (PC_ELEN
+ * otherwise) and may appear more than once. */
+pc_status percache_kv_get_batch(percache_ctx *ctx, int32_t layer, const int32_t *slots_host, int32_t n, void *k_out_dev,
+                                void *v_out_dev, int32_t n_tokens, void *stream);
 /* Appends n_tokens tokens ([n_kv_heads, n_tokens, head_dim] bf16 each) behind the tokens a slot already holds (an
  * empty slot is allowed): the decoding stage grows a sequence's own K/V token by token (Sec. 2.1). */
 pc_status percache_kv_append(percache_ctx *ctx, int32_t layer, int32_t slot, const void *k_dev, const void *v_dev,
@@ -208,6 +223,27 @@ pc_status percache_prefill_reuse(percache_ctx *ctx, int32_t layer, const void *x
                                  const int32_t *n_chunks_host, int32_t max_chunks,
                                  void *attn_out_dev, void *k_fresh_out_dev, void *v_fresh_out_dev,
                                  void *workspace_dev, size_t workspace_bytes, void *stream);
+
+/* Device-resident chunk lists.  percache_chunk_table_put validates a chunk list exactly as percache_prefill_reuse
+ * does (against layer `layer` of the slot table; used_len_host == NULL takes that layer's stored lengths), writes it
+ * as a table into caller-owned device memory (table_dev, 16-byte aligned, at least percache_chunk_table_bytes) on the
+ * stream, and keeps a host copy in the context.  The *_table calls then take the table in place of the three host
+ * arrays: they check the host copy against the slot table as it is NOW (occupancy, lengths and slot formats of the
+ * layers they touch, L_pre + t_fresh <= max_pos; PC_ELEN / PC_ESLOT if a slot has changed since the put), enqueue
+ * kernels only, and are safe to capture into a HIP graph.  Writing another list of the same batch and max_chunks into
+ * the same table_dev (ordered on the stream, outside the graph) changes what the next replay of a captured call reads;
+ * the captured launch shapes stay those of the list at capture time, which is correct for any list and best for
+ * lists of similar length.  percache_chunk_table_drop forgets the host copy (the memory stays the caller's).
+ * Workspace of the *_table calls: as for the host-list calls with the table's max_chunks. */
+size_t percache_chunk_table_bytes(const percache_ctx *ctx, int32_t batch, int32_t max_chunks);
+pc_status percache_chunk_table_put(percache_ctx *ctx, void *table_dev, size_t table_bytes, int32_t layer, int32_t batch,
+                                   const int32_t *slot_ids_host, const int32_t *used_len_host,
+                                   const int32_t *n_chunks_host, int32_t max_chunks, void *stream);
+pc_status percache_chunk_table_drop(percache_ctx *ctx, const void *table_dev);
+pc_status percache_prefill_reuse_table(percache_ctx *ctx, int32_t layer, const void *x_fresh_dev, const void *wqkv_dev,
+                                       int32_t batch, int32_t t_fresh, const void *table_dev, void *attn_out_dev,
+                                       void *k_fresh_out_dev, void *v_fresh_out_dev, void *workspace_dev,
+                                       size_t workspace_bytes, void *stream);
 
 /* The two halves of percache_prefill_reuse as separate calls (same arguments and checks), so
  * that each can be measured and tested on its own.
@@ -298,6 +334,14 @@ pc_status percache_stack_reuse(percache_ctx *ctx, const percache_block_weights *
                                const int32_t *save_slots_host, int32_t n_save, void *h_out_dev, void *workspace_dev,
                                size_t workspace_bytes, void *stream);
 
+/* percache_stack_reuse with the chunk list in a device-resident table (see percache_chunk_table_put; no save slots):
+ * kernels only, so the whole stack can be captured into a HIP graph and replayed (App. B.1: the same per-block
+ * sequence runs for every layer and every query with the same shapes). */
+pc_status percache_stack_reuse_table(percache_ctx *ctx, const percache_block_weights *layers_host, int32_t n_layers,
+                                     int32_t ffn, float eps, const void *h_in_dev, int32_t batch, int32_t t_fresh,
+                                     const void *table_dev, void *h_out_dev, void *workspace_dev, size_t workspace_bytes,
+                                     void *stream);
+
 /* Decoding step (Sec. 2.1: after prefill the model emits one token at a time, each attending to everything before
  * it): percache_stack_reuse for n_new >= 1 new tokens per query (h_in_dev [batch, n_new, hidden]) whose chunk
  * list names everything already stored -- the reused knowledge chunks, then the slots that hold the prompt's own
@@ -320,6 +364,22 @@ pc_status percache_stack_decode(percache_ctx *ctx, const percache_block_weights 
 typedef enum { PC_KERNEL_LOOKUP = 0, PC_KERNEL_QKV_ROPE = 1, PC_KERNEL_ATTENTION = 2 } pc_kernel;
 pc_status percache_profile_enable(percache_ctx *ctx, int32_t on);
 pc_status percache_profile_read(percache_ctx *ctx, int32_t kernel, float *sum_ms_host, int32_t *count_host);
+
+/* ---------------------------------------------------------------- achievable peaks (measurement aids)
+ * The paper reports where its time goes (Sec. 5.3 breakdowns); here every kernel of the path is priced against a
+ * roofline, and these two calls measure what the device sustains on each resource with a kernel that does nothing
+ * else, so that a fraction can be quoted against the published peak and against the achievable one.  The caller times
+ * them with events on the stream.
+ *   percache_peak_mfma_bf16: every compute unit runs `iters` x 64 register-resident 32x32x16 bf16 matrix instructions
+ *     per wavefront (two wavefronts per SIMD), on constant operands (random_operands = 0) or on random ones (the
+ *     sustained clock depends on the data's bit activity); *flops_out_host receives the flop count of the launch.
+ *   percache_peak_stream_read: reads `bytes` bytes of buf_dev once, every workgroup one contiguous range.
+ *   scratch_dev: at least percache_peak_scratch_bytes(ctx) bytes, written by both (contents meaningless). */
+size_t percache_peak_scratch_bytes(const percache_ctx *ctx);
+pc_status percache_peak_mfma_bf16(percache_ctx *ctx, int32_t iters, int32_t random_operands, void *scratch_dev,
+                                  size_t scratch_bytes, double *flops_out_host, void *stream);
+pc_status percache_peak_stream_read(percache_ctx *ctx, const void *buf_dev, size_t bytes, void *scratch_dev,
+                                    size_t scratch_bytes, void *stream);
 
 #ifdef __cplusplus
 }

@@ -24,13 +24,16 @@ EXPORTS = [
     "percache_arena_bytes", "percache_create", "percache_destroy", "percache_last_error",
     "percache_bank_put", "percache_bank_size", "percache_lookup_workspace_bytes", "percache_lookup",
     "percache_lookup_noalloc", "percache_lookup_topk", "percache_bank_refresh_scan",
-    "percache_kv_put", "percache_kv_put_batch", "percache_kv_get", "percache_kv_evict", "percache_kv_len",
+    "percache_kv_put", "percache_kv_put_batch", "percache_kv_get", "percache_kv_get_batch", "percache_kv_evict", "percache_kv_len",
     "percache_kv_slice", "percache_kv_append", "percache_stack_workspace_bytes", "percache_stack_reuse",
     "percache_stack_decode",
     "percache_tree_create", "percache_tree_destroy", "percache_tree_match", "percache_tree_insert",
     "percache_tree_nodes", "percache_tree_bytes",
     "percache_prefill_workspace_bytes", "percache_prefill_reuse", "percache_qkv_rope", "percache_attention_reuse",
+    "percache_chunk_table_bytes", "percache_chunk_table_put", "percache_chunk_table_drop",
+    "percache_prefill_reuse_table", "percache_stack_reuse_table",
     "percache_profile_enable", "percache_profile_read",
+    "percache_peak_scratch_bytes", "percache_peak_mfma_bf16", "percache_peak_stream_read",
 ]
 KERNEL_LOOKUP, KERNEL_QKV_ROPE, KERNEL_ATTENTION = 0, 1, 2
 
@@ -86,12 +89,19 @@ def load_library() -> ctypes.CDLL:
         "percache_kv_put": (_i32, [_vp, _i32, _i32, _vp, _vp, _i32, _vp]),
         "percache_kv_put_batch": (_i32, [_vp, _i32, _pi32, _i32, _vp, _vp, _i32, _vp]),
         "percache_kv_get": (_i32, [_vp, _i32, _i32, _vp, _vp, _pi32, _vp]),
+        "percache_kv_get_batch": (_i32, [_vp, _i32, _pi32, _i32, _vp, _vp, _i32, _vp]),
         "percache_kv_evict": (_i32, [_vp, _i32, _i32]),
         "percache_kv_len": (_i32, [_vp, _i32, _i32]),
         "percache_prefill_workspace_bytes": (_sz, [_vp, _i32, _i32, _i32]),
         "percache_prefill_reuse": (_i32, [_vp, _i32, _vp, _vp, _i32, _i32, _pi32, _pi32, _pi32, _i32, _vp, _vp, _vp, _vp, _sz, _vp]),
         "percache_qkv_rope": (_i32, [_vp, _vp, _vp, _i32, _i32, _pi32, _pi32, _pi32, _i32, _i32, _vp, _vp, _vp, _vp, _sz, _vp]),
         "percache_attention_reuse": (_i32, [_vp, _i32, _vp, _vp, _vp, _i32, _i32, _pi32, _pi32, _pi32, _i32, _i32, _vp, _vp, _sz, _vp]),
+        "percache_chunk_table_bytes": (_sz, [_vp, _i32, _i32]),
+        "percache_chunk_table_put": (_i32, [_vp, _vp, _sz, _i32, _i32, _pi32, _pi32, _pi32, _i32, _vp]),
+        "percache_chunk_table_drop": (_i32, [_vp, _vp]),
+        "percache_prefill_reuse_table": (_i32, [_vp, _i32, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+        "percache_stack_reuse_table": (_i32, [_vp, ctypes.POINTER(BlockWeights), _i32, _i32, ctypes.c_float, _vp, _i32, _i32,
+                                              _vp, _vp, _vp, _sz, _vp]),
         "percache_kv_slice": (_i32, [_vp, _i32, _vp, _vp, _i32, _pi32, _pi32, _i32, _vp]),
         "percache_kv_append": (_i32, [_vp, _i32, _i32, _vp, _vp, _i32, _vp]),
         "percache_stack_decode": (_i32, [_vp, ctypes.POINTER(BlockWeights), _i32, _i32, ctypes.c_float, _vp, _i32, _i32,
@@ -108,6 +118,9 @@ def load_library() -> ctypes.CDLL:
         "percache_tree_bytes": (ctypes.c_int64, [_vp]),
         "percache_profile_enable": (_i32, [_vp, _i32]),
         "percache_profile_read": (_i32, [_vp, _i32, ctypes.POINTER(ctypes.c_float), _pi32]),
+        "percache_peak_scratch_bytes": (_sz, [_vp]),
+        "percache_peak_mfma_bf16": (_i32, [_vp, _i32, _i32, _vp, _sz, ctypes.POINTER(ctypes.c_double), _vp]),
+        "percache_peak_stream_read": (_i32, [_vp, _vp, _sz, _vp, _sz, _vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -196,6 +209,29 @@ class Percache:
         self._check(self.lib.percache_profile_read(self.ctx, kernel, ctypes.byref(ms), ctypes.byref(n)))
         return ms.value, n.value
 
+    # ------------------------------------------------------------------ achievable peaks (measurement aids)
+    def _peak_scratch(self):
+        import torch
+        need = self.lib.percache_peak_scratch_bytes(self.ctx)
+        if getattr(self, "_peak_ws", None) is None or self._peak_ws.numel() < need:
+            self._peak_ws = torch.empty(need, dtype=torch.uint8, device=self.device)
+        return self._peak_ws
+
+    def percache_peak_mfma_bf16(self, iters: int, random_operands: bool) -> float:
+        """Enqueues the register-resident bf16 MFMA loop; returns the flop count of the launch."""
+        ws = self._peak_scratch()
+        fl = ctypes.c_double(0.0)
+        self._check(self.lib.percache_peak_mfma_bf16(self.ctx, iters, 1 if random_operands else 0, _ptr(ws), ws.numel(),
+                                                     ctypes.byref(fl), _stream()))
+        return fl.value
+
+    def percache_peak_stream_read(self, buf) -> int:
+        """Enqueues one streaming read of ``buf``; returns the bytes read."""
+        ws = self._peak_scratch()
+        nbytes = buf.numel() * buf.element_size()
+        self._check(self.lib.percache_peak_stream_read(self.ctx, _ptr(buf), nbytes, _ptr(ws), ws.numel(), _stream()))
+        return nbytes // 16 * 16
+
     # ------------------------------------------------------------------ front tier
     def percache_bank_put(self, index: int, emb):
         self._check(self.lib.percache_bank_put(self.ctx, index, _ptr(emb), emb.shape[0], _stream()))
@@ -276,6 +312,17 @@ class Percache:
         assert cnt.value == n
         return k, v
 
+    def percache_kv_get_batch(self, layer: int, slots, n_tokens: int, k_out=None, v_out=None):
+        """The first n_tokens tokens of every slot named, as [n, Hkv, n_tokens, D] tensors (one launch)."""
+        import torch
+        arr, p = _host_i32(slots)
+        shape = (len(arr), self.cfg.n_kv_heads, n_tokens, self.cfg.head_dim)
+        if k_out is None:
+            k_out = torch.empty(shape, dtype=torch.bfloat16, device=self.device)
+            v_out = torch.empty(shape, dtype=torch.bfloat16, device=self.device)
+        self._check(self.lib.percache_kv_get_batch(self.ctx, layer, p, len(arr), _ptr(k_out), _ptr(v_out), n_tokens, _stream()))
+        return k_out, v_out
+
     def percache_kv_slice(self, layer: int, k, v, bounds, slots):
         """k, v: [Hkv, seq_len, D]; piece j = tokens [bounds[j], bounds[j+1]) goes to slot slots[j] (< 0: skipped)."""
         b, bp = _host_i32(bounds)
@@ -320,6 +367,46 @@ class Percache:
                                                     ul_p, nc_p, max_chunks, _ptr(attn_out), _ptr(k_fresh_out),
                                                     _ptr(v_fresh_out), ws, need, _stream()))
         return attn_out
+
+    # device-resident chunk lists: a table tensor written once, then calls that enqueue kernels only
+    def percache_chunk_table_put(self, slot_ids, used_len=None, n_chunks=None, layer: int = 0, table=None):
+        """Writes the chunk list into ``table`` (a uint8 CUDA tensor, created if None) and returns it with its max_chunks."""
+        import torch
+        batch = len(slot_ids)
+        keep, ids_p, ul_p, nc_p, max_chunks = self._chunk_args(batch, slot_ids, used_len, n_chunks)
+        need = self.lib.percache_chunk_table_bytes(self.ctx, batch, max_chunks)
+        if table is None:
+            table = torch.empty(need, dtype=torch.uint8, device=self.device)
+        self._check(self.lib.percache_chunk_table_put(self.ctx, _ptr(table), table.numel(), layer, batch, ids_p, ul_p, nc_p,
+                                                      max_chunks, _stream()))
+        table.max_chunks = max_chunks
+        return table
+
+    def percache_chunk_table_drop(self, table):
+        self._check(self.lib.percache_chunk_table_drop(self.ctx, _ptr(table)))
+
+    def prefill_workspace(self, batch, t_fresh, max_chunks):
+        """(pointer, bytes) of the binding's workspace tensor, grown if needed: for callers that must not allocate later."""
+        need = self.percache_prefill_workspace_bytes(batch, t_fresh, max_chunks)
+        return self._workspace(need), need
+
+    def percache_prefill_reuse_table(self, layer, x_fresh, wqkv, table, attn_out, k_fresh_out=None, v_fresh_out=None):
+        batch, t_fresh, _ = x_fresh.shape
+        need = self.percache_prefill_workspace_bytes(batch, t_fresh, table.max_chunks)
+        ws = self._workspace(need)
+        self._check(self.lib.percache_prefill_reuse_table(self.ctx, layer, _ptr(x_fresh), _ptr(wqkv), batch, t_fresh, _ptr(table),
+                                                          _ptr(attn_out), _ptr(k_fresh_out), _ptr(v_fresh_out), ws, need, _stream()))
+        return attn_out
+
+    def percache_stack_reuse_table(self, layers, ffn: int, eps: float, h_in, table, h_out, weights=None):
+        """``weights``: the marshalled layer array of an earlier call (returned), to keep host work out of a hot loop."""
+        batch, t_fresh, _ = h_in.shape
+        arr = weights if weights is not None else self._weights(layers)
+        need = self.percache_stack_workspace_bytes(batch, t_fresh, table.max_chunks, ffn)
+        ws = self._workspace(need)
+        self._check(self.lib.percache_stack_reuse_table(self.ctx, arr, len(layers), ffn, eps, _ptr(h_in), batch, t_fresh,
+                                                        _ptr(table), _ptr(h_out), ws, need, _stream()))
+        return arr
 
     def percache_qkv_rope(self, layer, x_fresh, wqkv, slot_ids=None, used_len=None, n_chunks=None,
                           q_out=None, k_out=None, v_out=None):

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpercache.so")
-SOURCES = ["context.hip", "kvstore.hip", "lookup.hip", "qkv_rope_gemm.hip", "reuse_attention.hip", "prefill.hip", "block.hip", "cache_tree.cpp"]
+SOURCES = ["context.hip", "kvstore.hip", "lookup.hip", "qkv_rope_gemm.hip", "reuse_attention.hip", "prefill.hip", "block.hip", "peaks.hip", "cache_tree.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,

@@ -397,7 +397,8 @@ static pc_status run_stack(percache_ctx *ctx, const percache_block_weights *laye
                            const int32_t *slot_ids_host, const int32_t *used_len_host, const int32_t *n_chunks_host,
                            int32_t max_chunks, const int32_t *save_bounds_host, const int32_t *save_slots_host,
                            int32_t n_save, const int32_t *append_slots_host, void *h_out_dev, void *workspace_dev,
-                           size_t workspace_bytes, void *stream) {
+                           size_t workspace_bytes, void *stream, const int32_t *table_dev = nullptr,
+                           const pc_table_shadow *shadow = nullptr) {
   if (!ctx) return PC_EINVAL;
   const percache_config &c = ctx->cfg;
   if (append_slots_host && batch >= 1 && t_fresh >= 1) {
@@ -440,6 +441,8 @@ static pc_status run_stack(percache_ctx *ctx, const percache_block_weights *laye
     if (st != PC_OK) return st;
     if (rows_l != rows) return pc::fail(ctx, PC_ELEN, "the chunks' stored lengths differ between layer 0 and layer %d", l);
   }
+  if (shadow && rows != shadow->rows)
+    return pc::fail(ctx, PC_ELEN, "the slots' formats or lengths no longer match the device chunk table: put it again");
   const int formats = pc::table_formats(rows, pc::tbl_stride(max_chunks), batch);
   const long M = (long)batch * t_fresh;
   if (M * (long)(ffn > c.hidden ? ffn : c.hidden) >= (1L << 31)) return pc::fail(ctx, PC_ESHAPE, "activation larger than 2^31 elements");
@@ -470,8 +473,12 @@ static pc_status run_stack(percache_ctx *ctx, const percache_block_weights *laye
     if (tiles < min_tiles) min_tiles = tiles;
   }
   hipStream_t s = (hipStream_t)stream;
-  st = pc::upload_table(ctx, rows, ws.pf.table, s);
-  if (st != PC_OK) return st;
+  if (table_dev) {
+    ws.pf.table = const_cast<int32_t *>(table_dev);  // the list is on the device already: nothing to copy
+  } else {
+    st = pc::upload_table(ctx, rows, ws.pf.table, s);
+    if (st != PC_OK) return st;
+  }
   const int H = c.hidden, A = c.n_q_heads * c.head_dim;
   const __bf16 *h_cur = (const __bf16 *)h_in_dev;
   __bf16 *h_out = (__bf16 *)h_out_dev;
@@ -548,6 +555,18 @@ pc_status percache_stack_reuse(percache_ctx *ctx, const percache_block_weights *
                                int32_t n_save, void *h_out_dev, void *workspace_dev, size_t workspace_bytes, void *stream) {
   return run_stack(ctx, layers_host, n_layers, ffn, eps, h_in_dev, batch, t_fresh, slot_ids_host, used_len_host, n_chunks_host,
                    max_chunks, save_bounds_host, save_slots_host, n_save, nullptr, h_out_dev, workspace_dev, workspace_bytes, stream);
+}
+
+pc_status percache_stack_reuse_table(percache_ctx *ctx, const percache_block_weights *layers_host, int32_t n_layers,
+                                     int32_t ffn, float eps, const void *h_in_dev, int32_t batch, int32_t t_fresh,
+                                     const void *table_dev, void *h_out_dev, void *workspace_dev, size_t workspace_bytes,
+                                     void *stream) {
+  if (!ctx) return PC_EINVAL;
+  const pc_table_shadow *sh = pc::find_table(ctx, table_dev, batch);
+  if (!sh) return PC_EINVAL;
+  return run_stack(ctx, layers_host, n_layers, ffn, eps, h_in_dev, batch, t_fresh, sh->ids.data(), sh->used.data(),
+                   sh->n_chunks.data(), sh->max_chunks, nullptr, nullptr, 0, nullptr, h_out_dev, workspace_dev, workspace_bytes,
+                   stream, (const int32_t *)table_dev, sh);
 }
 
 pc_status percache_stack_decode(percache_ctx *ctx, const percache_block_weights *layers_host, int32_t n_layers, int32_t ffn,

@@ -139,6 +139,19 @@ pc_status upload_table(percache_ctx *ctx, const std::vector<int32_t> &rows, int3
   return PC_OK;
 }
 
+const pc_table_shadow *find_table(percache_ctx *ctx, const void *table_dev, int32_t batch) {
+  auto it = ctx->tables.find(table_dev);
+  if (!table_dev || it == ctx->tables.end()) {
+    fail(ctx, PC_EINVAL, "table_dev %p was not written by percache_chunk_table_put on this context", table_dev);
+    return nullptr;
+  }
+  if (it->second.batch != batch) {
+    fail(ctx, PC_EINVAL, "the chunk table holds %d queries, the call has %d", it->second.batch, batch);
+    return nullptr;
+  }
+  return &it->second;
+}
+
 int max_splits_for(const percache_config &c, int n_cu, int32_t batch, int32_t t_fresh) {
   long rows = (long)(c.n_q_heads / c.n_kv_heads) * t_fresh;
   long base = (long)batch * c.n_kv_heads * ((rows + 127) / 128);
@@ -275,6 +288,46 @@ void percache_destroy(percache_ctx *ctx) {
     for (hipEvent_t e : ctx->prof_end[k]) (void)hipEventDestroy(e);
   }
   delete ctx;
+}
+
+size_t percache_chunk_table_bytes(const percache_ctx *ctx, int32_t batch, int32_t max_chunks) {
+  if (!ctx || batch < 1 || max_chunks < 0) return 0;
+  return pc::align_up((size_t)batch * pc::tbl_stride(max_chunks) * sizeof(int32_t));
+}
+
+pc_status percache_chunk_table_put(percache_ctx *ctx, void *table_dev, size_t table_bytes, int32_t layer, int32_t batch,
+                                   const int32_t *slot_ids_host, const int32_t *used_len_host,
+                                   const int32_t *n_chunks_host, int32_t max_chunks, void *stream) {
+  if (!ctx) return PC_EINVAL;
+  if (!table_dev || (uintptr_t)table_dev % 16) return pc::fail(ctx, PC_EINVAL, "table_dev is NULL or not 16-byte aligned");
+  pc_table_shadow sh;
+  // (a list is valid for every call whose fresh length still fits max_pos: checked against one fresh token here, against
+  // the real count by the call that uses the table)
+  pc_status st = pc::build_chunk_table(ctx, layer, batch, 1, slot_ids_host, used_len_host, n_chunks_host, max_chunks, sh.rows);
+  if (st != PC_OK) return st;
+  const size_t need = percache_chunk_table_bytes(ctx, batch, max_chunks);
+  if (table_bytes < need) return pc::fail(ctx, PC_ENOMEM, "chunk table has %zu bytes, need %zu", table_bytes, need);
+  const int stride = pc::tbl_stride(max_chunks);
+  sh.batch = batch;
+  sh.max_chunks = max_chunks;
+  sh.ids.assign((size_t)batch * max_chunks, 0);
+  sh.used.assign((size_t)batch * max_chunks, 0);
+  sh.n_chunks.assign(n_chunks_host, n_chunks_host + batch);
+  for (int b = 0; b < batch; ++b)
+    for (int ci = 0; ci < n_chunks_host[b]; ++ci) {
+      sh.ids[(size_t)b * max_chunks + ci] = sh.rows[(size_t)b * stride + pc::kTblHeader + 2 * ci];
+      sh.used[(size_t)b * max_chunks + ci] = sh.rows[(size_t)b * stride + pc::kTblHeader + 2 * ci + 1];
+    }
+  st = pc::upload_table(ctx, sh.rows, (int32_t *)table_dev, (hipStream_t)stream);
+  if (st != PC_OK) return st;
+  ctx->tables[table_dev] = std::move(sh);
+  return PC_OK;
+}
+
+pc_status percache_chunk_table_drop(percache_ctx *ctx, const void *table_dev) {
+  if (!ctx) return PC_EINVAL;
+  if (!ctx->tables.erase(table_dev)) return pc::fail(ctx, PC_EINVAL, "table_dev %p is not known to this context", table_dev);
+  return PC_OK;
 }
 
 pc_status percache_profile_enable(percache_ctx *ctx, int32_t on) {

@@ -450,6 +450,31 @@ pc_status percache_kv_get(percache_ctx *ctx, int32_t layer, int32_t slot, void *
   return PC_OK;
 }
 
+pc_status percache_kv_get_batch(percache_ctx *ctx, int32_t layer, const int32_t *slots_host, int32_t n, void *k_out_dev,
+                                void *v_out_dev, int32_t n_tokens, void *stream) {
+  if (!ctx) return PC_EINVAL;
+  if (!slots_host || n < 1) return pc::fail(ctx, PC_EINVAL, "slots_host is NULL or n < 1");
+  if (!k_out_dev || !v_out_dev) return pc::fail(ctx, PC_EINVAL, "k_out_dev / v_out_dev is NULL");
+  if (((uintptr_t)k_out_dev | (uintptr_t)v_out_dev) % 16) return pc::fail(ctx, PC_EINVAL, "outputs must be 16-byte aligned");
+  const percache_config &c = ctx->cfg;
+  if (n_tokens < 1 || n_tokens > c.slot_capacity) return pc::fail(ctx, PC_ELEN, "n_tokens %d outside [1,%d]", n_tokens, c.slot_capacity);
+  for (int i = 0; i < n; ++i) {
+    pc_status st = check_slot(ctx, layer, slots_host[i]);
+    if (st != PC_OK) return st;
+    const int have = ctx->slot_len[(size_t)layer * c.n_slots + slots_host[i]];
+    if (have <= 0) return pc::fail(ctx, PC_ESLOT, "slot %d of layer %d is empty", slots_host[i], layer);
+    if (have < n_tokens) return pc::fail(ctx, PC_ELEN, "slot %d holds %d tokens, %d asked for", slots_host[i], have, n_tokens);
+  }
+  const size_t per_chunk = (size_t)c.n_kv_heads * n_tokens * c.head_dim;
+  for (int i0 = 0; i0 < n; i0 += 64) {
+    const int cnt = n - i0 < 64 ? n - i0 : 64;
+    pc_status st = launch_copy<false>(ctx, layer, slots_host + i0, cnt, (void *)((__bf16 *)k_out_dev + per_chunk * i0),
+                                      (void *)((__bf16 *)v_out_dev + per_chunk * i0), n_tokens, (hipStream_t)stream);
+    if (st != PC_OK) return st;
+  }
+  return PC_OK;
+}
+
 pc_status percache_kv_evict(percache_ctx *ctx, int32_t layer, int32_t slot) {
   pc_status st = check_slot(ctx, layer, slot);
   if (st != PC_OK) return st;

@@ -7,6 +7,7 @@
 #include <cstdint>
 #include <cstdio>
 #include <string>
+#include <unordered_map>
 #include <vector>
 
 #include "percache.h"
@@ -57,6 +58,14 @@ constexpr size_t kStaticScratchBytes = 1u << 20;
 
 }  // namespace pc
 
+// Host copy of a chunk list that lives on the device (percache_chunk_table_put): what the table-taking calls validate
+// against the slot table without reading device memory.
+struct pc_table_shadow {
+  int batch = 0, max_chunks = 0;
+  std::vector<int32_t> ids, used, n_chunks;  // [batch * max_chunks], [batch * max_chunks] (resolved lengths), [batch]
+  std::vector<int32_t> rows;                  // the device table's contents
+};
+
 struct percache_ctx {
   percache_config cfg;
   char *arena = nullptr;
@@ -82,6 +91,7 @@ struct percache_ctx {
   bool stage_used[pc::kStageRing] = {};
   size_t stage_ints = 0;
   int stage_next = 0;
+  std::unordered_map<const void *, pc_table_shadow> tables;  // device chunk tables known to this context
   int n_cu = 256;
   // this device's copy of the library's file-scope scratch array (resolved once per device at create), for the
   // entry points that must not take a workspace
@@ -112,6 +122,10 @@ pc_status build_chunk_table(percache_ctx *ctx, int32_t layer, int32_t batch, int
 // Copies table rows to device memory through the pinned ring, ordered on `stream`.
 pc_status upload_table(percache_ctx *ctx, const std::vector<int32_t> &rows, int32_t *dst_dev,
                        hipStream_t stream);
+
+// The host copy of a device chunk table for a call on `batch` queries; nullptr (with the error set) if the table is
+// unknown to the context or was built for another batch size.
+const pc_table_shadow *find_table(percache_ctx *ctx, const void *table_dev, int32_t batch);
 
 // Workspace carving for the prefill calls.
 struct PrefillWs {

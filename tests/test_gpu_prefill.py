@@ -64,6 +64,21 @@ def test_kv_store_round_trip_and_errors():
     with pytest.raises(PercacheError) as e:
         pc.percache_kv_put_batch(1, [1, 1], kb[:2], vb[:2])
     assert e.value.status == -1
+    # ... and read back in one launch: whole chunks in another order with a repeat, then a shorter prefix of each
+    order = [2, 4, 4, 0]
+    kg, vg = pc.percache_kv_get_batch(1, order, 70)
+    kp, vp = pc.percache_kv_get_batch(1, order, 33)
+    torch.cuda.synchronize()
+    src = {4: 0, 0: 1, 2: 2}
+    for i, s in enumerate(order):
+        assert torch.equal(kg[i], kb[src[s]]) and torch.equal(vg[i], vb[src[s]])
+        assert torch.equal(kp[i], kb[src[s]][:, :33]) and torch.equal(vp[i], vb[src[s]][:, :33])
+    with pytest.raises(PercacheError) as e:
+        pc.percache_kv_get_batch(1, [2, 4], 71)               # more tokens than the slots hold
+    assert e.value.status == -4
+    with pytest.raises(PercacheError) as e:
+        pc.percache_kv_get_batch(1, [2, 3], 10)               # slot 3 of layer 1 is empty
+    assert e.value.status == -3
     pc.percache_kv_evict(1, 0)
     k = bf16(np.zeros((2, 129, 64), np.float32))
     for args, status in [((0, 6, k[:, :8], k[:, :8]), -3), ((2, 0, k[:, :8], k[:, :8]), -3), ((0, 1, k, k), -4)]:
@@ -368,15 +383,17 @@ def test_config4_full_size_one_query_in_full_and_sampled_rows():
 
 
 def test_peaked_softmax_through_the_fused_path():
-    """A peaked case through projection + RoPE + attention in one call (hidden states x8: scores up to about +-25).
+    """A peaked case through projection + RoPE + attention in one call (hidden states x4: scores up to about +-30).
     The GPU rounds q and k to bf16 once (relative error at most 2^-9 per element), the oracle does not, so a score
     moves by at most  eps_s(i, j) = (2 * 2^-9 + 2^-18) * sum_d |q_id k_jd| / sqrt(D).  With delta_i the largest
     eps_s of row i, every probability changes by a factor within [e^-2delta, e^2delta], the l1 distance of the two
     probability rows is at most e^(2 delta) - 1, and because both rows sum to one
         |o'_i - o_i| <= (e^(2 delta_i) - 1 + 2^-8) * max_j |v_j - o_i|      (2^-8: bf16 rounding of p and of v)
     element by element.  The bound is computed here from the oracle's own q, k, v, o; a mistake in the running
-    maximum, the rescale or the row sum shows as an error of the size of |v| itself."""
-    w = wl.config1(x_scale=8.0, seed=23, t_fresh=96)
+    maximum, the rescale or the row sum shows as an error of the size of |v| itself.  That bound is a worst case
+    (every rounding error aligned); the typical score error is |score| 2^-9 sqrt(2), so on average over the output
+    the error must also stay below (max|score| 2^-9 sqrt(2) + 2^-8) times the mean spread."""
+    w = wl.config1(x_scale=4.0, seed=23, t_fresh=96)
     pc = make_ctx(w)
     fill_slots(pc, w, w.slot_ids.reshape(-1))
     out = host(pc.percache_prefill_reuse(0, bf16(w.X), bf16(w.Wqkv), w.slot_ids, w.used_len)[0])
@@ -384,7 +401,7 @@ def test_peaked_softmax_through_the_fused_path():
     sk, sv, ids = w.compact_store(0)
     O, Kf, Vf, Q = oracle.prefill_reuse(w.X[0], w.Wqkv, w.n_q_heads, w.n_kv_heads, w.head_dim, w.rope_theta, sk, sv, ids, w.used_len[0])
     D, T, G = w.head_dim, w.t_fresh, w.n_q_heads // w.n_kv_heads
-    worst_ratio, peak_score = 0.0, 0.0
+    worst_ratio, peak_score, err_sum, spread_sum, n_el = 0.0, 0.0, 0.0, 0.0, 0
     for h in range(w.n_q_heads):
         kv = h // G
         K_all = np.concatenate([sk[c, kv, :u] for c, u in zip(ids, w.used_len[0])] + [Kf[kv]]).astype(np.float64)
@@ -401,9 +418,14 @@ def test_peaked_softmax_through_the_fused_path():
             bound = (np.expm1(2 * delta[i]) + 2.0 ** -8) * spread + 1e-6
             err = np.abs(out[i, h * D:(h + 1) * D] - o[i])
             worst_ratio = max(worst_ratio, float((err / bound).max()))
+            err_sum += float(err.sum())
+            spread_sum += float(spread.sum())
+            n_el += D
     fro = np.linalg.norm(out - O) / np.linalg.norm(O)
-    print(f"peaked fused path: largest |score| {peak_score:.1f}, worst error / bound {worst_ratio:.3f}, rel-fro {fro:.3e}", flush=True)
-    assert peak_score > 15.0 and worst_ratio <= 1.0
+    typical = (peak_score * 2.0 ** -9 * np.sqrt(2.0) + 2.0 ** -8) * spread_sum / n_el
+    print(f"peaked fused path: largest |score| {peak_score:.1f}, worst error / bound {worst_ratio:.3f}, mean-abs error "
+          f"{err_sum / n_el:.3e} (typical-error bar {typical:.3e}), rel-fro {fro:.3e}", flush=True)
+    assert peak_score > 15.0 and worst_ratio <= 1.0 and err_sum / n_el <= typical
     pc.close()
 
 
