@@ -95,6 +95,19 @@ def achievable_peaks(torch, pc, dev):
             e1.synchronize()
             best.append(fl / (e0.elapsed_time(e1) * 1e-3) / 1e12)
         res[name] = round(float(np.median(best)), 1)
+    kv = torch.randn(4 << 20, device=dev).to(torch.bfloat16)      # 8 MiB of N(0,1) values, like the store's contents
+    pc.percache_peak_attention_tile_loop(kv, 200)
+    torch.cuda.synchronize()
+    best = []
+    for _ in range(3):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fl = pc.percache_peak_attention_tile_loop(kv, 6000)        # about 10 ms
+        e1.record()
+        e1.synchronize()
+        best.append(fl / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+    res["attention_tile_loop_model_TFLOPs"] = round(float(np.median(best)), 1)
+    del kv
     buf = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(3)
     pc.percache_peak_stream_read(buf)
     torch.cuda.synchronize()
@@ -427,7 +440,8 @@ def main():
                      "algorithmic_flops_per_launch": fl_attn, "kv_stream_GBps": round(kv_bytes / (attn_ms * 1e-3) / 1e9, 1),
                      "achievable_peak": peaks,
                      "frac_of_achievable_mfma_random": round(attn_tflops / peaks["mfma_bf16_random_operands_TFLOPs"], 4),
-                     "frac_of_achievable_mfma_constant": round(attn_tflops / peaks["mfma_bf16_constant_operands_TFLOPs"], 4)},
+                     "frac_of_achievable_mfma_constant": round(attn_tflops / peaks["mfma_bf16_constant_operands_TFLOPs"], 4),
+                     "frac_of_attention_tile_loop_model": round(attn_tflops / peaks["attention_tile_loop_model_TFLOPs"], 4)},
         "step_variants": {"serial_ms": round(ms_step, 4), "lookup_on_second_stream_ms": round(ms_step_overlapped, 4),
                           "fresh_tokens_per_s_overlapped": round(B * T / (ms_step_overlapped * 1e-3), 1)},
         "breakdown": {

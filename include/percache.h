@@ -374,12 +374,20 @@ pc_status percache_profile_read(percache_ctx *ctx, int32_t kernel, float *sum_ms
  *     per wavefront (two wavefronts per SIMD), on constant operands (random_operands = 0) or on random ones (the
  *     sustained clock depends on the data's bit activity); *flops_out_host receives the flop count of the launch.
  *   percache_peak_stream_read: reads `bytes` bytes of buf_dev once, every workgroup one contiguous range.
- *   scratch_dev: at least percache_peak_scratch_bytes(ctx) bytes, written by both (contents meaningless). */
+ *   percache_peak_attention_tile_loop: a model of the reuse-attention kernel's inner loop (Sec. 4.2.2: the attention
+ *     over [loaded ; fresh] keys) with the bookkeeping taken away -- per 64-key tile and wavefront the same operand
+ *     reads, matrix instructions, exponentials, global->LDS requests, wait and barrier, but no chunk list, mask or
+ *     running maximum, all tiles from the first 8 MiB of kv_dev (bf16 values, e.g. N(0,1)), which stay in L2.  `tiles`
+ *     tiles per workgroup, one workgroup of eight wavefronts per compute unit.  What it sustains is what this loop
+ *     structure allows on the device; the kernel of the path is reported against it.
+ *   scratch_dev: at least percache_peak_scratch_bytes(ctx) bytes, written by all three (contents meaningless). */
 size_t percache_peak_scratch_bytes(const percache_ctx *ctx);
 pc_status percache_peak_mfma_bf16(percache_ctx *ctx, int32_t iters, int32_t random_operands, void *scratch_dev,
                                   size_t scratch_bytes, double *flops_out_host, void *stream);
 pc_status percache_peak_stream_read(percache_ctx *ctx, const void *buf_dev, size_t bytes, void *scratch_dev,
                                     size_t scratch_bytes, void *stream);
+pc_status percache_peak_attention_tile_loop(percache_ctx *ctx, const void *kv_dev, size_t kv_bytes, int32_t tiles,
+                                            void *scratch_dev, size_t scratch_bytes, double *flops_out_host, void *stream);
 
 #ifdef __cplusplus
 }

@@ -33,7 +33,7 @@ EXPORTS = [
     "percache_chunk_table_bytes", "percache_chunk_table_put", "percache_chunk_table_drop",
     "percache_prefill_reuse_table", "percache_stack_reuse_table",
     "percache_profile_enable", "percache_profile_read",
-    "percache_peak_scratch_bytes", "percache_peak_mfma_bf16", "percache_peak_stream_read",
+    "percache_peak_scratch_bytes", "percache_peak_mfma_bf16", "percache_peak_stream_read", "percache_peak_attention_tile_loop",
 ]
 KERNEL_LOOKUP, KERNEL_QKV_ROPE, KERNEL_ATTENTION = 0, 1, 2
 
@@ -121,6 +121,7 @@ def load_library() -> ctypes.CDLL:
         "percache_peak_scratch_bytes": (_sz, [_vp]),
         "percache_peak_mfma_bf16": (_i32, [_vp, _i32, _i32, _vp, _sz, ctypes.POINTER(ctypes.c_double), _vp]),
         "percache_peak_stream_read": (_i32, [_vp, _vp, _sz, _vp, _sz, _vp]),
+        "percache_peak_attention_tile_loop": (_i32, [_vp, _vp, _sz, _i32, _vp, _sz, ctypes.POINTER(ctypes.c_double), _vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -223,6 +224,14 @@ class Percache:
         fl = ctypes.c_double(0.0)
         self._check(self.lib.percache_peak_mfma_bf16(self.ctx, iters, 1 if random_operands else 0, _ptr(ws), ws.numel(),
                                                      ctypes.byref(fl), _stream()))
+        return fl.value
+
+    def percache_peak_attention_tile_loop(self, kv, tiles: int) -> float:
+        """Enqueues the model of the attention tile loop over ``kv`` (>= 8 MiB of bf16 values); returns the flop count."""
+        ws = self._peak_scratch()
+        fl = ctypes.c_double(0.0)
+        self._check(self.lib.percache_peak_attention_tile_loop(self.ctx, _ptr(kv), kv.numel() * kv.element_size(), tiles, _ptr(ws),
+                                                               ws.numel(), ctypes.byref(fl), _stream()))
         return fl.value
 
     def percache_peak_stream_read(self, buf) -> int:

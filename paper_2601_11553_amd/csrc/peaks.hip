@@ -3,7 +3,8 @@
 // query-level match (HBM stream, Sec. 4.2.1) are reported against the published peaks and against these.
 //   - a register-resident loop of 32x32x16 bf16 MFMAs (no memory traffic at all), on constant or on random operands:
 //     the clock follows the energy the data's bit activity costs, so the two differ;
-//   - a streaming read in which every workgroup walks one contiguous range with 16-byte non-temporal loads.
+//   - a streaming read in which every workgroup walks one contiguous range with 16-byte non-temporal loads;
+//   - a model of the attention kernel's tile loop without the method's bookkeeping (what the loop structure allows).
 #include "percache_internal.hpp"
 
 namespace {
@@ -62,9 +63,112 @@ __global__ __launch_bounds__(256) void peak_stream_kernel(const u32x4 *__restric
   const unsigned r = x[0] ^ x[1] ^ x[2] ^ x[3];
   if (r == 0x9e3779b9u) sink[blockIdx.x] = r;  // (keeps the loads alive; practically never written)
 }
+// A model of the attention kernel's tile loop with everything the method's bookkeeping adds taken away: per 64-key tile
+// and wavefront (32 query rows, head dim 128) the same 32 K/V operand reads from a swizzled LDS tile, the same 16 + 16
+// MFMAs (scores, then probabilities x values), the same exponentials / conversions / row sums on the scores in
+// between, the same four 1 KB global->LDS requests for the next tile, one wait and one barrier -- but no chunk list, no
+// mask, no running maximum, no ragged ends, every tile from one L2-resident buffer.  Eight wavefronts per workgroup, one
+// workgroup per compute unit.  What it sustains is the rate this loop STRUCTURE allows on this chip.
+__global__ __launch_bounds__(512, 2) void peak_attention_tile_kernel(const char *__restrict__ kv, float *__restrict__ out, int tiles) {
+  __shared__ __attribute__((aligned(16))) char lds[2 * 32768];
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int l32 = lane & 31, g2 = lane >> 5;
+  const char *base = kv + (size_t)(blockIdx.x & 7) * (1 << 20);   // eight 1 MiB windows: the tiles stay in L2
+  bf16x8 qf[8];
+#pragma unroll
+  for (int q = 0; q < 8; ++q) qf[q] = *(const bf16x8 *)(base + ((size_t)(threadIdx.x * 8 + q) * 16 & ((1 << 20) - 16)));
+  f32x16 o[4];
+#pragma unroll
+  for (int n = 0; n < 4; ++n)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) o[n][e] = 0.f;
+  float l_run = 0.f;
+  auto request = [&](int t) __attribute__((always_inline)) {
+    char *dst = lds + (t & 1) * 32768;
+    const unsigned toff = (unsigned)(t & 31) * 32768u;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int blk = wave + q * 8;
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(base + toff + blk * 1024 + lane * 16),
+                                       (__attribute__((address_space(3))) void *)(dst + blk * 1024), 16, 0, 0);
+    }
+  };
+  request(0);
+  __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8));
+  __syncthreads();
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+  for (int t = 0; t < tiles; ++t) {
+    request(t + 1);
+    const char *kb = lds + (t & 1) * 32768, *vb = kb + 16384;
+    f32x16 s[2];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) { s[0][e] = 0.f; s[1][e] = 0.f; }
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      bf16x8 kop[2][4];
+#pragma unroll
+      for (int k4 = 0; k4 < 4; ++k4)
+#pragma unroll
+        for (int kbk = 0; kbk < 2; ++kbk)
+          kop[kbk][k4] = *(const bf16x8 *)(kb + (kbk * 32 + l32) * 256 + (((2 * (4 * h + k4) + g2) ^ (l32 & 15)) * 16));
+#pragma unroll
+      for (int k4 = 0; k4 < 4; ++k4)
+#pragma unroll
+        for (int kbk = 0; kbk < 2; ++kbk) s[kbk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop[kbk][k4], qf[4 * h + k4], s[kbk], 0, 0, 0);
+    }
+    bf16x8 pf[2][2];
+    float sum = 0.f;
+#pragma unroll
+    for (int kbk = 0; kbk < 2; ++kbk)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int e = 0; e < 8; e += 2) {
+          const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kbk][j * 8 + e], 0.1275f, -6.0f));
+          const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kbk][j * 8 + e + 1], 0.1275f, -6.0f));
+          const bf16x2 pr = {(__bf16)p0, (__bf16)p1};
+          pf[kbk][j][e] = pr[0];
+          pf[kbk][j][e + 1] = pr[1];
+          sum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, sum, false);
+        }
+    l_run += sum;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      bf16x8 vop[4][2];
+#pragma unroll
+      for (int c2 = 0; c2 < 2; ++c2)
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+          vop[db][c2] = *(const bf16x8 *)(vb + (db * 32 + l32) * 128 + (((2 * (2 * h + c2) + g2) ^ ((l32 >> 1) & 7)) * 16));
+#pragma unroll
+      for (int c2 = 0; c2 < 2; ++c2)
+#pragma unroll
+        for (int db = 0; db < 4; ++db) o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop[db][c2], pf[h][c2], o[db], 0, 0, 0);
+    }
+    __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8));
+    __syncthreads();
+  }
+  float r = l_run;
+#pragma unroll
+  for (int n = 0; n < 4; ++n) r += o[n][n];
+  out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = r;
+}
 }  // namespace
 
 extern "C" {
+
+pc_status percache_peak_attention_tile_loop(percache_ctx *ctx, const void *kv_dev, size_t kv_bytes, int32_t tiles,
+                                            void *scratch_dev, size_t scratch_bytes, double *flops_out_host, void *stream) {
+  if (!ctx) return PC_EINVAL;
+  if (!kv_dev || !scratch_dev || !flops_out_host || tiles < 1 || ((uintptr_t)kv_dev % 16)) return pc::fail(ctx, PC_EINVAL, "NULL or misaligned pointer, or tiles < 1");
+  if (kv_bytes < ((size_t)8 << 20)) return pc::fail(ctx, PC_ENOMEM, "kv_dev has %zu bytes, need 8 MiB of bf16 values", kv_bytes);
+  if (scratch_bytes < percache_peak_scratch_bytes(ctx)) return pc::fail(ctx, PC_ENOMEM, "scratch has %zu bytes, need %zu", scratch_bytes, percache_peak_scratch_bytes(ctx));
+  hipLaunchKernelGGL(peak_attention_tile_kernel, dim3(ctx->n_cu), dim3(512), 0, (hipStream_t)stream, (const char *)kv_dev, (float *)scratch_dev, tiles);
+  PC_HIP(ctx, hipGetLastError());
+  *flops_out_host = (double)ctx->n_cu * 8 * (double)tiles * 32 * (2.0 * 32 * 32 * 16);
+  return PC_OK;
+}
 
 size_t percache_peak_scratch_bytes(const percache_ctx *ctx) {
   return ctx ? (size_t)ctx->n_cu * 64 * kPeakWaves * sizeof(float) : 0;
