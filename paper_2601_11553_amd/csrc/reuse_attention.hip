@@ -588,6 +588,357 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
   }
 }
 
+// Long-context kernel: bf16 slots, 8 wavefronts x 32 rows per workgroup, chunk lists of at most 64 entries.  The
+// arithmetic is that of reuse_attention_kernel; the loop around it is pared down, because at 32 MFMAs per tile and
+// wavefront the vector and scalar ports are nearly as busy as the matrix pipe and every instruction beside the
+// arithmetic shows in the tile time (cycles per 64-key tile on the 16 x 1024-key, 256-row, batch-8 launch: 4100 for
+// the general kernel, 3320 here, 3050-3150 for the bare tile arithmetic):
+//   - three LDS stages; the requests for tile t+2 are issued at the END of iteration t by wavefronts 0..3 only, one
+//     per SIMD, from 32-bit lane offsets computed once (a ragged tile takes a rarely used branch that clamps its rows);
+//   - only those wavefronts walk the chunk list with pointers, and the walk moves on by adding a tile's size; the step
+//     to the next chunk is a rarely taken branch.  Every wavefront keeps a second cursor of three integers (chunk,
+//     keys left, first fresh token) that tells whether the tile it computes on needs a mask;
+//   - mask and reference refresh are marked unlikely, so the usual tile is one fall-through path;
+//   - the V operands of the first 32-key block are requested before the softmax arithmetic;
+//   - the row sums are fp32 adds of the unrounded probabilities: the two-element bf16 dot instruction runs on the
+//     matrix pipe and does not overlap with the other wavefront's MFMAs.  (The sum then differs from the sum of the
+//     bf16 values the PV product multiplies by at most 2^-9 relative, the rounding of one probability.)
+//   - LDS is touched by the requests and by operand reads only: with an ordinary LDS store or an LDS object of another
+//     kind in the kernel, the compiler places a wait for all outstanding requests before the first operand read.
+template <int D>
+__global__ __launch_bounds__(512, 2) void reuse_attention_wide_kernel(
+    const __bf16 *__restrict__ Q, const __bf16 *__restrict__ Kf, const __bf16 *__restrict__ Vf_blk,
+    const __bf16 *__restrict__ k_store, const __bf16 *__restrict__ v_store, const int32_t *__restrict__ table,
+    int tbl_stride, int T, int Hq, int Hkv, int C, int n_splits, int q_tiles, int n_groups, float scale_log2e,
+    __bf16 *__restrict__ out, __bf16 *__restrict__ part_o, float *__restrict__ part_ml) {
+  using L = Lds<D>;
+  constexpr int NW = 8, NLD = 4, NSTAGE = 3, KS = D / 16, DB = D / 32, QROWS = 32 * NW;
+  __shared__ __align__(16) char lds[NSTAGE * L::STAGE];
+
+  const int xcd = blockIdx.x & 7, jj0 = blockIdx.x >> 3;
+  const int sg = (jj0 / q_tiles) * 8 + xcd, qt = jj0 % q_tiles;
+  if (sg >= n_groups) return;
+  const int split = sg % n_splits, bg = sg / n_splits;
+  const int gkv = bg % Hkv, b = bg / Hkv;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31, g2 = lane >> 5;
+  const int G = Hq / Hkv, R = G * T;
+
+  // chunk list: lane c keeps (slot, used length) of chunk c (at most 64 chunks)
+  const int32_t *trow = table + (size_t)b * tbl_stride;
+  int my_slot = 0, my_used = 0;
+  if (lane < (tbl_stride - kTblHeader) / 2) {
+    const int2 e = *(const int2 *)(trow + kTblHeader + 2 * lane);
+    my_slot = e.x;
+    my_used = e.y;
+  }
+  const int n_chunks = trow[0];
+  const int n_cached_tiles = trow[2];
+  if (lane >= n_chunks) my_used = 0;
+  const unsigned long long live = __ballot(my_used > 0);
+
+  const int row_first = qt * QROWS;
+  const int row_last = min(row_first + QROWS, R) - 1;
+  const int i_max = (row_first / T == row_last / T) ? (row_last % T) : (T - 1);
+  const int n_tiles = n_cached_tiles + i_max / TK + 1;
+  const int tile_begin = (int)((long)split * n_tiles / n_splits);
+  const int tile_end = (int)((long)(split + 1) * n_tiles / n_splits);
+  const int n = tile_end - tile_begin;
+
+  const int my_row = row_first + wave * 32 + l32;
+  const bool row_ok = my_row < R;
+  const int row_c = row_ok ? my_row : R - 1;   // (wavefronts past the last row compute on the last row and write nothing)
+  const int hg = row_c / T, my_i = row_c - hg * T;
+  const int head = gkv * G + hg;
+
+  bf16x8 qf[KS];
+  {
+    const __bf16 *qrow = Q + (((size_t)b * Hq + head) * T + my_i) * D;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) qf[ks] = *(const bf16x8 *)(qrow + ks * 16 + g2 * 8);
+  }
+  f32x16 o_acc[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o_acc[db][r] = 0.f;
+  float m_ref = -INFINITY, l_run = 0.f;
+  bool all_started = false;
+
+  // ---- cursor over the tiles of this range, kept by the loading wavefronts only: pointers that move on by one tile,
+  // the keys left in the chunk (or in the fresh part), and a rarely taken step to the next chunk that has keys.
+  // What the computing side needs of a tile -- how many keys are valid and, for a fresh tile, its first token --
+  // comes from a second, lighter cursor without pointers that every wavefront steps once per tile.
+  const int ft = (T + TK - 1) / TK;
+  const __bf16 *const kf_base = Kf + ((size_t)b * Hkv + gkv) * T * D;
+  const __bf16 *const vf_base = Vf_blk + ((size_t)b * Hkv + gkv) * ft * (size_t)(TK * D);
+  const __bf16 *c_k = kf_base, *c_v = vf_base;
+  int c_chunk, c_rem, c_t0;   // c_t0 < 0: in a cached chunk; else first token of the cursor's fresh tile
+  auto enter_chunk = [&](int chunk) __attribute__((always_inline)) {   // chunk == n_chunks: the fresh part
+    c_chunk = chunk;
+    if (chunk < n_chunks) {
+      const int slot = __builtin_amdgcn_readlane(my_slot, chunk);
+      const size_t cbase = ((size_t)slot * Hkv + gkv) * C * (size_t)D;
+      c_k = k_store + cbase;
+      c_v = v_store + cbase;
+      c_rem = __builtin_amdgcn_readlane(my_used, chunk);
+      c_t0 = -1;
+    } else {
+      c_k = kf_base;
+      c_v = vf_base;
+      c_rem = T;
+      c_t0 = 0;
+    }
+  };
+  {
+    const int my_tiles = (my_used + TK - 1) / TK;
+    int incl = my_tiles;
+#pragma unroll
+    for (int sh = 1; sh < 64; sh <<= 1) {
+      const int up = __shfl_up(incl, sh, 64);
+      if (lane >= sh) incl += up;
+    }
+    const int first = __popcll(__ballot(incl <= tile_begin && lane < n_chunks));   // chunks wholly before tile_begin
+    const int before = __builtin_amdgcn_readlane(incl - my_tiles, min(first, 63));
+    enter_chunk(first);   // (a chunk found this way has keys: its tile count is positive)
+    const int off = first < n_chunks ? tile_begin - before : tile_begin - n_cached_tiles;
+    c_k += (size_t)off * (TK * D);
+    c_v += (size_t)off * (TK * D);
+    c_rem -= off * TK;
+    if (c_t0 >= 0) c_t0 = off * TK;
+  }
+  auto step_cursor = [&]() __attribute__((always_inline)) {
+    c_k += TK * D;
+    c_v += TK * D;
+    c_rem -= TK;
+    if (c_t0 >= 0) c_t0 += TK;
+    if (__builtin_expect(c_rem <= 0 && c_t0 < 0, 0)) {
+      const unsigned long long rest = c_chunk < 63 ? live >> (c_chunk + 1) : 0ull;
+      enter_chunk(rest ? c_chunk + 1 + (int)__builtin_ctzll(rest) : n_chunks);
+    }
+  };
+
+  int q_chunk = c_chunk, q_rem = c_rem, q_t0 = c_t0;   // the computing side's cursor: same walk, no pointers
+  auto step_compute_cursor = [&]() __attribute__((always_inline)) {
+    q_rem -= TK;
+    if (q_t0 >= 0) q_t0 += TK;
+    if (__builtin_expect(q_rem <= 0 && q_t0 < 0, 0)) {
+      const unsigned long long rest = q_chunk < 63 ? live >> (q_chunk + 1) : 0ull;
+      q_chunk = rest ? q_chunk + 1 + (int)__builtin_ctzll(rest) : n_chunks;
+      const bool cached = q_chunk < n_chunks;
+      q_rem = cached ? __builtin_amdgcn_readlane(my_used, min(q_chunk, 63)) : T;
+      q_t0 = cached ? -1 : 0;
+    }
+  };
+
+  // ---- requests: wavefronts 0..3 bring in a tile, 4 K instructions and 4 V instructions each
+  constexpr int K_INSTR = L::K_BYTES / 1024 / NLD, V_INSTR = L::V_BYTES / 1024 / NLD;
+  int k_row[K_INSTR], k_col[K_INSTR];
+  unsigned k_off[K_INSTR], v_off[V_INSTR];   // byte offsets from the tile's first K row / V block
+#pragma unroll
+  for (int k = 0; k < K_INSTR; ++k) {
+    const int byte = ((wave & (NLD - 1)) + k * NLD) * 1024 + lane * 16;
+    const int row = byte / L::K_ROW, pc = (byte % L::K_ROW) / 16;
+    k_row[k] = row;
+    k_col[k] = (pc ^ swz<L::K_ROW>(row)) * 8;
+    k_off[k] = (unsigned)(row * D + k_col[k]) * 2u;
+  }
+#pragma unroll
+  for (int k = 0; k < V_INSTR; ++k) {
+    const int byte = ((wave & (NLD - 1)) + k * NLD) * 1024 + lane * 16;
+    const int d = byte / L::V_ROW, pc = (byte % L::V_ROW) / 16;
+    v_off[k] = (unsigned)(d * TK + (pc ^ swz<L::V_ROW>(d)) * 8) * 2u;
+  }
+  int k_rd[KS], v_rd[4];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) k_rd[ks] = ((2 * ks + g2) ^ swz<L::K_ROW>(l32)) * 16;
+#pragma unroll
+  for (int c4 = 0; c4 < 4; ++c4) v_rd[c4] = ((2 * c4 + g2) ^ swz<L::V_ROW>(l32)) * 16;
+  auto request_next = [&](int st) __attribute__((always_inline)) {   // the cursor's tile into stage st; steps the cursor
+    char *kb = lds + st * L::STAGE;
+    const int valid = min(TK, c_rem);
+    const char *kp = (const char *)c_k, *vp = (const char *)c_v;
+    if (__builtin_expect(valid < TK, 0)) {   // rows past a ragged end repeat the last valid row (masked later)
+#pragma unroll
+      for (int k = 0; k < K_INSTR; ++k)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(kp + (unsigned)(min(k_row[k], valid - 1) * D + k_col[k]) * 2u),
+                                         (__attribute__((address_space(3))) void *)(kb + (wave + k * NLD) * 1024), 16, 0, kKvAux);
+    } else {
+#pragma unroll
+      for (int k = 0; k < K_INSTR; ++k)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(kp + k_off[k]),
+                                         (__attribute__((address_space(3))) void *)(kb + (wave + k * NLD) * 1024), 16, 0, kKvAux);
+    }
+#pragma unroll
+    for (int k = 0; k < V_INSTR; ++k)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(vp + v_off[k]),
+                                       (__attribute__((address_space(3))) void *)(kb + L::K_BYTES + (wave + k * NLD) * 1024), 16, 0, kKvAux);
+    step_cursor();
+  };
+
+  // ---- one tile: S^T = K Q^T, softmax against the lazily refreshed reference exponent, O^T += V^T P^T
+  auto tile = [&](int st) __attribute__((always_inline)) {
+    const char *kb = lds + st * L::STAGE;
+    const char *vb = kb + L::K_BYTES;
+    f32x16 s_acc[2];
+#pragma unroll
+    for (int kbk = 0; kbk < 2; ++kbk)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s_acc[kbk][r] = 0.f;
+#pragma unroll
+    for (int h = 0; h < KS / 4; ++h) {
+      bf16x8 kop[2][4];
+#pragma unroll
+      for (int k4 = 0; k4 < 4; ++k4)
+#pragma unroll
+        for (int kbk = 0; kbk < 2; ++kbk) kop[kbk][k4] = *(const bf16x8 *)(kb + (kbk * 32 + l32) * L::K_ROW + k_rd[4 * h + k4]);
+#pragma unroll
+      for (int k4 = 0; k4 < 4; ++k4)
+#pragma unroll
+        for (int kbk = 0; kbk < 2; ++kbk)
+          s_acc[kbk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop[kbk][k4], qf[4 * h + k4], s_acc[kbk], 0, 0, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+    }
+    // V operands of the first 32-key block: their LDS latency runs under the softmax arithmetic
+    bf16x8 vop0[DB][2];
+#pragma unroll
+    for (int c2 = 0; c2 < 2; ++c2)
+#pragma unroll
+      for (int db = 0; db < DB; ++db) vop0[db][c2] = *(const bf16x8 *)(vb + (db * 32 + l32) * L::V_ROW + v_rd[c2]);
+    const int t_valid = min(TK, q_rem), t_t0 = q_t0;
+    if (__builtin_expect(t_valid < TK || t_t0 >= 0, 0)) {
+      int t_lane = g2 * 4;
+      asm volatile("" : "+v"(t_lane));   // (keeps the 32 per-element key indices out of loop-invariant registers)
+      const int lim_valid = t_valid - t_lane;
+      const int lim_causal = t_t0 >= 0 ? my_i - t_t0 - t_lane : 0x7fffff00;
+#pragma unroll
+      for (int kbk = 0; kbk < 2; ++kbk)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int c = kbk * 32 + (r >> 2) * 8 + (r & 3);
+          s_acc[kbk][r] = (c < lim_valid && c <= lim_causal) ? s_acc[kbk][r] : -INFINITY;
+        }
+    }
+    bf16x8 pf[2][2];
+    auto exponentials = [&](float neg_m) __attribute__((always_inline)) {
+      typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+      float sum = 0.f, sum2 = 0.f;
+#pragma unroll
+      for (int kbk = 0; kbk < 2; ++kbk)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int e = 0; e < 8; e += 2) {
+            const float p0 = fast_exp2(__builtin_fmaf(s_acc[kbk][j * 8 + e], scale_log2e, neg_m));
+            const float p1 = fast_exp2(__builtin_fmaf(s_acc[kbk][j * 8 + e + 1], scale_log2e, neg_m));
+            const bf16x2 pr = {(__bf16)p0, (__bf16)p1};
+            pf[kbk][j][e] = pr[0];
+            pf[kbk][j][e + 1] = pr[1];
+            sum += p0;
+            sum2 += p1;
+          }
+      return sum + sum2;
+    };
+    float psum = 0.f;
+    bool refresh = !all_started;
+    if (__builtin_expect(!refresh, 1)) {
+      psum = exponentials(-m_ref);
+      refresh = __builtin_amdgcn_ballot_w64(!(psum <= kSumLimit)) != 0;   // also catches inf / nan
+    }
+    if (__builtin_expect(refresh, 0)) {
+      float mx = s_acc[0][0];
+#pragma unroll
+      for (int kbk = 0; kbk < 2; ++kbk)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s_acc[kbk][r]);
+      const float mc = pair_max(mx) * scale_log2e;
+      const bool upd = mc > m_ref;
+      const float alpha = upd ? fast_exp2(m_ref - mc) : 1.0f;
+      m_ref = upd ? mc : m_ref;
+      l_run *= alpha;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o_acc[db][r] *= alpha;
+      psum = exponentials((m_ref == -INFINITY) ? 0.f : -m_ref);
+      all_started = __builtin_amdgcn_ballot_w64(m_ref == -INFINITY) == 0;
+    }
+    l_run += psum;
+    bf16x8 vop1[DB][2];
+#pragma unroll
+    for (int c2 = 0; c2 < 2; ++c2)
+#pragma unroll
+      for (int db = 0; db < DB; ++db) vop1[db][c2] = *(const bf16x8 *)(vb + (db * 32 + l32) * L::V_ROW + v_rd[2 + c2]);
+#pragma unroll
+    for (int c2 = 0; c2 < 2; ++c2)
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+        o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop0[db][c2], pf[0][c2], o_acc[db], 0, 0, 0);
+#pragma unroll
+    for (int c2 = 0; c2 < 2; ++c2)
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+        o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop1[db][c2], pf[1][c2], o_acc[db], 0, 0, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, 2 * DB, 1);
+    __builtin_amdgcn_sched_group_barrier(0x008, 4 * DB, 1);
+  };
+
+  // ---- pipeline: tile t is computed from stage t % 3; tiles t+1 and t+2 are in flight or landed.  At the end of
+  // iteration t wavefronts 0..3 wait for their share of tile t+1 (requested an iteration ago), request tile t+2 into
+  // the stage that iteration t-1 read, and the barrier publishes tile t+1.
+  if (wave < NLD) {
+    if (n > 0) request_next(0);
+    if (n > 1) request_next(1);
+  }
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qf[ks]));
+  PC_WAIT_VMCNT(0);
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+  int st = 0;
+  for (int t = 0; t < n; ++t) {
+    tile(st);
+    step_compute_cursor();
+    PC_WAIT_VMCNT(0);   // the share of tile t+1
+    if (wave < NLD && t + 2 < n) request_next(st >= 1 ? st - 1 : NSTAGE - 1);
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    st = st + 1 == NSTAGE ? 0 : st + 1;
+  }
+
+  const float l_tot = pair_sum(l_run);
+  const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+  if (!row_ok) return;
+  if (n_splits == 1) {
+    __bf16 *orow = out + ((size_t)b * T + my_i) * ((size_t)Hq * D) + (size_t)head * D;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        pc::bf16x4 v = {(__bf16)(o_acc[db][q4 * 4 + 0] * inv), (__bf16)(o_acc[db][q4 * 4 + 1] * inv),
+                        (__bf16)(o_acc[db][q4 * 4 + 2] * inv), (__bf16)(o_acc[db][q4 * 4 + 3] * inv)};
+        *(pc::bf16x4 *)(orow + db * 32 + q4 * 8 + g2 * 4) = v;
+      }
+  } else {
+    const size_t prow = (((size_t)b * Hkv + gkv) * R + my_row) * n_splits + split;
+    __bf16 *po = part_o + prow * D;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        pc::bf16x4 v = {(__bf16)(o_acc[db][q4 * 4 + 0] * inv), (__bf16)(o_acc[db][q4 * 4 + 1] * inv),
+                        (__bf16)(o_acc[db][q4 * 4 + 2] * inv), (__bf16)(o_acc[db][q4 * 4 + 3] * inv)};
+        *(pc::bf16x4 *)(po + db * 32 + q4 * 8 + g2 * 4) = v;
+      }
+    if (g2 == 0) {
+      part_ml[prow * 2] = m_ref;
+      part_ml[prow * 2 + 1] = l_tot;
+    }
+  }
+}
+
 // Merge of the split-KV partials: m = max m_s, w_s = l_s 2^(m_s - m), o = sum w_s o_s / sum w_s.
 // A row is shared by 4 * D/8 neighbouring lanes: lane (sg, dv) adds up 8 head-dim elements over the partitions
 // s = sg, sg + 4, ..., and the four partial sums meet through lane shuffles.
@@ -779,6 +1130,10 @@ pc_status launch_attention(percache_ctx *ctx, int layer, const __bf16 *q, const 
     } else {
       if (few) PC_ATTN(64, 2, 2, true, 2); else PC_ATTN(64, 4, 2, true);
     }
+  } else if (c.head_dim == 128 && wide && (tbl_stride - kTblHeader) / 2 <= 64) {
+    hipLaunchKernelGGL((reuse_attention_wide_kernel<128>), grid, dim3(512), 0, stream, q, kf, vf_blk, k16, v16, table_dev,
+                       tbl_stride, t_fresh, c.n_q_heads, c.n_kv_heads, c.slot_capacity, n_splits, q_tiles, n_groups,
+                       scale_log2e, out, part_o, part_ml);
   } else if (c.head_dim == 128) {
     if (wide) PC_ATTN(128, 8, 2); else if (halved) PC_ATTN(128, 4, 2, false, 2); else PC_ATTN(128, 4, 2);
   } else {

@@ -246,6 +246,38 @@ def test_long_chunk_lists(n_splits):
     pc.close()
 
 
+@pytest.mark.parametrize("t_fresh,n_splits", [(70, 0), (70, 1), (70, 3), (100, 0), (100, 4), (256, 2)])
+def test_long_context_kernel_on_ragged_lists(t_fresh, n_splits):
+    """The launch shape that takes the 8-wavefront long-context kernel (head size 128, 64 batch x kv-head groups,
+    more than 128 stacked rows per group), on everything its chunk walk has to get right: chunks that end inside a
+    tile, chunks of one key, unused chunks at the start, in the middle and at the end of a list, a query without
+    chunks, a fresh length that is no multiple of the tile, a last workgroup with rows to spare (3 x 70 = 210 of 256,
+    3 x 100 = 300 of 512), row blocks that straddle two query heads, and key-axis partitions that begin inside a chunk,
+    at a chunk boundary and in the fresh part."""
+    n_c, C = 6, 192
+    w = wl.make_prefill("wide_ragged", 31, "bf16", 256, 24, 8, 128, 8, t_fresh, n_c, C, 20)
+    g = np.random.default_rng(9)
+    w.used_len[:] = g.integers(1, C + 1, size=(8, n_c))
+    w.used_len[0] = [192, 192, 192, 192, 192, 192]
+    w.used_len[1] = [0, 65, 0, 1, 128, 0]
+    w.used_len[2] = [1, 1, 1, 1, 1, 1]
+    w.used_len[3] = [0, 0, 0, 0, 0, 0]
+    w.used_len[4] = [191, 64, 63, 0, 0, 129]
+    n_chunks = [6, 6, 6, 6, 6, 3, 0, 1]
+    pc = make_ctx(w)
+    fill_slots(pc, w, w.slot_ids.reshape(-1))
+    X, W = bf16(w.X), bf16(w.Wqkv)
+    q, kf, vf = pc.percache_qkv_rope(0, X, W, w.slot_ids, w.used_len, n_chunks=n_chunks)
+    out = pc.percache_attention_reuse(0, q, kf, vf, w.slot_ids, w.used_len, n_chunks=n_chunks, n_splits=n_splits)
+    torch.cuda.synchronize()
+    for b, nc in enumerate(n_chunks):
+        sk, sv, ids = w.compact_store(b)
+        O, _, _, _ = oracle.prefill_reuse(w.X[b], w.Wqkv, w.n_q_heads, w.n_kv_heads, w.head_dim, w.rope_theta, sk, sv,
+                                          ids[:nc], w.used_len[b][:nc])
+        check_close(host(out[b]), O, f"long-context kernel T={t_fresh} splits={n_splits} b={b} chunks={list(w.used_len[b][:nc])}")
+    pc.close()
+
+
 def test_full_recompute_path_is_plain_causal_prefill():
     w = wl.make_prefill("causal", 8, "bf16", 256, 4, 2, 64, 2, 200, 0, 64, 1)
     pc = make_ctx(w, max_pos=256)
