@@ -139,6 +139,89 @@ __device__ __forceinline__ void mainloop(char *lds, WRow w_row, const T *__restr
   }
 }
 
+// The same main loop for a workgroup of 8 wavefronts on 256 weight rows x 64*NTB tokens: two 128-row halves side by
+// side over one token tile, so the token rows are brought in once for twice the features (L2 -> LDS bytes per flop
+// drop by a third at NTB = 3).  Wavefront w: half w >> 2, feature blocks (fb_lo, fb_hi) counted over all 8 blocks of
+// 32 rows, token group wt.  One workgroup per CU (2 x 56 KB of LDS at NTB = 3).
+template <int NTB>
+struct WideShape {
+  static constexpr int NWV = 8, BFW = 256;
+  static constexpr int BT = 64 * NTB;
+  static constexpr int W_BYTES = BFW * ROW, X_BYTES = BT * ROW, STAGE = W_BYTES + X_BYTES;
+  static constexpr int W_INSTR = W_BYTES / 1024 / NWV, X_INSTR = X_BYTES / 1024 / NWV;
+  static constexpr int LDS_BYTES = 2 * STAGE;
+  static_assert(W_BYTES % (1024 * NWV) == 0 && X_BYTES % (1024 * NWV) == 0, "whole instructions per wavefront");
+};
+
+template <int NTB, class T, class WRow>
+__device__ __forceinline__ void mainloop_wide(char *lds, WRow w_row, const T *__restrict__ X, int ldx, int m0, int M, int K,
+                                              int fb_lo, int fb_hi, int wt, f32x16 (&acc)[2][NTB]) {
+  using S = WideShape<NTB>;
+  using V8 = typename Vec8<T>::type;
+  constexpr int NWV = S::NWV;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, g = lane >> 5;
+  const T *w_src[S::W_INSTR];
+  const T *x_src[S::X_INSTR];
+#pragma unroll
+  for (int k = 0; k < S::W_INSTR; ++k) {
+    const int row = (wave + k * NWV) * 8 + (lane >> 3);
+    w_src[k] = w_row(row) + (((lane & 7) ^ swz128(row)) * 8);
+  }
+#pragma unroll
+  for (int k = 0; k < S::X_INSTR; ++k) {
+    const int row = (wave + k * NWV) * 8 + (lane >> 3);
+    x_src[k] = X + (size_t)min(m0 + row, M - 1) * ldx + (((lane & 7) ^ swz128(row)) * 8);
+  }
+  auto fetch = [&](int kt, int st) __attribute__((always_inline)) {
+    char *base = lds + st * S::STAGE;
+#pragma unroll
+    for (int k = 0; k < S::W_INSTR; ++k)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(w_src[k] + kt * BK),
+                                       (__attribute__((address_space(3))) void *)(base + (wave + k * NWV) * 1024), 16, 0, 0);
+#pragma unroll
+    for (int k = 0; k < S::X_INSTR; ++k)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(x_src[k] + kt * BK),
+                                       (__attribute__((address_space(3))) void *)(base + S::W_BYTES + (wave + k * NWV) * 1024), 16, 0, 0);
+  };
+  int rd[BK / 16];
+#pragma unroll
+  for (int ks = 0; ks < BK / 16; ++ks) rd[ks] = ((2 * ks + g) ^ swz128(l32)) * 16;
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int t = 0; t < NTB; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[a][t][r] = 0.f;
+  const int nk = K / BK;
+  fetch(0, 0);
+  wait_vmcnt0();
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+  for (int kt = 0; kt < nk; ++kt) {
+    const int st = kt & 1;
+    if (kt + 1 < nk) fetch(kt + 1, st ^ 1);
+    const char *wl = lds + st * S::STAGE + (fb_lo * 32 + l32) * ROW;
+    const char *wh = lds + st * S::STAGE + (fb_hi * 32 + l32) * ROW;
+    const char *xb = lds + st * S::STAGE + S::W_BYTES + ((wt * NTB) * 32 + l32) * ROW;
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      V8 a_lo = *(const V8 *)(wl + rd[ks]);
+      V8 a_hi = *(const V8 *)(wh + rd[ks]);
+#pragma unroll
+      for (int t = 0; t < NTB; ++t) {
+        V8 b = *(const V8 *)(xb + t * 32 * ROW + rd[ks]);
+        acc[0][t] = mma(a_lo, b, acc[0][t]);
+        acc[1][t] = mma(a_hi, b, acc[1][t]);
+      }
+    }
+    wait_vmcnt0();
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+  }
+}
+
 // The same contraction for workgroups that own only a few k-steps (a slice of a split contraction): NS LDS stages,
 // all of them requested before the first MFMA, so that a workgroup with up to NS k-steps pays one memory latency
 // instead of one per step.  A stage is refilled (k-step kt + NS) once every wavefront has finished reading it.

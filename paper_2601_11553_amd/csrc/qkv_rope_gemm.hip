@@ -18,8 +18,9 @@ using pc::gemm::pack4;
 // NTB: 32-token blocks per wavefront (1 -> 64-token tile, 2 -> 128-token tile, 3 -> 192-token tile: 80 KB of LDS,
 // still two workgroups per CU).
 // EXTRA: the bias / head-norm variants (see QkvExtras) are compiled in.
-template <int D, int NTB, bool EXTRA>
-__global__ __launch_bounds__(256, 2) void qkv_rope_kernel(const __bf16 *__restrict__ X, const __bf16 *__restrict__ W, int M,
+// WIDE: 8 wavefronts on two heads (256 features) x the same token tile, one workgroup per CU (D = 128, no EXTRA).
+template <int D, int NTB, bool EXTRA, bool WIDE = false>
+__global__ __launch_bounds__(WIDE ? 512 : 256, WIDE ? 1 : 2) void qkv_rope_kernel(const __bf16 *__restrict__ X, const __bf16 *__restrict__ W, int M,
                                                           int H, int t_fresh, int Hq, int Hkv,
                                                           const int32_t *__restrict__ table, int tbl_stride,
                                                           const float2 *__restrict__ rope, __bf16 *__restrict__ Q,
@@ -27,21 +28,25 @@ __global__ __launch_bounds__(256, 2) void qkv_rope_kernel(const __bf16 *__restri
   constexpr int BT = 64 * NTB;
   extern __shared__ __align__(16) char lds[];  // Shape<NTB>::LDS_BYTES
 
+  static_assert(!WIDE || (D == 128 && !EXTRA), "the wide tile is built for head size 128 without the variants");
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int wf = wave & 1, wt = wave >> 1;
+  const int wf = wave & 1, wt = (wave >> 1) & 1, half = wave >> 2;  // (half: which of the tile's two heads; 0 unless WIDE)
   const int l32 = lane & 31, g = lane >> 5;
-  const int f0 = blockIdx.x * BF;  // first feature of the tile
-  const int m0 = blockIdx.y * BT;  // first token row of the tile
+  const int f0 = blockIdx.x * (WIDE ? 2 * BF : BF);  // first feature of the tile
+  const int m0 = blockIdx.y * BT;                     // first token row of the tile
 
   // feature blocks (of 32) this wavefront owns: the low half of a rotation pair and its partner
-  const int fb_lo = (D == 128) ? wf : 2 * wf;
-  const int fb_hi = (D == 128) ? wf + 2 : 2 * wf + 1;
+  const int fb_lo = (D == 128) ? 4 * half + wf : 2 * wf;
+  const int fb_hi = (D == 128) ? 4 * half + wf + 2 : 2 * wf + 1;
 
   f32x16 acc[2][NTB];
-  pc::gemm::mainloop<NTB>(lds, [&](int row) __attribute__((always_inline)) { return W + (size_t)(f0 + row) * H; }, X, H, m0, M, H, fb_lo, fb_hi, acc);
+  if constexpr (WIDE)
+    pc::gemm::mainloop_wide<NTB>(lds, [&](int row) __attribute__((always_inline)) { return W + (size_t)(f0 + row) * H; }, X, H, m0, M, H, fb_lo, fb_hi, wt, acc);
+  else
+    pc::gemm::mainloop<NTB>(lds, [&](int row) __attribute__((always_inline)) { return W + (size_t)(f0 + row) * H; }, X, H, m0, M, H, fb_lo, fb_hi, acc);
 
   // ---- epilogue: RoPE at position L_pre[b] + i on fp32, one rounding to bf16, head-major stores
-  const int head = (D == 128) ? blockIdx.x : 2 * blockIdx.x + wf;
+  const int head = WIDE ? 2 * blockIdx.x + half : (D == 128) ? blockIdx.x : 2 * blockIdx.x + wf;
   const int m_base = (D == 128) ? wf * 32 : 0;  // index of the low element inside the head
   __bf16 *dst;
   int hh, n_heads;
@@ -344,6 +349,20 @@ pc_status launch_qkv_rope(percache_ctx *ctx, const __bf16 *x, const __bf16 *w, i
       const long cost = (tiles + 2L * ctx->n_cu - 1) / (2L * ctx->n_cu) * cand;
       if (best < 0 || cost < best) { best = cost; ntb = cand; }
     }
+  }
+  // Two heads per workgroup (8 wavefronts, one workgroup per CU) when all its tiles fit one round: the token rows
+  // are brought into LDS once for twice the features.
+  const int n_heads_all = c.n_q_heads + 2 * c.n_kv_heads;
+  if (c.head_dim == 128 && !extras.any() && n_heads_all % 2 == 0 && M >= 1024 &&
+      (long)(n_heads_all / 2) * ((M + 191) / 192) <= ctx->n_cu) {
+    constexpr int lds_bytes = pc::gemm::WideShape<3>::LDS_BYTES;
+    PC_HIP(ctx, hipFuncSetAttribute((const void *)qkv_rope_kernel<128, 3, false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
+    prof_begin(ctx, PC_KERNEL_QKV_ROPE, stream);
+    hipLaunchKernelGGL((qkv_rope_kernel<128, 3, false, true>), dim3(n_heads_all / 2, (M + 191) / 192), dim3(512), lds_bytes, stream, x, w, M,
+                       c.hidden, t_fresh, c.n_q_heads, c.n_kv_heads, table_dev, tbl_stride, rope, q, k, v, extras);
+    prof_end(ctx, PC_KERNEL_QKV_ROPE, stream);
+    PC_HIP(ctx, hipGetLastError());
+    return PC_OK;
   }
   dim3 grid(F / BF, (M + 64 * ntb - 1) / (64 * ntb));
 #define PC_LAUNCH_E(DD, NN, EE)                                                                                        \
