@@ -24,7 +24,8 @@ __global__ __launch_bounds__(WIDE ? 512 : 256, WIDE ? 1 : 2) void qkv_rope_kerne
                                                           int H, int t_fresh, int Hq, int Hkv,
                                                           const int32_t *__restrict__ table, int tbl_stride,
                                                           const float2 *__restrict__ rope, __bf16 *__restrict__ Q,
-                                                          __bf16 *__restrict__ K, __bf16 *__restrict__ V, pc::QkvExtras ex) {
+                                                          __bf16 *__restrict__ K, __bf16 *__restrict__ V, pc::QkvExtras ex,
+                                                          __bf16 *__restrict__ V_blk) {
   constexpr int BT = 64 * NTB;
   extern __shared__ __align__(16) char lds[];  // Shape<NTB>::LDS_BYTES
 
@@ -139,6 +140,17 @@ __global__ __launch_bounds__(WIDE ? 512 : 256, WIDE ? 1 : 2) void qkv_rope_kerne
       if (m_ok) {
         *(uint2 *)(row + mm) = pack4(lo[0], lo[1], lo[2], lo[3]);
         *(uint2 *)(row + mm + D / 2) = pack4(hi[0], hi[1], hi[2], hi[3]);
+        if (V_blk && !rotate) {
+          // also as the 64-key blocks [D][64] the attention kernel reads for the fresh part (t_fresh is a multiple of
+          // 64 here: no padding to write); the 32 lanes of a half wavefront hold 32 consecutive tokens of one feature
+          const int tin = i & 63;
+          __bf16 *vb = V_blk + ((((size_t)b * n_heads + hh) * (t_fresh >> 6) + (i >> 6)) * D) * 64 + (tin & ~15) + pc::blocked_key(tin & 15);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            vb[(size_t)(mm + e) * 64] = (__bf16)lo[e];
+            vb[(size_t)(mm + e + D / 2) * 64] = (__bf16)hi[e];
+          }
+        }
       }
     }
   }
@@ -353,13 +365,15 @@ pc_status launch_qkv_rope(percache_ctx *ctx, const __bf16 *x, const __bf16 *w, i
   // Two heads per workgroup (8 wavefronts, one workgroup per CU) when all its tiles fit one round: the token rows
   // are brought into LDS once for twice the features.
   const int n_heads_all = c.n_q_heads + 2 * c.n_kv_heads;
+  __bf16 *vb_large = (v_blk && v_blk_done && t_fresh % 64 == 0) ? v_blk : nullptr;  // the large tiles lay V out for the attention kernel too
+  if (vb_large) *v_blk_done = true;
   if (c.head_dim == 128 && !extras.any() && n_heads_all % 2 == 0 && M >= 1024 &&
       (long)(n_heads_all / 2) * ((M + 191) / 192) <= ctx->n_cu) {
     constexpr int lds_bytes = pc::gemm::WideShape<3>::LDS_BYTES;
     PC_HIP(ctx, hipFuncSetAttribute((const void *)qkv_rope_kernel<128, 3, false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
     prof_begin(ctx, PC_KERNEL_QKV_ROPE, stream);
     hipLaunchKernelGGL((qkv_rope_kernel<128, 3, false, true>), dim3(n_heads_all / 2, (M + 191) / 192), dim3(512), lds_bytes, stream, x, w, M,
-                       c.hidden, t_fresh, c.n_q_heads, c.n_kv_heads, table_dev, tbl_stride, rope, q, k, v, extras);
+                       c.hidden, t_fresh, c.n_q_heads, c.n_kv_heads, table_dev, tbl_stride, rope, q, k, v, extras, vb_large);
     prof_end(ctx, PC_KERNEL_QKV_ROPE, stream);
     PC_HIP(ctx, hipGetLastError());
     return PC_OK;
@@ -371,7 +385,7 @@ pc_status launch_qkv_rope(percache_ctx *ctx, const __bf16 *x, const __bf16 *w, i
     if (lds_bytes > 64 * 1024) /* above the default limit: opt in */                                                  \
       PC_HIP(ctx, hipFuncSetAttribute((const void *)qkv_rope_kernel<DD, NN, EE>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes)); \
     hipLaunchKernelGGL((qkv_rope_kernel<DD, NN, EE>), grid, dim3(256), lds_bytes, stream, x, w, M, c.hidden, t_fresh,  \
-                       c.n_q_heads, c.n_kv_heads, table_dev, tbl_stride, rope, q, k, v, extras);                      \
+                       c.n_q_heads, c.n_kv_heads, table_dev, tbl_stride, rope, q, k, v, extras, vb_large);            \
   } while (0)
 #define PC_LAUNCH(DD, NN)                                                                                             \
   do {                                                                                                                \
