@@ -63,14 +63,16 @@ __global__ __launch_bounds__(256) void peak_stream_kernel(const u32x4 *__restric
   const unsigned r = x[0] ^ x[1] ^ x[2] ^ x[3];
   if (r == 0x9e3779b9u) sink[blockIdx.x] = r;  // (keeps the loads alive; practically never written)
 }
-// A model of the attention kernel's tile loop with everything the method's bookkeeping adds taken away: per 64-key tile
-// and wavefront (32 query rows, head dim 128) the same 32 K/V operand reads from a swizzled LDS tile, the same 16 + 16
-// MFMAs (scores, then probabilities x values), the same exponentials / conversions / row sums on the scores in
-// between, the same four 1 KB global->LDS requests for the next tile, one wait and one barrier -- but no chunk list, no
-// mask, no running maximum, no ragged ends, every tile from one L2-resident buffer.  Eight wavefronts per workgroup, one
-// workgroup per compute unit.  What it sustains is the rate this loop STRUCTURE allows on this chip.
+// A model of the long-context attention kernel's tile loop with everything the method's bookkeeping adds taken away:
+// per 64-key tile and wavefront (32 query rows, head dim 128) the same 32 K/V operand reads from a swizzled LDS tile,
+// the same 16 + 16 MFMAs (scores, then probabilities x values), the same exponentials / conversions / fp32 row sums on
+// the scores in between, three LDS stages with the eight 1 KB global->LDS requests for the tile after next issued at
+// the end of the iteration by wavefronts 0..3, one wait and one barrier -- but no chunk list, no mask, no running
+// maximum, no ragged ends, every tile from one L2-resident buffer.  Eight wavefronts per workgroup, one workgroup per
+// compute unit.  What it sustains is the rate this loop STRUCTURE allows on this chip.
 __global__ __launch_bounds__(512, 2) void peak_attention_tile_kernel(const char *__restrict__ kv, float *__restrict__ out, int tiles) {
-  __shared__ __attribute__((aligned(16))) char lds[2 * 32768];
+  constexpr int STAGE = 32768, NST = 3, NLD = 4;
+  __shared__ __attribute__((aligned(16))) char lds[NST * STAGE];
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int l32 = lane & 31, g2 = lane >> 5;
   const char *base = kv + (size_t)(blockIdx.x & 7) * (1 << 20);   // eight 1 MiB windows: the tiles stay in L2
@@ -83,24 +85,25 @@ __global__ __launch_bounds__(512, 2) void peak_attention_tile_kernel(const char 
 #pragma unroll
     for (int e = 0; e < 16; ++e) o[n][e] = 0.f;
   float l_run = 0.f;
-  auto request = [&](int t) __attribute__((always_inline)) {
-    char *dst = lds + (t & 1) * 32768;
+  auto request = [&](int t, int st) __attribute__((always_inline)) {
+    if (wave >= NLD) return;
+    char *dst = lds + st * STAGE;
     const unsigned toff = (unsigned)(t & 31) * 32768u;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int blk = wave + q * 8;
+    for (int q = 0; q < 8; ++q) {
+      const int blk = wave + q * NLD;
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(base + toff + blk * 1024 + lane * 16),
                                        (__attribute__((address_space(3))) void *)(dst + blk * 1024), 16, 0, 0);
     }
   };
-  request(0);
+  request(0, 0);
+  request(1, 1);
   __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8));
-  __syncthreads();
+  __builtin_amdgcn_s_barrier();
   typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+  int st = 0;
   for (int t = 0; t < tiles; ++t) {
-    request(t + 1);
-    const char *kb = lds + (t & 1) * 32768, *vb = kb + 16384;
+    const char *kb = lds + st * STAGE, *vb = kb + 16384;
     f32x16 s[2];
 #pragma unroll
     for (int e = 0; e < 16; ++e) { s[0][e] = 0.f; s[1][e] = 0.f; }
@@ -118,7 +121,7 @@ __global__ __launch_bounds__(512, 2) void peak_attention_tile_kernel(const char 
         for (int kbk = 0; kbk < 2; ++kbk) s[kbk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop[kbk][k4], qf[4 * h + k4], s[kbk], 0, 0, 0);
     }
     bf16x8 pf[2][2];
-    float sum = 0.f;
+    float sum = 0.f, sum2 = 0.f;
 #pragma unroll
     for (int kbk = 0; kbk < 2; ++kbk)
 #pragma unroll
@@ -130,9 +133,10 @@ __global__ __launch_bounds__(512, 2) void peak_attention_tile_kernel(const char 
           const bf16x2 pr = {(__bf16)p0, (__bf16)p1};
           pf[kbk][j][e] = pr[0];
           pf[kbk][j][e + 1] = pr[1];
-          sum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, sum, false);
+          sum += p0;
+          sum2 += p1;
         }
-    l_run += sum;
+    l_run += sum + sum2;
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       bf16x8 vop[4][2];
@@ -146,8 +150,10 @@ __global__ __launch_bounds__(512, 2) void peak_attention_tile_kernel(const char 
 #pragma unroll
         for (int db = 0; db < 4; ++db) o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop[db][c2], pf[h][c2], o[db], 0, 0, 0);
     }
-    __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8));
-    __syncthreads();
+    __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8));   // this wavefront's share of tile t+1 has landed
+    request(t + 2, st >= 1 ? st - 1 : NST - 1);             // into the stage that iteration t-1 read
+    __builtin_amdgcn_s_barrier();
+    st = st + 1 == NST ? 0 : st + 1;
   }
   float r = l_run;
 #pragma unroll

@@ -588,7 +588,8 @@ __global__ __launch_bounds__(64 * NW, 2) void reuse_attention_kernel(
   }
 }
 
-// Long-context kernel: bf16 slots, 8 wavefronts x 32 rows per workgroup, chunk lists of at most 64 entries.  The
+// Long-context kernel: bf16 slots, 8 wavefronts x 32 rows per workgroup, chunk lists of at most 64 entries (both head
+// sizes; the figures below are for head size 128).  The
 // arithmetic is that of reuse_attention_kernel; the loop around it is pared down, because at 32 MFMAs per tile and
 // wavefront the vector and scalar ports are nearly as busy as the matrix pipe and every instruction beside the
 // arithmetic shows in the tile time (cycles per 64-key tile on the 16 x 1024-key, 256-row, batch-8 launch: 4100 for
@@ -1136,6 +1137,10 @@ pc_status launch_attention(percache_ctx *ctx, int layer, const __bf16 *q, const 
                        scale_log2e, out, part_o, part_ml);
   } else if (c.head_dim == 128) {
     if (wide) PC_ATTN(128, 8, 2); else if (halved) PC_ATTN(128, 4, 2, false, 2); else PC_ATTN(128, 4, 2);
+  } else if (wide && (tbl_stride - kTblHeader) / 2 <= 64) {
+    hipLaunchKernelGGL((reuse_attention_wide_kernel<64>), grid, dim3(512), 0, stream, q, kf, vf_blk, k16, v16, table_dev,
+                       tbl_stride, t_fresh, c.n_q_heads, c.n_kv_heads, c.slot_capacity, n_splits, q_tiles, n_groups,
+                       scale_log2e, out, part_o, part_ml);
   } else {
     if (wide) PC_ATTN(64, 8, 4); else PC_ATTN(64, 4, 4);
   }

@@ -246,8 +246,9 @@ def test_long_chunk_lists(n_splits):
     pc.close()
 
 
-@pytest.mark.parametrize("t_fresh,n_splits", [(70, 0), (70, 1), (70, 3), (100, 0), (100, 4), (256, 2)])
-def test_long_context_kernel_on_ragged_lists(t_fresh, n_splits):
+@pytest.mark.parametrize("t_fresh,n_splits,head_dim", [(70, 0, 128), (70, 1, 128), (70, 3, 128), (100, 0, 128), (100, 4, 128),
+                                                       (256, 2, 128), (70, 0, 64), (100, 3, 64), (192, 1, 64)])
+def test_long_context_kernel_on_ragged_lists(t_fresh, n_splits, head_dim):
     """The launch shape that takes the 8-wavefront long-context kernel (head size 128, 64 batch x kv-head groups,
     more than 128 stacked rows per group), on everything its chunk walk has to get right: chunks that end inside a
     tile, chunks of one key, unused chunks at the start, in the middle and at the end of a list, a query without
@@ -255,15 +256,18 @@ def test_long_context_kernel_on_ragged_lists(t_fresh, n_splits):
     3 x 100 = 300 of 512), row blocks that straddle two query heads, and key-axis partitions that begin inside a chunk,
     at a chunk boundary and in the fresh part."""
     n_c, C = 6, 192
-    w = wl.make_prefill("wide_ragged", 31, "bf16", 256, 24, 8, 128, 8, t_fresh, n_c, C, 20)
+    if head_dim == 128:
+        w = wl.make_prefill("wide_ragged", 31, "bf16", 256, 24, 8, 128, 8, t_fresh, n_c, C, 20)
+    else:   # 0.5B-shaped heads (7 query heads per kv head), 16 queries x 2 kv heads x at least 2 row blocks
+        w = wl.make_prefill("wide_ragged64", 32, "bf16", 128, 14, 2, 64, 16, t_fresh, n_c, C, 24)
     g = np.random.default_rng(9)
-    w.used_len[:] = g.integers(1, C + 1, size=(8, n_c))
+    w.used_len[:] = g.integers(1, C + 1, size=(w.batch, n_c))
     w.used_len[0] = [192, 192, 192, 192, 192, 192]
     w.used_len[1] = [0, 65, 0, 1, 128, 0]
     w.used_len[2] = [1, 1, 1, 1, 1, 1]
     w.used_len[3] = [0, 0, 0, 0, 0, 0]
     w.used_len[4] = [191, 64, 63, 0, 0, 129]
-    n_chunks = [6, 6, 6, 6, 6, 3, 0, 1]
+    n_chunks = [6, 6, 6, 6, 6, 3, 0, 1] + [int(x) for x in g.integers(0, n_c + 1, size=w.batch - 8)]
     pc = make_ctx(w)
     fill_slots(pc, w, w.slot_ids.reshape(-1))
     X, W = bf16(w.X), bf16(w.Wqkv)
