@@ -367,7 +367,7 @@ pc_status percache_profile_read(percache_ctx *ctx, int32_t kernel, float *sum_ms
 
 /* ---------------------------------------------------------------- achievable peaks (measurement aids)
  * The paper reports where its time goes (Sec. 5.3 breakdowns); here every kernel of the path is priced against a
- * roofline, and these two calls measure what the device sustains on each resource with a kernel that does nothing
+ * roofline, and these calls measure what the device sustains on each resource with a kernel that does nothing
  * else, so that a fraction can be quoted against the published peak and against the achievable one.  The caller times
  * them with events on the stream.
  *   percache_peak_mfma_bf16: every compute unit runs `iters` x 64 register-resident 32x32x16 bf16 matrix instructions
@@ -376,7 +376,7 @@ pc_status percache_profile_read(percache_ctx *ctx, int32_t kernel, float *sum_ms
  *   percache_peak_stream_read: reads `bytes` bytes of buf_dev once, every workgroup one contiguous range.
  *   percache_peak_attention_tile_loop: a model of the reuse-attention kernel's inner loop (Sec. 4.2.2: the attention
  *     over [loaded ; fresh] keys) with the bookkeeping taken away -- per 64-key tile and wavefront the same operand
- *     reads, matrix instructions, exponentials, global->LDS requests, wait and barrier, but no chunk list, mask or
+ *     reads, matrix instructions, exponentials, global->LDS requests (three LDS stages), wait and barrier, but no chunk list, mask or
  *     running maximum, all tiles from the first 8 MiB of kv_dev (bf16 values, e.g. N(0,1)), which stay in L2.  `tiles`
  *     tiles per workgroup, one workgroup of eight wavefronts per compute unit.  What it sustains is what this loop
  *     structure allows on the device; the kernel of the path is reported against it.
