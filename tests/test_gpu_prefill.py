@@ -282,6 +282,18 @@ def test_long_context_kernel_on_ragged_lists(t_fresh, n_splits, head_dim):
     pc.close()
 
 
+@pytest.mark.parametrize("head_dim,t_fresh", [(64, 320), (128, 320), (64, 300)])
+def test_large_projection_tiles_lay_out_fresh_v_themselves(head_dim, t_fresh):
+    """More token rows than the few-row kernels take: the large projection tiles write V token-major and, when the
+    fresh length is a multiple of 64, as the 64-key blocks the attention kernel reads (no repack launch); a length
+    that is not takes the repack kernel.  Both must give the oracle's attention output and fresh K/V."""
+    hq, hkv = (8, 2) if head_dim == 64 else (6, 2)
+    w = wl.make_prefill("v_blocks", 77, "bf16", 256, hq, hkv, head_dim, 2, t_fresh, 2, 128, 6)
+    w.used_len[0] = [128, 70]
+    w.used_len[1] = [1, 128]
+    _run_and_check(w, f"v blocks D={head_dim} T={t_fresh}")
+
+
 def test_full_recompute_path_is_plain_causal_prefill():
     w = wl.make_prefill("causal", 8, "bf16", 256, 4, 2, 64, 2, 200, 0, 64, 1)
     pc = make_ctx(w, max_pos=256)
