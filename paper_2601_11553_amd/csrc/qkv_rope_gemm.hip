@@ -235,7 +235,8 @@ template <int D>
 __global__ __launch_bounds__(256) void reduce_rope_kernel(const float *__restrict__ P, int n_k, int M, int F, int t_fresh, int Hq,
                                                           int Hkv, const int32_t *__restrict__ table, int tbl_stride,
                                                           const float2 *__restrict__ rope, __bf16 *__restrict__ Q,
-                                                          __bf16 *__restrict__ K, __bf16 *__restrict__ V, pc::QkvExtras ex) {
+                                                          __bf16 *__restrict__ K, __bf16 *__restrict__ V, pc::QkvExtras ex,
+                                                          __bf16 *__restrict__ V_blk) {
   constexpr int QUADS = D / 8;
   const long gid = (long)blockIdx.x * blockDim.x + threadIdx.x;
   const int n_heads_all = Hq + 2 * Hkv;
@@ -298,6 +299,15 @@ __global__ __launch_bounds__(256) void reduce_rope_kernel(const float *__restric
   __bf16 *row = dst + (((size_t)b * n_heads + hh) * t_fresh + i) * D;
   *(uint2 *)(row + mm) = pack4(l4[0], l4[1], l4[2], l4[3]);
   *(uint2 *)(row + mm + D / 2) = pack4(h4[0], h4[1], h4[2], h4[3]);
+  if (V_blk && !rotate) {  // also as the 64-key blocks [D][64] of the attention kernel (t_fresh is a multiple of 64 here)
+    const int tin = i & 63;
+    __bf16 *vb = V_blk + ((((size_t)b * n_heads + hh) * (t_fresh >> 6) + (i >> 6)) * D) * 64 + (tin & ~15) + pc::blocked_key(tin & 15);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      vb[(size_t)(mm + e) * 64] = (__bf16)l4[e];
+      vb[(size_t)(mm + e + D / 2) * 64] = (__bf16)h4[e];
+    }
+  }
 }
 
 }  // namespace
@@ -340,12 +350,14 @@ pc_status launch_qkv_rope(percache_ctx *ctx, const __bf16 *x, const __bf16 *w, i
     if (st != PC_OK) return st;
     const long threads = (long)M * (c.n_q_heads + 2 * c.n_kv_heads) * (c.head_dim / 8);
     const dim3 rgrid((unsigned)((threads + 255) / 256));
+    __bf16 *vb = (v_blk && v_blk_done && t_fresh % 64 == 0) ? v_blk : nullptr;  // also lay V out for the attention kernel
+    if (vb) *v_blk_done = true;
     if (c.head_dim == 128)
       hipLaunchKernelGGL(reduce_rope_kernel<128>, rgrid, dim3(256), 0, stream, gemm_part, nk, M, F, t_fresh, c.n_q_heads,
-                         c.n_kv_heads, table_dev, tbl_stride, rope, q, k, v, extras);
+                         c.n_kv_heads, table_dev, tbl_stride, rope, q, k, v, extras, vb);
     else
       hipLaunchKernelGGL(reduce_rope_kernel<64>, rgrid, dim3(256), 0, stream, gemm_part, nk, M, F, t_fresh, c.n_q_heads,
-                         c.n_kv_heads, table_dev, tbl_stride, rope, q, k, v, extras);
+                         c.n_kv_heads, table_dev, tbl_stride, rope, q, k, v, extras, vb);
     prof_end(ctx, PC_KERNEL_QKV_ROPE, stream);
     PC_HIP(ctx, hipGetLastError());
     return PC_OK;
