@@ -492,11 +492,16 @@ def main():
         pc.close()
         del pc
         torch.cuda.empty_cache()
-        out["breakdown"]["cfg4_layer_8bit_slots"] = bench_fp8_slots(torch, wl, binding, Percache, dev, bf, w, X, W)
-        torch.cuda.empty_cache()
-        out["breakdown"]["cfg1_layer"] = bench_cfg1(torch, wl, binding, Percache, dev, bf)
-        out["breakdown"]["cfg2_stack"] = bench_cfg2(torch, wl, Percache, dev, bf)
         pc = None
+        # (side measurements: one that fails is reported as such and does not take the step's figures with it)
+        for name, fn in (("cfg4_layer_8bit_slots", lambda: bench_fp8_slots(torch, wl, binding, Percache, dev, bf, w, X, W)),
+                         ("cfg1_layer", lambda: bench_cfg1(torch, wl, binding, Percache, dev, bf)),
+                         ("cfg2_stack", lambda: bench_cfg2(torch, wl, Percache, dev, bf))):
+            try:
+                out["breakdown"][name] = fn()
+            except Exception as e:  # noqa: BLE001
+                out["breakdown"][name] = {"error": f"{type(e).__name__}: {e}"}
+            torch.cuda.empty_cache()
 
     # ------------------------------------------------------------------ CPU oracle on a bounded sample
     if not args.no_cpu_baseline:
