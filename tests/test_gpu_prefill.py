@@ -282,6 +282,33 @@ def test_long_context_kernel_on_ragged_lists(t_fresh, n_splits, head_dim):
     pc.close()
 
 
+@pytest.mark.parametrize("n_c,n_splits", [(64, 0), (64, 4), (40, 1)])
+def test_long_context_kernel_on_full_width_lists(n_c, n_splits):
+    """The same kernel with as many chunks as its register-held list takes (64) and with 40: one-tile chunks of ragged
+    length, unused ones at both ends and in runs, per-query counts from none to all."""
+    C = 64
+    w = wl.make_prefill("wide_lists", 41, "bf16", 256, 24, 8, 128, 8, 70, n_c, C, n_c + 8)
+    g = np.random.default_rng(11)
+    w.used_len[:] = g.integers(0, C + 1, size=(8, n_c))
+    w.used_len[0, :3] = 0
+    w.used_len[0, -2:] = 0
+    w.used_len[1, 10:30] = 0
+    w.used_len[2] = C
+    n_chunks = [n_c, n_c, n_c, n_c - 1, 33 if n_c >= 33 else n_c, 1, 0, n_c]
+    pc = make_ctx(w)
+    fill_slots(pc, w, w.slot_ids.reshape(-1))
+    X, W = bf16(w.X), bf16(w.Wqkv)
+    q, kf, vf = pc.percache_qkv_rope(0, X, W, w.slot_ids, w.used_len, n_chunks=n_chunks)
+    out = pc.percache_attention_reuse(0, q, kf, vf, w.slot_ids, w.used_len, n_chunks=n_chunks, n_splits=n_splits)
+    torch.cuda.synchronize()
+    for b, nc in enumerate(n_chunks):
+        sk, sv, ids = w.compact_store(b)
+        O, _, _, _ = oracle.prefill_reuse(w.X[b], w.Wqkv, w.n_q_heads, w.n_kv_heads, w.head_dim, w.rope_theta, sk, sv,
+                                          ids[:nc], w.used_len[b][:nc])
+        check_close(host(out[b]), O, f"long-context kernel, {n_c}-entry lists, splits={n_splits} b={b}")
+    pc.close()
+
+
 @pytest.mark.parametrize("head_dim,t_fresh", [(64, 320), (128, 320), (64, 300)])
 def test_large_projection_tiles_lay_out_fresh_v_themselves(head_dim, t_fresh):
     """More token rows than the few-row kernels take: the large projection tiles write V token-major and, when the
