@@ -282,10 +282,11 @@ def test_long_context_kernel_on_ragged_lists(t_fresh, n_splits, head_dim):
     pc.close()
 
 
-@pytest.mark.parametrize("n_c,n_splits", [(64, 0), (64, 4), (40, 1)])
+@pytest.mark.parametrize("n_c,n_splits", [(64, 0), (64, 4), (40, 1), (66, 0)])
 def test_long_context_kernel_on_full_width_lists(n_c, n_splits):
     """The same kernel with as many chunks as its register-held list takes (64) and with 40: one-tile chunks of ragged
-    length, unused ones at both ends and in runs, per-query counts from none to all."""
+    length, unused ones at both ends and in runs, per-query counts from none to all.  66 entries: the same launch shape
+    falls back to the general 8-wavefront kernel, which reads entries past the 64th from memory."""
     C = 64
     w = wl.make_prefill("wide_lists", 41, "bf16", 256, 24, 8, 128, 8, 70, n_c, C, n_c + 8)
     g = np.random.default_rng(11)
