@@ -940,6 +940,448 @@ __global__ __launch_bounds__(512, 2) void reuse_attention_wide_kernel(
   }
 }
 
+// The same long-context kernel over 8-bit slots (every chunk of the launch in an 8-bit slot; head size 128; at most 32
+// tiles per chunk): cached tiles arrive as codes (half a stage), a lane's 16-byte LDS read carries the operands of two
+// k-steps and is turned into bf16 on the way to the MFMA, the fresh tiles stay bf16.  The scales of a chunk's tiles sit
+// in one register per wavefront (lane j: K scale of tile j, lane 32 + j: V scale), requested one chunk ahead.
+template <int D>
+__global__ __launch_bounds__(512, 2) void reuse_attention_wide8_kernel(
+    const __bf16 *__restrict__ Q, const __bf16 *__restrict__ Kf, const __bf16 *__restrict__ Vf_blk,
+    const uint8_t *__restrict__ k_store, const uint8_t *__restrict__ v_store, const float *__restrict__ k_scale,
+    const float *__restrict__ v_scale, int n_slots16, const int32_t *__restrict__ table,
+    int tbl_stride, int T, int Hq, int Hkv, int C, int n_splits, int q_tiles, int n_groups, float scale_log2e,
+    __bf16 *__restrict__ out, __bf16 *__restrict__ part_o, float *__restrict__ part_ml) {
+  using L = Lds<D>;
+  constexpr int NW = 8, NLD = 4, NSTAGE = 3, KS = D / 16, DB = D / 32, QROWS = 32 * NW;
+  __shared__ __align__(16) char lds[NSTAGE * L::STAGE];
+
+  const int xcd = blockIdx.x & 7, jj0 = blockIdx.x >> 3;
+  const int sg = (jj0 / q_tiles) * 8 + xcd, qt = jj0 % q_tiles;
+  if (sg >= n_groups) return;
+  const int split = sg % n_splits, bg = sg / n_splits;
+  const int gkv = bg % Hkv, b = bg / Hkv;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31, g2 = lane >> 5;
+  const int G = Hq / Hkv, R = G * T;
+
+  // chunk list: lane c keeps (slot, used length) of chunk c (at most 64 chunks)
+  const int32_t *trow = table + (size_t)b * tbl_stride;
+  int my_slot = 0, my_used = 0;
+  if (lane < (tbl_stride - kTblHeader) / 2) {
+    const int2 e = *(const int2 *)(trow + kTblHeader + 2 * lane);
+    my_slot = e.x;
+    my_used = e.y;
+  }
+  const int n_chunks = trow[0];
+  const int n_cached_tiles = trow[2];
+  if (lane >= n_chunks) my_used = 0;
+  const unsigned long long live = __ballot(my_used > 0);
+
+  const int row_first = qt * QROWS;
+  const int row_last = min(row_first + QROWS, R) - 1;
+  const int i_max = (row_first / T == row_last / T) ? (row_last % T) : (T - 1);
+  const int n_tiles = n_cached_tiles + i_max / TK + 1;
+  const int tile_begin = (int)((long)split * n_tiles / n_splits);
+  const int tile_end = (int)((long)(split + 1) * n_tiles / n_splits);
+  const int n = tile_end - tile_begin;
+
+  const int my_row = row_first + wave * 32 + l32;
+  const bool row_ok = my_row < R;
+  const int row_c = row_ok ? my_row : R - 1;   // (wavefronts past the last row compute on the last row and write nothing)
+  const int hg = row_c / T, my_i = row_c - hg * T;
+  const int head = gkv * G + hg;
+
+  bf16x8 qf[KS];
+  {
+    const __bf16 *qrow = Q + (((size_t)b * Hq + head) * T + my_i) * D;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) qf[ks] = *(const bf16x8 *)(qrow + 32 * (ks >> 1) + 16 * g2 + 8 * (ks & 1));
+  }
+  f32x16 o_acc[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o_acc[db][r] = 0.f;
+  float m_ref = -INFINITY, l_run = 0.f;
+  bool all_started = false;
+
+  // ---- cursor over the tiles of this range, kept by the loading wavefronts only: pointers that move on by one tile,
+  // the keys left in the chunk (or in the fresh part), and a rarely taken step to the next chunk that has keys.
+  // What the computing side needs of a tile -- how many keys are valid and, for a fresh tile, its first token --
+  // comes from a second, lighter cursor without pointers that every wavefront steps once per tile.
+  const int ft = (T + TK - 1) / TK;
+  const __bf16 *const kf_base = Kf + ((size_t)b * Hkv + gkv) * T * D;
+  const __bf16 *const vf_base = Vf_blk + ((size_t)b * Hkv + gkv) * ft * (size_t)(TK * D);
+  const char *c_k = (const char *)kf_base, *c_v = (const char *)vf_base;   // bytes: a cached tile is TK * D of them, a fresh one twice that
+  int c_chunk, c_rem, c_t0;   // c_t0 < 0: in a cached chunk; else first token of the cursor's fresh tile
+  auto enter_chunk = [&](int chunk) __attribute__((always_inline)) {   // chunk == n_chunks: the fresh part
+    c_chunk = chunk;
+    if (chunk < n_chunks) {
+      const int slot = __builtin_amdgcn_readlane(my_slot, chunk) - n_slots16;   // (every chunk of this launch sits in an 8-bit slot)
+      const size_t cbase = ((size_t)slot * Hkv + gkv) * C * (size_t)D;
+      c_k = (const char *)k_store + cbase;
+      c_v = (const char *)v_store + cbase;
+      c_rem = __builtin_amdgcn_readlane(my_used, chunk);
+      c_t0 = -1;
+    } else {
+      c_k = (const char *)kf_base;
+      c_v = (const char *)vf_base;
+      c_rem = T;
+      c_t0 = 0;
+    }
+  };
+  int off0 = 0;   // tile inside its chunk at which this range starts
+  {
+    const int my_tiles = (my_used + TK - 1) / TK;
+    int incl = my_tiles;
+#pragma unroll
+    for (int sh = 1; sh < 64; sh <<= 1) {
+      const int up = __shfl_up(incl, sh, 64);
+      if (lane >= sh) incl += up;
+    }
+    const int first = __popcll(__ballot(incl <= tile_begin && lane < n_chunks));   // chunks wholly before tile_begin
+    const int before = __builtin_amdgcn_readlane(incl - my_tiles, min(first, 63));
+    enter_chunk(first);   // (a chunk found this way has keys: its tile count is positive)
+    const int off = first < n_chunks ? tile_begin - before : tile_begin - n_cached_tiles;
+    c_k += (size_t)off * (TK * D) * (c_t0 >= 0 ? 2 : 1);
+    c_v += (size_t)off * (TK * D) * (c_t0 >= 0 ? 2 : 1);
+    c_rem -= off * TK;
+    off0 = off;
+    if (c_t0 >= 0) c_t0 = off * TK;
+  }
+  auto step_cursor = [&]() __attribute__((always_inline)) {
+    c_k += c_t0 >= 0 ? 2 * TK * D : TK * D;
+    c_v += c_t0 >= 0 ? 2 * TK * D : TK * D;
+    c_rem -= TK;
+    if (c_t0 >= 0) c_t0 += TK;
+    if (__builtin_expect(c_rem <= 0 && c_t0 < 0, 0)) {
+      const unsigned long long rest = c_chunk < 63 ? live >> (c_chunk + 1) : 0ull;
+      enter_chunk(rest ? c_chunk + 1 + (int)__builtin_ctzll(rest) : n_chunks);
+    }
+  };
+
+  // the computing side's cursor: same walk, no pointers, plus the tile's place in its chunk and the chunk's scales:
+  // lane j < 32 holds the K scale of the chunk's tile j, lane 32 + j its V scale (a chunk has at most 32 tiles here);
+  // the scales of the chunk after this one are requested when this one is entered
+  int q_chunk = c_chunk, q_rem = c_rem, q_t0 = c_t0, q_off = c_t0 < 0 ? off0 : 0;
+  const int tpc = C / TK;
+  auto chunk_scales = [&](int chunk) __attribute__((always_inline)) {
+    float v = 1.f;
+    if (chunk < n_chunks) {
+      const int slot = __builtin_amdgcn_readlane(my_slot, min(chunk, 63)) - n_slots16;
+      const size_t base = ((size_t)slot * Hkv + gkv) * tpc;
+      if ((lane & 31) < tpc) v = (lane < 32 ? k_scale : v_scale)[base + (lane & 31)];
+    }
+    return v;
+  };
+  auto next_live = [&](int chunk) __attribute__((always_inline)) {
+    const unsigned long long rest = chunk < 63 ? live >> (chunk + 1) : 0ull;
+    return rest ? chunk + 1 + (int)__builtin_ctzll(rest) : n_chunks;
+  };
+  float sc_cur = chunk_scales(q_chunk), sc_nxt = chunk_scales(next_live(q_chunk));
+  auto step_compute_cursor = [&]() __attribute__((always_inline)) {
+    q_rem -= TK;
+    q_off += 1;
+    if (q_t0 >= 0) q_t0 += TK;
+    if (__builtin_expect(q_rem <= 0 && q_t0 < 0, 0)) {
+      q_chunk = next_live(q_chunk);
+      const bool cached = q_chunk < n_chunks;
+      q_rem = cached ? __builtin_amdgcn_readlane(my_used, min(q_chunk, 63)) : T;
+      q_t0 = cached ? -1 : 0;
+      q_off = 0;
+      sc_cur = sc_nxt;
+      sc_nxt = chunk_scales(next_live(q_chunk));
+    }
+  };
+
+  // ---- requests: wavefronts 0..3 bring in a tile, 4 K instructions and 4 V instructions each
+  constexpr int K_INSTR = L::K_BYTES / 1024 / NLD, V_INSTR = L::V_BYTES / 1024 / NLD;
+  unsigned k_off[K_INSTR], v_off[V_INSTR];   // byte offsets from the tile's first K row / V block
+#pragma unroll
+  for (int k = 0; k < K_INSTR; ++k) {
+    const int byte = ((wave & (NLD - 1)) + k * NLD) * 1024 + lane * 16;
+    const int row = byte / L::K_ROW, pc = (byte % L::K_ROW) / 16;
+    k_off[k] = (unsigned)(row * D + (pc ^ swz<L::K_ROW>(row)) * 8) * 2u;
+  }
+#pragma unroll
+  for (int k = 0; k < V_INSTR; ++k) {
+    const int byte = ((wave & (NLD - 1)) + k * NLD) * 1024 + lane * 16;
+    const int d = byte / L::V_ROW, pc = (byte % L::V_ROW) / 16;
+    v_off[k] = (unsigned)(d * TK + (pc ^ swz<L::V_ROW>(d)) * 8) * 2u;
+  }
+  // 8-bit tiles: K rows of D bytes, V^T rows of TK bytes, 16-byte chunks XOR-swizzled by the row ((row >> 1) & 7 for
+  // rows of 128 bytes, (row >> 2) & 3 for rows of 64); 8 + 8 request instructions per tile, two of each per loading wavefront
+  constexpr int K8_ROW = D, V8_ROW = TK;
+  constexpr int K8_INSTR = TK * K8_ROW / 1024 / NLD, V8_INSTR = D * V8_ROW / 1024 / NLD;
+  auto swz8 = [](int row_bytes, int row) { return row_bytes == 128 ? ((row >> 1) & 7) : ((row >> 2) & 3); };
+  unsigned k8_off[K8_INSTR], v8_off[V8_INSTR];
+#pragma unroll
+  for (int k = 0; k < K8_INSTR; ++k) {
+    const int byte = ((wave & (NLD - 1)) + k * NLD) * 1024 + lane * 16;
+    const int row = byte / K8_ROW, pc = (byte % K8_ROW) / 16;
+    k8_off[k] = (unsigned)(row * K8_ROW + (pc ^ swz8(K8_ROW, row)) * 16);
+  }
+#pragma unroll
+  for (int k = 0; k < V8_INSTR; ++k) {
+    const int byte = ((wave & (NLD - 1)) + k * NLD) * 1024 + lane * 16;
+    const int d = byte / V8_ROW, pc = (byte % V8_ROW) / 16;
+    v8_off[k] = (unsigned)(d * V8_ROW + (pc ^ swz8(V8_ROW, d)) * 16);
+  }
+  // operand reads: the head dim is walked in the order 32 j + 16 g2 + 8 jj (k-step 2 j + jj) by K, Q and the fresh K alike
+  int k_rd[KS], v_rd[4], k8_rd[KS / 2], v8_rd[2];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) k_rd[ks] = ((4 * (ks >> 1) + 2 * g2 + (ks & 1)) ^ swz<L::K_ROW>(l32)) * 16;
+#pragma unroll
+  for (int c4 = 0; c4 < 4; ++c4) v_rd[c4] = ((2 * c4 + g2) ^ swz<L::V_ROW>(l32)) * 16;
+#pragma unroll
+  for (int j = 0; j < KS / 2; ++j) k8_rd[j] = ((2 * j + g2) ^ swz8(K8_ROW, l32)) * 16;
+#pragma unroll
+  for (int J = 0; J < 2; ++J) v8_rd[J] = ((2 * J + g2) ^ swz8(V8_ROW, l32)) * 16;
+  auto request_next = [&](int st) __attribute__((always_inline)) {   // the cursor's tile into stage st; steps the cursor
+    char *kb = lds + st * L::STAGE;
+    const int valid = min(TK, c_rem);
+    const char *kp = c_k, *vp = c_v;
+    if (c_t0 < 0) {   // a tile of codes: half a stage
+#pragma unroll
+      for (int k = 0; k < K8_INSTR; ++k) {
+        unsigned o = k8_off[k];
+        if (__builtin_expect(valid < TK, 0)) {   // rows past a ragged end repeat the last valid row (masked later)
+          int lane_v = lane;
+          asm volatile("" : "+v"(lane_v));   // (recomputed here so that nothing of it stays in registers across the loop)
+          const int byte = ((wave & (NLD - 1)) + k * NLD) * 1024 + lane_v * 16;
+          const int row = byte / K8_ROW, pc = (byte % K8_ROW) / 16;
+          o = (unsigned)(min(row, valid - 1) * K8_ROW + (pc ^ swz8(K8_ROW, row)) * 16);
+        }
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(kp + o),
+                                         (__attribute__((address_space(3))) void *)(kb + (wave + k * NLD) * 1024), 16, 0, kKvAux);
+      }
+#pragma unroll
+      for (int k = 0; k < V8_INSTR; ++k)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(vp + v8_off[k]),
+                                         (__attribute__((address_space(3))) void *)(kb + L::K_BYTES + (wave + k * NLD) * 1024), 16, 0, kKvAux);
+      step_cursor();
+      return;
+    }
+    if (__builtin_expect(valid < TK, 0)) {   // rows past a ragged end repeat the last valid row (masked later)
+#pragma unroll
+      for (int k = 0; k < K_INSTR; ++k) {
+        int lane_v = lane;
+        asm volatile("" : "+v"(lane_v));
+        const int byte = ((wave & (NLD - 1)) + k * NLD) * 1024 + lane_v * 16;
+        const int row = byte / L::K_ROW, pc = (byte % L::K_ROW) / 16;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(kp + (unsigned)(min(row, valid - 1) * D + (pc ^ swz<L::K_ROW>(row)) * 8) * 2u),
+                                         (__attribute__((address_space(3))) void *)(kb + (wave + k * NLD) * 1024), 16, 0, kKvAux);
+      }
+    } else {
+#pragma unroll
+      for (int k = 0; k < K_INSTR; ++k)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(kp + k_off[k]),
+                                         (__attribute__((address_space(3))) void *)(kb + (wave + k * NLD) * 1024), 16, 0, kKvAux);
+    }
+#pragma unroll
+    for (int k = 0; k < V_INSTR; ++k)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(vp + v_off[k]),
+                                       (__attribute__((address_space(3))) void *)(kb + L::K_BYTES + (wave + k * NLD) * 1024), 16, 0, kKvAux);
+    step_cursor();
+  };
+
+  // ---- one tile: S^T = K Q^T, softmax against the lazily refreshed reference exponent, O^T += V^T P^T
+  auto tile = [&](int st) __attribute__((always_inline)) {
+    const char *kb = lds + st * L::STAGE;
+    const char *vb = kb + L::K_BYTES;
+    const bool is8 = q_t0 < 0;   // a tile of codes (cached) or a bf16 tile (fresh)
+    f32x16 s_acc[2];
+#pragma unroll
+    for (int kbk = 0; kbk < 2; ++kbk)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s_acc[kbk][r] = 0.f;
+    if (is8) {
+      // one 16-byte read per key block and pair of k-steps, turned into two bf16 operands (exact: power-of-two scale)
+      const float ks8 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, sc_cur), q_off));
+#pragma unroll
+      for (int h = 0; h < KS / 4; ++h) {
+        pc::u32x4 raw[2][2];
+#pragma unroll
+        for (int j2 = 0; j2 < 2; ++j2)
+#pragma unroll
+          for (int kbk = 0; kbk < 2; ++kbk) raw[kbk][j2] = *(const pc::u32x4 *)(kb + (kbk * 32 + l32) * K8_ROW + k8_rd[2 * h + j2]);
+#pragma unroll
+        for (int j2 = 0; j2 < 2; ++j2)
+#pragma unroll
+          for (int kbk = 0; kbk < 2; ++kbk) {
+            const bf16x8 a0 = codes_to_bf16(raw[kbk][j2][0], raw[kbk][j2][1], ks8);
+            const bf16x8 a1 = codes_to_bf16(raw[kbk][j2][2], raw[kbk][j2][3], ks8);
+            s_acc[kbk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qf[4 * h + 2 * j2], s_acc[kbk], 0, 0, 0);
+            s_acc[kbk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qf[4 * h + 2 * j2 + 1], s_acc[kbk], 0, 0, 0);
+          }
+      }
+    } else {
+#pragma unroll
+      for (int h = 0; h < KS / 4; ++h) {
+        bf16x8 kop[2][4];
+#pragma unroll
+        for (int k4 = 0; k4 < 4; ++k4)
+#pragma unroll
+          for (int kbk = 0; kbk < 2; ++kbk) kop[kbk][k4] = *(const bf16x8 *)(kb + (kbk * 32 + l32) * L::K_ROW + k_rd[4 * h + k4]);
+#pragma unroll
+        for (int k4 = 0; k4 < 4; ++k4)
+#pragma unroll
+          for (int kbk = 0; kbk < 2; ++kbk)
+            s_acc[kbk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop[kbk][k4], qf[4 * h + k4], s_acc[kbk], 0, 0, 0);
+      }
+    }
+    const int t_valid = min(TK, q_rem), t_t0 = q_t0;
+    if (__builtin_expect(t_valid < TK || t_t0 >= 0, 0)) {
+      int t_lane = g2 * 4;
+      asm volatile("" : "+v"(t_lane));   // (keeps the 32 per-element key indices out of loop-invariant registers)
+      const int lim_valid = t_valid - t_lane;
+      const int lim_causal = t_t0 >= 0 ? my_i - t_t0 - t_lane : 0x7fffff00;
+#pragma unroll
+      for (int kbk = 0; kbk < 2; ++kbk)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int c = kbk * 32 + (r >> 2) * 8 + (r & 3);
+          s_acc[kbk][r] = (c < lim_valid && c <= lim_causal) ? s_acc[kbk][r] : -INFINITY;
+        }
+    }
+    bf16x8 pf[2][2];
+    auto exponentials = [&](float neg_m) __attribute__((always_inline)) {
+      typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+      float sum = 0.f, sum2 = 0.f;
+#pragma unroll
+      for (int kbk = 0; kbk < 2; ++kbk)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int e = 0; e < 8; e += 2) {
+            const float p0 = fast_exp2(__builtin_fmaf(s_acc[kbk][j * 8 + e], scale_log2e, neg_m));
+            const float p1 = fast_exp2(__builtin_fmaf(s_acc[kbk][j * 8 + e + 1], scale_log2e, neg_m));
+            const bf16x2 pr = {(__bf16)p0, (__bf16)p1};
+            pf[kbk][j][e] = pr[0];
+            pf[kbk][j][e + 1] = pr[1];
+            sum += p0;
+            sum2 += p1;
+          }
+      return sum + sum2;
+    };
+    float psum = 0.f;
+    bool refresh = !all_started;
+    if (__builtin_expect(!refresh, 1)) {
+      psum = exponentials(-m_ref);
+      refresh = __builtin_amdgcn_ballot_w64(!(psum <= kSumLimit)) != 0;   // also catches inf / nan
+    }
+    if (__builtin_expect(refresh, 0)) {
+      float mx = s_acc[0][0];
+#pragma unroll
+      for (int kbk = 0; kbk < 2; ++kbk)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s_acc[kbk][r]);
+      const float mc = pair_max(mx) * scale_log2e;
+      const bool upd = mc > m_ref;
+      const float alpha = upd ? fast_exp2(m_ref - mc) : 1.0f;
+      m_ref = upd ? mc : m_ref;
+      l_run *= alpha;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o_acc[db][r] *= alpha;
+      psum = exponentials((m_ref == -INFINITY) ? 0.f : -m_ref);
+      all_started = __builtin_amdgcn_ballot_w64(m_ref == -INFINITY) == 0;
+    }
+    l_run += psum;
+    if (is8) {
+      const float vs8 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, sc_cur), 32 + q_off));
+      pc::u32x4 vraw0[DB], vraw1[DB];
+#pragma unroll
+      for (int db = 0; db < DB; ++db) vraw0[db] = *(const pc::u32x4 *)(vb + (db * 32 + l32) * V8_ROW + v8_rd[0]);
+#pragma unroll
+      for (int db = 0; db < DB; ++db) vraw1[db] = *(const pc::u32x4 *)(vb + (db * 32 + l32) * V8_ROW + v8_rd[1]);
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        const bf16x8 a0 = codes_to_bf16(vraw0[db][0], vraw0[db][1], vs8);
+        const bf16x8 a1 = codes_to_bf16(vraw0[db][2], vraw0[db][3], vs8);
+        o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, pf[0][0], o_acc[db], 0, 0, 0);
+        o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, pf[0][1], o_acc[db], 0, 0, 0);
+      }
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        const bf16x8 a0 = codes_to_bf16(vraw1[db][0], vraw1[db][1], vs8);
+        const bf16x8 a1 = codes_to_bf16(vraw1[db][2], vraw1[db][3], vs8);
+        o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, pf[1][0], o_acc[db], 0, 0, 0);
+        o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, pf[1][1], o_acc[db], 0, 0, 0);
+      }
+    } else {
+#pragma unroll
+      for (int hh = 0; hh < 2; ++hh) {   // (the few fresh tiles: operands read where they are used)
+        bf16x8 vop[DB][2];
+#pragma unroll
+        for (int c2 = 0; c2 < 2; ++c2)
+#pragma unroll
+          for (int db = 0; db < DB; ++db) vop[db][c2] = *(const bf16x8 *)(vb + (db * 32 + l32) * L::V_ROW + v_rd[2 * hh + c2]);
+#pragma unroll
+        for (int c2 = 0; c2 < 2; ++c2)
+#pragma unroll
+          for (int db = 0; db < DB; ++db)
+            o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop[db][c2], pf[hh][c2], o_acc[db], 0, 0, 0);
+      }
+    }
+  };
+
+  // ---- pipeline: tile t is computed from stage t % 3; tiles t+1 and t+2 are in flight or landed.  At the end of
+  // iteration t wavefronts 0..3 wait for their share of tile t+1 (requested an iteration ago), request tile t+2 into
+  // the stage that iteration t-1 read, and the barrier publishes tile t+1.
+  if (wave < NLD) {
+    if (n > 0) request_next(0);
+    if (n > 1) request_next(1);
+  }
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qf[ks]));
+  PC_WAIT_VMCNT(0);
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+  int st = 0;
+  for (int t = 0; t < n; ++t) {
+    tile(st);
+    step_compute_cursor();
+    PC_WAIT_VMCNT(0);   // the share of tile t+1
+    if (wave < NLD && t + 2 < n) request_next(st >= 1 ? st - 1 : NSTAGE - 1);
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    st = st + 1 == NSTAGE ? 0 : st + 1;
+  }
+
+  const float l_tot = pair_sum(l_run);
+  const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+  if (!row_ok) return;
+  if (n_splits == 1) {
+    __bf16 *orow = out + ((size_t)b * T + my_i) * ((size_t)Hq * D) + (size_t)head * D;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        pc::bf16x4 v = {(__bf16)(o_acc[db][q4 * 4 + 0] * inv), (__bf16)(o_acc[db][q4 * 4 + 1] * inv),
+                        (__bf16)(o_acc[db][q4 * 4 + 2] * inv), (__bf16)(o_acc[db][q4 * 4 + 3] * inv)};
+        *(pc::bf16x4 *)(orow + db * 32 + q4 * 8 + g2 * 4) = v;
+      }
+  } else {
+    const size_t prow = (((size_t)b * Hkv + gkv) * R + my_row) * n_splits + split;
+    __bf16 *po = part_o + prow * D;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        pc::bf16x4 v = {(__bf16)(o_acc[db][q4 * 4 + 0] * inv), (__bf16)(o_acc[db][q4 * 4 + 1] * inv),
+                        (__bf16)(o_acc[db][q4 * 4 + 2] * inv), (__bf16)(o_acc[db][q4 * 4 + 3] * inv)};
+        *(pc::bf16x4 *)(po + db * 32 + q4 * 8 + g2 * 4) = v;
+      }
+    if (g2 == 0) {
+      part_ml[prow * 2] = m_ref;
+      part_ml[prow * 2 + 1] = l_tot;
+    }
+  }
+}
+
 // Merge of the split-KV partials: m = max m_s, w_s = l_s 2^(m_s - m), o = sum w_s o_s / sum w_s.
 // A row is shared by 4 * D/8 neighbouring lanes: lane (sg, dv) adds up 8 head-dim elements over the partitions
 // s = sg, sg + 4, ..., and the four partial sums meet through lane shuffles.
@@ -1125,6 +1567,10 @@ pc_status launch_attention(percache_ctx *ctx, int layer, const __bf16 *q, const 
     } else {
       if (few) PC_ATTN(64, 2, 2, true, 2, true); else PC_ATTN(64, 4, 2, true, 1, true);
     }
+  } else if (use8 && c.head_dim == 128 && wide && (tbl_stride - kTblHeader) / 2 <= 64 && c.slot_capacity / TK <= 32) {
+    hipLaunchKernelGGL((reuse_attention_wide8_kernel<128>), grid, dim3(512), 0, stream, q, kf, vf_blk, (const uint8_t *)ks,
+                       (const uint8_t *)vs, ksc, vsc, ctx->n_slots16, table_dev, tbl_stride, t_fresh, c.n_q_heads, c.n_kv_heads,
+                       c.slot_capacity, n_splits, q_tiles, n_groups, scale_log2e, out, part_o, part_ml);
   } else if (use8) {
     if (c.head_dim == 128) {
       if (few) PC_ATTN(128, 2, 2, true, 2); else if (wide) PC_ATTN(128, 8, 2, true); else PC_ATTN(128, 4, 2, true);

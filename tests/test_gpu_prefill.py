@@ -282,6 +282,40 @@ def test_long_context_kernel_on_ragged_lists(t_fresh, n_splits, head_dim):
     pc.close()
 
 
+@pytest.mark.parametrize("t_fresh,n_splits,n16", [(70, 0, 0), (100, 3, 0), (256, 1, 0), (70, 2, 3), (192, 0, 3)])
+def test_long_context_kernel_over_8bit_slots(t_fresh, n_splits, n16):
+    """The long-context launch shape over 8-bit slots: every chunk of the call in an 8-bit slot (a store of 8-bit slots
+    only, and one whose first three slots are bf16 slots that the call does not name, so slot ids are offset), ragged and
+    unused chunks, ranges that begin inside a chunk (the chunk's scales are picked by the tile's place in it), fresh
+    tiles in bf16.  Reference: the oracle on what each slot reads back."""
+    from oracle import kv_fp8
+    n_c, C = 6, 192
+    w = wl.make_prefill("wide_8bit", 51, "bf16", 256, 24, 8, 128, 8, t_fresh, n_c, C, 20)
+    if n16:
+        w.slot_ids[:] = n16 + w.slot_ids % (w.n_slots - n16)
+    g = np.random.default_rng(13)
+    w.used_len[:] = g.integers(1, C + 1, size=(8, n_c))
+    w.used_len[1] = [0, 65, 0, 1, 128, 0]
+    w.used_len[2] = [1, 1, 1, 1, 1, 1]
+    w.used_len[3] = 0
+    w.used_len[4] = [191, 64, 63, 0, 0, 129]
+    n_chunks = [6, 6, 6, 6, 6, 3, 0, 1]
+    pc = make_ctx(w, kv_fp8=n16 == 0, n_slots_8bit=w.n_slots - n16 if n16 else 0)
+    fill_slots(pc, w, w.slot_ids.reshape(-1))
+    X, W = bf16(w.X), bf16(w.Wqkv)
+    q, kf, vf = pc.percache_qkv_rope(0, X, W, w.slot_ids, w.used_len, n_chunks=n_chunks)
+    out = pc.percache_attention_reuse(0, q, kf, vf, w.slot_ids, w.used_len, n_chunks=n_chunks, n_splits=n_splits)
+    torch.cuda.synchronize()
+    for b, nc in enumerate(n_chunks):
+        sk, sv, ids = w.compact_store(b)
+        sk = np.stack([kv_fp8.round_trip(wl.round_bf16(x)) for x in sk]) if len(sk) else sk
+        sv = np.stack([kv_fp8.round_trip(wl.round_bf16(x)) for x in sv]) if len(sv) else sv
+        O, _, _, _ = oracle.prefill_reuse(w.X[b], w.Wqkv, w.n_q_heads, w.n_kv_heads, w.head_dim, w.rope_theta, sk, sv,
+                                          ids[:nc], w.used_len[b][:nc])
+        check_close(host(out[b]), O, f"long-context kernel, 8-bit slots, T={t_fresh} splits={n_splits} first 8-bit slot {n16} b={b}")
+    pc.close()
+
+
 @pytest.mark.parametrize("n_c,n_splits", [(64, 0), (64, 4), (40, 1), (66, 0)])
 def test_long_context_kernel_on_full_width_lists(n_c, n_splits):
     """The same kernel with as many chunks as its register-held list takes (64) and with 40: one-tile chunks of ragged
