@@ -940,10 +940,15 @@ __global__ __launch_bounds__(512, 2) void reuse_attention_wide_kernel(
   }
 }
 
-// The same long-context kernel over 8-bit slots (every chunk of the launch in an 8-bit slot; head size 128; at most 32
-// tiles per chunk): cached tiles arrive as codes (half a stage), a lane's 16-byte LDS read carries the operands of two
-// k-steps and is turned into bf16 on the way to the MFMA, the fresh tiles stay bf16.  The scales of a chunk's tiles sit
-// in one register per wavefront (lane j: K scale of tile j, lane 32 + j: V scale), requested one chunk ahead.
+// The long-context kernel over 8-bit slots (every chunk of the launch in an 8-bit slot; head size 128; at most 32 tiles
+// per chunk).  Cached tiles arrive as codes (16 KB instead of 32) in a ring of three code stages; one tile ahead of the
+// arithmetic the workgroup turns a tile's codes into the bf16 tile layout of the bf16 kernel ONCE -- every thread 16 K
+// codes and 16 V codes, exact (power-of-two scales) -- into one of two bf16 stages, so the tile arithmetic is that of
+// the bf16 kernel and no wavefront converts what another one converts too (with every wavefront converting the whole
+// tile for itself the vector port was the busiest unit: 256 conversions per tile and wavefront).  The fresh tiles are
+// bf16 already and are requested straight into their bf16 stage.  The converted values are stored with ds_write
+// instructions the compiler does not see as stores to the LDS array: with ordinary stores to it, it waits for every
+// outstanding request before each operand read.
 template <int D>
 __global__ __launch_bounds__(512, 2) void reuse_attention_wide8_kernel(
     const __bf16 *__restrict__ Q, const __bf16 *__restrict__ Kf, const __bf16 *__restrict__ Vf_blk,
@@ -952,8 +957,11 @@ __global__ __launch_bounds__(512, 2) void reuse_attention_wide8_kernel(
     int tbl_stride, int T, int Hq, int Hkv, int C, int n_splits, int q_tiles, int n_groups, float scale_log2e,
     __bf16 *__restrict__ out, __bf16 *__restrict__ part_o, float *__restrict__ part_ml) {
   using L = Lds<D>;
-  constexpr int NW = 8, NLD = 4, NSTAGE = 3, KS = D / 16, DB = D / 32, QROWS = 32 * NW;
-  __shared__ __align__(16) char lds[NSTAGE * L::STAGE];
+  constexpr int NW = 8, NLD = 4, KS = D / 16, DB = D / 32, QROWS = 32 * NW;
+  constexpr int K8_ROW = D, V8_ROW = TK, K8_BYTES = TK * K8_ROW, V8_BYTES = D * V8_ROW, CST = K8_BYTES + V8_BYTES, NCST = 3;
+  static_assert(D == 128, "one 16-byte code chunk per thread and tile half");
+  __shared__ __align__(16) char lds[2 * L::STAGE + NCST * CST];
+  char *const codes = lds + 2 * L::STAGE;
 
   const int xcd = blockIdx.x & 7, jj0 = blockIdx.x >> 3;
   const int sg = (jj0 / q_tiles) * 8 + xcd, qt = jj0 % q_tiles;
@@ -995,7 +1003,7 @@ __global__ __launch_bounds__(512, 2) void reuse_attention_wide8_kernel(
   {
     const __bf16 *qrow = Q + (((size_t)b * Hq + head) * T + my_i) * D;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) qf[ks] = *(const bf16x8 *)(qrow + 32 * (ks >> 1) + 16 * g2 + 8 * (ks & 1));
+    for (int ks = 0; ks < KS; ++ks) qf[ks] = *(const bf16x8 *)(qrow + ks * 16 + g2 * 8);
   }
   f32x16 o_acc[DB];
 #pragma unroll
@@ -1005,32 +1013,15 @@ __global__ __launch_bounds__(512, 2) void reuse_attention_wide8_kernel(
   float m_ref = -INFINITY, l_run = 0.f;
   bool all_started = false;
 
-  // ---- cursor over the tiles of this range, kept by the loading wavefronts only: pointers that move on by one tile,
-  // the keys left in the chunk (or in the fresh part), and a rarely taken step to the next chunk that has keys.
-  // What the computing side needs of a tile -- how many keys are valid and, for a fresh tile, its first token --
-  // comes from a second, lighter cursor without pointers that every wavefront steps once per tile.
   const int ft = (T + TK - 1) / TK;
-  const __bf16 *const kf_base = Kf + ((size_t)b * Hkv + gkv) * T * D;
-  const __bf16 *const vf_base = Vf_blk + ((size_t)b * Hkv + gkv) * ft * (size_t)(TK * D);
-  const char *c_k = (const char *)kf_base, *c_v = (const char *)vf_base;   // bytes: a cached tile is TK * D of them, a fresh one twice that
-  int c_chunk, c_rem, c_t0;   // c_t0 < 0: in a cached chunk; else first token of the cursor's fresh tile
-  auto enter_chunk = [&](int chunk) __attribute__((always_inline)) {   // chunk == n_chunks: the fresh part
-    c_chunk = chunk;
-    if (chunk < n_chunks) {
-      const int slot = __builtin_amdgcn_readlane(my_slot, chunk) - n_slots16;   // (every chunk of this launch sits in an 8-bit slot)
-      const size_t cbase = ((size_t)slot * Hkv + gkv) * C * (size_t)D;
-      c_k = (const char *)k_store + cbase;
-      c_v = (const char *)v_store + cbase;
-      c_rem = __builtin_amdgcn_readlane(my_used, chunk);
-      c_t0 = -1;
-    } else {
-      c_k = (const char *)kf_base;
-      c_v = (const char *)vf_base;
-      c_rem = T;
-      c_t0 = 0;
-    }
+  const char *const kf_base = (const char *)(Kf + ((size_t)b * Hkv + gkv) * T * D);
+  const char *const vf_base = (const char *)(Vf_blk + ((size_t)b * Hkv + gkv) * ft * (size_t)(TK * D));
+  auto next_live = [&](int chunk) __attribute__((always_inline)) {
+    const unsigned long long rest = chunk < 63 ? live >> (chunk + 1) : 0ull;
+    return rest ? chunk + 1 + (int)__builtin_ctzll(rest) : n_chunks;
   };
-  int off0 = 0;   // tile inside its chunk at which this range starts
+  // where the range starts: chunk `first` (n_chunks: the fresh part), tile `off0` inside it
+  int first, off0;
   {
     const int my_tiles = (my_used + TK - 1) / TK;
     int incl = my_tiles;
@@ -1039,80 +1030,34 @@ __global__ __launch_bounds__(512, 2) void reuse_attention_wide8_kernel(
       const int up = __shfl_up(incl, sh, 64);
       if (lane >= sh) incl += up;
     }
-    const int first = __popcll(__ballot(incl <= tile_begin && lane < n_chunks));   // chunks wholly before tile_begin
+    first = __popcll(__ballot(incl <= tile_begin && lane < n_chunks));   // chunks wholly before tile_begin
     const int before = __builtin_amdgcn_readlane(incl - my_tiles, min(first, 63));
-    enter_chunk(first);   // (a chunk found this way has keys: its tile count is positive)
-    const int off = first < n_chunks ? tile_begin - before : tile_begin - n_cached_tiles;
-    c_k += (size_t)off * (TK * D) * (c_t0 >= 0 ? 2 : 1);
-    c_v += (size_t)off * (TK * D) * (c_t0 >= 0 ? 2 : 1);
-    c_rem -= off * TK;
-    off0 = off;
-    if (c_t0 >= 0) c_t0 = off * TK;
+    off0 = first < n_chunks ? tile_begin - before : tile_begin - n_cached_tiles;
   }
-  auto step_cursor = [&]() __attribute__((always_inline)) {
-    c_k += c_t0 >= 0 ? 2 * TK * D : TK * D;
-    c_v += c_t0 >= 0 ? 2 * TK * D : TK * D;
-    c_rem -= TK;
-    if (c_t0 >= 0) c_t0 += TK;
-    if (__builtin_expect(c_rem <= 0 && c_t0 < 0, 0)) {
-      const unsigned long long rest = c_chunk < 63 ? live >> (c_chunk + 1) : 0ull;
-      enter_chunk(rest ? c_chunk + 1 + (int)__builtin_ctzll(rest) : n_chunks);
-    }
-  };
 
-  // the computing side's cursor: same walk, no pointers, plus the tile's place in its chunk and the chunk's scales:
-  // lane j < 32 holds the K scale of the chunk's tile j, lane 32 + j its V scale (a chunk has at most 32 tiles here);
-  // the scales of the chunk after this one are requested when this one is entered
-  int q_chunk = c_chunk, q_rem = c_rem, q_t0 = c_t0, q_off = c_t0 < 0 ? off0 : 0;
-  const int tpc = C / TK;
-  auto chunk_scales = [&](int chunk) __attribute__((always_inline)) {
-    float v = 1.f;
+  // ---- the loading wavefronts' cursor over the CACHED tiles of the range (byte pointers into the 8-bit stores); it
+  // stops at the fresh part, whose tiles are addressed by their index
+  const char *c_k = nullptr, *c_v = nullptr;
+  int c_chunk = first, c_rem = 0;   // c_chunk == n_chunks: no cached tile left
+  auto enter_chunk = [&](int chunk) __attribute__((always_inline)) {
+    c_chunk = chunk;
     if (chunk < n_chunks) {
-      const int slot = __builtin_amdgcn_readlane(my_slot, min(chunk, 63)) - n_slots16;
-      const size_t base = ((size_t)slot * Hkv + gkv) * tpc;
-      if ((lane & 31) < tpc) v = (lane < 32 ? k_scale : v_scale)[base + (lane & 31)];
-    }
-    return v;
-  };
-  auto next_live = [&](int chunk) __attribute__((always_inline)) {
-    const unsigned long long rest = chunk < 63 ? live >> (chunk + 1) : 0ull;
-    return rest ? chunk + 1 + (int)__builtin_ctzll(rest) : n_chunks;
-  };
-  float sc_cur = chunk_scales(q_chunk), sc_nxt = chunk_scales(next_live(q_chunk));
-  auto step_compute_cursor = [&]() __attribute__((always_inline)) {
-    q_rem -= TK;
-    q_off += 1;
-    if (q_t0 >= 0) q_t0 += TK;
-    if (__builtin_expect(q_rem <= 0 && q_t0 < 0, 0)) {
-      q_chunk = next_live(q_chunk);
-      const bool cached = q_chunk < n_chunks;
-      q_rem = cached ? __builtin_amdgcn_readlane(my_used, min(q_chunk, 63)) : T;
-      q_t0 = cached ? -1 : 0;
-      q_off = 0;
-      sc_cur = sc_nxt;
-      sc_nxt = chunk_scales(next_live(q_chunk));
+      const int slot = __builtin_amdgcn_readlane(my_slot, chunk) - n_slots16;   // (every chunk of this launch sits in an 8-bit slot)
+      const size_t cbase = ((size_t)slot * Hkv + gkv) * C * (size_t)D;
+      c_k = (const char *)k_store + cbase;
+      c_v = (const char *)v_store + cbase;
+      c_rem = __builtin_amdgcn_readlane(my_used, chunk);
     }
   };
-
-  // ---- requests: wavefronts 0..3 bring in a tile, 4 K instructions and 4 V instructions each
+  enter_chunk(first);
+  if (first < n_chunks) {
+    c_k += (size_t)off0 * (TK * D);
+    c_v += (size_t)off0 * (TK * D);
+    c_rem -= off0 * TK;
+  }
+  // request instructions of this lane: code tiles (two K and two V instructions per loading wavefront) and bf16 tiles
+  constexpr int K8_INSTR = K8_BYTES / 1024 / NLD, V8_INSTR = V8_BYTES / 1024 / NLD;
   constexpr int K_INSTR = L::K_BYTES / 1024 / NLD, V_INSTR = L::V_BYTES / 1024 / NLD;
-  unsigned k_off[K_INSTR], v_off[V_INSTR];   // byte offsets from the tile's first K row / V block
-#pragma unroll
-  for (int k = 0; k < K_INSTR; ++k) {
-    const int byte = ((wave & (NLD - 1)) + k * NLD) * 1024 + lane * 16;
-    const int row = byte / L::K_ROW, pc = (byte % L::K_ROW) / 16;
-    k_off[k] = (unsigned)(row * D + (pc ^ swz<L::K_ROW>(row)) * 8) * 2u;
-  }
-#pragma unroll
-  for (int k = 0; k < V_INSTR; ++k) {
-    const int byte = ((wave & (NLD - 1)) + k * NLD) * 1024 + lane * 16;
-    const int d = byte / L::V_ROW, pc = (byte % L::V_ROW) / 16;
-    v_off[k] = (unsigned)(d * TK + (pc ^ swz<L::V_ROW>(d)) * 8) * 2u;
-  }
-  // 8-bit tiles: K rows of D bytes, V^T rows of TK bytes, 16-byte chunks XOR-swizzled by the row ((row >> 1) & 7 for
-  // rows of 128 bytes, (row >> 2) & 3 for rows of 64); 8 + 8 request instructions per tile, two of each per loading wavefront
-  constexpr int K8_ROW = D, V8_ROW = TK;
-  constexpr int K8_INSTR = TK * K8_ROW / 1024 / NLD, V8_INSTR = D * V8_ROW / 1024 / NLD;
   auto swz8 = [](int row_bytes, int row) { return row_bytes == 128 ? ((row >> 1) & 7) : ((row >> 2) & 3); };
   unsigned k8_off[K8_INSTR], v8_off[V8_INSTR];
 #pragma unroll
@@ -1127,110 +1072,156 @@ __global__ __launch_bounds__(512, 2) void reuse_attention_wide8_kernel(
     const int d = byte / V8_ROW, pc = (byte % V8_ROW) / 16;
     v8_off[k] = (unsigned)(d * V8_ROW + (pc ^ swz8(V8_ROW, d)) * 16);
   }
-  // operand reads: the head dim is walked in the order 32 j + 16 g2 + 8 jj (k-step 2 j + jj) by K, Q and the fresh K alike
-  int k_rd[KS], v_rd[4], k8_rd[KS / 2], v8_rd[2];
-#pragma unroll
-  for (int ks = 0; ks < KS; ++ks) k_rd[ks] = ((4 * (ks >> 1) + 2 * g2 + (ks & 1)) ^ swz<L::K_ROW>(l32)) * 16;
-#pragma unroll
-  for (int c4 = 0; c4 < 4; ++c4) v_rd[c4] = ((2 * c4 + g2) ^ swz<L::V_ROW>(l32)) * 16;
-#pragma unroll
-  for (int j = 0; j < KS / 2; ++j) k8_rd[j] = ((2 * j + g2) ^ swz8(K8_ROW, l32)) * 16;
-#pragma unroll
-  for (int J = 0; J < 2; ++J) v8_rd[J] = ((2 * J + g2) ^ swz8(V8_ROW, l32)) * 16;
-  auto request_next = [&](int st) __attribute__((always_inline)) {   // the cursor's tile into stage st; steps the cursor
-    char *kb = lds + st * L::STAGE;
+  // the cursor's tile of codes into code stage cs; steps the cursor (wavefronts 0..3; call only while a cached tile is left)
+  auto request_codes = [&](int cs) __attribute__((always_inline)) {
+    char *dst = codes + cs * CST;
     const int valid = min(TK, c_rem);
-    const char *kp = c_k, *vp = c_v;
-    if (c_t0 < 0) {   // a tile of codes: half a stage
 #pragma unroll
-      for (int k = 0; k < K8_INSTR; ++k) {
-        unsigned o = k8_off[k];
-        if (__builtin_expect(valid < TK, 0)) {   // rows past a ragged end repeat the last valid row (masked later)
-          int lane_v = lane;
-          asm volatile("" : "+v"(lane_v));   // (recomputed here so that nothing of it stays in registers across the loop)
-          const int byte = ((wave & (NLD - 1)) + k * NLD) * 1024 + lane_v * 16;
-          const int row = byte / K8_ROW, pc = (byte % K8_ROW) / 16;
-          o = (unsigned)(min(row, valid - 1) * K8_ROW + (pc ^ swz8(K8_ROW, row)) * 16);
-        }
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(kp + o),
-                                         (__attribute__((address_space(3))) void *)(kb + (wave + k * NLD) * 1024), 16, 0, kKvAux);
-      }
-#pragma unroll
-      for (int k = 0; k < V8_INSTR; ++k)
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(vp + v8_off[k]),
-                                         (__attribute__((address_space(3))) void *)(kb + L::K_BYTES + (wave + k * NLD) * 1024), 16, 0, kKvAux);
-      step_cursor();
-      return;
-    }
-    if (__builtin_expect(valid < TK, 0)) {   // rows past a ragged end repeat the last valid row (masked later)
-#pragma unroll
-      for (int k = 0; k < K_INSTR; ++k) {
+    for (int k = 0; k < K8_INSTR; ++k) {
+      unsigned o = k8_off[k];
+      if (__builtin_expect(valid < TK, 0)) {   // rows past a ragged end repeat the last valid row (masked later)
         int lane_v = lane;
-        asm volatile("" : "+v"(lane_v));
+        asm volatile("" : "+v"(lane_v));   // (recomputed here so that nothing of it stays in registers across the loop)
         const int byte = ((wave & (NLD - 1)) + k * NLD) * 1024 + lane_v * 16;
-        const int row = byte / L::K_ROW, pc = (byte % L::K_ROW) / 16;
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(kp + (unsigned)(min(row, valid - 1) * D + (pc ^ swz<L::K_ROW>(row)) * 8) * 2u),
-                                         (__attribute__((address_space(3))) void *)(kb + (wave + k * NLD) * 1024), 16, 0, kKvAux);
+        const int row = byte / K8_ROW, pc = (byte % K8_ROW) / 16;
+        o = (unsigned)(min(row, valid - 1) * K8_ROW + (pc ^ swz8(K8_ROW, row)) * 16);
       }
-    } else {
-#pragma unroll
-      for (int k = 0; k < K_INSTR; ++k)
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(kp + k_off[k]),
-                                         (__attribute__((address_space(3))) void *)(kb + (wave + k * NLD) * 1024), 16, 0, kKvAux);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(c_k + o),
+                                       (__attribute__((address_space(3))) void *)(dst + (wave + k * NLD) * 1024), 16, 0, kKvAux);
     }
 #pragma unroll
-    for (int k = 0; k < V_INSTR; ++k)
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(vp + v_off[k]),
+    for (int k = 0; k < V8_INSTR; ++k)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(c_v + v8_off[k]),
+                                       (__attribute__((address_space(3))) void *)(dst + K8_BYTES + (wave + k * NLD) * 1024), 16, 0, kKvAux);
+    c_k += TK * D;
+    c_v += TK * D;
+    c_rem -= TK;
+    if (__builtin_expect(c_rem <= 0, 0)) enter_chunk(next_live(c_chunk));
+  };
+  // fresh tile fi (first token fi * TK) into bf16 stage st (wavefronts 0..3)
+  auto request_fresh = [&](int fi, int st) __attribute__((always_inline)) {
+    char *kb = lds + st * L::STAGE;
+    const int valid = min(TK, T - fi * TK);
+    const char *kp = kf_base + (size_t)fi * (TK * D * 2), *vp = vf_base + (size_t)fi * (TK * D * 2);
+#pragma unroll
+    for (int k = 0; k < K_INSTR; ++k) {
+      const int byte = ((wave & (NLD - 1)) + k * NLD) * 1024 + lane * 16;
+      const int row = byte / L::K_ROW, pc = (byte % L::K_ROW) / 16;
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(kp + (unsigned)(min(row, valid - 1) * D + (pc ^ swz<L::K_ROW>(row)) * 8) * 2u),
+                                       (__attribute__((address_space(3))) void *)(kb + (wave + k * NLD) * 1024), 16, 0, kKvAux);
+    }
+#pragma unroll
+    for (int k = 0; k < V_INSTR; ++k) {
+      const int byte = ((wave & (NLD - 1)) + k * NLD) * 1024 + lane * 16;
+      const int d = byte / L::V_ROW, pc = (byte % L::V_ROW) / 16;
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(vp + (unsigned)(d * TK + (pc ^ swz<L::V_ROW>(d)) * 8) * 2u),
                                        (__attribute__((address_space(3))) void *)(kb + L::K_BYTES + (wave + k * NLD) * 1024), 16, 0, kKvAux);
-    step_cursor();
+    }
   };
 
-  // ---- one tile: S^T = K Q^T, softmax against the lazily refreshed reference exponent, O^T += V^T P^T
+  // ---- every wavefront's cursor over ALL tiles of the range, one tile ahead of the arithmetic: is the tile cached,
+  // how many of its keys are valid, its place in its chunk and the chunk's scales: lane j < 32 holds the K scale of the
+  // chunk's tile j, lane 32 + j its V scale; the scales of the chunk after this one are requested when this one is entered
+  const int tpc = C / TK;
+  auto chunk_scales = [&](int chunk) __attribute__((always_inline)) {
+    float v = 1.f;
+    if (chunk < n_chunks) {
+      const int slot = __builtin_amdgcn_readlane(my_slot, min(chunk, 63)) - n_slots16;
+      const size_t base = ((size_t)slot * Hkv + gkv) * tpc;
+      if ((lane & 31) < tpc) v = (lane < 32 ? k_scale : v_scale)[base + (lane & 31)];
+    }
+    return v;
+  };
+  int r_chunk = first, r_off = off0;
+  int r_rem = first < n_chunks ? __builtin_amdgcn_readlane(my_used, min(first, 63)) - off0 * TK : T - off0 * TK;
+  int r_t0 = first < n_chunks ? -1 : off0 * TK;
+  float sc_cur = chunk_scales(r_chunk), sc_nxt = chunk_scales(next_live(r_chunk));
+  auto step_ready_cursor = [&]() __attribute__((always_inline)) {
+    r_rem -= TK;
+    r_off += 1;
+    if (r_t0 >= 0) r_t0 += TK;
+    if (__builtin_expect(r_rem <= 0 && r_t0 < 0, 0)) {
+      r_chunk = next_live(r_chunk);
+      const bool cached = r_chunk < n_chunks;
+      r_rem = cached ? __builtin_amdgcn_readlane(my_used, min(r_chunk, 63)) : T;
+      r_t0 = cached ? -1 : 0;
+      r_off = 0;
+      sc_cur = sc_nxt;
+      sc_nxt = chunk_scales(next_live(r_chunk));
+    }
+  };
+  // operand reads of the tile arithmetic (bf16 tile layout)
+  int k_rd[KS], v_rd[4];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) k_rd[ks] = ((2 * ks + g2) ^ swz<L::K_ROW>(l32)) * 16;
+#pragma unroll
+  for (int c4 = 0; c4 < 4; ++c4) v_rd[c4] = ((2 * c4 + g2) ^ swz<L::V_ROW>(l32)) * 16;
+  // conversion share of this thread: K row tid / 8, code chunk tid % 8 (elements 16 c .. 16 c + 15 -> bf16 chunks 2c, 2c + 1);
+  // V^T row tid / 4, code chunk m = tid % 4 = 2 J + a (byte p of a row holds the key that the bf16 block holds at
+  // element p with bits 3 and 4 swapped: the chunk's first 8 codes are bf16 chunk 4 J + a, its last 8 chunk 4 J + 2 + a)
+  const int ck_row = tid >> 3, ck_c = tid & 7, cv_row = tid >> 2, cv_m = tid & 3;
+  const int ck_src = ck_row * K8_ROW + ((ck_c ^ swz8(K8_ROW, ck_row)) * 16);
+  const int cv_src = K8_BYTES + cv_row * V8_ROW + ((cv_m ^ swz8(V8_ROW, cv_row)) * 16);
+  const int ck_dst0 = ck_row * L::K_ROW + (((2 * ck_c) ^ swz<L::K_ROW>(ck_row)) * 16);
+  const int ck_dst1 = ck_row * L::K_ROW + (((2 * ck_c + 1) ^ swz<L::K_ROW>(ck_row)) * 16);
+  const int cv_dst0 = L::K_BYTES + cv_row * L::V_ROW + (((4 * (cv_m >> 1) + (cv_m & 1)) ^ swz<L::V_ROW>(cv_row)) * 16);
+  const int cv_dst1 = L::K_BYTES + cv_row * L::V_ROW + (((4 * (cv_m >> 1) + 2 + (cv_m & 1)) ^ swz<L::V_ROW>(cv_row)) * 16);
+  const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) char *)lds;
+  auto store16 = [&](int byte_off, bf16x8 v) __attribute__((always_inline)) {
+    const unsigned addr = lds_base + (unsigned)byte_off;
+    asm volatile("ds_write_b128 %0, %1" : : "v"(addr), "v"(v) : "memory");
+  };
+  // makes the tile the ready cursor points at ready in bf16 stage st: converts its codes (from code stage cs) or, for a
+  // fresh tile, requests it; returns with the cursor's (valid keys, first fresh token or -1) in the two references
+  auto make_ready = [&](int cs, int st, int &valid_out, int &t0_out) __attribute__((always_inline)) {
+    valid_out = min(TK, r_rem);
+    t0_out = r_t0;
+    if (r_t0 < 0) {
+      const float ks8 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, sc_cur), r_off));
+      const float vs8 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, sc_cur), 32 + r_off));
+      const char *src = codes + cs * CST;
+      const pc::u32x4 kr = *(const pc::u32x4 *)(src + ck_src), vr = *(const pc::u32x4 *)(src + cv_src);
+      store16(st * L::STAGE + ck_dst0, codes_to_bf16(kr[0], kr[1], ks8));
+      store16(st * L::STAGE + ck_dst1, codes_to_bf16(kr[2], kr[3], ks8));
+      store16(st * L::STAGE + cv_dst0, codes_to_bf16(vr[0], vr[1], vs8));
+      store16(st * L::STAGE + cv_dst1, codes_to_bf16(vr[2], vr[3], vs8));
+    } else if (wave < NLD) {
+      request_fresh(r_t0 / TK, st);
+    }
+    step_ready_cursor();
+  };
+  int m_valid = TK, m_t0 = -1;   // of the tile the arithmetic is on
+
   auto tile = [&](int st) __attribute__((always_inline)) {
     const char *kb = lds + st * L::STAGE;
     const char *vb = kb + L::K_BYTES;
-    const bool is8 = q_t0 < 0;   // a tile of codes (cached) or a bf16 tile (fresh)
     f32x16 s_acc[2];
 #pragma unroll
     for (int kbk = 0; kbk < 2; ++kbk)
 #pragma unroll
       for (int r = 0; r < 16; ++r) s_acc[kbk][r] = 0.f;
-    if (is8) {
-      // one 16-byte read per key block and pair of k-steps, turned into two bf16 operands (exact: power-of-two scale)
-      const float ks8 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, sc_cur), q_off));
 #pragma unroll
-      for (int h = 0; h < KS / 4; ++h) {
-        pc::u32x4 raw[2][2];
+    for (int h = 0; h < KS / 4; ++h) {
+      bf16x8 kop[2][4];
 #pragma unroll
-        for (int j2 = 0; j2 < 2; ++j2)
+      for (int k4 = 0; k4 < 4; ++k4)
 #pragma unroll
-          for (int kbk = 0; kbk < 2; ++kbk) raw[kbk][j2] = *(const pc::u32x4 *)(kb + (kbk * 32 + l32) * K8_ROW + k8_rd[2 * h + j2]);
+        for (int kbk = 0; kbk < 2; ++kbk) kop[kbk][k4] = *(const bf16x8 *)(kb + (kbk * 32 + l32) * L::K_ROW + k_rd[4 * h + k4]);
 #pragma unroll
-        for (int j2 = 0; j2 < 2; ++j2)
+      for (int k4 = 0; k4 < 4; ++k4)
 #pragma unroll
-          for (int kbk = 0; kbk < 2; ++kbk) {
-            const bf16x8 a0 = codes_to_bf16(raw[kbk][j2][0], raw[kbk][j2][1], ks8);
-            const bf16x8 a1 = codes_to_bf16(raw[kbk][j2][2], raw[kbk][j2][3], ks8);
-            s_acc[kbk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qf[4 * h + 2 * j2], s_acc[kbk], 0, 0, 0);
-            s_acc[kbk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qf[4 * h + 2 * j2 + 1], s_acc[kbk], 0, 0, 0);
-          }
-      }
-    } else {
-#pragma unroll
-      for (int h = 0; h < KS / 4; ++h) {
-        bf16x8 kop[2][4];
-#pragma unroll
-        for (int k4 = 0; k4 < 4; ++k4)
-#pragma unroll
-          for (int kbk = 0; kbk < 2; ++kbk) kop[kbk][k4] = *(const bf16x8 *)(kb + (kbk * 32 + l32) * L::K_ROW + k_rd[4 * h + k4]);
-#pragma unroll
-        for (int k4 = 0; k4 < 4; ++k4)
-#pragma unroll
-          for (int kbk = 0; kbk < 2; ++kbk)
-            s_acc[kbk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop[kbk][k4], qf[4 * h + k4], s_acc[kbk], 0, 0, 0);
-      }
+        for (int kbk = 0; kbk < 2; ++kbk)
+          s_acc[kbk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop[kbk][k4], qf[4 * h + k4], s_acc[kbk], 0, 0, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
     }
-    const int t_valid = min(TK, q_rem), t_t0 = q_t0;
+    // V operands of the first 32-key block: their LDS latency runs under the softmax arithmetic
+    bf16x8 vop0[DB][2];
+#pragma unroll
+    for (int c2 = 0; c2 < 2; ++c2)
+#pragma unroll
+      for (int db = 0; db < DB; ++db) vop0[db][c2] = *(const bf16x8 *)(vb + (db * 32 + l32) * L::V_ROW + v_rd[c2]);
+    const int t_valid = m_valid, t_t0 = m_t0;
     if (__builtin_expect(t_valid < TK || t_t0 >= 0, 0)) {
       int t_lane = g2 * 4;
       asm volatile("" : "+v"(t_lane));   // (keeps the 32 per-element key indices out of loop-invariant registers)
@@ -1289,66 +1280,62 @@ __global__ __launch_bounds__(512, 2) void reuse_attention_wide8_kernel(
       all_started = __builtin_amdgcn_ballot_w64(m_ref == -INFINITY) == 0;
     }
     l_run += psum;
-    if (is8) {
-      const float vs8 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, sc_cur), 32 + q_off));
-      pc::u32x4 vraw0[DB], vraw1[DB];
+    bf16x8 vop1[DB][2];
 #pragma unroll
-      for (int db = 0; db < DB; ++db) vraw0[db] = *(const pc::u32x4 *)(vb + (db * 32 + l32) * V8_ROW + v8_rd[0]);
+    for (int c2 = 0; c2 < 2; ++c2)
 #pragma unroll
-      for (int db = 0; db < DB; ++db) vraw1[db] = *(const pc::u32x4 *)(vb + (db * 32 + l32) * V8_ROW + v8_rd[1]);
+      for (int db = 0; db < DB; ++db) vop1[db][c2] = *(const bf16x8 *)(vb + (db * 32 + l32) * L::V_ROW + v_rd[2 + c2]);
 #pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        const bf16x8 a0 = codes_to_bf16(vraw0[db][0], vraw0[db][1], vs8);
-        const bf16x8 a1 = codes_to_bf16(vraw0[db][2], vraw0[db][3], vs8);
-        o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, pf[0][0], o_acc[db], 0, 0, 0);
-        o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, pf[0][1], o_acc[db], 0, 0, 0);
-      }
+    for (int c2 = 0; c2 < 2; ++c2)
 #pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        const bf16x8 a0 = codes_to_bf16(vraw1[db][0], vraw1[db][1], vs8);
-        const bf16x8 a1 = codes_to_bf16(vraw1[db][2], vraw1[db][3], vs8);
-        o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, pf[1][0], o_acc[db], 0, 0, 0);
-        o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, pf[1][1], o_acc[db], 0, 0, 0);
-      }
-    } else {
+      for (int db = 0; db < DB; ++db)
+        o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop0[db][c2], pf[0][c2], o_acc[db], 0, 0, 0);
 #pragma unroll
-      for (int hh = 0; hh < 2; ++hh) {   // (the few fresh tiles: operands read where they are used)
-        bf16x8 vop[DB][2];
+    for (int c2 = 0; c2 < 2; ++c2)
 #pragma unroll
-        for (int c2 = 0; c2 < 2; ++c2)
-#pragma unroll
-          for (int db = 0; db < DB; ++db) vop[db][c2] = *(const bf16x8 *)(vb + (db * 32 + l32) * L::V_ROW + v_rd[2 * hh + c2]);
-#pragma unroll
-        for (int c2 = 0; c2 < 2; ++c2)
-#pragma unroll
-          for (int db = 0; db < DB; ++db)
-            o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop[db][c2], pf[hh][c2], o_acc[db], 0, 0, 0);
-      }
-    }
+      for (int db = 0; db < DB; ++db)
+        o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop1[db][c2], pf[1][c2], o_acc[db], 0, 0, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, 2 * DB, 1);
+    __builtin_amdgcn_sched_group_barrier(0x008, 4 * DB, 1);
   };
 
-  // ---- pipeline: tile t is computed from stage t % 3; tiles t+1 and t+2 are in flight or landed.  At the end of
-  // iteration t wavefronts 0..3 wait for their share of tile t+1 (requested an iteration ago), request tile t+2 into
-  // the stage that iteration t-1 read, and the barrier publishes tile t+1.
+  // ---- pipeline.  Iteration t: make tile t+1 ready in bf16 stage (t+1) & 1 (its codes were requested two iterations
+  // ago and published by the last barrier; that stage was last read in iteration t-1), run the arithmetic on tile t in
+  // stage t & 1, then wait for everything this wavefront has in flight (codes of tile t+2, a fresh tile t+1, its own
+  // converted stores), request the codes of tile t+3 into the code stage that iteration t-1 emptied, barrier.
+  int n_cached_left = 0;   // cached tiles of the range not requested yet (loading wavefronts)
+  {
+    const int cached_total = first < n_chunks ? min(n, n_cached_tiles - tile_begin) : 0;
+    n_cached_left = cached_total;
+  }
   if (wave < NLD) {
-    if (n > 0) request_next(0);
-    if (n > 1) request_next(1);
+#pragma unroll
+    for (int i = 0; i < NCST; ++i)
+      if (n_cached_left > 0) { request_codes(i); --n_cached_left; }
   }
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qf[ks]));
-  PC_WAIT_VMCNT(0);
+  __builtin_amdgcn_s_waitcnt(0);
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
-  int st = 0;
+  int nx_valid = TK, nx_t0 = -1;
+  if (n > 0) make_ready(0, 0, nx_valid, nx_t0);
+  __builtin_amdgcn_s_waitcnt(0);
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+  int cs = 1;   // code stage of tile t+1
   for (int t = 0; t < n; ++t) {
-    tile(st);
-    step_compute_cursor();
-    PC_WAIT_VMCNT(0);   // the share of tile t+1
-    if (wave < NLD && t + 2 < n) request_next(st >= 1 ? st - 1 : NSTAGE - 1);
+    m_valid = nx_valid;
+    m_t0 = nx_t0;
+    if (t + 1 < n) make_ready(cs, (t + 1) & 1, nx_valid, nx_t0);
+    tile(t & 1);
+    __builtin_amdgcn_s_waitcnt(0);
+    // the code stage of tile t (emptied at the top of iteration t-1, or in the prologue) takes tile t+3
+    if (wave < NLD && n_cached_left > 0) { request_codes(cs >= 1 ? cs - 1 : NCST - 1); --n_cached_left; }
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    st = st + 1 == NSTAGE ? 0 : st + 1;
+    cs = cs + 1 == NCST ? 0 : cs + 1;
   }
 
   const float l_tot = pair_sum(l_run);
