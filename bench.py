@@ -33,7 +33,7 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
 # HBM bytes per launch of the attention kernel on this workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled
 # by a 1 GiB copy (summary under profiles/).  Valid only for the kernel source the counters were taken with.
-ATTN_TRAFFIC = {"source_sha256_16": "f8291b003fb1a615", "read_bytes": 2 * 320769.0 * 1024, "write_bytes": 55296.0 * 1024}
+ATTN_TRAFFIC = {"source_sha256_16": "e611ef23623c4215", "read_bytes": 2 * 317801.7 * 1024, "write_bytes": 55296.0 * 1024}
 
 
 def attention_traffic():
