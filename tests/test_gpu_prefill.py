@@ -304,8 +304,10 @@ def test_long_context_kernel_over_8bit_slots(t_fresh, n_splits, n16):
     fill_slots(pc, w, w.slot_ids.reshape(-1))
     X, W = bf16(w.X), bf16(w.Wqkv)
     q, kf, vf = pc.percache_qkv_rope(0, X, W, w.slot_ids, w.used_len, n_chunks=n_chunks)
-    out = pc.percache_attention_reuse(0, q, kf, vf, w.slot_ids, w.used_len, n_chunks=n_chunks, n_splits=n_splits)
+    out = pc.percache_attention_reuse(0, q, kf, vf, w.slot_ids, w.used_len, n_chunks=n_chunks, n_splits=n_splits).clone()
+    again = pc.percache_attention_reuse(0, q, kf, vf, w.slot_ids, w.used_len, n_chunks=n_chunks, n_splits=n_splits)
     torch.cuda.synchronize()
+    assert torch.equal(out, again), "the same call twice gives other bits"
     for b, nc in enumerate(n_chunks):
         sk, sv, ids = w.compact_store(b)
         sk = np.stack([kv_fp8.round_trip(wl.round_bf16(x)) for x in sk]) if len(sk) else sk
