@@ -488,6 +488,182 @@ __global__ __launch_bounds__(256, 2) void lookup_batched_kernel(const _Float16 *
 }
 
 // ---------------------------------------------------------------------------------------------------
+// The same product on larger tiles, for the best match alone (k = 1) and enough probes to fill them: 256 bank rows x
+// 256 probes per workgroup of 8 wavefronts, one workgroup per CU.  A CU takes in at most 64 bytes per clock from L2,
+// which a 128 x 128 tile needs for as long as its MFMAs run; at 256 x 256 the operand bytes per flop halve.
+// Wavefront (wa, wb) owns bank-row blocks 2 wa, 2 wa + 1 and probe blocks 4 wb .. 4 wb + 3 (eight accumulators).
+// Two LDS stages of 64 k-elements (64 KB each, 128-byte rows, chunk ^= (row >> 1) & 7), and one software pipeline
+// over all the k-steps of all the workgroup's tiles: the operands of the next 16 k-elements are read from LDS while
+// the MFMAs of the current ones run, and the one barrier of a k-step sits before its last quarter -- there every
+// wavefront has read the rest of the current stage into registers (so the stage can be requested again: two k-steps
+// ahead) and the next stage has landed (its first operands are read under that last quarter's MFMAs).
+// ---------------------------------------------------------------------------------------------------
+constexpr int kBigTile = 256;
+constexpr int kBigLds = 2 * 2 * kBigTile * 128;  // two stages of (256 + 256) rows x 128 bytes
+
+__global__ __launch_bounds__(512, 1) void lookup_big_kernel(const _Float16 *__restrict__ bank, const float *__restrict__ inv_norm,
+                                                            int N, int d, const _Float16 *__restrict__ probes, int n_probes,
+                                                            int p_pad, int n_groups, int p_tiles, Best *__restrict__ partial) {
+  extern __shared__ __align__(16) char smem[];
+  constexpr int ROW = 128, HALF = kBigTile * ROW, STAGE = 2 * HALF;
+  // the probe tiles of one bank group run next to each other on ONE XCD (workgroup ids go round-robin over the 8):
+  // the group's rows come from HBM once and are re-read from that XCD's L2
+  const int xcd = blockIdx.x & 7, jj = blockIdx.x >> 3;
+  const int group = (jj / p_tiles) * 8 + xcd, p_tile = jj % p_tiles;
+  if (group >= n_groups) return;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wa = wave & 3, wb = wave >> 2;
+  const int l32 = lane & 31, g = lane >> 5;
+  const int n_tiles = (N + kBigTile - 1) / kBigTile;
+  const int tile_begin = (int)((long)group * n_tiles / n_groups), tile_end = (int)((long)(group + 1) * n_tiles / n_groups);
+  const int m0 = p_tile * kBigTile;
+  const int nk = d / 64;
+  const int n_steps = (tile_end - tile_begin) * nk;
+
+  // requests: instruction i of a stage fills its bytes [1024 i, 1024 i + 1024), i.e. rows 8 i .. 8 i + 7 (i < 32: bank
+  // rows, else probes); wavefronts 0-3 bring the bank rows, 4-7 the probes, eight instructions each
+  const bool loads_bank = wave < 4;
+  const int my_row = (wave & 3) * 64 + (lane >> 3);  // + 8 k
+  const int my_chunk = lane & 7;
+  const _Float16 *src[8];
+  int f_tile = tile_begin, f_kt = 0;  // what the next request brings
+  auto aim = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const int row = my_row + 8 * k;
+      const size_t at = loads_bank ? (size_t)min(f_tile * kBigTile + row, N - 1) : (size_t)min(m0 + row, n_probes - 1);
+      src[k] = (loads_bank ? bank : probes) + at * d + ((my_chunk ^ pc::gemm::swz128(row)) * 8);
+    }
+  };
+  auto request = [&](int st) __attribute__((always_inline)) {
+    char *base = smem + st * STAGE + (loads_bank ? 0 : HALF) + (wave & 3) * 8192;
+#pragma unroll
+    for (int k = 0; k < 8; ++k)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src[k] + f_kt * 64),
+                                       (__attribute__((address_space(3))) void *)(base + k * 1024), 16, 0, 0);
+    if (++f_kt == nk) {
+      f_kt = 0;
+      ++f_tile;
+      if (loads_bank && f_tile < tile_end) aim();
+    }
+  };
+
+  // operand reads: this lane's row inside a 32-row block is l32; k-quarter q of a stage is chunk 2 q + g
+  int rd[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) rd[q] = ((2 * q + g) ^ pc::gemm::swz128(l32)) * 16;
+  const int a_off = (2 * wa * 32 + l32) * ROW, b_off = HALF + (4 * wb * 32 + l32) * ROW;
+  f16x8 oa[2][2], ob[2][4];  // two register sets
+  auto read_ops = [&](int set, int st, int q) __attribute__((always_inline)) {
+    const char *base = smem + st * STAGE + rd[q];
+#pragma unroll
+    for (int a = 0; a < 2; ++a) oa[set][a] = *(const f16x8 *)(base + a_off + a * 32 * ROW);
+#pragma unroll
+    for (int t = 0; t < 4; ++t) ob[set][t] = *(const f16x8 *)(base + b_off + t * 32 * ROW);
+  };
+  pc::f32x16 acc[2][4];
+  auto mma_ops = [&](int set) __attribute__((always_inline)) {
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+      for (int a = 0; a < 2; ++a) acc[a][t] = pc::gemm::mma(oa[set][a], ob[set][t], acc[a][t]);
+  };
+  // one MFMA, one LDS read, ... : the reads of the next quarter go out under the MFMAs of this one
+  auto interleave = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < 6; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+  };
+
+  TopK<1> best[4];  // this lane's rows for probes m0 + (4 wb + t) * 32 + l32
+#pragma unroll
+  for (int t = 0; t < 4; ++t) best[t].clear();
+
+  if (n_steps > 0) {
+    aim();
+    request(0);
+    pc::gemm::wait_vmcnt0();
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    if (n_steps > 1) request(1);
+    read_ops(0, 0, 0);
+  }
+  int step = 0;
+  for (int tile = tile_begin; tile < tile_end; ++tile) {
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[a][t][r] = 0.f;
+    for (int kt = 0; kt < nk; ++kt, ++step) {
+      const int st = step & 1;
+      read_ops(1, st, 1);
+      mma_ops(0);
+      interleave();
+      read_ops(0, st, 2);
+      mma_ops(1);
+      interleave();
+      read_ops(1, st, 3);
+      mma_ops(0);
+      interleave();
+      // every read of this stage is in registers and this wavefront's part of the next stage has landed
+      __builtin_amdgcn_s_waitcnt(7 << 4);
+      asm volatile("" ::: "memory");
+      __builtin_amdgcn_s_barrier();
+      asm volatile("" ::: "memory");
+      if (step + 2 < n_steps) request(st);
+      read_ops(0, st ^ 1, 0);  // (past the last k-step: whatever the other stage holds, never multiplied)
+      mma_ops(1);
+      interleave();
+    }
+    // cosines of this tile's rows (up to the probe's own norm, which the finalize kernel divides by)
+    const int r0 = tile * kBigTile;
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const int row0 = r0 + (2 * wa + a) * 32 + q4 * 8 + g * 4;
+        const f32x4 inv4 = *(const f32x4 *)(inv_norm + min(row0, (N - 1) & ~3));  // rows come in aligned fours
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int row = row0 + e;
+#pragma unroll
+          for (int t = 0; t < 4; ++t)
+            if (row < N) best[t].insert(acc[a][t][q4 * 4 + e] * inv4[e], row);
+        }
+      }
+  }
+  // the two lanes of a probe, then the four wavefronts (wa) that hold other rows of the same probes
+  __builtin_amdgcn_s_waitcnt(7 << 4);
+  __syncthreads();
+  Best *red = (Best *)smem;  // [wb][wa][4 * 32]
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    float s = best[t].s[0];
+    int i = best[t].i[0];
+    const float s2 = __shfl_xor(s, 32, 64);
+    const int i2 = __shfl_xor(i, 32, 64);
+    if (better(s2, i2, s, i)) { s = s2; i = i2; }
+    if (g == 0) red[(wb * 4 + wa) * 128 + t * 32 + l32] = Best{s, i};
+  }
+  __syncthreads();
+  if (tid < kBigTile) {  // one thread per probe of the tile: probe wb2 * 128 + within
+    const int wb2 = tid >> 7, within = tid & 127;
+    Best b = red[(wb2 * 4) * 128 + within];
+#pragma unroll
+    for (int w = 1; w < 4; ++w) {
+      const Best c = red[(wb2 * 4 + w) * 128 + within];
+      if (better(c.s, c.idx, b.s, b.idx)) b = c;
+    }
+    partial[(size_t)group * p_pad + m0 + tid] = b;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------
 // Up to 128 probes in one pass of the bank (embedding widths of 512, 768 and 1024 elements).
 // One workgroup per CU; wavefront w keeps ITS 32 probes in registers as the N-side operands of the 32x32x16 product
 // (d/4 registers per lane: one wavefront per SIMD), and all four wavefronts multiply the same 32-row blocks of the
@@ -712,6 +888,27 @@ BatchShape batch_shape(int n_cu, int N, int n_probes) {
   return b;
 }
 
+// Launch shape of the 256 x 256 kernel: 256-probe tiles x groups of consecutive 256-row bank tiles, one workgroup per
+// CU (a multiple of 8 groups, so that a group's probe tiles share an XCD), every group at least one tile.
+struct BigShape {
+  int p_tiles, groups;
+};
+BigShape big_shape(int n_cu, int N, int n_probes) {
+  BigShape b;
+  b.p_tiles = (n_probes + kBigTile - 1) / kBigTile;
+  const int n_tiles = (N + kBigTile - 1) / kBigTile;
+  b.groups = n_cu / b.p_tiles / 8 * 8;
+  if (b.groups < 8) b.groups = 8;
+  if (b.groups > n_tiles) b.groups = n_tiles;
+  return b;
+}
+// whether the 256-probe tiles are filled well enough to beat the 128-probe ones (at most a third of padding)
+bool big_tiles_pay(int n_probes) {
+  if (n_probes <= kWideUpTo) return false;
+  const long padded = (long)(n_probes + kBigTile - 1) / kBigTile * kBigTile;
+  return padded * 3 <= (long)n_probes * 4;
+}
+
 template <int NPB, int CHB, int NSTG, int K>
 pc_status launch_stream(percache_ctx *ctx, const StreamShape &sh, hipStream_t st, int N, int d, const _Float16 *pp, int np,
                         Best *partial, const RowScan &rs) {
@@ -798,6 +995,24 @@ pc_status run_lookup(percache_ctx *ctx, const void *probes_dev, int32_t n_probes
 #undef PC_WIDE
     return PC_OK;
   }
+  if (k == 1 && big_tiles_pay(n_probes) && d % 64 == 0) {
+    // many probes, best match only: the matrix-core bound product on 256 x 256 tiles, one workgroup per CU
+    const BigShape bg = big_shape(ctx->n_cu, N, n_probes);
+    static bool big_lds_set = false;  // dynamic LDS above 64 KB must be opted into once
+    if (!big_lds_set) {
+      PC_HIP(ctx, hipFuncSetAttribute((const void *)lookup_big_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kBigLds));
+      big_lds_set = true;
+    }
+    pc::prof_begin(ctx, PC_KERNEL_LOOKUP, st);
+    hipLaunchKernelGGL(lookup_big_kernel, dim3((unsigned)((bg.groups + 7) / 8 * 8 * bg.p_tiles)), dim3(512), kBigLds, st, ctx->bank, ctx->bank_inv, N, d,
+                       probes, n_probes, bg.p_tiles * kBigTile, bg.groups, bg.p_tiles, partial);
+    pc::prof_end(ctx, PC_KERNEL_LOOKUP, st);
+    PC_HIP(ctx, hipGetLastError());
+    hipLaunchKernelGGL(lookup_finalize_kernel<1>, dim3(n_probes), dim3(kFinalizeThreads), 0, st, partial, bg.groups, bg.p_tiles * kBigTile, probes, d, tau, 1,
+                       idx_out_dev, sim_out_dev, hit_out_dev);
+    PC_HIP(ctx, hipGetLastError());
+    return PC_OK;
+  }
   if (n_probes > kBatchedFrom) {
     // many probes: matrix-core bound product instead of repeated streaming passes
     const BatchShape bs = batch_shape(ctx->n_cu, N, n_probes);
@@ -876,6 +1091,10 @@ size_t percache_lookup_workspace_bytes(const percache_ctx *ctx, int32_t n_probes
     const size_t p_tiles = ((size_t)n_probes + 127) / 128;
     const size_t batched = (4 * (size_t)ctx->n_cu + p_tiles) * 128;
     if (batched > lists) lists = batched;
+    // the 256 x 256 kernel: groups * p_tiles <= max(n_cu, 8 p_tiles) workgroups of 256 lists
+    const size_t p_big = ((size_t)n_probes + kBigTile - 1) / kBigTile;
+    const size_t big = ((size_t)ctx->n_cu > 8 * p_big ? (size_t)ctx->n_cu : 8 * p_big) * kBigTile;
+    if (big > lists) lists = big;
     // the 128-probe pass: one list per workgroup and probe
     const size_t wide_grid = (size_t)ctx->cfg.bank_capacity / (32 * kWideMaxBlocksPerWg) + 1;
     const size_t wide = (wide_grid > (size_t)ctx->n_cu ? wide_grid : (size_t)ctx->n_cu) * kWideProbes;
