@@ -535,19 +535,25 @@ __global__ __launch_bounds__(512, 1) void lookup_big_kernel(const _Float16 *__re
       src[k] = (loads_bank ? bank : probes) + at * d + ((my_chunk ^ pc::gemm::swz128(row)) * 8);
     }
   };
-  auto request = [&](int st) __attribute__((always_inline)) {
+  // instructions k0 .. k1 - 1 of the request for k-step (f_tile, f_kt) into stage st
+  auto request_part = [&](int st, int k0, int k1) __attribute__((always_inline)) {
     char *base = smem + st * STAGE + (loads_bank ? 0 : HALF) + (wave & 3) * 8192;
 #pragma unroll
-    for (int k = 0; k < 8; ++k)
+    for (int k = k0; k < k1; ++k)
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src[k] + f_kt * 64),
                                        (__attribute__((address_space(3))) void *)(base + k * 1024), 16, 0, 0);
+  };
+  // on to the next k-step; past the last one the cursor stays on valid rows (requests made then land in a stage that
+  // nobody reads any more)
+  auto advance = [&]() __attribute__((always_inline)) {
     if (++f_kt == nk) {
       f_kt = 0;
-      ++f_tile;
-      if (loads_bank && f_tile < tile_end) aim();
+      if (f_tile + 1 < tile_end) {
+        ++f_tile;
+        if (loads_bank) aim();
+      }
     }
   };
-
   // operand reads: this lane's row inside a 32-row block is l32; k-quarter q of a stage is chunk 2 q + g
   int rd[4];
 #pragma unroll
@@ -568,12 +574,15 @@ __global__ __launch_bounds__(512, 1) void lookup_big_kernel(const _Float16 *__re
 #pragma unroll
       for (int a = 0; a < 2; ++a) acc[a][t] = pc::gemm::mma(oa[set][a], ob[set][t], acc[a][t]);
   };
-  // one MFMA, one LDS read, ... : the reads of the next quarter go out under the MFMAs of this one
-  auto interleave = [&]() __attribute__((always_inline)) {
+  // one MFMA, one LDS read, ... : the reads of the next quarter go out under the MFMAs of this one, and so do
+  // `loads` request instructions (a CU's 64 per k-step issued in one burst hold every wavefront in the issue queue
+  // for the thousand cycles the texture path needs for them)
+  auto interleave = [&](int loads) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < 6; ++i) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
       __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      if ((i & 1) == 0 && i / 2 < loads) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
     }
     __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
   };
@@ -584,11 +593,12 @@ __global__ __launch_bounds__(512, 1) void lookup_big_kernel(const _Float16 *__re
 
   if (n_steps > 0) {
     aim();
-    request(0);
+    request_part(0, 0, 8);
+    advance();
     pc::gemm::wait_vmcnt0();
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    if (n_steps > 1) request(1);
+    request_part(1, 0, 3);  // (the rest of it under the first two quarters below)
     read_ops(0, 0, 0);
   }
   int step = 0;
@@ -599,43 +609,69 @@ __global__ __launch_bounds__(512, 1) void lookup_big_kernel(const _Float16 *__re
       for (int t = 0; t < 4; ++t)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[a][t][r] = 0.f;
+    const int row_mine = tile * kBigTile + 2 * wa * 32 + lane;
+    const float inv_mine = row_mine < N ? inv_norm[row_mine] : __builtin_nanf("");  // (in flight under the tile's k-steps)
     for (int kt = 0; kt < nk; ++kt, ++step) {
       const int st = step & 1;
+      // the request for the next k-step was begun behind the last barrier: the rest of its instructions
+      request_part(st ^ 1, 3, 6);
       read_ops(1, st, 1);
       mma_ops(0);
-      interleave();
+      interleave(3);
+      request_part(st ^ 1, 6, 8);
       read_ops(0, st, 2);
       mma_ops(1);
-      interleave();
+      interleave(2);
+      advance();
       read_ops(1, st, 3);
       mma_ops(0);
-      interleave();
+      interleave(0);
       // every read of this stage is in registers and this wavefront's part of the next stage has landed
       __builtin_amdgcn_s_waitcnt(7 << 4);
       asm volatile("" ::: "memory");
       __builtin_amdgcn_s_barrier();
       asm volatile("" ::: "memory");
-      if (step + 2 < n_steps) request(st);
-      read_ops(0, st ^ 1, 0);  // (past the last k-step: whatever the other stage holds, never multiplied)
+      request_part(st, 0, 3);      // k-step step + 2 (past the end: see advance())
+      read_ops(0, st ^ 1, 0);      // (past the last k-step: whatever the other stage holds, never multiplied)
       mma_ops(1);
-      interleave();
+      interleave(3);
     }
     // cosines of this tile's rows (up to the probe's own norm, which the finalize kernel divides by)
     const int r0 = tile * kBigTile;
+    {
+      // Lane L of the wavefront has fetched the inverse norm of the wavefront's row L (of 64) while the tile was
+      // multiplied -- NaN past the end of the bank, which no comparison below ever prefers -- and a lane takes the
+      // ones of its own rows from there.  Its 32 rows are visited in rising order, so "greater" alone keeps the
+      // lowest row among equals, within the tile and against earlier tiles.
+      float ls[4];
+      int lc[4];
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+      for (int t = 0; t < 4; ++t) { ls[t] = -INFINITY; lc[t] = 0; }
 #pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        const int row0 = r0 + (2 * wa + a) * 32 + q4 * 8 + g * 4;
-        const f32x4 inv4 = *(const f32x4 *)(inv_norm + min(row0, (N - 1) & ~3));  // rows come in aligned fours
+      for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int row = row0 + e;
+        for (int q4 = 0; q4 < 4; ++q4) {
+          float inv[4];
 #pragma unroll
-          for (int t = 0; t < 4; ++t)
-            if (row < N) best[t].insert(acc[a][t][q4 * 4 + e] * inv4[e], row);
+          for (int e = 0; e < 4; ++e) inv[e] = __shfl(inv_mine, a * 32 + q4 * 8 + g * 4 + e, 64);
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+              const float v = acc[a][t][q4 * 4 + e] * inv[e];
+              lc[t] = v > ls[t] ? a * 16 + q4 * 4 + e : lc[t];
+              ls[t] = fmaxf(ls[t], v);
+            }
+          __builtin_amdgcn_sched_barrier(0);  // (four exchanged norms live at a time, not thirty-two)
         }
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const int row = r0 + (2 * wa + (lc[t] >> 4)) * 32 + ((lc[t] >> 2) & 3) * 8 + g * 4 + (lc[t] & 3);
+        const bool up = ls[t] > best[t].s[0];
+        best[t].s[0] = up ? ls[t] : best[t].s[0];
+        best[t].i[0] = up ? row : best[t].i[0];
       }
+    }
   }
   // the two lanes of a probe, then the four wavefronts (wa) that hold other rows of the same probes
   __builtin_amdgcn_s_waitcnt(7 << 4);
