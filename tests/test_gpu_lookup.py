@@ -145,6 +145,42 @@ def test_ties_and_zero_vectors_in_the_128_probe_pass(n_probes, k):
         _compare_topk(bank, probes, k, idx, sim)
 
 
+@pytest.mark.parametrize("n_rows,d,n_probes", [(75, 512, 200), (300, 64, 256), (1031, 192, 600), (5000, 1024, 1000),
+                                                (257, 128, 1152), (256, 256, 768), (3, 64, 250)])
+def test_ties_zero_vectors_and_ragged_ends_in_the_256_probe_tiles(n_rows, d, n_probes):
+    """The matrix-product kernel on 256 x 256 tiles (best match only, probe counts that fill its tiles to three
+    quarters or more): exact ties (lowest row wins) inside one lane's rows, across lanes, across wavefronts and
+    across tiles; a zero row and a zero probe; banks that end inside a tile, inside a 32-row block, or hold fewer
+    rows than one block; a single k-step (64 elements) and many."""
+    g = np.random.default_rng(n_rows + d)
+    bank = wl.round_f16(g.standard_normal((n_rows, d)).astype(np.float32))
+    probes = wl.round_f16(g.standard_normal((n_probes, d)).astype(np.float32))
+    probes[1] = 0.0
+    if n_rows >= 75:
+        bank[7] = 0.0
+        bank[40] = bank[12] * 2.0     # same cosine as row 12: another 32-row block, another wavefront
+        bank[13] = bank[12] * 0.5     # the next row: same lane or its neighbour
+        bank[70] = bank[12] * 0.25
+        probes[0] = bank[12]
+        probes[n_probes - 1] = bank[70]
+    if n_rows >= 300:
+        bank[n_rows - 1] = bank[12] * 4.0   # the bank's last row, in a later tile: the earlier tile's row keeps the match
+        bank[290] = bank[280]               # a tie that the later tile opens and wins by row order
+        probes[5] = bank[290]
+    pc = _ctx(n_rows + 3, d)
+    pc.percache_bank_put(0, f16(bank))
+    idx, sim, hit = pc.percache_lookup(f16(probes), 0.5)
+    torch.cuda.synchronize()
+    o_idx, o_sim, o_hit, o_sim2 = oracle.lookup(bank, probes, 0.5)
+    if n_rows >= 75:
+        assert idx[0].item() == 12 and idx[n_probes - 1].item() == 12
+    if n_rows >= 300:
+        assert idx[5].item() == 280
+    assert idx[1].item() == 0
+    _compare(bank, probes, 0.5, idx, sim, hit)
+    # scaled copies have equal cosines only up to rounding of the norms: the planted rows are checked above, the rest by _compare
+
+
 def test_overwrite_rows_and_error_paths():
     d = 128
     g = np.random.default_rng(6)
