@@ -153,73 +153,117 @@ struct WideShape {
   static_assert(W_BYTES % (1024 * NWV) == 0 && X_BYTES % (1024 * NWV) == 0, "whole instructions per wavefront");
 };
 
+// One software pipeline over the k-steps: the operands of the next 16 k-elements are read from LDS into a second
+// register set while the MFMAs of the current ones run, and the one barrier of a k-step sits before its last quarter.
+// There every wavefront has the rest of the current stage in registers, so the stage is requested again (two k-steps
+// ahead; the request's instructions go out between the MFMAs of the following quarters, a burst of them would hold
+// every wavefront in the issue queue), and the next stage has landed: its first operands are read under the last
+// quarter's MFMAs.  Wavefronts 0-3 request the weight rows (8 instructions each), 4-7 the token rows (2 NTB each).
 template <int NTB, class T, class WRow>
 __device__ __forceinline__ void mainloop_wide(char *lds, WRow w_row, const T *__restrict__ X, int ldx, int m0, int M, int K,
                                               int fb_lo, int fb_hi, int wt, f32x16 (&acc)[2][NTB]) {
   using S = WideShape<NTB>;
   using V8 = typename Vec8<T>::type;
-  constexpr int NWV = S::NWV;
+  static_assert(BK == 64, "four quarters of 16 k-elements");
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, g = lane >> 5;
-  const T *w_src[S::W_INSTR];
-  const T *x_src[S::X_INSTR];
+  const bool loads_w = wave < 4;
+  constexpr int W_PER = S::W_BYTES / 1024 / 4, X_PER = S::X_BYTES / 1024 / 4;  // instructions per wavefront and stage
+  static_assert(W_PER == 8 && X_PER <= 8 && X_PER >= 4, "request split below");
+  const T *src[8];
 #pragma unroll
-  for (int k = 0; k < S::W_INSTR; ++k) {
-    const int row = (wave + k * NWV) * 8 + (lane >> 3);
-    w_src[k] = w_row(row) + (((lane & 7) ^ swz128(row)) * 8);
+  for (int k = 0; k < 8; ++k) {
+    const int row = ((wave & 3) * (loads_w ? W_PER : X_PER) + (k < (loads_w ? W_PER : X_PER) ? k : 0)) * 8 + (lane >> 3);
+    src[k] = (loads_w ? w_row(row) : X + (size_t)min(m0 + row, M - 1) * ldx) + (((lane & 7) ^ swz128(row)) * 8);
   }
+  char *const dst = lds + (loads_w ? 0 : S::W_BYTES) + (wave & 3) * (loads_w ? W_PER : X_PER) * 1024;
+  const int nk = K / BK;
+  int f_kt = 0;  // the k-step the next request brings (past the last one: the last one again, into a stage nobody reads)
+  // instructions k0 .. k1 - 1 of that request (a token wavefront has fewer: the surplus is skipped)
+  auto request_part = [&](int st, int k0, int k1) __attribute__((always_inline)) {
+    if (loads_w) {
 #pragma unroll
-  for (int k = 0; k < S::X_INSTR; ++k) {
-    const int row = (wave + k * NWV) * 8 + (lane >> 3);
-    x_src[k] = X + (size_t)min(m0 + row, M - 1) * ldx + (((lane & 7) ^ swz128(row)) * 8);
-  }
-  auto fetch = [&](int kt, int st) __attribute__((always_inline)) {
-    char *base = lds + st * S::STAGE;
+      for (int k = k0; k < k1; ++k)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src[k] + f_kt * BK),
+                                         (__attribute__((address_space(3))) void *)(dst + st * S::STAGE + k * 1024), 16, 0, 0);
+    } else {
 #pragma unroll
-    for (int k = 0; k < S::W_INSTR; ++k)
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(w_src[k] + kt * BK),
-                                       (__attribute__((address_space(3))) void *)(base + (wave + k * NWV) * 1024), 16, 0, 0);
-#pragma unroll
-    for (int k = 0; k < S::X_INSTR; ++k)
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(x_src[k] + kt * BK),
-                                       (__attribute__((address_space(3))) void *)(base + S::W_BYTES + (wave + k * NWV) * 1024), 16, 0, 0);
+      for (int k = k0; k < (k1 < X_PER ? k1 : X_PER); ++k)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src[k] + f_kt * BK),
+                                         (__attribute__((address_space(3))) void *)(dst + st * S::STAGE + k * 1024), 16, 0, 0);
+    }
   };
-  int rd[BK / 16];
+  auto advance = [&]() __attribute__((always_inline)) { f_kt = f_kt + 1 < nk ? f_kt + 1 : f_kt; };
+
+  int rd[4];
 #pragma unroll
-  for (int ks = 0; ks < BK / 16; ++ks) rd[ks] = ((2 * ks + g) ^ swz128(l32)) * 16;
+  for (int q = 0; q < 4; ++q) rd[q] = ((2 * q + g) ^ swz128(l32)) * 16;
+  const int lo_off = (fb_lo * 32 + l32) * ROW, hi_off = (fb_hi * 32 + l32) * ROW, x_off = S::W_BYTES + ((wt * NTB) * 32 + l32) * ROW;
+  V8 oa[2][2], ob[2][NTB];  // two register sets
+  auto read_ops = [&](int set, int st, int q) __attribute__((always_inline)) {
+    const char *base = lds + st * S::STAGE + rd[q];
+    oa[set][0] = *(const V8 *)(base + lo_off);
+    oa[set][1] = *(const V8 *)(base + hi_off);
+#pragma unroll
+    for (int t = 0; t < NTB; ++t) ob[set][t] = *(const V8 *)(base + x_off + t * 32 * ROW);
+  };
+  auto mma_ops = [&](int set) __attribute__((always_inline)) {
+#pragma unroll
+    for (int t = 0; t < NTB; ++t) {
+      acc[0][t] = mma(oa[set][0], ob[set][t], acc[0][t]);
+      acc[1][t] = mma(oa[set][1], ob[set][t], acc[1][t]);
+    }
+  };
+  // one MFMA, one LDS read, ... and `loads` request instructions among them
+  auto interleave = [&](int loads) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < NTB + 2; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      if ((i & 1) == 0 && i / 2 < loads) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, 2 * NTB - (NTB + 2), 0);
+  };
 #pragma unroll
   for (int a = 0; a < 2; ++a)
 #pragma unroll
     for (int t = 0; t < NTB; ++t)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[a][t][r] = 0.f;
-  const int nk = K / BK;
-  fetch(0, 0);
+
+  request_part(0, 0, 8);
+  advance();
   wait_vmcnt0();
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
+  request_part(1, 0, 3);  // (the rest of it under the first two quarters below)
+  read_ops(0, 0, 0);
   for (int kt = 0; kt < nk; ++kt) {
     const int st = kt & 1;
-    if (kt + 1 < nk) fetch(kt + 1, st ^ 1);
-    const char *wl = lds + st * S::STAGE + (fb_lo * 32 + l32) * ROW;
-    const char *wh = lds + st * S::STAGE + (fb_hi * 32 + l32) * ROW;
-    const char *xb = lds + st * S::STAGE + S::W_BYTES + ((wt * NTB) * 32 + l32) * ROW;
-#pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      V8 a_lo = *(const V8 *)(wl + rd[ks]);
-      V8 a_hi = *(const V8 *)(wh + rd[ks]);
-#pragma unroll
-      for (int t = 0; t < NTB; ++t) {
-        V8 b = *(const V8 *)(xb + t * 32 * ROW + rd[ks]);
-        acc[0][t] = mma(a_lo, b, acc[0][t]);
-        acc[1][t] = mma(a_hi, b, acc[1][t]);
-      }
-    }
-    wait_vmcnt0();
+    request_part(st ^ 1, 3, 6);
+    read_ops(1, st, 1);
+    mma_ops(0);
+    interleave(3);
+    request_part(st ^ 1, 6, 8);
+    read_ops(0, st, 2);
+    mma_ops(1);
+    interleave(2);
+    advance();
+    read_ops(1, st, 3);
+    mma_ops(0);
+    interleave(0);
+    // every read of this stage is in registers and this wavefront's part of the next stage has landed
+    __builtin_amdgcn_s_waitcnt(7 << 4);
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
+    request_part(st, 0, 3);    // k-step kt + 2
+    read_ops(0, st ^ 1, 0);    // (past the last k-step: whatever the other stage holds, never multiplied)
+    mma_ops(1);
+    interleave(3);
   }
+  wait_vmcnt0();  // (the surplus request of the last k-steps)
+  __builtin_amdgcn_s_barrier();
 }
 
 // The same contraction for workgroups that own only a few k-steps (a slice of a split contraction): NS LDS stages,
