@@ -33,8 +33,21 @@ __global__ __launch_bounds__(WIDE ? 512 : 256, WIDE ? 1 : 2) void qkv_rope_kerne
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wf = wave & 1, wt = (wave >> 1) & 1, half = wave >> 2;  // (half: which of the tile's two heads; 0 unless WIDE)
   const int l32 = lane & 31, g = lane >> 5;
-  const int f0 = blockIdx.x * (WIDE ? 2 * BF : BF);  // first feature of the tile
-  const int m0 = blockIdx.y * BT;                     // first token row of the tile
+  int bx = blockIdx.x, by = blockIdx.y;
+  if constexpr (WIDE) {
+    // One tile per CU: give each XCD (workgroup ids go round-robin over the 8) a compact patch of the tile grid, so
+    // that the weight and token rows its tiles share are fetched into its L2 once.  Ids of one XCD become consecutive
+    // positions, and positions walk strips of `sw` feature tiles, token tile by token tile.
+    const int nx = gridDim.x, ny = gridDim.y, total = nx * ny;
+    const int id = blockIdx.y * nx + blockIdx.x, xcd = id & 7;
+    const int pos = xcd * (total >> 3) + min(xcd, total & 7) + (id >> 3);
+    const int sw = nx % 5 == 0 ? 5 : nx % 4 == 0 ? 4 : nx % 3 == 0 ? 3 : nx % 2 == 0 ? 2 : 1;
+    const int strip = pos / (sw * ny), within = pos - strip * (sw * ny);
+    by = within / sw;
+    bx = strip * sw + (within - by * sw);
+  }
+  const int f0 = bx * (WIDE ? 2 * BF : BF);  // first feature of the tile
+  const int m0 = by * BT;                     // first token row of the tile
 
   // feature blocks (of 32) this wavefront owns: the low half of a rotation pair and its partner
   const int fb_lo = (D == 128) ? 4 * half + wf : 2 * wf;
@@ -47,7 +60,7 @@ __global__ __launch_bounds__(WIDE ? 512 : 256, WIDE ? 1 : 2) void qkv_rope_kerne
     pc::gemm::mainloop<NTB>(lds, [&](int row) __attribute__((always_inline)) { return W + (size_t)(f0 + row) * H; }, X, H, m0, M, H, fb_lo, fb_hi, acc);
 
   // ---- epilogue: RoPE at position L_pre[b] + i on fp32, one rounding to bf16, head-major stores
-  const int head = WIDE ? 2 * blockIdx.x + half : (D == 128) ? blockIdx.x : 2 * blockIdx.x + wf;
+  const int head = WIDE ? 2 * bx + half : (D == 128) ? bx : 2 * bx + wf;
   const int m_base = (D == 128) ? wf * 32 : 0;  // index of the low element inside the head
   __bf16 *dst;
   int hh, n_heads;
