@@ -488,24 +488,36 @@ __global__ __launch_bounds__(256, 2) void lookup_batched_kernel(const _Float16 *
 }
 
 // ---------------------------------------------------------------------------------------------------
-// The same product on larger tiles, for the best match alone (k = 1) and enough probes to fill them: 256 bank rows x
-// 256 probes per workgroup of 8 wavefronts, one workgroup per CU.  A CU takes in at most 64 bytes per clock from L2,
-// which a 128 x 128 tile needs for as long as its MFMAs run; at 256 x 256 the operand bytes per flop halve.
-// Wavefront (wa, wb) owns bank-row blocks 2 wa, 2 wa + 1 and probe blocks 4 wb .. 4 wb + 3 (eight accumulators).
-// Two LDS stages of 64 k-elements (64 KB each, 128-byte rows, chunk ^= (row >> 1) & 7), and one software pipeline
-// over all the k-steps of all the workgroup's tiles: the operands of the next 16 k-elements are read from LDS while
-// the MFMAs of the current ones run, and the one barrier of a k-step sits before its last quarter -- there every
-// wavefront has read the rest of the current stage into registers (so the stage can be requested again: two k-steps
-// ahead) and the next stage has landed (its first operands are read under that last quarter's MFMAs).
+// The same product on larger tiles, for the best match alone (k = 1): 256 bank rows x PT probes (256, or 128 where
+// that pads less) per workgroup of 8 wavefronts, one workgroup per CU.  A CU takes in at most 64 bytes per clock from
+// L2, which a 128 x 128 tile needs for as long as its MFMAs run; at 256 x 256 the operand bytes per flop halve.
+// Wavefront (wa, wb) owns bank-row blocks 2 wa, 2 wa + 1 and probe blocks NB wb .. NB wb + NB - 1 (NB = PT / 64).
+// LDS stages of 64 k-elements (128-byte rows, chunk ^= (row >> 1) & 7) in a ring of NSTG: as many as fit (two of
+// 64 KB at PT = 256, three of 48 KB at PT = 128); a request has NSTG - 1 k-steps to land in.  (128-row tiles with a
+// ring of five for up to 128 probes were tried: 0.104 ms against 0.097, a k-step of so little arithmetic is all
+// barrier.)  One software pipeline runs over all the k-steps of all the
+// workgroup's tiles: the operands of the next 16 k-elements are read from LDS while the MFMAs of the current ones
+// run, and the one barrier of a k-step sits before its last quarter -- there every wavefront has read the rest of the
+// current stage into registers (so the stage can be requested again, NSTG k-steps ahead) and the next stage has
+// landed (its first operands are read under that last quarter's MFMAs).
 // ---------------------------------------------------------------------------------------------------
-constexpr int kBigTile = 256;
-constexpr int kBigLds = 2 * 2 * kBigTile * 128;  // two stages of (256 + 256) rows x 128 bytes
+constexpr int kBigRows = 256;
+template <int PT>
+struct BigTile {
+  static constexpr int A_BYTES = kBigRows * 128, B_BYTES = PT * 128, STAGE = A_BYTES + B_BYTES;
+  static constexpr int NSTG = 160 * 1024 / STAGE;
+  static constexpr int LDS = NSTG * STAGE;
+  static constexpr int A_PER = A_BYTES / 1024 / 4, B_PER = B_BYTES / 1024 / 4;  // request instructions per wavefront and stage
+  static_assert((PT == 256 || PT == 128) && NSTG >= 2 && NSTG <= 5, "tile");
+};
 
+template <int PT>
 __global__ __launch_bounds__(512, 1) void lookup_big_kernel(const _Float16 *__restrict__ bank, const float *__restrict__ inv_norm,
                                                             int N, int d, const _Float16 *__restrict__ probes, int n_probes,
                                                             int p_pad, int n_groups, int p_tiles, Best *__restrict__ partial) {
   extern __shared__ __align__(16) char smem[];
-  constexpr int ROW = 128, HALF = kBigTile * ROW, STAGE = 2 * HALF;
+  using BT = BigTile<PT>;
+  constexpr int ROW = 128, RT = kBigRows, NSTG = BT::NSTG, STAGE = BT::STAGE, NA = RT / 128, NB = PT / 64;
   // the probe tiles of one bank group run next to each other on ONE XCD (workgroup ids go round-robin over the 8):
   // the group's rows come from HBM once and are re-read from that XCD's L2
   const int xcd = blockIdx.x & 7, jj = blockIdx.x >> 3;
@@ -514,36 +526,44 @@ __global__ __launch_bounds__(512, 1) void lookup_big_kernel(const _Float16 *__re
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wa = wave & 3, wb = wave >> 2;
   const int l32 = lane & 31, g = lane >> 5;
-  const int n_tiles = (N + kBigTile - 1) / kBigTile;
+  const int n_tiles = (N + RT - 1) / RT;
   const int tile_begin = (int)((long)group * n_tiles / n_groups), tile_end = (int)((long)(group + 1) * n_tiles / n_groups);
-  const int m0 = p_tile * kBigTile;
+  const int m0 = p_tile * PT;
   const int nk = d / 64;
-  const int n_steps = (tile_end - tile_begin) * nk;
 
-  // requests: instruction i of a stage fills its bytes [1024 i, 1024 i + 1024), i.e. rows 8 i .. 8 i + 7 (i < 32: bank
-  // rows, else probes); wavefronts 0-3 bring the bank rows, 4-7 the probes, eight instructions each
+  // requests: instruction i of a half-stage fills its bytes [1024 i, 1024 i + 1024), i.e. rows 8 i .. 8 i + 7;
+  // wavefronts 0-3 bring the bank rows (A_PER instructions each), 4-7 the probes (B_PER each)
   const bool loads_bank = wave < 4;
-  const int my_row = (wave & 3) * 64 + (lane >> 3);  // + 8 k
+  const int per = loads_bank ? BT::A_PER : BT::B_PER;
+  const int my_row = (wave & 3) * per * 8 + (lane >> 3);  // + 8 k
   const int my_chunk = lane & 7;
   const _Float16 *src[8];
   int f_tile = tile_begin, f_kt = 0;  // what the next request brings
   auto aim = [&]() __attribute__((always_inline)) {
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
-      const int row = my_row + 8 * k;
-      const size_t at = loads_bank ? (size_t)min(f_tile * kBigTile + row, N - 1) : (size_t)min(m0 + row, n_probes - 1);
+      const int row = my_row + 8 * (k < per ? k : 0);
+      const size_t at = loads_bank ? (size_t)min(f_tile * RT + row, N - 1) : (size_t)min(m0 + row, n_probes - 1);
       src[k] = (loads_bank ? bank : probes) + at * d + ((my_chunk ^ pc::gemm::swz128(row)) * 8);
     }
   };
-  // instructions k0 .. k1 - 1 of the request for k-step (f_tile, f_kt) into stage st
-  auto request_part = [&](int st, int k0, int k1) __attribute__((always_inline)) {
-    char *base = smem + st * STAGE + (loads_bank ? 0 : HALF) + (wave & 3) * 8192;
+  char *const dst = smem + (loads_bank ? 0 : BT::A_BYTES) + (wave & 3) * per * 1024;
+  // instructions k0 .. k1 - 1 of the request for k-step (f_tile, f_kt) into ring slot `slot` (a wavefront has A_PER
+  // or B_PER of them: the surplus is skipped)
+  auto request_part = [&](int slot, int k0, int k1) __attribute__((always_inline)) {
+    if (loads_bank) {
 #pragma unroll
-    for (int k = k0; k < k1; ++k)
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src[k] + f_kt * 64),
-                                       (__attribute__((address_space(3))) void *)(base + k * 1024), 16, 0, 0);
+      for (int k = k0; k < (k1 < BT::A_PER ? k1 : BT::A_PER); ++k)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src[k] + f_kt * 64),
+                                         (__attribute__((address_space(3))) void *)(dst + slot * STAGE + k * 1024), 16, 0, 0);
+    } else {
+#pragma unroll
+      for (int k = k0; k < (k1 < BT::B_PER ? k1 : BT::B_PER); ++k)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src[k] + f_kt * 64),
+                                         (__attribute__((address_space(3))) void *)(dst + slot * STAGE + k * 1024), 16, 0, 0);
+    }
   };
-  // on to the next k-step; past the last one the cursor stays on valid rows (requests made then land in a stage that
+  // on to the next k-step; past the last one the cursor stays on valid rows (requests made then land in a slot that
   // nobody reads any more)
   auto advance = [&]() __attribute__((always_inline)) {
     if (++f_kt == nk) {
@@ -558,97 +578,108 @@ __global__ __launch_bounds__(512, 1) void lookup_big_kernel(const _Float16 *__re
   int rd[4];
 #pragma unroll
   for (int q = 0; q < 4; ++q) rd[q] = ((2 * q + g) ^ pc::gemm::swz128(l32)) * 16;
-  const int a_off = (2 * wa * 32 + l32) * ROW, b_off = HALF + (4 * wb * 32 + l32) * ROW;
-  f16x8 oa[2][2], ob[2][4];  // two register sets
-  auto read_ops = [&](int set, int st, int q) __attribute__((always_inline)) {
-    const char *base = smem + st * STAGE + rd[q];
+  const int a_off = (NA * wa * 32 + l32) * ROW, b_off = BT::A_BYTES + (NB * wb * 32 + l32) * ROW;
+  f16x8 oa[2][NA], ob[2][NB];  // two register sets
+  auto read_ops = [&](int set, int slot, int q) __attribute__((always_inline)) {
+    const char *base = smem + slot * STAGE + rd[q];
 #pragma unroll
-    for (int a = 0; a < 2; ++a) oa[set][a] = *(const f16x8 *)(base + a_off + a * 32 * ROW);
+    for (int a = 0; a < NA; ++a) oa[set][a] = *(const f16x8 *)(base + a_off + a * 32 * ROW);
 #pragma unroll
-    for (int t = 0; t < 4; ++t) ob[set][t] = *(const f16x8 *)(base + b_off + t * 32 * ROW);
+    for (int t = 0; t < NB; ++t) ob[set][t] = *(const f16x8 *)(base + b_off + t * 32 * ROW);
   };
-  pc::f32x16 acc[2][4];
+  pc::f32x16 acc[NA][NB];
   auto mma_ops = [&](int set) __attribute__((always_inline)) {
 #pragma unroll
-    for (int t = 0; t < 4; ++t)
+    for (int t = 0; t < NB; ++t)
 #pragma unroll
-      for (int a = 0; a < 2; ++a) acc[a][t] = pc::gemm::mma(oa[set][a], ob[set][t], acc[a][t]);
+      for (int a = 0; a < NA; ++a) acc[a][t] = pc::gemm::mma(oa[set][a], ob[set][t], acc[a][t]);
   };
   // one MFMA, one LDS read, ... : the reads of the next quarter go out under the MFMAs of this one, and so do
   // `loads` request instructions (a CU's 64 per k-step issued in one burst hold every wavefront in the issue queue
   // for the thousand cycles the texture path needs for them)
   auto interleave = [&](int loads) __attribute__((always_inline)) {
+    constexpr int READS = NA + NB, MMAS = NA * NB;
 #pragma unroll
-    for (int i = 0; i < 6; ++i) {
+    for (int i = 0; i < (READS < MMAS ? READS : MMAS); ++i) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
       __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
       if ((i & 1) == 0 && i / 2 < loads) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
     }
-    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+    if (MMAS > READS) __builtin_amdgcn_sched_group_barrier(0x008, MMAS - READS, 0);
   };
 
-  TopK<1> best[4];  // this lane's rows for probes m0 + (4 wb + t) * 32 + l32
+  TopK<1> best[NB];  // this lane's rows for probes m0 + (NB wb + t) * 32 + l32
 #pragma unroll
-  for (int t = 0; t < 4; ++t) best[t].clear();
+  for (int t = 0; t < NB; ++t) best[t].clear();
 
-  if (n_steps > 0) {
+  if (tile_begin < tile_end) {  // the first k-step, then whole requests for the next NSTG - 2 and the first part of one more
     aim();
     request_part(0, 0, 8);
     advance();
     pc::gemm::wait_vmcnt0();
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    request_part(1, 0, 3);  // (the rest of it under the first two quarters below)
+#pragma unroll
+    for (int s2 = 1; s2 < NSTG - 1; ++s2) {
+      request_part(s2, 0, 8);
+      advance();
+    }
+    request_part(NSTG - 1, 0, 3);  // (the rest of it under the first two quarters below)
     read_ops(0, 0, 0);
   }
-  int step = 0;
+  int slot = 0;  // ring slot of this k-step
   for (int tile = tile_begin; tile < tile_end; ++tile) {
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < NA; ++a)
 #pragma unroll
-      for (int t = 0; t < 4; ++t)
+      for (int t = 0; t < NB; ++t)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[a][t][r] = 0.f;
-    const int row_mine = tile * kBigTile + 2 * wa * 32 + lane;
-    const float inv_mine = row_mine < N ? inv_norm[row_mine] : __builtin_nanf("");  // (in flight under the tile's k-steps)
-    for (int kt = 0; kt < nk; ++kt, ++step) {
-      const int st = step & 1;
-      // the request for the next k-step was begun behind the last barrier: the rest of its instructions
-      request_part(st ^ 1, 3, 6);
-      read_ops(1, st, 1);
+    const int row_mine = tile * RT + NA * wa * 32 + lane;
+    const float inv_mine = row_mine < N && lane < NA * 32 ? inv_norm[row_mine] : __builtin_nanf("");  // (in flight under the tile's k-steps)
+    for (int kt = 0; kt < nk; ++kt) {
+      const int slot_prev = slot == 0 ? NSTG - 1 : slot - 1, slot_next = slot == NSTG - 1 ? 0 : slot + 1;
+      // a request was begun behind the last barrier, into the slot that k-step gave up: the rest of its instructions
+      request_part(slot_prev, 3, 6);
+      read_ops(1, slot, 1);
       mma_ops(0);
       interleave(3);
-      request_part(st ^ 1, 6, 8);
-      read_ops(0, st, 2);
+      request_part(slot_prev, 6, 8);
+      read_ops(0, slot, 2);
       mma_ops(1);
       interleave(2);
       advance();
-      read_ops(1, st, 3);
+      read_ops(1, slot, 3);
       mma_ops(0);
       interleave(0);
-      // every read of this stage is in registers and this wavefront's part of the next stage has landed
-      __builtin_amdgcn_s_waitcnt(7 << 4);
+      // every read of this stage is in registers and this wavefront's part of the next stage has landed: all of its
+      // requests but the NSTG - 2 latest ones, which are for later k-steps
+      constexpr int LEAVE_A = (NSTG - 2) * BT::A_PER, LEAVE_B = (NSTG - 2) * BT::B_PER;  // (vmcnt: bits 3:0 and 15:14)
+      static_assert(LEAVE_A < 64 && LEAVE_B < 64, "vmcnt");
+      if (loads_bank) __builtin_amdgcn_s_waitcnt((LEAVE_A & 0xf) | (7 << 4) | ((LEAVE_A >> 4) << 14));
+      else __builtin_amdgcn_s_waitcnt((LEAVE_B & 0xf) | (7 << 4) | ((LEAVE_B >> 4) << 14));
       asm volatile("" ::: "memory");
       __builtin_amdgcn_s_barrier();
       asm volatile("" ::: "memory");
-      request_part(st, 0, 3);      // k-step step + 2 (past the end: see advance())
-      read_ops(0, st ^ 1, 0);      // (past the last k-step: whatever the other stage holds, never multiplied)
+      request_part(slot, 0, 3);       // the k-step NSTG ahead (past the end: see advance())
+      read_ops(0, slot_next, 0);      // (past the last k-step: whatever that slot holds, never multiplied)
       mma_ops(1);
       interleave(3);
+      slot = slot_next;
     }
     // cosines of this tile's rows (up to the probe's own norm, which the finalize kernel divides by)
-    const int r0 = tile * kBigTile;
+    const int r0 = tile * RT;
     {
-      // Lane L of the wavefront has fetched the inverse norm of the wavefront's row L (of 64) while the tile was
+      // Lane L of the wavefront has fetched the inverse norm of the wavefront's row L (of NA * 32) while the tile was
       // multiplied -- NaN past the end of the bank, which no comparison below ever prefers -- and a lane takes the
       // ones of its own rows from there.  Its 32 rows are visited in rising order, so "greater" alone keeps the
       // lowest row among equals, within the tile and against earlier tiles.
-      float ls[4];
-      int lc[4];
+      float ls[NB];
+      int lc[NB];
 #pragma unroll
-      for (int t = 0; t < 4; ++t) { ls[t] = -INFINITY; lc[t] = 0; }
+      for (int t = 0; t < NB; ++t) { ls[t] = -INFINITY; lc[t] = 0; }
 #pragma unroll
-      for (int a = 0; a < 2; ++a)
+      for (int a = 0; a < NA; ++a)
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
           float inv[4];
@@ -657,7 +688,7 @@ __global__ __launch_bounds__(512, 1) void lookup_big_kernel(const _Float16 *__re
 #pragma unroll
           for (int e = 0; e < 4; ++e)
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
+            for (int t = 0; t < NB; ++t) {
               const float v = acc[a][t][q4 * 4 + e] * inv[e];
               lc[t] = v > ls[t] ? a * 16 + q4 * 4 + e : lc[t];
               ls[t] = fmaxf(ls[t], v);
@@ -665,8 +696,8 @@ __global__ __launch_bounds__(512, 1) void lookup_big_kernel(const _Float16 *__re
           __builtin_amdgcn_sched_barrier(0);  // (four exchanged norms live at a time, not thirty-two)
         }
 #pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        const int row = r0 + (2 * wa + (lc[t] >> 4)) * 32 + ((lc[t] >> 2) & 3) * 8 + g * 4 + (lc[t] & 3);
+      for (int t = 0; t < NB; ++t) {
+        const int row = r0 + (NA * wa + (lc[t] >> 4)) * 32 + ((lc[t] >> 2) & 3) * 8 + g * 4 + (lc[t] & 3);
         const bool up = ls[t] > best[t].s[0];
         best[t].s[0] = up ? ls[t] : best[t].s[0];
         best[t].i[0] = up ? row : best[t].i[0];
@@ -676,23 +707,23 @@ __global__ __launch_bounds__(512, 1) void lookup_big_kernel(const _Float16 *__re
   // the two lanes of a probe, then the four wavefronts (wa) that hold other rows of the same probes
   __builtin_amdgcn_s_waitcnt(7 << 4);
   __syncthreads();
-  Best *red = (Best *)smem;  // [wb][wa][4 * 32]
+  Best *red = (Best *)smem;  // [wb][wa][NB * 32]
 #pragma unroll
-  for (int t = 0; t < 4; ++t) {
+  for (int t = 0; t < NB; ++t) {
     float s = best[t].s[0];
     int i = best[t].i[0];
     const float s2 = __shfl_xor(s, 32, 64);
     const int i2 = __shfl_xor(i, 32, 64);
     if (better(s2, i2, s, i)) { s = s2; i = i2; }
-    if (g == 0) red[(wb * 4 + wa) * 128 + t * 32 + l32] = Best{s, i};
+    if (g == 0) red[(wb * 4 + wa) * (NB * 32) + t * 32 + l32] = Best{s, i};
   }
   __syncthreads();
-  if (tid < kBigTile) {  // one thread per probe of the tile: probe wb2 * 128 + within
-    const int wb2 = tid >> 7, within = tid & 127;
-    Best b = red[(wb2 * 4) * 128 + within];
+  if (tid < PT) {  // one thread per probe of the tile: probe wb2 * NB * 32 + within
+    const int wb2 = tid / (NB * 32), within = tid % (NB * 32);
+    Best b = red[(wb2 * 4) * (NB * 32) + within];
 #pragma unroll
     for (int w = 1; w < 4; ++w) {
-      const Best c = red[(wb2 * 4 + w) * 128 + within];
+      const Best c = red[(wb2 * 4 + w) * (NB * 32) + within];
       if (better(c.s, c.idx, b.s, b.idx)) b = c;
     }
     partial[(size_t)group * p_pad + m0 + tid] = b;
@@ -929,10 +960,10 @@ BatchShape batch_shape(int n_cu, int N, int n_probes) {
 struct BigShape {
   int p_tiles, groups;
 };
-BigShape big_shape(int n_cu, int N, int n_probes) {
+BigShape big_shape(int n_cu, int N, int n_probes, int pt) {
   BigShape b;
-  b.p_tiles = (n_probes + kBigTile - 1) / kBigTile;
-  const int n_tiles = (N + kBigTile - 1) / kBigTile;
+  b.p_tiles = (n_probes + pt - 1) / pt;
+  const int n_tiles = (N + kBigRows - 1) / kBigRows;
   b.groups = n_cu / b.p_tiles / 8 * 8;
   if (b.groups < 8) b.groups = 8;
   if (b.groups > n_tiles) b.groups = n_tiles;
@@ -941,7 +972,7 @@ BigShape big_shape(int n_cu, int N, int n_probes) {
 // whether the 256-probe tiles are filled well enough to beat the 128-probe ones (at most a third of padding)
 bool big_tiles_pay(int n_probes) {
   if (n_probes <= kWideUpTo) return false;
-  const long padded = (long)(n_probes + kBigTile - 1) / kBigTile * kBigTile;
+  const long padded = (long)(n_probes + 255) / 256 * 256;
   return padded * 3 <= (long)n_probes * 4;
 }
 
@@ -1031,20 +1062,28 @@ pc_status run_lookup(percache_ctx *ctx, const void *probes_dev, int32_t n_probes
 #undef PC_WIDE
     return PC_OK;
   }
-  if (k == 1 && big_tiles_pay(n_probes) && d % 64 == 0) {
-    // many probes, best match only: the matrix-core bound product on 256 x 256 tiles, one workgroup per CU
-    const BigShape bg = big_shape(ctx->n_cu, N, n_probes);
+  if (k == 1 && n_probes > kBatchedFrom && d % 64 == 0) {
+    // many probes, best match only: the matrix-core product on 256-row tiles, one workgroup per CU; 256-probe tiles
+    // where the probes fill them to three quarters, else 128-probe tiles
+    const int pt = big_tiles_pay(n_probes) ? 256 : 128;
+    const BigShape bg = big_shape(ctx->n_cu, N, n_probes, pt);
     static bool big_lds_set = false;  // dynamic LDS above 64 KB must be opted into once
     if (!big_lds_set) {
-      PC_HIP(ctx, hipFuncSetAttribute((const void *)lookup_big_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kBigLds));
+      PC_HIP(ctx, hipFuncSetAttribute((const void *)lookup_big_kernel<256>, hipFuncAttributeMaxDynamicSharedMemorySize, BigTile<256>::LDS));
+      PC_HIP(ctx, hipFuncSetAttribute((const void *)lookup_big_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, BigTile<128>::LDS));
       big_lds_set = true;
     }
+    const dim3 grid((unsigned)((bg.groups + 7) / 8 * 8 * bg.p_tiles));
     pc::prof_begin(ctx, PC_KERNEL_LOOKUP, st);
-    hipLaunchKernelGGL(lookup_big_kernel, dim3((unsigned)((bg.groups + 7) / 8 * 8 * bg.p_tiles)), dim3(512), kBigLds, st, ctx->bank, ctx->bank_inv, N, d,
-                       probes, n_probes, bg.p_tiles * kBigTile, bg.groups, bg.p_tiles, partial);
+    if (pt == 256)
+      hipLaunchKernelGGL(lookup_big_kernel<256>, grid, dim3(512), BigTile<256>::LDS, st, ctx->bank, ctx->bank_inv, N, d, probes, n_probes,
+                         bg.p_tiles * pt, bg.groups, bg.p_tiles, partial);
+    else
+      hipLaunchKernelGGL(lookup_big_kernel<128>, grid, dim3(512), BigTile<128>::LDS, st, ctx->bank, ctx->bank_inv, N, d, probes, n_probes,
+                         bg.p_tiles * pt, bg.groups, bg.p_tiles, partial);
     pc::prof_end(ctx, PC_KERNEL_LOOKUP, st);
     PC_HIP(ctx, hipGetLastError());
-    hipLaunchKernelGGL(lookup_finalize_kernel<1>, dim3(n_probes), dim3(kFinalizeThreads), 0, st, partial, bg.groups, bg.p_tiles * kBigTile, probes, d, tau, 1,
+    hipLaunchKernelGGL(lookup_finalize_kernel<1>, dim3(n_probes), dim3(kFinalizeThreads), 0, st, partial, bg.groups, bg.p_tiles * pt, probes, d, tau, 1,
                        idx_out_dev, sim_out_dev, hit_out_dev);
     PC_HIP(ctx, hipGetLastError());
     return PC_OK;
@@ -1128,8 +1167,8 @@ size_t percache_lookup_workspace_bytes(const percache_ctx *ctx, int32_t n_probes
     const size_t batched = (4 * (size_t)ctx->n_cu + p_tiles) * 128;
     if (batched > lists) lists = batched;
     // the 256 x 256 kernel: groups * p_tiles <= max(n_cu, 8 p_tiles) workgroups of 256 lists
-    const size_t p_big = ((size_t)n_probes + kBigTile - 1) / kBigTile;
-    const size_t big = ((size_t)ctx->n_cu > 8 * p_big ? (size_t)ctx->n_cu : 8 * p_big) * kBigTile;
+    const size_t p_big = ((size_t)n_probes + 127) / 128;
+    const size_t big = ((size_t)ctx->n_cu > 8 * p_big ? (size_t)ctx->n_cu : 8 * p_big) * 256;
     if (big > lists) lists = big;
     // the 128-probe pass: one list per workgroup and probe
     const size_t wide_grid = (size_t)ctx->cfg.bank_capacity / (32 * kWideMaxBlocksPerWg) + 1;
