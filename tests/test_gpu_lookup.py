@@ -147,11 +147,12 @@ def test_ties_and_zero_vectors_in_the_128_probe_pass(n_probes, k):
 
 @pytest.mark.parametrize("n_rows,d,n_probes", [(75, 512, 200), (300, 64, 256), (1031, 192, 600), (5000, 1024, 1000),
                                                 (257, 128, 1152), (256, 256, 768), (3, 64, 250),
-                                                (1031, 192, 150), (300, 64, 100), (5000, 1024, 170), (75, 128, 33), (600, 256, 300)])
+                                                (1031, 192, 150), (300, 64, 100), (5000, 1024, 170), (75, 128, 33), (600, 256, 300),
+                                                (700, 128, 3000), (1, 64, 300), (2100, 2048, 384)])
 def test_ties_zero_vectors_and_ragged_ends_in_the_256_row_tiles(n_rows, d, n_probes):
     """The matrix-product kernel on 256-row tiles (best match only; 256-probe tiles where the probes fill them to three
-    quarters, 128-probe tiles with the deeper ring otherwise -- the last five cases): exact ties (lowest row wins) inside one lane's rows, across lanes, across wavefronts and
-    across tiles; a zero row and a zero probe; banks that end inside a tile, inside a 32-row block, or hold fewer
+    quarters, 128-probe tiles with the deeper ring otherwise; more probe tiles than CUs / 8; a one-row bank): exact ties
+    (lowest row wins) inside one lane's rows, across lanes, across wavefronts and across tiles; a zero row and a zero probe; banks that end inside a tile, inside a 32-row block, or hold fewer
     rows than one block; a single k-step (64 elements) and many."""
     g = np.random.default_rng(n_rows + d)
     bank = wl.round_f16(g.standard_normal((n_rows, d)).astype(np.float32))
