@@ -108,6 +108,9 @@ def test_kv_store_round_trip_and_errors():
     # enough tiles that the launcher takes its 192-token tiles (more than two workgroups per CU otherwise), ragged last tile
     dict(hidden=256, n_q_heads=24, n_kv_heads=8, head_dim=128, batch=13, t_fresh=131, n_chunks=1, chunk_tokens=64, n_slots=16),
     dict(hidden=192, n_q_heads=48, n_kv_heads=16, head_dim=64, batch=7, t_fresh=250, n_chunks=1, chunk_tokens=64, n_slots=8),
+    # the two-head tiles of 8 wavefronts with 7 x 7 and 4 x 6 tile grids (other strip widths of the XCD patches), 2 and 6 k-steps
+    dict(hidden=128, n_q_heads=10, n_kv_heads=2, head_dim=128, batch=6, t_fresh=200, n_chunks=1, chunk_tokens=64, n_slots=8),
+    dict(hidden=384, n_q_heads=4, n_kv_heads=2, head_dim=128, batch=9, t_fresh=128, n_chunks=2, chunk_tokens=64, n_slots=20),
 ])
 def test_qkv_rope_matches_oracle(shape):
     w = wl.make_prefill("proj", 5, "bf16", last_used_len=shape["chunk_tokens"] - 3, **shape)
