@@ -360,7 +360,10 @@ pc_status percache_stack_decode(percache_ctx *ctx, const percache_block_weights 
  * the device-side counterpart).  percache_profile_read waits for the recorded events, returns the summed
  * duration in milliseconds and the number of launches since the last read or enable, and clears the record
  * (at most 256 launches per kernel are kept).  kernel: 0 lookup stream pass, 1 QKV projection + RoPE,
- * 2 reuse attention (main kernel, without the split merge). */
+ * 2 reuse attention (main kernel, without the split merge).
+ * on: 0 switches the events off, 1 brackets all three kinds, any other value is a mask in which bit (kernel + 1)
+ * selects a kind (4 = the projection only, 8 = attention only, ...): an event pair costs a few microseconds on the
+ * stream, so a caller that times a whole step asks only for the kernel it needs. */
 typedef enum { PC_KERNEL_LOOKUP = 0, PC_KERNEL_QKV_ROPE = 1, PC_KERNEL_ATTENTION = 2 } pc_kernel;
 pc_status percache_profile_enable(percache_ctx *ctx, int32_t on);
 pc_status percache_profile_read(percache_ctx *ctx, int32_t kernel, float *sum_ms_host, int32_t *count_host);

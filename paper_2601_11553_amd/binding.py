@@ -201,8 +201,10 @@ class Percache:
         p = (self._ws.data_ptr() + 255) // 256 * 256
         return p
 
-    def percache_profile_enable(self, on: bool = True):
-        self._check(self.lib.percache_profile_enable(self.ctx, 1 if on else 0))
+    def percache_profile_enable(self, on=True, kernels=None):
+        """``kernels``: the kinds to bracket with events (default: all three)."""
+        flag = 0 if not on else 1 if kernels is None else sum(1 << (k + 1) for k in set(kernels))
+        self._check(self.lib.percache_profile_enable(self.ctx, flag))
 
     def percache_profile_read(self, kernel: int):
         """(summed milliseconds, launches) of one kernel kind since the last read; waits for the events."""

@@ -162,11 +162,11 @@ int max_splits_for(const percache_config &c, int n_cu, int32_t batch, int32_t t_
 }
 
 void prof_begin(percache_ctx *ctx, int kind, hipStream_t stream) {
-  if (!ctx->prof_on || ctx->prof_n[kind] >= kProfMax) return;
+  if (!(ctx->prof_mask >> kind & 1) || ctx->prof_n[kind] >= kProfMax) return;
   (void)hipEventRecord(ctx->prof_beg[kind][ctx->prof_n[kind]], stream);
 }
 void prof_end(percache_ctx *ctx, int kind, hipStream_t stream) {
-  if (!ctx->prof_on || ctx->prof_n[kind] >= kProfMax) return;
+  if (!(ctx->prof_mask >> kind & 1) || ctx->prof_n[kind] >= kProfMax) return;
   (void)hipEventRecord(ctx->prof_end[kind][ctx->prof_n[kind]], stream);
   ++ctx->prof_n[kind];
 }
@@ -332,6 +332,7 @@ pc_status percache_chunk_table_drop(percache_ctx *ctx, const void *table_dev) {
 
 pc_status percache_profile_enable(percache_ctx *ctx, int32_t on) {
   if (!ctx) return PC_EINVAL;
+  if (on < 0 || on > 15) return pc::fail(ctx, PC_EINVAL, "profile switch %d: 0, 1 or a mask of bits 1..3", on);
   if (on && ctx->prof_beg[0].empty()) {
     for (int k = 0; k < 3; ++k) {
       ctx->prof_beg[k].resize(pc::kProfMax);
@@ -342,7 +343,7 @@ pc_status percache_profile_enable(percache_ctx *ctx, int32_t on) {
       }
     }
   }
-  ctx->prof_on = on != 0;
+  ctx->prof_mask = on == 1 ? 7u : ((unsigned)on >> 1) & 7u;
   for (int k = 0; k < 3; ++k) ctx->prof_n[k] = 0;
   return PC_OK;
 }

@@ -97,7 +97,7 @@ struct percache_ctx {
   // entry points that must not take a workspace
   void *static_scratch = nullptr;
   // optional kernel timing (event pairs per kernel kind)
-  bool prof_on = false;
+  unsigned prof_mask = 0;  // bit k: launches of kernel kind k are bracketed by events
   std::vector<hipEvent_t> prof_beg[3], prof_end[3];
   int prof_n[3] = {0, 0, 0};
   std::string err;

@@ -361,6 +361,34 @@ def test_large_projection_tiles_lay_out_fresh_v_themselves(head_dim, t_fresh):
     _run_and_check(w, f"v blocks D={head_dim} T={t_fresh}")
 
 
+def test_kernel_timing_switch_selects_kernel_kinds():
+    """The per-kernel event pairs: all kinds, a selection of kinds, off; a value outside the mask is refused."""
+    from paper_2601_11553_amd import binding
+    from paper_2601_11553_amd.binding import PercacheError
+    w = wl.config1()
+    pc = make_ctx(w)
+    fill_slots(pc, w, w.slot_ids.reshape(-1))
+    call = lambda: pc.percache_prefill_reuse(0, bf16(w.X), bf16(w.Wqkv), w.slot_ids, w.used_len)
+    counts = lambda: [pc.percache_profile_read(k)[1] for k in (binding.KERNEL_LOOKUP, binding.KERNEL_QKV_ROPE, binding.KERNEL_ATTENTION)]
+    pc.percache_profile_enable(True)
+    call(); call()
+    ms_attn, n_attn = pc.percache_profile_read(binding.KERNEL_ATTENTION)
+    assert n_attn == 2 and 0.0 < ms_attn < 50.0
+    assert counts() == [0, 2, 0]          # (the read above cleared the attention record)
+    pc.percache_profile_enable(True, kernels=[binding.KERNEL_ATTENTION])
+    call()
+    assert counts() == [0, 0, 1]
+    pc.percache_profile_enable(True, kernels=[binding.KERNEL_QKV_ROPE, binding.KERNEL_LOOKUP])
+    call()
+    assert counts() == [0, 1, 0]
+    pc.percache_profile_enable(False)
+    call()
+    assert counts() == [0, 0, 0]
+    with pytest.raises(PercacheError):
+        pc._check(pc.lib.percache_profile_enable(pc.ctx, 16))
+    pc.close()
+
+
 def test_full_recompute_path_is_plain_causal_prefill():
     w = wl.make_prefill("causal", 8, "bf16", 256, 4, 2, 64, 2, 200, 0, 64, 1)
     pc = make_ctx(w, max_pos=256)
