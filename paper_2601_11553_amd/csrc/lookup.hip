@@ -407,90 +407,13 @@ __global__ __launch_bounds__(kFinalizeThreads) void lookup_finalize_kernel(const
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Many probes at once (more than a streaming pass or two): the scan is a matrix product E P^T and is bound by the
-// matrix cores, not by the stream of the bank.  A workgroup takes 128 probes and walks `tiles_per_wg` consecutive
-// 128-row tiles of the bank with the shared projection main loop (fp16 operands); the bank rows are the M side, so a
-// lane holds, for ONE probe, 32 rows per tile, scales them by the rows' inverse norms and feeds a running sorted
-// list.  Lists are merged across the two lanes and the two wavefronts that share a probe; the per-workgroup lists
-// go to the same finalize kernel as the streaming pass.
-// ---------------------------------------------------------------------------------------------------
-template <int K>
-__global__ __launch_bounds__(256, 2) void lookup_batched_kernel(const _Float16 *__restrict__ bank, const float *__restrict__ inv_norm,
-                                                                int N, int d, const _Float16 *__restrict__ probes, int n_probes,
-                                                                int tiles_per_wg, int p_pad, int n_groups, int p_tiles,
-                                                                Best *__restrict__ partial) {
-  constexpr int NTB = 2;
-  // workgroup ids go round-robin over the 8 XCDs: the probe tiles of one bank group are made consecutive on ONE XCD,
-  // so the group's rows are fetched from HBM once and re-read from that XCD's L2
-  const int xcd = blockIdx.x & 7, jj = blockIdx.x >> 3;
-  const int group = (jj / p_tiles) * 8 + xcd, p_tile = jj % p_tiles;
-  if (group >= n_groups) return;
-  __shared__ __align__(16) char lds[pc::gemm::Shape<NTB>::LDS_BYTES];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wf = wave & 1, wt = wave >> 1;
-  const int l32 = lane & 31, g = lane >> 5;
-  const int n_tiles = (N + 127) / 128;
-  const int tile_begin = group * tiles_per_wg, tile_end = min(n_tiles, tile_begin + tiles_per_wg);
-  const int m0 = p_tile * 128;  // first probe of the tile
-  TopK<K> best[NTB];                // this lane's rows for probes m0 + (wt*2 + t)*32 + l32
-#pragma unroll
-  for (int t = 0; t < NTB; ++t) best[t].clear();
-  for (int tile = tile_begin; tile < tile_end; ++tile) {
-    const int r0 = tile * 128;
-    pc::f32x16 acc[2][NTB];
-    pc::gemm::mainloop<NTB>(lds, [&](int row) __attribute__((always_inline)) { return bank + (size_t)min(r0 + row, N - 1) * d; },
-                            probes, d, m0, n_probes, d, 2 * wf, 2 * wf + 1, acc);
-#pragma unroll
-    for (int a = 0; a < 2; ++a)
-#pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        const int row0 = r0 + (2 * wf + a) * 32 + q4 * 8 + g * 4;
-        const f32x4 inv4 = *(const f32x4 *)(inv_norm + min(row0, (N - 1) & ~3));  // rows come in aligned fours
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int row = row0 + e;
-#pragma unroll
-          for (int t = 0; t < NTB; ++t)
-            if (row < N) best[t].insert(acc[a][t][q4 * 4 + e] * inv4[e], row);
-        }
-      }
-  }
-  // the two lanes of a probe, then the two wavefronts (wf) that hold other rows of the same probes
-  __syncthreads();
-  Best *red = (Best *)lds;  // [wt][wf][NTB*32][K]
-#pragma unroll
-  for (int t = 0; t < NTB; ++t) {
-#pragma unroll
-    for (int j = 0; j < K; ++j) {
-      float s = best[t].s[0];
-      int i = best[t].i[0];
-      const float s2 = __shfl_xor(s, 32, 64);
-      const int i2 = __shfl_xor(i, 32, 64);
-      if (better(s2, i2, s, i)) { s = s2; i = i2; }
-      best[t].pop_if(i != INT_MAX && best[t].i[0] == i);
-      if (g == 0) red[((wt * 2 + wf) * (NTB * 32) + t * 32 + l32) * K + j] = Best{s, i};
-    }
-  }
-  __syncthreads();
-  if (tid < 128) {  // one thread per probe of the tile: probe index wt2*64 + t*32 + l = tid
-    const int wt2 = tid >> 6, within = tid & 63;
-    const Best *la = red + ((wt2 * 2 + 0) * (NTB * 32) + within) * K, *lb = red + ((wt2 * 2 + 1) * (NTB * 32) + within) * K;
-    int ha = 0, hb = 0;
-    Best *out = partial + ((size_t)group * p_pad + m0 + tid) * K;
-    for (int j = 0; j < K; ++j) {
-      const Best a = ha < K ? la[ha] : Best{-INFINITY, INT_MAX}, b = hb < K ? lb[hb] : Best{-INFINITY, INT_MAX};
-      const bool take_a = b.idx == INT_MAX || (a.idx != INT_MAX && better(a.s, a.idx, b.s, b.idx));
-      out[j] = take_a ? a : b;
-      ha += take_a;
-      hb += !take_a;
-    }
-  }
-}
-
-// ---------------------------------------------------------------------------------------------------
-// The same product on larger tiles, for the best match alone (k = 1): 256 bank rows x PT probes (256, or 128 where
-// that pads less) per workgroup of 8 wavefronts, one workgroup per CU.  A CU takes in at most 64 bytes per clock from
-// L2, which a 128 x 128 tile needs for as long as its MFMAs run; at 256 x 256 the operand bytes per flop halve.
+// Many probes at once (more than the one-pass kernels take): the scan is a matrix product E P^T and is bound by the
+// matrix cores, not by the stream of the bank.  Tiles of 256 bank rows x PT probes (256, or 128 where that pads less
+// and for top-k calls, whose sorted lists need the registers) per workgroup of 8 wavefronts, one workgroup per CU,
+// which walks a group of consecutive bank tiles; the bank rows are the M side, so a lane holds, for ONE probe, 32 rows
+// per tile, scales them by the rows' inverse norms and keeps its best (or a running sorted list of K).  A CU takes in
+// at most 64 bytes per clock from L2, which a 128 x 128 tile would need for as long as its MFMAs run; at 256 x 256
+// the operand bytes per flop halve.
 // Wavefront (wa, wb) owns bank-row blocks 2 wa, 2 wa + 1 and probe blocks NB wb .. NB wb + NB - 1 (NB = PT / 64).
 // LDS stages of 64 k-elements (128-byte rows, chunk ^= (row >> 1) & 7) in a ring of NSTG: as many as fit (two of
 // 64 KB at PT = 256, three of 48 KB at PT = 128); a request has NSTG - 1 k-steps to land in.  (128-row tiles with a
@@ -511,7 +434,7 @@ struct BigTile {
   static_assert((PT == 256 || PT == 128) && NSTG >= 2 && NSTG <= 5, "tile");
 };
 
-template <int PT>
+template <int PT, int K>
 __global__ __launch_bounds__(512, 1) void lookup_big_kernel(const _Float16 *__restrict__ bank, const float *__restrict__ inv_norm,
                                                             int N, int d, const _Float16 *__restrict__ probes, int n_probes,
                                                             int p_pad, int n_groups, int p_tiles, Best *__restrict__ partial) {
@@ -608,7 +531,8 @@ __global__ __launch_bounds__(512, 1) void lookup_big_kernel(const _Float16 *__re
     if (MMAS > READS) __builtin_amdgcn_sched_group_barrier(0x008, MMAS - READS, 0);
   };
 
-  TopK<1> best[NB];  // this lane's rows for probes m0 + (NB wb + t) * 32 + l32
+  static_assert(K == 1 || PT == 128, "the sorted lists of a top-k call need the registers that 256-probe tiles take");
+  TopK<K> best[NB];  // this lane's rows for probes m0 + (NB wb + t) * 32 + l32
 #pragma unroll
   for (int t = 0; t < NB; ++t) best[t].clear();
 
@@ -669,7 +593,7 @@ __global__ __launch_bounds__(512, 1) void lookup_big_kernel(const _Float16 *__re
     }
     // cosines of this tile's rows (up to the probe's own norm, which the finalize kernel divides by)
     const int r0 = tile * RT;
-    {
+    if constexpr (K == 1) {
       // Lane L of the wavefront has fetched the inverse norm of the wavefront's row L (of NA * 32) while the tile was
       // multiplied -- NaN past the end of the bank, which no comparison below ever prefers -- and a lane takes the
       // ones of its own rows from there.  Its 32 rows are visited in rising order, so "greater" alone keeps the
@@ -702,31 +626,63 @@ __global__ __launch_bounds__(512, 1) void lookup_big_kernel(const _Float16 *__re
         best[t].s[0] = up ? ls[t] : best[t].s[0];
         best[t].i[0] = up ? row : best[t].i[0];
       }
+    } else {
+      // the k best: the same exchanged norms, every scaled product offered to the lane's sorted list (an insertion
+      // happens only when it beats the list's last entry; NaN, past the end of the bank, never does)
+#pragma unroll
+      for (int a = 0; a < NA; ++a)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          float inv[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) inv[e] = __shfl(inv_mine, a * 32 + q4 * 8 + g * 4 + e, 64);
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+#pragma unroll
+            for (int t = 0; t < NB; ++t)
+              best[t].insert(acc[a][t][q4 * 4 + e] * inv[e], r0 + (NA * wa + a) * 32 + q4 * 8 + g * 4 + e);
+          __builtin_amdgcn_sched_barrier(0);
+        }
     }
   }
-  // the two lanes of a probe, then the four wavefronts (wa) that hold other rows of the same probes
+  // the two lanes of a probe, then the four wavefronts (wa) that hold other rows of the same probes: K rounds of
+  // "the best head wins and is popped" between the lanes, then a merge of the four sorted lists
   __builtin_amdgcn_s_waitcnt(7 << 4);
   __syncthreads();
-  Best *red = (Best *)smem;  // [wb][wa][NB * 32]
+  Best *red = (Best *)smem;  // [wb][wa][NB * 32][K]
 #pragma unroll
   for (int t = 0; t < NB; ++t) {
-    float s = best[t].s[0];
-    int i = best[t].i[0];
-    const float s2 = __shfl_xor(s, 32, 64);
-    const int i2 = __shfl_xor(i, 32, 64);
-    if (better(s2, i2, s, i)) { s = s2; i = i2; }
-    if (g == 0) red[(wb * 4 + wa) * (NB * 32) + t * 32 + l32] = Best{s, i};
+#pragma unroll
+    for (int j = 0; j < K; ++j) {
+      float s = best[t].s[0];
+      int i = best[t].i[0];
+      const float s2 = __shfl_xor(s, 32, 64);
+      const int i2 = __shfl_xor(i, 32, 64);
+      if (better(s2, i2, s, i)) { s = s2; i = i2; }
+      if constexpr (K > 1) best[t].pop_if(i != INT_MAX && best[t].i[0] == i);
+      if (g == 0) red[((wb * 4 + wa) * (NB * 32) + t * 32 + l32) * K + j] = Best{s, i};
+    }
   }
   __syncthreads();
   if (tid < PT) {  // one thread per probe of the tile: probe wb2 * NB * 32 + within
     const int wb2 = tid / (NB * 32), within = tid % (NB * 32);
-    Best b = red[(wb2 * 4) * (NB * 32) + within];
+    const Best *lst[4];
+    int head[4];
 #pragma unroll
-    for (int w = 1; w < 4; ++w) {
-      const Best c = red[(wb2 * 4 + w) * (NB * 32) + within];
-      if (better(c.s, c.idx, b.s, b.idx)) b = c;
+    for (int w = 0; w < 4; ++w) { lst[w] = red + ((wb2 * 4 + w) * (NB * 32) + within) * K; head[w] = 0; }
+    Best *out = partial + ((size_t)group * p_pad + m0 + tid) * K;
+    for (int j = 0; j < K; ++j) {
+      Best b{-INFINITY, INT_MAX};
+      int from = 0;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const Best c = head[w] < K ? lst[w][head[w]] : Best{-INFINITY, INT_MAX};
+        if (c.idx != INT_MAX && (b.idx == INT_MAX || better(c.s, c.idx, b.s, b.idx))) { b = c; from = w; }
+      }
+      out[j] = b;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) head[w] += (w == from && b.idx != INT_MAX);
     }
-    partial[(size_t)group * p_pad + m0 + tid] = b;
   }
 }
 
@@ -939,24 +895,8 @@ constexpr int kMaxTopK = 8;
 constexpr int kBatchedFrom = 32;  // more probes than one streaming pass takes: the 128-probe pass or the matrix-product kernel
 constexpr int kWideUpTo = 128;    // one such pass; beyond it the matrix-product kernel is the faster one
 
-// Launch shape of the batched kernel: 128-probe tiles x groups of consecutive 128-row bank tiles, about four
-// workgroups per CU in total.
-struct BatchShape {
-  int p_tiles, tiles_per_wg, groups;
-};
-BatchShape batch_shape(int n_cu, int N, int n_probes) {
-  BatchShape b;
-  b.p_tiles = (n_probes + 127) / 128;
-  const int n_tiles = (N + 127) / 128;
-  const long want = 4L * n_cu;
-  b.tiles_per_wg = (int)(((long)n_tiles * b.p_tiles + want - 1) / want);
-  if (b.tiles_per_wg < 1) b.tiles_per_wg = 1;
-  b.groups = (n_tiles + b.tiles_per_wg - 1) / b.tiles_per_wg;
-  return b;
-}
-
-// Launch shape of the 256 x 256 kernel: 256-probe tiles x groups of consecutive 256-row bank tiles, one workgroup per
-// CU (a multiple of 8 groups, so that a group's probe tiles share an XCD), every group at least one tile.
+// Launch shape of the 256-row kernel: probe tiles x groups of consecutive 256-row bank tiles, one workgroup per CU (a
+// multiple of 8 groups, so that a group's probe tiles share an XCD), every group at least one tile.
 struct BigShape {
   int p_tiles, groups;
 };
@@ -969,7 +909,7 @@ BigShape big_shape(int n_cu, int N, int n_probes, int pt) {
   if (b.groups > n_tiles) b.groups = n_tiles;
   return b;
 }
-// whether the 256-probe tiles are filled well enough to beat the 128-probe ones (at most a third of padding)
+// whether 256-probe tiles are filled well enough to beat 128-probe ones (at most a third of padding)
 bool big_tiles_pay(int n_probes) {
   if (n_probes <= kWideUpTo) return false;
   const long padded = (long)(n_probes + 255) / 256 * 256;
@@ -1062,50 +1002,32 @@ pc_status run_lookup(percache_ctx *ctx, const void *probes_dev, int32_t n_probes
 #undef PC_WIDE
     return PC_OK;
   }
-  if (k == 1 && n_probes > kBatchedFrom && d % 64 == 0) {
-    // many probes, best match only: the matrix-core product on 256-row tiles, one workgroup per CU; 256-probe tiles
-    // where the probes fill them to three quarters, else 128-probe tiles
-    const int pt = big_tiles_pay(n_probes) ? 256 : 128;
+  if (n_probes > kBatchedFrom) {  // (d is a multiple of 64: percache_create checks it)
+    // many probes: the matrix-core product on 256-row tiles, one workgroup per CU; 256-probe tiles where the probes
+    // fill them to three quarters (best match only: a top-k call's lists need their registers), else 128-probe tiles
+    const int pt = k == 1 && big_tiles_pay(n_probes) ? 256 : 128;
     const BigShape bg = big_shape(ctx->n_cu, N, n_probes, pt);
     static bool big_lds_set = false;  // dynamic LDS above 64 KB must be opted into once
     if (!big_lds_set) {
-      PC_HIP(ctx, hipFuncSetAttribute((const void *)lookup_big_kernel<256>, hipFuncAttributeMaxDynamicSharedMemorySize, BigTile<256>::LDS));
-      PC_HIP(ctx, hipFuncSetAttribute((const void *)lookup_big_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, BigTile<128>::LDS));
+      PC_HIP(ctx, hipFuncSetAttribute((const void *)lookup_big_kernel<256, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, BigTile<256>::LDS));
+      PC_HIP(ctx, hipFuncSetAttribute((const void *)lookup_big_kernel<128, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, BigTile<128>::LDS));
+      PC_HIP(ctx, hipFuncSetAttribute((const void *)lookup_big_kernel<128, kMaxTopK>, hipFuncAttributeMaxDynamicSharedMemorySize, BigTile<128>::LDS));
       big_lds_set = true;
     }
     const dim3 grid((unsigned)((bg.groups + 7) / 8 * 8 * bg.p_tiles));
     pc::prof_begin(ctx, PC_KERNEL_LOOKUP, st);
-    if (pt == 256)
-      hipLaunchKernelGGL(lookup_big_kernel<256>, grid, dim3(512), BigTile<256>::LDS, st, ctx->bank, ctx->bank_inv, N, d, probes, n_probes,
-                         bg.p_tiles * pt, bg.groups, bg.p_tiles, partial);
-    else
-      hipLaunchKernelGGL(lookup_big_kernel<128>, grid, dim3(512), BigTile<128>::LDS, st, ctx->bank, ctx->bank_inv, N, d, probes, n_probes,
-                         bg.p_tiles * pt, bg.groups, bg.p_tiles, partial);
-    pc::prof_end(ctx, PC_KERNEL_LOOKUP, st);
-    PC_HIP(ctx, hipGetLastError());
-    hipLaunchKernelGGL(lookup_finalize_kernel<1>, dim3(n_probes), dim3(kFinalizeThreads), 0, st, partial, bg.groups, bg.p_tiles * pt, probes, d, tau, 1,
-                       idx_out_dev, sim_out_dev, hit_out_dev);
-    PC_HIP(ctx, hipGetLastError());
-    return PC_OK;
-  }
-  if (n_probes > kBatchedFrom) {
-    // many probes: matrix-core bound product instead of repeated streaming passes
-    const BatchShape bs = batch_shape(ctx->n_cu, N, n_probes);
-    dim3 grid((unsigned)((bs.groups + 7) / 8 * 8 * bs.p_tiles));
-    pc::prof_begin(ctx, PC_KERNEL_LOOKUP, st);
-    if (k == 1)
-      hipLaunchKernelGGL(lookup_batched_kernel<1>, grid, dim3(256), 0, st, ctx->bank, ctx->bank_inv, N, d, probes, n_probes,
-                         bs.tiles_per_wg, bs.p_tiles * 128, bs.groups, bs.p_tiles, partial);
-    else
-      hipLaunchKernelGGL(lookup_batched_kernel<kMaxTopK>, grid, dim3(256), 0, st, ctx->bank, ctx->bank_inv, N, d, probes, n_probes,
-                         bs.tiles_per_wg, bs.p_tiles * 128, bs.groups, bs.p_tiles, partial);
+#define PC_BIG(PP, KK)                                                                                                 \
+  hipLaunchKernelGGL((lookup_big_kernel<PP, KK>), grid, dim3(512), (BigTile<PP>::LDS), st, ctx->bank, ctx->bank_inv, N, d, probes, n_probes, \
+                     bg.p_tiles * pt, bg.groups, bg.p_tiles, partial)
+    if (k > 1) PC_BIG(128, kMaxTopK); else if (pt == 256) PC_BIG(256, 1); else PC_BIG(128, 1);
+#undef PC_BIG
     pc::prof_end(ctx, PC_KERNEL_LOOKUP, st);
     PC_HIP(ctx, hipGetLastError());
     if (k == 1)
-      hipLaunchKernelGGL(lookup_finalize_kernel<1>, dim3(n_probes), dim3(kFinalizeThreads), 0, st, partial, bs.groups, bs.p_tiles * 128, probes, d, tau, 1,
+      hipLaunchKernelGGL(lookup_finalize_kernel<1>, dim3(n_probes), dim3(kFinalizeThreads), 0, st, partial, bg.groups, bg.p_tiles * pt, probes, d, tau, 1,
                          idx_out_dev, sim_out_dev, hit_out_dev);
     else
-      hipLaunchKernelGGL(lookup_finalize_kernel<kMaxTopK>, dim3(n_probes), dim3(kFinalizeThreads), 0, st, partial, bs.groups, bs.p_tiles * 128, probes, d,
+      hipLaunchKernelGGL(lookup_finalize_kernel<kMaxTopK>, dim3(n_probes), dim3(kFinalizeThreads), 0, st, partial, bg.groups, bg.p_tiles * pt, probes, d,
                          tau, k, idx_out_dev, sim_out_dev, hit_out_dev);
     PC_HIP(ctx, hipGetLastError());
     return PC_OK;
@@ -1162,11 +1084,7 @@ size_t percache_lookup_workspace_bytes(const percache_ctx *ctx, int32_t n_probes
   if (!ctx || n_probes < 0) return 0;
   size_t lists = (size_t)max_stream_grid(ctx) * kPassProbes;
   if (n_probes > kBatchedFrom) {
-    // groups * p_tiles <= n_tiles * p_tiles / tiles_per_wg + p_tiles <= 4 n_cu + p_tiles, whatever the bank size
-    const size_t p_tiles = ((size_t)n_probes + 127) / 128;
-    const size_t batched = (4 * (size_t)ctx->n_cu + p_tiles) * 128;
-    if (batched > lists) lists = batched;
-    // the 256 x 256 kernel: groups * p_tiles <= max(n_cu, 8 p_tiles) workgroups of 256 lists
+    // the 256-row kernel: groups * p_tiles <= max(n_cu, 8 p_tiles) workgroups of at most 256 lists
     const size_t p_big = ((size_t)n_probes + 127) / 128;
     const size_t big = ((size_t)ctx->n_cu > 8 * p_big ? (size_t)ctx->n_cu : 8 * p_big) * 256;
     if (big > lists) lists = big;
